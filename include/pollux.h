@@ -1,0 +1,187 @@
+/*
+ * pollux.h -- C ABI of the MI355X (gfx950) library for the PolluxSched search
+ * hot path (Pollux, arXiv 2008.12260, Sec. 4.2-4.3): batched fitness evaluation
+ * of a population of allocation matrices, and one step of the population
+ * search.
+ *
+ * Conventions
+ *   - Every data pointer is a DEVICE pointer unless its comment says "host".
+ *     All buffers are owned by the caller; inputs are never written.
+ *   - Work is enqueued on the HIP stream passed as `hip_stream` (a hipStream_t
+ *     cast to void*, NULL = the default stream).  No call synchronises the
+ *     host except pollux_last_status.  Outputs are valid once the caller has
+ *     synchronised the stream.
+ *   - No call allocates or frees device memory; scratch space is the
+ *     caller-provided `workspace` (size from pollux_workspace_size, 256-byte
+ *     aligned).  Two calls that overlap in time must use different workspaces.
+ *   - Return value: PX_OK (0) or a negative PX_E_* code.  Arguments that can be
+ *     checked on the host are checked before anything is launched.  Conditions
+ *     that depend on device data are OR-ed into a status word inside the
+ *     workspace (PX_ST_* bits), read back with pollux_last_status.
+ *   - Matrices are row-major with the last index contiguous.
+ */
+#ifndef POLLUX_H
+#define POLLUX_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define POLLUX_VERSION 100
+
+typedef struct {
+    int32_t P;         /* candidates in the population                          */
+    int32_t J;         /* jobs (running and pending), rows of an allocation matrix */
+    int32_t N;         /* nodes, columns of an allocation matrix                */
+    int32_t Gm;        /* points of the per-GPU batch-size grid of each job     */
+    int32_t Gs;        /* gradient-accumulation steps considered: s = 0..Gs-1   */
+    int32_t precision; /* 0 = fp64 arithmetic, 1 = fp32 arithmetic              */
+    int32_t flags;     /* PX_FLAG_* */
+} pollux_dims;
+
+enum {
+    PX_FLAG_NO_REALLOC_PENALTY = 1,   /* skip the re-allocation penalty of Sec. 4.2         */
+    PX_FLAG_NO_CONSTRAINT_CHECK = 2   /* fitness is Eq. 14 even for infeasible candidates  */
+};
+
+/* Rows of job_params[PX_NPARAM][J] (structure of arrays, fp64).
+ * The first seven are theta_sys of Sec. 4.1 (Eq. 12); PHI and M0 complete the
+ * goodput-function triple (theta_sys, phi_t, M0) each job reports. */
+enum {
+    PX_ALPHA_G = 0,   /* alpha_grad  [s]           Eq. 8  */
+    PX_BETA_G,        /* beta_grad   [s / example] Eq. 8  */
+    PX_ALPHA_SL,      /* alpha_sync^local          Eq. 9  */
+    PX_BETA_SL,       /* beta_sync^local           Eq. 9  */
+    PX_ALPHA_SN,      /* alpha_sync^node           Eq. 9  */
+    PX_BETA_SN,       /* beta_sync^node            Eq. 9  */
+    PX_GAMMA,         /* overlap exponent, 1 <= gamma <= 10 (Eq. 10, Sec. 4.1) */
+    PX_PHI,           /* pre-conditioned gradient noise scale phi_t > 0 (Eq. 5-6) */
+    PX_M0,            /* initial batch size M0 >= 1 (Sec. 3)                     */
+    PX_MMAX,          /* upper batch-size limit, M0 <= M_max <= 2^52 (Sec. 3.1)  */
+    PX_WEIGHT,        /* weight of the job in the generalized mean, >= 0        */
+    PX_AGE_T,         /* age T_j of the job [s] (Sec. 4.2, re-allocation penalty) */
+    PX_RESTARTS_R,    /* re-allocations R_j so far                               */
+    PX_NPARAM
+};
+
+enum {
+    PX_OK = 0,
+    PX_E_INVALID_ARG = -1,       /* null pointer, non-positive size, non-finite p or delta, delta < 0,
+                                    unknown precision, elite_k outside 1..P, aliasing children/parents */
+    PX_E_WORKSPACE = -2,         /* workspace null, misaligned or smaller than pollux_workspace_size */
+    PX_E_UNSUPPORTED_ARCH = -3,  /* the current device is not gfx950 */
+    PX_E_HIP = -4                /* a HIP runtime call failed (launch, attribute query, copy) */
+};
+
+/* bits of the status word */
+enum {
+    PX_ST_BAD_PARAM = 1,    /* a job parameter outside the domain documented at PX_* above,
+                               or alpha_grad = beta_grad = 0 */
+    PX_ST_ZERO_FAIR = 2,    /* a job's fair-share goodput is 0: its SPEEDUP is set to 0 */
+    PX_ST_BAD_RESTART = 4,  /* T_j - R_j * delta <= 0 for some job (penalty enabled) */
+    PX_ST_NEG_ALLOC = 8     /* a negative entry in population or current_alloc */
+};
+
+/* Bytes of workspace needed by pollux_fitness and pollux_ga_step for `dims`
+ * (one figure that covers both).  Host call, no device access. */
+int pollux_workspace_size(const pollux_dims *dims, size_t *bytes /* host, out */);
+
+/*
+ * FITNESS_p of every candidate (Sec. 4.2, Eq. 14) with the per-job tuning it
+ * needs (Sec. 4.1, Eq. 13).
+ *
+ * For candidate c and job j, with K = sum_n A[c,j,n] GPUs on
+ * nodes = #{n : A[c,j,n] > 0} nodes, the goodput model (Eq. 4 = Eq. 7 x Eq. 6,
+ * with Eq. 8-11) is evaluated at every point of the grid
+ * m in m_grid[j,0..Gm), s in 0..Gs-1 with total batch size
+ * M = K*m*(s+1) restricted to M0 <= M <= M_max, and the maximum is taken; ties
+ * go to the lowest flat index i_m*Gs + s.  SPEEDUP_j (Eq. 15) divides by the
+ * same maximum for the fair-share allocation (fair_share[j] = GPUs, nodes).
+ * A job whose row differs from current_alloc[j] while current_alloc[j] holds
+ * at least one GPU is multiplied by (T_j - R_j*delta)/(T_j + delta).  A job
+ * with K = 0 or no feasible grid point has goodput and SPEEDUP 0.
+ * fitness[c] = (sum_j w_j SPEEDUP_j^p / sum_j w_j)^(1/p)  (p = 0: weighted
+ * geometric mean), with IEEE limits for SPEEDUP = 0 (p < 0 or p = 0 gives 0).
+ * Constraint check ("Interference avoidance", Sec. 4.2, and node capacity):
+ * V = sum_n max(0, d_n - 1) + sum_n max(0, sum_j A[c,j,n] - node_capacity[n]),
+ * d_n = number of jobs with nodes >= 2 and A[c,j,n] > 0; when V > 0 the
+ * fitness is replaced by -V unless PX_FLAG_NO_CONSTRAINT_CHECK is set.
+ *
+ * fp64 (precision 0): best_goodput, speedup and fitness agree with a plain
+ * fp64 evaluation of the formulas to a few units in the last place.
+ * fp32 (precision 1): parameters are rounded to fp32 and all model arithmetic
+ * is fp32; outputs are still stored as fp64.
+ */
+int pollux_fitness(const pollux_dims *dims,              /* host */
+                   const int32_t *population,            /* [P,J,N] */
+                   const double *job_params,             /* [PX_NPARAM,J] */
+                   const int32_t *m_grid,                /* [J,Gm], values >= 1, duplicates allowed */
+                   const int32_t *fair_share,            /* [J,2] = (GPUs, nodes) of the fair share */
+                   const int32_t *current_alloc,         /* [J,N] */
+                   const int32_t *node_capacity,         /* [N] */
+                   double p, double delta,               /* fairness knob; re-allocation delay [s], >= 0 */
+                   void *workspace, size_t workspace_bytes,
+                   double *fitness,                      /* [P] out */
+                   int32_t *best_m,                      /* [P,J] out: m* (the batch size, not its index), -1 if none */
+                   int32_t *best_s,                      /* [P,J] out: s*, -1 if none */
+                   double *best_goodput,                 /* [P,J] out, may be NULL */
+                   double *speedup,                      /* [P,J] out, may be NULL: SPEEDUP_j after the penalty */
+                   int32_t *violations,                  /* [P] out, may be NULL: V */
+                   void *hip_stream);
+
+typedef struct {
+    uint64_t seed;           /* Philox key (low word, high word) */
+    uint32_t generation;     /* counter word 0 */
+    uint32_t elite_k;        /* survivors, 1..P: the best elite_k candidates are copied unchanged */
+    uint32_t mut_threshold;  /* per-job mutation probability * 2^32, rounded down */
+    uint32_t flags;          /* reserved, 0 */
+} pollux_ga_params;
+
+/*
+ * One generation of the population search (Sec. 4.3: candidates are perturbed
+ * and combined, then modified to satisfy node capacity and interference
+ * avoidance).  The paper leaves the operators open; this library defines them
+ * as follows, with every random draw taken from Philox4x32-10 (Salmon et al.,
+ * SC'11), key = seed, counter = (generation, child, item, tag), word 0 unless
+ * noted, and below(r, n) = (r * n) >> 32:
+ *   rank     candidates ordered by (fitness descending, index ascending), NaN last;
+ *   c < elite_k   child c = the candidate of rank c, verbatim;
+ *   c >= elite_k  parents a, b = ranks below(word0, elite_k), below(word1, elite_k)   (item 0, tag 0);
+ *                 row j comes from b if bit 0 is set, else from a                     (item j, tag 1);
+ *                 if word0 < mut_threshold                                             (item j, tag 2)
+ *                   then with (word0 % 3, n = below(word1, N))                         (item j, tag 3):
+ *                   0: row[n] += 1;  1: row[n] -= 1 if positive;
+ *                   2: row := 0 except row[n] = min(sum of row, node_capacity[n]);
+ *                 repair capacity: for each node over capacity, walking jobs cyclically
+ *                   from below(word0, J) (item n, tag 4), remove GPUs until it fits;
+ *                 repair interference: nodes in ascending order; of the multi-node jobs
+ *                   present keep the one with most GPUs there (lowest j on ties), zero
+ *                   the others there (their node counts drop, which later nodes see).
+ * All arithmetic is integer; the result is a pure function of the arguments.
+ */
+int pollux_ga_step(const pollux_dims *dims,              /* host; Gm, Gs, precision ignored */
+                   const int32_t *parents,               /* [P,J,N] */
+                   const double *fitness,                /* [P] */
+                   const int32_t *node_capacity,         /* [N] */
+                   const pollux_ga_params *params,       /* host */
+                   void *workspace, size_t workspace_bytes,
+                   int32_t *children,                    /* [P,J,N] out, must not overlap parents */
+                   void *hip_stream);
+
+/* Copies the status word of the last pollux_fitness call that used `workspace`
+ * to *host_out.  Synchronises `hip_stream`. */
+int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out /* host */);
+
+/* Text for a PX_* return code (static storage, never NULL). */
+const char *pollux_strerror(int code);
+
+/* POLLUX_VERSION of the built library. */
+int pollux_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* POLLUX_H */

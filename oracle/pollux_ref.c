@@ -155,7 +155,7 @@ static int job_is_bad(const pollux_ref_job *job, double weight)
     return !(job->gamma >= 1.0 && job->gamma <= 10.0) || !(job->alpha_g >= 0.0) || !(job->beta_g >= 0.0) ||
            !(job->alpha_sl >= 0.0) || !(job->beta_sl >= 0.0) || !(job->alpha_sn >= 0.0) ||
            !(job->beta_sn >= 0.0) || !(job->phi > 0.0) || !(job->M0 >= 1.0) || !(job->Mmax >= job->M0) ||
-           !(weight >= 0.0);
+           !(weight >= 0.0) || !(job->Mmax <= 4503599627370496.0) || !(job->alpha_g + job->beta_g > 0.0);
 }
 
 int pollux_fitness_ref(const pollux_ref_dims *d, const int32_t *population, const double *job_params,

@@ -43,7 +43,8 @@ enum {
 
 /* data-dependent conditions, OR-ed into *status */
 enum {
-    PXR_ST_BAD_PARAM = 1,      /* gamma outside [1,10], negative alpha/beta/weight, phi<=0, M0<1, M_max<M0 */
+    PXR_ST_BAD_PARAM = 1,      /* gamma outside [1,10], negative alpha/beta/weight, phi<=0, M0<1, M_max<M0,
+                                  M_max > 2^52 (M no longer exact in fp64), alpha_grad = beta_grad = 0 (T_grad = 0) */
     PXR_ST_ZERO_FAIR = 2,      /* fair-share goodput is zero: SPEEDUP set to 0 */
     PXR_ST_BAD_RESTART = 4,    /* T_j - R_j*delta <= 0 */
     PXR_ST_NEG_ALLOC = 8       /* a negative entry in an allocation matrix */

@@ -1,0 +1,173 @@
+"""Thin Python binding of libpollux_hip.so (C ABI in include/pollux.h).
+
+Argument marshalling only: every step of the path runs in the HIP kernels.
+torch is used for device memory and streams.  There is no CPU fallback: if the
+library has not been built, importing the entry points raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpollux_hip.so")
+
+NPARAM = 13
+PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
+PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK = 1, 2
+PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
+
+EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
+           "pollux_last_status")
+
+
+class PolluxError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} ({code})")
+
+
+class Dims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in ("P", "J", "N", "Gm", "Gs", "precision", "flags")]
+
+
+class GaParams(ctypes.Structure):
+    _fields_ = [("seed", ctypes.c_uint64), ("generation", ctypes.c_uint32), ("elite_k", ctypes.c_uint32),
+                ("mut_threshold", ctypes.c_uint32), ("flags", ctypes.c_uint32)]
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the built library; raise if it is missing (no fallback of any kind)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not built: run `python -c 'import __graft_entry__ as g; g.build()'`")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, d, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_double, ctypes.c_size_t
+        L.pollux_version.restype = i
+        L.pollux_version.argtypes = []
+        L.pollux_strerror.restype = ctypes.c_char_p
+        L.pollux_strerror.argtypes = [i]
+        L.pollux_workspace_size.restype = i
+        L.pollux_workspace_size.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
+        L.pollux_fitness.restype = i
+        L.pollux_fitness.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz] + [vp] * 6 + [vp]
+        L.pollux_ga_step.restype = i
+        L.pollux_ga_step.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp, sz, vp, vp]
+        L.pollux_last_status.restype = i
+        L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        _lib = L
+    return _lib
+
+
+def version() -> int:
+    return lib().pollux_version()
+
+
+def strerror(code: int) -> str:
+    return lib().pollux_strerror(code).decode()
+
+
+def workspace_size(dims: Dims) -> int:
+    n = ctypes.c_size_t(0)
+    rc = lib().pollux_workspace_size(ctypes.byref(dims), ctypes.byref(n))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_workspace_size")
+    return n.value
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_handle(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def pollux_fitness(dims: Dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity,
+                   p: float, delta: float, workspace, fitness, best_m, best_s, best_goodput=None, speedup=None,
+                   violations=None, stream=None) -> None:
+    """pollux_fitness of the C ABI on torch device tensors (already allocated, contiguous)."""
+    rc = lib().pollux_fitness(
+        ctypes.byref(dims), _ptr(population), _ptr(job_params), _ptr(m_grid), _ptr(fair_share), _ptr(current_alloc),
+        _ptr(node_capacity), float(p), float(delta), _ptr(workspace), workspace.numel() * workspace.element_size(),
+        _ptr(fitness), _ptr(best_m), _ptr(best_s), _ptr(best_goodput), _ptr(speedup), _ptr(violations),
+        _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_fitness")
+
+
+def pollux_ga_step(dims: Dims, parents, fitness, node_capacity, ga: GaParams, workspace, children, stream=None) -> None:
+    """pollux_ga_step of the C ABI on torch device tensors."""
+    rc = lib().pollux_ga_step(
+        ctypes.byref(dims), _ptr(parents), _ptr(fitness), _ptr(node_capacity), ctypes.byref(ga), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _ptr(children), _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_ga_step")
+
+
+def pollux_last_status(workspace, stream=None) -> int:
+    out = ctypes.c_int32(0)
+    rc = lib().pollux_last_status(_ptr(workspace), _stream_handle(stream), ctypes.byref(out))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_last_status")
+    return out.value
+
+
+class FitnessCall:
+    """Device buffers of one configuration plus the two entry points bound to them.
+
+    Allocation happens here, once; `run()` and `ga_step()` only marshal pointers.
+    """
+
+    def __init__(self, P, J, N, Gm, Gs, job_params, m_grid, fair_share, current_alloc, node_capacity,
+                 p=-1.0, delta=30.0, flags=0, precision=0, device="cuda:0"):
+        import torch
+        self.torch = torch
+        self.dims = Dims(P, J, N, Gm, Gs, precision, flags)
+        self.p, self.delta = float(p), float(delta)
+        dev = torch.device(device)
+        as_dev = lambda a, dt: torch.as_tensor(a, dtype=dt).contiguous().to(dev)
+        self.job_params = as_dev(job_params, torch.float64)
+        self.m_grid = as_dev(m_grid, torch.int32)
+        self.fair_share = as_dev(fair_share, torch.int32)
+        self.current_alloc = as_dev(current_alloc, torch.int32)
+        self.node_capacity = as_dev(node_capacity, torch.int32)
+        assert self.job_params.shape == (NPARAM, J) and self.m_grid.shape == (J, Gm)
+        assert self.fair_share.shape == (J, 2) and self.current_alloc.shape == (J, N) and self.node_capacity.shape == (N,)
+        self.workspace = torch.empty(workspace_size(self.dims), dtype=torch.uint8, device=dev)
+        assert self.workspace.data_ptr() % 256 == 0
+        self.fitness = torch.empty(P, dtype=torch.float64, device=dev)
+        self.best_m = torch.empty((P, J), dtype=torch.int32, device=dev)
+        self.best_s = torch.empty((P, J), dtype=torch.int32, device=dev)
+        self.best_goodput = torch.empty((P, J), dtype=torch.float64, device=dev)
+        self.speedup = torch.empty((P, J), dtype=torch.float64, device=dev)
+        self.violations = torch.empty(P, dtype=torch.int32, device=dev)
+
+    def run(self, population, stream=None, outputs="all"):
+        full = outputs == "all"
+        pollux_fitness(self.dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
+                       self.node_capacity, self.p, self.delta, self.workspace, self.fitness, self.best_m, self.best_s,
+                       self.best_goodput if full else None, self.speedup if full else None, self.violations,
+                       stream)
+
+    def status(self, stream=None) -> int:
+        return pollux_last_status(self.workspace, stream)
+
+    def ga_step(self, parents, children, seed, generation, elite_k, mut_threshold, fitness=None, stream=None):
+        ga = GaParams(seed, generation, elite_k, mut_threshold, 0)
+        pollux_ga_step(self.dims, parents, self.fitness if fitness is None else fitness, self.node_capacity, ga,
+                       self.workspace, children, stream)
+
+    def results(self) -> dict:
+        self.torch.cuda.synchronize()
+        return dict(fitness=self.fitness.cpu().numpy(), best_m=self.best_m.cpu().numpy(),
+                    best_s=self.best_s.cpu().numpy(), best_goodput=self.best_goodput.cpu().numpy(),
+                    speedup=self.speedup.cpu().numpy(), violations=self.violations.cpu().numpy(),
+                    status=self.status())

@@ -1,0 +1,125 @@
+// C ABI of the library (see include/pollux.h): argument checks on the host,
+// device check, then the launch functions.
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <string.h>
+
+#include "../../include/pollux.h"
+#include "pollux_host.h"
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+int g_arch_ok[kMaxDevices];   // 0 unknown, 1 gfx950, -1 something else
+
+int check_device()
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PX_E_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return PX_E_HIP;
+    if (g_arch_ok[dev] == 0) {
+        hipDeviceProp_t prop;
+        if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return PX_E_HIP;
+        g_arch_ok[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+    }
+    return g_arch_ok[dev] == 1 ? PX_OK : PX_E_UNSUPPORTED_ARCH;
+}
+
+bool dims_ok(const pollux_dims *d, bool need_grid)
+{
+    if (!d) return false;
+    if (d->P <= 0 || d->J <= 0 || d->N <= 0) return false;
+    if (need_grid && (d->Gm <= 0 || d->Gs <= 0)) return false;
+    if (d->precision != 0 && d->precision != 1) return false;
+    // flat indices of (candidate, job) pairs and of grid points are kept in 32 bits
+    if ((long long)d->P * d->J > 0x7FFFFFFFll) return false;
+    if (need_grid && (long long)d->Gm * d->Gs > 0x7FFFFFFFll) return false;
+    if (need_grid && (long long)d->J * d->Gm > 0x7FFFFFFFll) return false;
+    return true;
+}
+
+int check_workspace(const pollux_dims *d, const void *ws, size_t bytes)
+{
+    if (!ws || ((uintptr_t)ws & 255u) != 0) return PX_E_WORKSPACE;
+    if (bytes < px::workspace_layout(*d).total) return PX_E_WORKSPACE;
+    return PX_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int pollux_version(void) { return POLLUX_VERSION; }
+
+const char *pollux_strerror(int code)
+{
+    switch (code) {
+        case PX_OK: return "success";
+        case PX_E_INVALID_ARG: return "invalid argument";
+        case PX_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case PX_E_UNSUPPORTED_ARCH: return "current device is not gfx950";
+        case PX_E_HIP: return "HIP runtime error";
+        default: return "unknown error code";
+    }
+}
+
+int pollux_workspace_size(const pollux_dims *dims, size_t *bytes)
+{
+    if (!bytes || !dims_ok(dims, false)) return PX_E_INVALID_ARG;
+    *bytes = px::workspace_layout(*dims).total;
+    return PX_OK;
+}
+
+int pollux_fitness(const pollux_dims *dims, const int32_t *population, const double *job_params, const int32_t *m_grid,
+                   const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
+                   double delta, void *workspace, size_t workspace_bytes, double *fitness, int32_t *best_m,
+                   int32_t *best_s, double *best_goodput, double *speedup, int32_t *violations, void *hip_stream)
+{
+    if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
+    if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !fitness ||
+        !best_m || !best_s)
+        return PX_E_INVALID_ARG;
+    if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
+    if (dims->precision != 0) return PX_E_INVALID_ARG;   // fp32 arithmetic: not built yet
+    int rc = check_workspace(dims, workspace, workspace_bytes);
+    if (rc != PX_OK) return rc;
+    rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
+                              workspace, fitness, best_m, best_s, best_goodput, speedup, violations,
+                              (hipStream_t)hip_stream);
+}
+
+int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double *fitness,
+                   const int32_t *node_capacity, const pollux_ga_params *params, void *workspace,
+                   size_t workspace_bytes, int32_t *children, void *hip_stream)
+{
+    if (!dims_ok(dims, false)) return PX_E_INVALID_ARG;
+    if (!parents || !fitness || !node_capacity || !params || !children) return PX_E_INVALID_ARG;
+    if (params->elite_k < 1u || params->elite_k > (uint32_t)dims->P) return PX_E_INVALID_ARG;
+    if (dims->J > 32768) return PX_E_INVALID_ARG;         // per-job node counts live in LDS during repair
+    const size_t bytes = sizeof(int32_t) * (size_t)dims->P * dims->J * dims->N;
+    const char *a = (const char *)parents, *b = (const char *)children;
+    if (a < b + bytes && b < a + bytes) return PX_E_INVALID_ARG;
+    int rc = check_workspace(dims, workspace, workspace_bytes);
+    if (rc != PX_OK) return rc;
+    rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_ga_step(dims, parents, fitness, node_capacity, params, workspace, children,
+                              (hipStream_t)hip_stream);
+}
+
+int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out)
+{
+    if (!workspace || !host_out) return PX_E_INVALID_ARG;
+    const char *ws = (const char *)workspace;
+    pollux_dims d = {1, 1, 1, 1, 1, 0, 0};
+    const size_t off = px::workspace_layout(d).status;    // the status word sits at a fixed offset
+    if (hipMemcpyAsync(host_out, ws + off, sizeof(int32_t), hipMemcpyDeviceToHost, (hipStream_t)hip_stream) != hipSuccess)
+        return PX_E_HIP;
+    if (hipStreamSynchronize((hipStream_t)hip_stream) != hipSuccess) return PX_E_HIP;
+    return PX_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,79 @@
+// Device-side building blocks shared by the fitness and search kernels:
+// 64-lane wavefront exchange through DPP and ds_swizzle, and wave reductions.
+// gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace px {
+
+constexpr int kWave = 64;
+
+__device__ __forceinline__ int lane_id() { return (int)__builtin_amdgcn_mbcnt_hi(~0u, __builtin_amdgcn_mbcnt_lo(~0u, 0u)); }
+
+// ---- lane exchange ---------------------------------------------------------
+// Every lane receives the value of a partner lane chosen so that six steps
+// combine all 64 lanes: quad permutes (partner = lane^1, lane^2), mirror
+// within 8 and within 16 lanes (DPP), lane^16 (ds_swizzle in bit mode:
+// and 0x1F, or 0, xor 0x10), and lane^32 (ds_bpermute).
+template <int STEP>
+__device__ __forceinline__ int exchange(int v)
+{
+    if constexpr (STEP == 0) return __builtin_amdgcn_update_dpp(v, v, 0xB1, 0xF, 0xF, false);   // quad_perm [1,0,3,2]
+    if constexpr (STEP == 1) return __builtin_amdgcn_update_dpp(v, v, 0x4E, 0xF, 0xF, false);   // quad_perm [2,3,0,1]
+    if constexpr (STEP == 2) return __builtin_amdgcn_update_dpp(v, v, 0x141, 0xF, 0xF, false);  // row_half_mirror
+    if constexpr (STEP == 3) return __builtin_amdgcn_update_dpp(v, v, 0x140, 0xF, 0xF, false);  // row_mirror
+    if constexpr (STEP == 4) return __builtin_amdgcn_ds_swizzle(v, 0x401F);                     // lane ^ 16
+    return __builtin_amdgcn_ds_bpermute((lane_id() ^ 32) << 2, v);                              // lane ^ 32
+}
+
+template <int STEP>
+__device__ __forceinline__ double exchange(double v)
+{
+    int lo = __double2loint(v), hi = __double2hiint(v);
+    return __hiloint2double(exchange<STEP>(hi), exchange<STEP>(lo));
+}
+
+template <int STEP>
+__device__ __forceinline__ long long exchange(long long v)
+{
+    int lo = (int)(v & 0xFFFFFFFFll), hi = (int)(v >> 32);
+    return ((long long)exchange<STEP>(hi) << 32) | (long long)(unsigned)exchange<STEP>(lo);
+}
+
+template <int STEP = 0>
+__device__ __forceinline__ long long wave_sum(long long v)
+{
+    v += exchange<STEP>(v);
+    if constexpr (STEP < 5) return wave_sum<STEP + 1>(v);
+    return v;
+}
+
+template <int STEP = 0>
+__device__ __forceinline__ int wave_sum(int v)
+{
+    v += exchange<STEP>(v);
+    if constexpr (STEP < 5) return wave_sum<STEP + 1>(v);
+    return v;
+}
+
+template <int STEP = 0>
+__device__ __forceinline__ int wave_min(int v)
+{
+    int o = exchange<STEP>(v);
+    v = o < v ? o : v;
+    if constexpr (STEP < 5) return wave_min<STEP + 1>(v);
+    return v;
+}
+
+template <int STEP = 0>
+__device__ __forceinline__ double wave_max(double v)
+{
+    double o = exchange<STEP>(v);
+    v = o > v ? o : v;
+    if constexpr (STEP < 5) return wave_max<STEP + 1>(v);
+    return v;
+}
+
+}  // namespace px

@@ -1,0 +1,56 @@
+// Host-side declarations shared by the translation units of the library:
+// workspace layout and the launch functions behind the C ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/pollux.h"
+
+namespace px {
+
+// Byte offsets of the sections of the caller's workspace (each 256-byte aligned).
+struct WorkspaceLayout {
+    size_t status;    // int32 status word
+    size_t rs;        // double [Gs]      1/(s+1)
+    size_t tg;        // double [J,Gm]    T_grad(m_i)
+    size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
+    size_t denom;     // double [J]       fair-share goodput
+    size_t factor;    // double [J]       re-allocation factor
+    size_t running;   // int32  [J]       job holds GPUs in current_alloc
+    size_t S;         // double [P,J]     SPEEDUP after the penalty
+    size_t nodes;     // int32  [P,J]     nodes occupied by the row
+    size_t order;     // int32  [P]       candidates by rank (search step)
+    size_t total;
+};
+
+inline WorkspaceLayout workspace_layout(const pollux_dims &d)
+{
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    WorkspaceLayout L;
+    size_t o = 0;
+    const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
+    L.status = o;  o = up(o + 256);
+    L.rs = o;      o = up(o + 8 * Gs);
+    L.tg = o;      o = up(o + 8 * J * Gm);
+    L.lntg = o;    o = up(o + 8 * J * Gm);
+    L.denom = o;   o = up(o + 8 * J);
+    L.factor = o;  o = up(o + 8 * J);
+    L.running = o; o = up(o + 4 * J);
+    L.S = o;       o = up(o + 8 * P * J);
+    L.nodes = o;   o = up(o + 4 * P * J);
+    L.order = o;   o = up(o + 4 * P);
+    L.total = o;
+    return L;
+}
+
+int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
+                   const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
+                   double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
+                   double *best_goodput, double *speedup, int32_t *violations, hipStream_t stream);
+
+int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
+                   const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
+
+}  // namespace px

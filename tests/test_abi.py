@@ -1,0 +1,77 @@
+"""The C-ABI library loads, exports every symbol declared in include/pollux.h, and
+rejects bad arguments on the host before touching a device (no GPU needed)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2008_12260_amd as px
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "pollux.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(pollux_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_functions()
+    assert set(names) == set(px.EXPORTS)
+    L = px.lib()
+    for n in names:
+        assert getattr(L, n) is not None
+    assert px.version() == 100
+    assert px.strerror(0) == "success" and "workspace" in px.strerror(px.PX_E_WORKSPACE)
+    assert px.strerror(-99) == "unknown error code"
+
+
+def test_workspace_size_grows_with_the_problem_and_rejects_bad_dims():
+    small = px.workspace_size(px.Dims(16, 8, 4, 32, 8, 0, 0))
+    big = px.workspace_size(px.Dims(4096, 1000, 256, 128, 32, 0, 0))
+    assert 0 < small < big and small % 256 == 0
+    assert big >= 4096 * 1000 * 12
+    for bad in (px.Dims(0, 8, 4, 32, 8, 0, 0), px.Dims(16, -1, 4, 32, 8, 0, 0), px.Dims(16, 8, 0, 32, 8, 0, 0),
+                px.Dims(16, 8, 4, 32, 8, 7, 0), px.Dims(70000, 70000, 4, 1, 1, 0, 0)):
+        with pytest.raises(px.PolluxError) as e:
+            px.workspace_size(bad)
+        assert e.value.code == px.PX_E_INVALID_ARG
+
+
+def test_entry_points_reject_bad_arguments_without_a_device():
+    L = px.lib()
+    d = px.Dims(16, 8, 4, 32, 8, 0, 0)
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    null = ctypes.c_void_p(0)
+    args = [fake] * 6 + [-1.0, 30.0, fake, 1 << 30] + [fake] * 6 + [null]
+    assert L.pollux_fitness(None, *args) == px.PX_E_INVALID_ARG
+    bad = list(args); bad[0] = null
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    bad = list(args); bad[6] = float("nan")
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    bad = list(args); bad[7] = -1.0
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    bad = list(args); bad[8] = null
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
+    bad = list(args); bad[8] = ctypes.c_void_p(0x1001)
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
+    bad = list(args); bad[9] = 16
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
+    d0 = px.Dims(16, 8, 4, 0, 8, 0, 0)
+    assert L.pollux_fitness(ctypes.byref(d0), *args) == px.PX_E_INVALID_ARG
+
+    ga = px.GaParams(1, 0, 8, 0, 0)
+    gargs = [fake, fake, fake, ctypes.byref(ga), fake, 1 << 30, ctypes.c_void_p(0x100000), null]
+    bad = list(gargs); bad[6] = fake                       # children alias parents
+    assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    ga0 = px.GaParams(1, 0, 0, 0, 0)
+    bad = list(gargs); bad[3] = ctypes.byref(ga0)
+    assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    ga17 = px.GaParams(1, 0, 17, 0, 0)
+    bad = list(gargs); bad[3] = ctypes.byref(ga17)
+    assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    bad = list(gargs); bad[4] = null
+    assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
+    assert L.pollux_last_status(null, null, None) == px.PX_E_INVALID_ARG

@@ -1,0 +1,138 @@
+"""GPU parity of pollux_fitness against the CPU oracle (element by element)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from parity import compare, run_gpu, run_oracle
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_fitness_matches_oracle_on_paper_shaped_configs(name):
+    wl = W.make(name)
+    ties = compare(wl, run_gpu(wl), run_oracle(wl))
+    assert ties == 0
+
+
+@pytest.mark.parametrize("p", [-10.0, -1.0, 0.0, 0.5, 1.0])
+def test_fairness_knob_values(p):
+    wl = W.make("physical")
+    assert compare(wl, run_gpu(wl, p=p), run_oracle(wl, p=p)) == 0
+
+
+@pytest.mark.parametrize("p", [-1.0, 0.5, 1.0])
+def test_mid_config_at_three_knob_values(p):
+    wl = W.make("mid")
+    sub = wl.population[:200]
+    assert compare(wl, run_gpu(wl, population=sub, p=p), run_oracle(wl, population=sub, p=p), population=sub) == 0
+
+
+def test_fair_share_candidate_scores_exactly_one():
+    for name in ("tiny", "physical", "mid"):
+        wl = W.make(name, current="fair")
+        for p in (-1.0, 0.0, 1.0):
+            r = run_gpu(wl, population=wl.population[:1], p=p)
+            assert np.all(r["speedup"][0] == 1.0) and r["fitness"][0] == 1.0 and r["status"] == 0
+
+
+@pytest.mark.parametrize("shape", [
+    dict(P=3, J=1, N=1, cap=8, Gm=1, Gs=1),
+    dict(P=5, J=7, N=3, cap=4, Gm=5, Gs=3),
+    dict(P=9, J=13, N=67, cap=2, Gm=70, Gs=5),        # ragged: N and Gm just past one wavefront
+    dict(P=4, J=6, N=130, cap=3, Gm=129, Gs=33),      # grid and s range just past a tile
+    dict(P=2, J=3, N=5, cap=4, Gm=200, Gs=70),
+    dict(P=1, J=300, N=9, cap=40, Gm=33, Gs=2),       # more jobs than threads of a workgroup
+])
+def test_ragged_and_degenerate_shapes(shape):
+    cfg = W.custom("ragged", **shape)
+    wl = W.make(cfg)
+    assert compare(wl, run_gpu(wl), run_oracle(wl)) == 0
+
+
+def test_flags_and_penalty_switch():
+    wl = W.make("physical")
+    for flags in (1, 2, 3):
+        assert compare(wl, run_gpu(wl, flags=flags), run_oracle(wl, flags=flags)) == 0
+
+
+def test_zero_delta_and_pending_current_jobs():
+    wl = W.make("physical")
+    cur = wl.current_alloc.copy()
+    cur[::3] = 0
+    assert compare(wl, run_gpu(wl, current=cur, delta=0.0), run_oracle(wl, current=cur, delta=0.0)) == 0
+    assert compare(wl, run_gpu(wl, current=cur), run_oracle(wl, current=cur)) == 0
+
+
+def test_special_parameter_regimes():
+    """gamma = 1 (plain sum), gamma = 10, zeroed synchronisation terms (exploration priors), huge and tiny phi."""
+    wl = W.make("physical")
+    jp = wl.job_params.copy()
+    ix = W.PARAM_INDEX
+    jp[ix["gamma"], 0::5] = 1.0
+    jp[ix["gamma"], 1::5] = 10.0
+    jp[ix["alpha_sync_local"], 2::5] = 0.0
+    jp[ix["beta_sync_local"], 2::5] = 0.0
+    jp[ix["beta_sync_node"], 3::5] = 0.0
+    jp[ix["alpha_sync_node"], 4::10] = 0.0
+    jp[ix["beta_sync_node"], 4::10] = 0.0
+    jp[ix["phi"], 0::7] = 1e12
+    jp[ix["phi"], 3::7] = 1e-3
+    assert compare(wl, run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp), job_params=jp) == 0
+
+
+def test_tight_batch_limits_and_nothing_feasible():
+    wl = W.make("physical")
+    jp = wl.job_params.copy()
+    ix = W.PARAM_INDEX
+    jp[ix["M_max"], 0::4] = jp[ix["M0"], 0::4]            # M must equal M0 exactly
+    jp[ix["M0"], 1::8] = 1e7                              # out of reach: goodput 0 everywhere, status ZERO_FAIR
+    jp[ix["M_max"], 1::8] = 3.2e8
+    jp[ix["M0"], 2::8] = 100.5                            # non-integer limits
+    jp[ix["M_max"], 2::8] = 1000.25
+    g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
+    assert r["status"] & 2
+    assert compare(wl, g, r, job_params=jp) == 0
+
+
+def test_status_bits():
+    wl = W.make("tiny")
+    ix = W.PARAM_INDEX
+    jp = wl.job_params.copy()
+    jp[ix["gamma"], 2] = 11.0
+    assert run_gpu(wl, job_params=jp)["status"] & 1
+    jp = wl.job_params.copy()
+    jp[ix["age_T"], 1] = 10.0
+    jp[ix["restarts_R"], 1] = 3.0
+    g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
+    assert g["status"] == r["status"] == 4
+    pop = wl.population.copy()
+    pop[2, 2, 1] = -1
+    assert run_gpu(wl, population=pop)["status"] == 8
+
+
+def test_starved_jobs_and_duplicate_batch_sizes():
+    wl = W.make("tiny")
+    pop = wl.population.copy()
+    pop[:, 5, :] = 0
+    for p in (-1.0, 0.0, 1.0):
+        assert compare(wl, run_gpu(wl, population=pop, p=p), run_oracle(wl, population=pop, p=p), population=pop) == 0
+    # a grid made of copies of few values: ties must go to the lowest index on both sides
+    wl.m_grid[:] = np.repeat(wl.m_grid[:, ::8], 8, axis=1)
+    assert compare(wl, run_gpu(wl), run_oracle(wl)) == 0
+
+
+def test_deterministic_across_runs():
+    wl = W.make("physical")
+    a, b = run_gpu(wl), run_gpu(wl)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations"):
+        assert np.array_equal(a[k], b[k], equal_nan=True)
+
+
+def test_large_config_on_sampled_candidates():
+    """Headline shape (1000 jobs, 256 nodes, 128 x 32 grid) on a seeded subset of its population."""
+    cfg = W.CONFIGS["large"]
+    wl = W.make(cfg, with_population=False)
+    idx = [0, 1, 3, 7, 1000, 4095]
+    sub = np.concatenate([W.candidates(cfg, i, 1) for i in idx])
+    assert compare(wl, run_gpu(wl, population=sub), run_oracle(wl, population=sub), population=sub) == 0

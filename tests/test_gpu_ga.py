@@ -1,0 +1,95 @@
+"""GPU parity of pollux_ga_step against the CPU oracle: bit-exact matrices."""
+import numpy as np
+import pytest
+
+import oracle as O
+import workloads as W
+from parity import run_oracle
+
+pytestmark = pytest.mark.gpu
+SEED = 0x2008_1226_0000_0001
+
+
+def gpu_call(wl, P=None):
+    import paper_2008_12260_amd as px
+    c = wl.cfg
+    return px.FitnessCall(c.P if P is None else P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share,
+                          wl.current_alloc, wl.node_capacity, p=c.p, delta=c.delta)
+
+
+@pytest.mark.parametrize("name,mut", [("tiny", 1 << 29), ("physical", 1 << 29), ("physical", 0xFFFFFFFF), ("mid", 1 << 29)])
+def test_single_step_matches_oracle(name, mut):
+    import torch
+    wl = W.make(name)
+    c = wl.cfg
+    fit = run_oracle(wl)["fitness"]
+    call = gpu_call(wl)
+    parents = torch.as_tensor(wl.population).cuda()
+    children = torch.empty_like(parents)
+    dfit = torch.as_tensor(fit).cuda()
+    for gen in (0, 5):
+        call.ga_step(parents, children, SEED, gen, c.P // 2, mut, fitness=dfit)
+        want = O.ga_step(wl.population, fit, wl.node_capacity, SEED, gen, c.P // 2, mut)
+        assert np.array_equal(children.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("shape", [
+    dict(P=4, J=1, N=1, cap=2, Gm=2, Gs=1),
+    dict(P=7, J=5, N=3, cap=1, Gm=2, Gs=1),
+    dict(P=6, J=300, N=70, cap=2, Gm=2, Gs=1),
+    dict(P=5, J=9, N=300, cap=3, Gm=2, Gs=1),
+])
+def test_ragged_shapes_and_heavy_repair(shape):
+    import torch
+    cfg = W.custom("ga_ragged", **shape)
+    wl = W.make(cfg)
+    rng = np.random.default_rng(3)
+    pop = wl.population + (rng.uniform(size=wl.population.shape) < 0.3)      # overload nodes, spread jobs
+    pop = pop.astype(np.int32)
+    fit = rng.choice([0.5, 0.7, -2.0, 1.0], cfg.P)                           # ties in the ranking
+    call = gpu_call(wl)
+    parents = torch.as_tensor(pop).cuda()
+    children = torch.empty_like(parents)
+    for elite in (1, cfg.P // 2, cfg.P):
+        call.ga_step(parents, children, SEED, 9, elite, 1 << 31, fitness=torch.as_tensor(fit).cuda())
+        want = O.ga_step(pop, fit, wl.node_capacity, SEED, 9, elite, 1 << 31)
+        assert np.array_equal(children.cpu().numpy(), want)
+
+
+@pytest.mark.parametrize("name,gens", [("physical", 30), ("mid", 100)])
+def test_search_loop_matches_oracle_every_generation(name, gens):
+    """fitness -> step -> fitness ... on both sides independently; matrices compared at every generation."""
+    import torch
+    wl = W.make(name)
+    c = wl.cfg
+    call = gpu_call(wl)
+    a = torch.as_tensor(wl.population).cuda()
+    b = torch.empty_like(a)
+    host = wl.population
+    mut = 1 << 29          # 1/8 per job
+    for gen in range(gens):
+        call.run(a, outputs="fitness")
+        call.ga_step(a, b, SEED, gen, c.P // 2, mut)
+        f = run_oracle(wl, population=host)["fitness"]
+        host = O.ga_step(host, f, wl.node_capacity, SEED, gen, c.P // 2, mut)
+        a, b = b, a
+        got = a.cpu().numpy()
+        assert np.array_equal(got, host), f"generation {gen}: {np.argwhere((got != host).any(axis=(1, 2))).ravel()[:8]}"
+    # the search made progress and kept feasibility
+    f_end = run_oracle(wl, population=host)
+    assert f_end["fitness"].max() >= run_oracle(wl)["fitness"].max()
+    assert np.all(f_end["violations"][c.P // 2:] == 0)
+
+
+def test_rejects_aliasing_and_bad_elite():
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("tiny")
+    call = gpu_call(wl)
+    a = torch.as_tensor(wl.population).cuda()
+    with pytest.raises(px.PolluxError):
+        call.ga_step(a, a, SEED, 0, 8, 0)
+    with pytest.raises(px.PolluxError):
+        call.ga_step(a, torch.empty_like(a), SEED, 0, 0, 0)
+    with pytest.raises(px.PolluxError):
+        call.ga_step(a, torch.empty_like(a), SEED, 0, 17, 0)
