@@ -1,0 +1,187 @@
+#!/usr/bin/env python3
+"""Benchmark of the PolluxSched search hot path on one MI355X.
+
+A step is one generation on the large configuration (4096 candidates, 1000
+jobs, 256 nodes x 8 GPUs, 128 x 32 grid): pollux_fitness on the current
+population followed by pollux_ga_step into the other buffer.  The reported
+value counts the (m, s) grid points the fitness call sweeps
+(P * J * Gm * Gs per step) over the wall time of the whole step.
+
+Prints one JSON line.  Inputs are synthetic and resident in HBM before the
+timed region starts.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 (FMA) x 2.4 GHz
+FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 divisions, each counted as one
+GA_SEED = 0x2008_1226_5EED_0001
+MUT_THRESHOLD = 1 << 29             # mutation probability 1/8 per job
+
+
+def cpu_baseline(wl, cfg, target_seconds=15.0):
+    """The CPU checker, as it stands, on a bounded sample of the same workload (fitness + search step)."""
+    import numpy as np
+    import oracle as O
+    import workloads as W
+
+    def one(count):
+        pop = W.candidates(cfg, 0, count)
+        t0 = time.perf_counter()
+        r = O.fitness(pop, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc, wl.node_capacity,
+                      cfg.p, cfg.delta, cfg.Gs)
+        O.ga_step(pop, r["fitness"], wl.node_capacity, GA_SEED, 0, max(1, count // 2), MUT_THRESHOLD)
+        return time.perf_counter() - t0
+
+    probe = 32
+    t_probe = one(probe)
+    count = int(min(cfg.P, max(64, probe * target_seconds / max(t_probe, 1e-6))))
+    count = max(64, (count // 64) * 64)
+    t = one(count)
+    evals = count * cfg.J * cfg.Gm * cfg.Gs
+    return {
+        "value": evals / t, "unit": "evals/s", "cores": O.threads(), "kind": "oracle",
+        "sample": f"candidates 0..{count - 1} of {cfg.P} (all {cfg.J} jobs, full {cfg.Gm}x{cfg.Gs} grid), "
+                  f"fitness + one search step, {t:.2f} s",
+        "seconds": t, "affinity_cpus": len(os.sched_getaffinity(0)),
+        "full_population_seconds_extrapolated": t * cfg.P / count,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", choices=["large", "mid", "physical", "tiny"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-ga-loop", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU; a population would shard over candidates, "
+                 "but no multi-GPU path exists. Use --gpus 1.")
+
+    import numpy as np
+    import torch
+    import paper_2008_12260_amd as px
+    import workloads as W
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    dev = torch.device("cuda:0")
+    cfg = W.CONFIGS[args.workload]
+    wl = W.make(cfg, with_population=False)
+    host_pop = W.candidates(cfg, 0, cfg.P)
+    call = px.FitnessCall(cfg.P, cfg.J, cfg.N, cfg.Gm, cfg.Gs, wl.job_params, wl.m_grid, wl.fair_share,
+                          wl.current_alloc, wl.node_capacity, p=cfg.p, delta=cfg.delta, device=dev)
+    a = torch.from_numpy(host_pop).to(dev)
+    del host_pop
+    b = torch.empty_like(a)
+    stream = torch.cuda.current_stream()
+    elite = cfg.P // 2
+
+    def step(gen, a, b):
+        call.run(a, stream=stream, outputs="fitness")
+        call.ga_step(a, b, GA_SEED, gen, elite, MUT_THRESHOLD, stream=stream)
+        return b, a
+
+    gen = 0
+    for _ in range(args.warmup):
+        a, b = step(gen, a, b)
+        gen += 1
+    torch.cuda.synchronize()
+
+    # timed region: exactly --steps generations; the sweep kernel of every step is bracketed by its own events
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    fit_ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in ev + fit_ev:          # create the underlying HIP events before the clock starts
+        e0.record(stream); e1.record(stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        px.pollux_set_sweep_events(*ev[k])
+        fit_ev[k][0].record(stream)
+        call.run(a, stream=stream, outputs="fitness")
+        fit_ev[k][1].record(stream)
+        call.ga_step(a, b, GA_SEED, gen, elite, MUT_THRESHOLD, stream=stream)
+        a, b = b, a
+        gen += 1
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    px.pollux_set_sweep_events(None, None)
+
+    status = call.status()
+    best_fitness = float(call.fitness.max().item())
+    elapsed = t1 - t0
+    evals_per_step = cfg.evals_per_call
+    sweep_ms = [e0.elapsed_time(e1) for e0, e1 in ev]
+    fit_ms = [e0.elapsed_time(e1) for e0, e1 in fit_ev]
+    sweep_avg_ms = sum(sweep_ms) / len(sweep_ms)
+    achieved_tflops = evals_per_step * FLOPS_PER_EVAL / (sweep_avg_ms * 1e-3) / 1e12
+
+    extra = {
+        "fitness_call_ms": sum(fit_ms) / len(fit_ms),
+        "sweep_kernel_ms": sweep_avg_ms,
+        "ga_step_ms": elapsed * 1e3 / args.steps - sum(fit_ms) / len(fit_ms),
+        "fitness_only_evals_per_s": evals_per_step / (sum(fit_ms) / len(fit_ms) * 1e-3),
+        "sweep_kernel_evals_per_s": evals_per_step / (sweep_avg_ms * 1e-3),
+        "population_bytes_per_s_in_sweep": 4.0 * cfg.P * cfg.J * cfg.N / (sweep_avg_ms * 1e-3),
+        "status_word": status, "best_fitness_after_run": best_fitness, "seed": cfg.seed,
+    }
+
+    if not args.no_ga_loop:
+        # the search loop on the mid configuration: 100 generations, fitness + step each
+        mcfg = W.CONFIGS["mid"]
+        mwl = W.make(mcfg)
+        mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid, mwl.fair_share,
+                               mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta, device=dev)
+        ma = torch.from_numpy(mwl.population).to(dev)
+        mb = torch.empty_like(ma)
+        for g in range(5):
+            mcall.run(ma, stream=stream, outputs="fitness")
+            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, MUT_THRESHOLD, stream=stream)
+            ma, mb = mb, ma
+        torch.cuda.synchronize()
+        tg0 = time.perf_counter()
+        for g in range(5, 105):
+            mcall.run(ma, stream=stream, outputs="fitness")
+            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, MUT_THRESHOLD, stream=stream)
+            ma, mb = mb, ma
+        torch.cuda.synchronize()
+        tg1 = time.perf_counter()
+        extra["ga_loop_mid_generations_per_s"] = 100.0 / (tg1 - tg0)
+        extra["ga_loop_mid_evals_per_s"] = 100.0 * mcfg.evals_per_call / (tg1 - tg0)
+
+    out = {
+        "metric": "(m,s) goodput evals/sec + GA generations/sec; % of FP64 VALU peak",
+        "value": evals_per_step * args.steps / elapsed,
+        "unit": "evals/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed * 1e3 / args.steps,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f64", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: P={cfg.P} candidates, J={cfg.J} jobs, {cfg.N} nodes x {cfg.cap} GPUs, "
+                               f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step per step",
+                   "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed},
+        "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                     "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL,
+                     "avg_launch_ms": sweep_avg_ms},
+        "extra": extra,
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(wl, cfg)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

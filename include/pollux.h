@@ -175,6 +175,16 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; Gm, Gs, precis
  * to *host_out.  Synchronises `hip_stream`. */
 int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out /* host */);
 
+/*
+ * Profiling aid.  While a pair of HIP events (hipEvent_t cast to void*) is
+ * registered, every pollux_fitness call records `start` immediately before and
+ * `stop` immediately after its grid-sweep kernel (the kernel that evaluates
+ * Eq. 4 over the (m, s) grid for every (candidate, job) pair), on the call's
+ * stream, so that a caller can time that kernel alone.  The registration is
+ * process-wide and not thread-safe; pass two NULLs to clear it.  Host call.
+ */
+int pollux_set_sweep_events(void *hip_event_start, void *hip_event_stop);
+
 /* Text for a PX_* return code (static storage, never NULL). */
 const char *pollux_strerror(int code);
 

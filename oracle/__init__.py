@@ -83,6 +83,8 @@ def lib():
         L.pollux_ref_repair.argtypes = [vp, i, i, vp, vp, ctypes.c_uint32, ctypes.c_uint32]
         L.pollux_ref_rank.restype = None
         L.pollux_ref_rank.argtypes = [vp, i, vp]
+        L.pollux_ref_threads.restype = i
+        L.pollux_ref_threads.argtypes = []
         _lib = L
     return _lib
 
@@ -102,6 +104,10 @@ def job(alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, M
 
 def job_from_params(job_params: np.ndarray, j: int) -> Job:
     return Job(*[float(job_params[k, j]) for k in range(10)])
+
+
+def threads() -> int:
+    return lib().pollux_ref_threads()
 
 
 def efficiency(phi, M0, M):

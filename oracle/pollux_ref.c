@@ -12,6 +12,20 @@
 #include <stdlib.h>
 #include <string.h>
 
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* threads the candidate loop will use */
+int pollux_ref_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
 /* ------------------------------------------------------------------ model */
 
 /* Sec. 3.1, Eq. 6: EFFICIENCY_t(M) = (phi_t + M0) / (phi_t + M). */

@@ -76,6 +76,9 @@ double pollux_ref_pmean(const double *speedup, const double *weight, int J, doub
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11) */
 void pollux_ref_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4]);
 
+/* threads used by the loop over candidates */
+int pollux_ref_threads(void);
+
 /* --- whole calls --- */
 int pollux_fitness_ref(const pollux_ref_dims *dims,
                        const int32_t *population,    /* [P,J,N] */

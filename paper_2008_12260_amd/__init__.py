@@ -18,7 +18,7 @@ PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK = 1, 2
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
-           "pollux_last_status")
+           "pollux_last_status", "pollux_set_sweep_events")
 
 
 class PolluxError(RuntimeError):
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.pollux_ga_step.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp, sz, vp, vp]
         L.pollux_last_status.restype = i
         L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        L.pollux_set_sweep_events.restype = i
+        L.pollux_set_sweep_events.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -118,6 +120,14 @@ def pollux_last_status(workspace, stream=None) -> int:
     if rc != PX_OK:
         raise PolluxError(rc, "pollux_last_status")
     return out.value
+
+
+def pollux_set_sweep_events(start=None, stop=None) -> None:
+    """Register (or clear) torch.cuda.Event objects recorded around the grid-sweep kernel."""
+    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
+    rc = lib().pollux_set_sweep_events(h(start), h(stop))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_set_sweep_events")
 
 
 class FitnessCall:

@@ -8,6 +8,10 @@
 #include "../../include/pollux.h"
 #include "pollux_host.h"
 
+namespace px {
+hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;
+}
+
 namespace {
 
 constexpr int kMaxDevices = 64;
@@ -108,6 +112,14 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (rc != PX_OK) return rc;
     return px::launch_ga_step(dims, parents, fitness, node_capacity, params, workspace, children,
                               (hipStream_t)hip_stream);
+}
+
+int pollux_set_sweep_events(void *hip_event_start, void *hip_event_stop)
+{
+    if ((hip_event_start == nullptr) != (hip_event_stop == nullptr)) return PX_E_INVALID_ARG;
+    px::g_sweep_start = (hipEvent_t)hip_event_start;
+    px::g_sweep_stop = (hipEvent_t)hip_event_stop;
+    return PX_OK;
 }
 
 int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out)

@@ -25,8 +25,8 @@
 // argmax of GOODPUT is the argmin of h over the feasible points.  The lane
 // keeps the minimum with one v_min_f64 per point: the low five mantissa bits of
 // h are replaced by s (so the minimum carries its own index and equal values
-// resolve to the smaller s), and infeasible points get their exponent forced to
-// the top of the range.  The perturbation is 2^-47 relative; the point each lane
+// resolve to the smaller s), and infeasible points are turned into quiet NaNs,
+// which the minimum ignores.  The perturbation is 2^-47 relative; the point each lane
 // elects is then evaluated again with the formulas in the paper's own order
 // (separate multiply and add, IEEE division), and the wave-wide argmax is taken
 // over those values with ties going to the lowest flat index, so the reported
@@ -47,17 +47,22 @@
 #include "../../include/pollux.h"
 #include "pollux_device.h"
 #include "pollux_host.h"
+#include "pollux_math.h"
 
 namespace px {
 
+constexpr int kWavesPerBlock = 4;
+constexpr int kRecipTable = 256;      // 1/K is tabled for K below this
+
 struct FitnessArgs {
     int P, J, N, Gm, Gs, flags;
+    int cand_per_wave, cand_groups;   // pairs kernel: candidates each wavefront walks, groups of 4 * cand_per_wave
     const int32_t *population, *m_grid, *fair_share, *current_alloc, *node_capacity;
     const double *job_params;
     double p, delta;
     // workspace
     int32_t *status;
-    double *rs, *tg, *lntg, *denom, *factor, *S;
+    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *denom, *factor, *S;
     int32_t *running, *nodes;
     // outputs
     double *fitness, *best_goodput, *speedup;
@@ -65,14 +70,12 @@ struct FitnessArgs {
 };
 
 struct Job {
-    double alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma, phi, M0, Mmax, a;
+    double alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma, phi, a;
 };
 
 __device__ __forceinline__ Job load_job(const double *__restrict__ jp, int J, int j)
 {
     Job q;
-    q.alpha_g = jp[(size_t)PX_ALPHA_G * J + j];
-    q.beta_g = jp[(size_t)PX_BETA_G * J + j];
     q.alpha_sl = jp[(size_t)PX_ALPHA_SL * J + j];
     q.beta_sl = jp[(size_t)PX_BETA_SL * J + j];
     q.alpha_sn = jp[(size_t)PX_ALPHA_SN * J + j];
@@ -80,25 +83,48 @@ __device__ __forceinline__ Job load_job(const double *__restrict__ jp, int J, in
     q.gamma = jp[(size_t)PX_GAMMA * J + j];
     q.inv_gamma = 1.0 / q.gamma;
     q.phi = jp[(size_t)PX_PHI * J + j];
-    q.M0 = jp[(size_t)PX_M0 * J + j];
-    q.Mmax = jp[(size_t)PX_MMAX * J + j];
-    q.a = q.phi + q.M0;
+    q.a = q.phi + jp[(size_t)PX_M0 * J + j];
     return q;
 }
 
 // ---- tables ------------------------------------------------------------------
-
+// Per job and grid point i (batch size m = m_grid[j,i]):
+//   tg   = T_grad(m) (Eq. 8)            lntg = ln T_grad(m)
+//   pu   = phi / m                      (u = phi / (K m) = pu / K)
+//   qh5  = floor(M_max / m) + 1/2       ql5  = ceil(M0 / m) - 1/2
+// M0 <= K m (s+1) <= M_max holds exactly when ceil(M0/m) <= K (s+1) <= floor(M_max/m),
+// i.e. for s between trunc(ql5 / K) and trunc(qh5 / K) - 1; the halves keep the
+// quotients at least 1/(2K) away from an integer, so a rounded 1/K cannot move them
+// across one.  Also rs[s] = 1/(s+1), rk[K] = 1/K, and the status word is cleared.
 __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 {
-    int t = blockIdx.x * blockDim.x + threadIdx.x;
+    const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) *a.status = 0;
-    if (t < a.Gs) a.rs[t] = 1.0 / (double)(t + 1);
+    const int rs_len = ((a.Gs + 31) / 32) * 32;
+    if (t < rs_len) a.rs[t] = 1.0 / (double)(t + 1);
+    if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
     if (t < a.J * a.Gm) {
-        int j = t / a.Gm;
-        double m = (double)a.m_grid[t];
-        double tg = a.job_params[(size_t)PX_ALPHA_G * a.J + j] + a.job_params[(size_t)PX_BETA_G * a.J + j] * m;   // Eq. 8
+        const int j = t / a.Gm;
+        const int mi = a.m_grid[t];
+        const double m = (double)mi;
+        const double tg = a.job_params[(size_t)PX_ALPHA_G * a.J + j] + a.job_params[(size_t)PX_BETA_G * a.J + j] * m;   // Eq. 8
         a.tg[t] = tg;
         a.lntg[t] = log(tg);
+        double qh = -1.5, ql = 1.0;
+        if (mi > 0) {
+            const double Mmax = a.job_params[(size_t)PX_MMAX * a.J + j], M0 = a.job_params[(size_t)PX_M0 * a.J + j];
+            qh = floor(Mmax / m);
+            if (m * (qh + 1.0) <= Mmax) qh += 1.0;
+            if (m * qh > Mmax) qh -= 1.0;
+            ql = ceil(M0 / m);
+            if (m * (ql - 1.0) >= M0) ql -= 1.0;
+            if (m * ql < M0) ql += 1.0;
+            if (!(ql >= 1.0)) ql = 1.0;
+            if (!(qh >= 0.0)) qh = -1.5;
+        }
+        a.pu[t] = mi > 0 ? a.job_params[(size_t)PX_PHI * a.J + j] / m : 0.0;
+        a.qh5[t] = qh + 0.5;
+        a.ql5[t] = ql - 0.5;
     }
 }
 
@@ -109,139 +135,213 @@ struct Best {
     int m, s;         // batch size and accumulation steps attaining it, -1/-1 if none
 };
 
-// Exact integer bounds on x = s + 1 from M0 <= Km * x <= Mmax, from a quotient that may be off by one.
-__device__ __forceinline__ void feasible_range(double Km, double rKm, double M0, double Mmax, int &lo, int &hi)
+struct JobTables {
+    const int32_t *__restrict__ m;
+    const double *__restrict__ tg, *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
+};
+
+__device__ __forceinline__ double vmin(double a, double b)
 {
-    double qh = floor(Mmax * rKm);
-    if (Km * (qh + 1.0) <= Mmax) qh += 1.0;
-    if (Km * qh > Mmax) qh -= 1.0;
-    double ql = ceil(M0 * rKm);
-    if (Km * (ql - 1.0) >= M0) ql -= 1.0;
-    if (Km * ql < M0) ql += 1.0;
-    ql = fmin(fmax(ql, 1.0), 1073741824.0);
-    qh = fmin(fmax(qh, 0.0), 1073741824.0);
-    lo = (int)ql;
-    hi = (int)qh;
+    double r;
+    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+__device__ __forceinline__ double vmax(double a, double b)
+{
+    double r;
+    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
+    return r;
+}
+
+// A value that is the same in every lane, moved to scalar registers.
+__device__ __forceinline__ double uniform(double v)
+{
+    return __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v)),
+                            __builtin_amdgcn_readfirstlane(__double2loint(v)));
+}
+
+template <int STEP = 0>
+__device__ __forceinline__ double wave_vmax(double v)
+{
+    v = vmax(v, exchange<STEP>(v));
+    if constexpr (STEP < 5) return wave_vmax<STEP + 1>(v);
+    return v;
 }
 
 // Eq. 4 at one grid point, in the paper's order of operations (no contraction).
 __device__ __forceinline__ double goodput_point(const Job &q, double Km, double tg, double last, int s)
 {
-    double M = Km * (double)(s + 1);
-    double t_iter = (double)s * tg + last;                       // Eq. 11
-    double throughput = M / t_iter;                              // Eq. 7
-    double efficiency = q.a / (q.phi + M);                       // Eq. 6
+    const double M = Km * (double)(s + 1);
+    const double t_iter = (double)s * tg + last;                 // Eq. 11
+    const double throughput = M / t_iter;                        // Eq. 7
+    const double efficiency = q.a / (q.phi + M);                 // Eq. 6
     return throughput * efficiency;                              // Eq. 4
 }
 
+// One grid point of the sweep, position B (a compile-time constant) inside a chunk.
+// Six VALU instructions, written out so that the constants sit where the encoding
+// allows them (one SGPR or literal-free inline constant per VOP3 instruction):
+//   x   = B * tg + A0              v_fma_f64, B as an SGPR pair
+//   h   = B0 * r + x               v_fma_f64, r = 1/(s+1) as an SGPR pair
+//   t   = sign-extended bit B of `bad`                       v_bfe_i32
+//   hi  = (t & quiet-NaN pattern) | hi(h)                    v_and_or_b32
+//   lo  = (31 & B) | (~31 & lo(h))                           v_bfi_b32
+//   kmin = min(kmin, key)                                    v_min_f64
+template <int B>
+__device__ __forceinline__ double sweep_point(double kmin, double tg, double A0, double B0, int bad, double r)
+{
+    double x, h;
+    const double bd = (double)B;
+    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(x) : "s"(bd), "v"(tg), "v"(A0));
+    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(h) : "v"(B0), "s"(r), "v"(x));
+    int t, hh, hl;
+    asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(t) : "v"(bad), "n"(B));
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(hh) : "v"(t), "s"(0x7FF80000), "v"(__double2hiint(h)));
+    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(hl) : "n"(B), "v"(__double2loint(h)));
+    return vmin(kmin, __hiloint2double(hh, hl));
+}
+
+template <int CH, int B = 0>
+__device__ __forceinline__ double sweep_points(double kmin, double tg, double A0, double B0, int bad,
+                                               const double *__restrict__ rs)
+{
+    if constexpr (B < CH) {
+        kmin = sweep_point<B>(kmin, tg, A0, B0, bad, uniform(rs[B]));
+        return sweep_points<CH, B + 1>(kmin, tg, A0, B0, bad, rs);
+    }
+    return kmin;
+}
+
+// The same with the reciprocals 1/(B+1) as compile-time constants (first chunk, s0 = 0).
+template <int CH, int B = 0>
+__device__ __forceinline__ double sweep_points_first(double kmin, double tg, double A0, double B0, int bad)
+{
+    if constexpr (B < CH) {
+        kmin = sweep_point<B>(kmin, tg, A0, B0, bad, 1.0 / (double)(B + 1));
+        return sweep_points_first<CH, B + 1>(kmin, tg, A0, B0, bad);
+    }
+    return kmin;
+}
+
+// CH grid points s = s0 .. s0+CH-1 of one batch size: key = h with the low five
+// mantissa bits replaced by the point's position b; an infeasible point becomes a
+// quiet NaN (v_min_f64 returns the other operand for a quiet NaN, so it never wins).
+// Returns the smallest key, +inf if no point is feasible.
+template <int CH>
+__device__ __forceinline__ double sweep_chunk(double tg, double A0, double B0, int bad, int s0,
+                                              const double *__restrict__ rs)
+{
+    if (s0 == 0) return sweep_points_first<CH>(__builtin_inf(), tg, A0, B0, bad);
+    return sweep_points<CH>(__builtin_inf(), tg, px_fma((double)s0, tg, A0), B0, bad, rs + s0);
+}
+
 // All 64 lanes call this with the same (job, K, nodes).  Every lane returns the same result.
-__device__ __forceinline__ Best sweep(const Job &q, const int32_t *__restrict__ mg, const double *__restrict__ tgv,
-                                      const double *__restrict__ lntgv, const double *__restrict__ rs, int Gm, int Gs,
-                                      int K, int nodes)
+template <int CH>
+__device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+                                      const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
     Best out = {0.0, -1, -1};
     if (K <= 0) return out;
     const int lane = lane_id();
     const double Kd = (double)K;
+    const double rK = K < kRecipTable ? rk[K] : 1.0 / Kd;
     // Eq. 9
     double ts = 0.0;
     if (K > 1) ts = (nodes == 1) ? q.alpha_sl + q.beta_sl * (double)(K - 2) : q.alpha_sn + q.beta_sn * (double)(K - 2);
     const int mode = (ts == 0.0) ? 0 : (q.gamma == 1.0 ? 1 : 2);
-    const double lnts = (mode == 2) ? log(ts) : 0.0;
+    const double lnts = (mode == 2) ? px_log(ts) : 0.0;
+    const double neg_gamma = -q.gamma;
 
     double kbest = __builtin_inf();   // smallest key seen by this lane
-    int ibest = -1, sbest = -1;
-    double last_best = 0.0, tg_best = 0.0, Km_best = 0.0;
-    int m_best = -1;
+    int ibest = -1, s0best = 0;
+    double last_best = 0.0, tg_best = 0.0;
 
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
         const int i = i0 + lane;
         const bool active = i < Gm;
-        const int m = active ? mg[i] : 0;
-        const double tg = active ? tgv[i] : 1.0;
+        const int il = active ? i : Gm - 1;
+        const double tg = tb.tg[il];
         double last;                                             // last pass of Eq. 10
         if (mode == 0) {
             last = tg;
         } else if (mode == 1) {
             last = tg + ts;
         } else {
-            double d = (active ? lntgv[i] : 0.0) - lnts;
-            double e = exp(-q.gamma * fabs(d));
-            last = fmax(tg, ts) * exp(log1p(e) * q.inv_gamma);
+            const double e = px_exp(neg_gamma * fabs(tb.lntg[il] - lnts));
+            last = vmax(tg, ts) * px_exp(px_log1p_unit(e) * q.inv_gamma);
         }
-        const bool usable = active && m > 0;
-        const double Km = usable ? Kd * (double)m : 1.0;
-        const double rKm = 1.0 / Km;
-        int lo, hi;
-        feasible_range(Km, rKm, q.M0, q.Mmax, lo, hi);
-        if (!usable) { lo = 1; hi = 0; }
-        const double u = q.phi * rKm;
-        const double A0 = fma(u, tg, last);
+        const double u = tb.pu[il] * rK;
+        const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
+        const int s_lo = (int)(tb.ql5[il] * rK);
+        int s_hi = (int)(tb.qh5[il] * rK) - 1;
+        s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
+        if (!active) s_hi = -1;
 
-        for (int s0 = 0; s0 < Gs; s0 += 32) {
+        for (int s0 = 0; s0 < Gs; s0 += CH) {
             // bit b of `bad` is set when s = s0 + b is infeasible for this lane
-            int first = lo - 1 - s0, lastb = hi - 1 - s0;
+            int first = s_lo - s0, lastb = s_hi - s0;
             first = first < 0 ? 0 : first;
-            lastb = lastb > 31 ? 31 : lastb;
-            uint32_t ok = (first <= lastb) ? (uint32_t)((0xFFFFFFFFu >> (31 - lastb)) & (0xFFFFFFFFu << first)) : 0u;
-            const int bad = (int)~ok;
-            const int cnt = (Gs - s0) < 32 ? (Gs - s0) : 32;
-            double kmin = __builtin_inf();
-#pragma unroll 8
-            for (int b = 0; b < cnt; ++b) {
-                const int s = s0 + b;
-                double h = fma(B0, rs[s], fma((double)s, tg, A0));
-                int hh = __double2hiint(h), hl = __double2loint(h);
-                hh |= __builtin_amdgcn_sbfe(bad, b, 1) & 0x7FE00000;      // infeasible: exponent to the top
-                hl = (hl & ~31) | b;                                      // carry the index
-                double key = __hiloint2double(hh, hl);
-                kmin = key < kmin ? key : kmin;
-            }
-            if (kmin < kbest && kmin < 0x1p1022) {
+            lastb = lastb > CH - 1 ? CH - 1 : lastb;
+            const uint32_t ok = (first <= lastb) ? ((0xFFFFFFFFu >> (31 - lastb)) & (0xFFFFFFFFu << first)) : 0u;
+            const double kmin = sweep_chunk<CH>(tg, A0, B0, (int)~ok, s0, rs);
+            if (kmin < kbest) {
                 kbest = kmin;
                 ibest = i;
-                sbest = s0 + (__double2loint(kmin) & 31);
-                last_best = last; tg_best = tg; Km_best = Km; m_best = m;
+                s0best = s0;
+                last_best = last;
+                tg_best = tg;
             }
         }
     }
 
     // the elected point of each lane, evaluated in the paper's order of operations
     double g = -1.0;
-    int flat = 0x7FFFFFFF;
+    int flat = 0x7FFFFFFF, m_best = -1, sbest = -1;
     if (ibest >= 0) {
-        g = goodput_point(q, Km_best, tg_best, last_best, sbest);
+        sbest = s0best + (__double2loint(kbest) & 31);
+        m_best = tb.m[ibest];
+        g = goodput_point(q, Kd * (double)m_best, tg_best, last_best, sbest);
         flat = ibest * Gs + sbest;
     }
-    const double gmax = wave_max(g);
+    const double gmax = wave_vmax(g);
     if (!(gmax > 0.0)) return out;
     const int fmin_ = wave_min(g == gmax ? flat : 0x7FFFFFFF);
-    const bool winner = (g == gmax) && (flat == fmin_);
-    const uint64_t wmask = __ballot(winner);
-    const int wl = __ffsll((unsigned long long)wmask) - 1;
+    const uint64_t wmask = __ballot((g == gmax) && (flat == fmin_));
+    const int wl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)wmask) - 1);
     out.goodput = gmax;
-    out.m = __shfl(m_best, wl);
-    out.s = __shfl(sbest, wl);
+    out.m = __builtin_amdgcn_readlane(m_best, wl);
+    out.s = __builtin_amdgcn_readlane(sbest, wl);
     return out;
+}
+
+__device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
+{
+    const size_t o = (size_t)j * a.Gm;
+    return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o};
 }
 
 // ---- per job -----------------------------------------------------------------
 
+template <int CH>
 __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int j = blockIdx.x * (blockDim.x >> 6) + wave;
+    const int j = blockIdx.x * kWavesPerBlock + wave;
     if (j >= a.J) return;
     const int lane = lane_id();
     const Job q = load_job(a.job_params, a.J, j);
-    const double w = a.job_params[(size_t)PX_WEIGHT * a.J + j];
-    const double T = a.job_params[(size_t)PX_AGE_T * a.J + j];
-    const double R = a.job_params[(size_t)PX_RESTARTS_R * a.J + j];
+    const double *__restrict__ jp = a.job_params;
+    const double alpha_g = jp[(size_t)PX_ALPHA_G * a.J + j], beta_g = jp[(size_t)PX_BETA_G * a.J + j];
+    const double M0 = jp[(size_t)PX_M0 * a.J + j], Mmax = jp[(size_t)PX_MMAX * a.J + j];
+    const double w = jp[(size_t)PX_WEIGHT * a.J + j];
+    const double T = jp[(size_t)PX_AGE_T * a.J + j];
+    const double R = jp[(size_t)PX_RESTARTS_R * a.J + j];
     int st = 0;
-    if (!(q.gamma >= 1.0 && q.gamma <= 10.0) || !(q.alpha_g >= 0.0) || !(q.beta_g >= 0.0) || !(q.alpha_sl >= 0.0) ||
-        !(q.beta_sl >= 0.0) || !(q.alpha_sn >= 0.0) || !(q.beta_sn >= 0.0) || !(q.phi > 0.0) || !(q.M0 >= 1.0) ||
-        !(q.Mmax >= q.M0) || !(w >= 0.0) || !(q.Mmax <= 4503599627370496.0) || !(q.alpha_g + q.beta_g > 0.0))
+    if (!(q.gamma >= 1.0 && q.gamma <= 10.0) || !(alpha_g >= 0.0) || !(beta_g >= 0.0) || !(q.alpha_sl >= 0.0) ||
+        !(q.beta_sl >= 0.0) || !(q.alpha_sn >= 0.0) || !(q.beta_sn >= 0.0) || !(q.phi > 0.0) || !(M0 >= 1.0) ||
+        !(Mmax >= M0) || !(w >= 0.0) || !(Mmax <= 4503599627370496.0) || !(alpha_g + beta_g > 0.0))
         st |= PX_ST_BAD_PARAM;
     // re-allocation penalty factor of Sec. 4.2
     const double factor = (T - R * a.delta) / (T + a.delta);
@@ -250,15 +350,14 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     long long csum = 0;
     int neg = 0;
     for (int n = lane; n < a.N; n += kWave) {
-        int c = a.current_alloc[(size_t)j * a.N + n];
+        const int c = a.current_alloc[(size_t)j * a.N + n];
         csum += c;
         neg |= c < 0;
     }
     const long long total = wave_sum(csum);
     if (__ballot(neg) != 0) st |= PX_ST_NEG_ALLOC;
     // denominator of Eq. 15: the same sweep at the fair-share allocation
-    const Best fair = sweep(q, a.m_grid + (size_t)j * a.Gm, a.tg + (size_t)j * a.Gm, a.lntg + (size_t)j * a.Gm, a.rs,
-                            a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
+    const Best fair = sweep<CH>(q, job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
     if (!(fair.goodput > 0.0)) st |= PX_ST_ZERO_FAIR;
     if (lane == 0) {
         a.denom[j] = fair.goodput;
@@ -269,47 +368,76 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
 }
 
 // ---- per (candidate, job) ------------------------------------------------------
+// Workgroup -> (job, group of candidates).  Workgroups are dealt to the eight XCDs
+// round-robin, so the job index is derived from (blockIdx % 8) first: all workgroups
+// of one job then run on one XCD and its tables stay in that XCD's L2.  Each of the
+// four wavefronts walks cand_per_wave candidates of that job.
 
+template <int CH>
 __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
 {
+    const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
+    const int j = (slot / a.cand_groups) * 8 + xcd;
+    const int group = slot % a.cand_groups;
+    if (j >= a.J) return;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const long long pair = (long long)blockIdx.x * (blockDim.x >> 6) + wave;
-    if (pair >= (long long)a.P * a.J) return;
-    const int c = (int)(pair / a.J);
-    const int j = (int)(pair - (long long)c * a.J);
     const int lane = lane_id();
-
-    // row reduce: K = sum, nodes = #positive, changed = differs from the current row
-    const int32_t *__restrict__ row = a.population + (size_t)pair * a.N;
-    const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
-    int ksum = 0, nodes = 0;
-    bool changed = false, neg = false;
-    for (int n0 = 0; n0 < a.N; n0 += kWave) {
-        const int n = n0 + lane;
-        const int v = n < a.N ? row[n] : 0;
-        const int cv = n < a.N ? cur[n] : 0;
-        ksum += v;
-        nodes += __popcll(__ballot(v > 0));
-        changed |= __ballot(v != cv) != 0;
-        neg |= __ballot(v < 0) != 0;
-    }
-    const int K = wave_sum(ksum);
-
     const Job q = load_job(a.job_params, a.J, j);
-    const Best best = sweep(q, a.m_grid + (size_t)j * a.Gm, a.tg + (size_t)j * a.Gm, a.lntg + (size_t)j * a.Gm, a.rs,
-                            a.Gm, a.Gs, K, nodes);
-    if (lane == 0) {
-        // Eq. 15 and the re-allocation penalty
-        const double d = a.denom[j];
-        double s_j = d > 0.0 ? best.goodput / d : 0.0;
-        if (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && changed && a.running[j]) s_j = s_j * a.factor[j];
-        a.S[pair] = s_j;
-        a.nodes[pair] = nodes;
-        a.best_m[pair] = best.m;
-        a.best_s[pair] = best.s;
-        if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-        if (a.speedup) a.speedup[pair] = s_j;
-        if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
+    const JobTables tb = job_tables(a, j);
+    const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
+    const double denom = a.denom[j];
+    const double factor = (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && a.running[j]) ? a.factor[j] : 1.0;
+    const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
+
+    for (int r = 0; r < a.cand_per_wave; ++r) {
+        const int c = (group * a.cand_per_wave + r) * kWavesPerBlock + wave;
+        if (c >= a.P) break;
+        const size_t pair = (size_t)c * a.J + j;
+        // row reduce: K = sum, nodes = #positive, changed = differs from the current row
+        const int32_t *__restrict__ row = a.population + pair * a.N;
+        int ksum = 0, nodes = 0;
+        bool changed = false, neg = false;
+        if (vec4) {
+            const int4 *__restrict__ row4 = (const int4 *)row;
+            const int4 *__restrict__ cur4 = (const int4 *)cur;
+            const int n4 = a.N >> 2;
+            for (int n0 = 0; n0 < n4; n0 += kWave) {
+                const int n = n0 + lane;
+                const int4 z = {0, 0, 0, 0};
+                const int4 v = n < n4 ? row4[n] : z;
+                const int4 cv = n < n4 ? cur4[n] : z;
+                ksum += (v.x + v.y) + (v.z + v.w);
+                nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
+                         __popcll(__ballot(v.w > 0));
+                changed |= __ballot(((v.x ^ cv.x) | (v.y ^ cv.y) | (v.z ^ cv.z) | (v.w ^ cv.w)) != 0) != 0;
+                neg |= __ballot((v.x | v.y | v.z | v.w) < 0) != 0;
+            }
+        } else {
+            for (int n0 = 0; n0 < a.N; n0 += kWave) {
+                const int n = n0 + lane;
+                const int v = n < a.N ? row[n] : 0;
+                const int cv = n < a.N ? cur[n] : 0;
+                ksum += v;
+                nodes += __popcll(__ballot(v > 0));
+                changed |= __ballot(v != cv) != 0;
+                neg |= __ballot(v < 0) != 0;
+            }
+        }
+        const int K = __builtin_amdgcn_readfirstlane(wave_sum(ksum));
+
+        const Best best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        if (lane == 0) {
+            // Eq. 15 and the re-allocation penalty
+            double s_j = denom > 0.0 ? best.goodput / denom : 0.0;
+            if (changed) s_j = s_j * factor;
+            a.S[pair] = s_j;
+            a.nodes[pair] = nodes;
+            a.best_m[pair] = best.m;
+            a.best_s[pair] = best.s;
+            if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+            if (a.speedup) a.speedup[pair] = s_j;
+            if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
+        }
     }
 }
 
@@ -401,8 +529,12 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.p = p; a.delta = delta;
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
+    a.rk = (double *)(ws + L.rk);
     a.tg = (double *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);
+    a.pu = (double *)(ws + L.pu);
+    a.qh5 = (double *)(ws + L.qh5);
+    a.ql5 = (double *)(ws + L.ql5);
     a.denom = (double *)(ws + L.denom);
     a.factor = (double *)(ws + L.factor);
     a.running = (int32_t *)(ws + L.running);
@@ -411,11 +543,29 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.fitness = fitness; a.best_goodput = best_goodput; a.speedup = speedup;
     a.best_m = best_m; a.best_s = best_s; a.violations = violations;
 
-    const long long table_items = (long long)d->J * d->Gm > d->Gs ? (long long)d->J * d->Gm : d->Gs;
-    hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
-    hipLaunchKernelGGL(jobs_kernel, dim3((unsigned)((d->J + 3) / 4)), dim3(256), 0, stream, a);
+    // unrolled s-chunk: the smallest of 8, 16, 32 that covers Gs (32 with several chunks beyond that)
+    const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
     const long long pairs = (long long)d->P * d->J;
-    hipLaunchKernelGGL(pairs_kernel, dim3((unsigned)((pairs + 3) / 4)), dim3(256), 0, stream, a);
+    // candidates per wavefront: enough wavefronts to fill the chip several times over, at most 16 per wavefront
+    long long per_wave = pairs / 40000;
+    per_wave = per_wave < 1 ? 1 : (per_wave > 16 ? 16 : per_wave);
+    a.cand_per_wave = (int)per_wave;
+    a.cand_groups = (int)((d->P + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
+    const unsigned pair_blocks = (unsigned)(8 * ((d->J + 7) / 8) * a.cand_groups);
+
+    long long table_items = (long long)d->J * d->Gm;
+    if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
+    if (table_items < kRecipTable) table_items = kRecipTable;
+    hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+    const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
+    if (ch == 8) hipLaunchKernelGGL(jobs_kernel<8>, job_grid, dim3(256), 0, stream, a);
+    else if (ch == 16) hipLaunchKernelGGL(jobs_kernel<16>, job_grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(jobs_kernel<32>, job_grid, dim3(256), 0, stream, a);
+    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
+    if (ch == 8) hipLaunchKernelGGL(pairs_kernel<8>, dim3(pair_blocks), dim3(256), 0, stream, a);
+    else if (ch == 16) hipLaunchKernelGGL(pairs_kernel<16>, dim3(pair_blocks), dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL(pairs_kernel<32>, dim3(pair_blocks), dim3(256), 0, stream, a);
+    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     hipLaunchKernelGGL(candidates_kernel, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }

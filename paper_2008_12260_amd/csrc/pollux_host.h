@@ -13,9 +13,13 @@ namespace px {
 // Byte offsets of the sections of the caller's workspace (each 256-byte aligned).
 struct WorkspaceLayout {
     size_t status;    // int32 status word
-    size_t rs;        // double [Gs]      1/(s+1)
+    size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
+    size_t rk;        // double [256]     1/K
     size_t tg;        // double [J,Gm]    T_grad(m_i)
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
+    size_t pu;        // double [J,Gm]    phi / m_i
+    size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
+    size_t ql5;       // double [J,Gm]    ceil(M0 / m_i) - 1/2
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
     size_t running;   // int32  [J]       job holds GPUs in current_alloc
@@ -32,9 +36,13 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     size_t o = 0;
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
-    L.rs = o;      o = up(o + 8 * Gs);
+    L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
+    L.rk = o;      o = up(o + 8 * 256);
     L.tg = o;      o = up(o + 8 * J * Gm);
     L.lntg = o;    o = up(o + 8 * J * Gm);
+    L.pu = o;      o = up(o + 8 * J * Gm);
+    L.qh5 = o;     o = up(o + 8 * J * Gm);
+    L.ql5 = o;     o = up(o + 8 * J * Gm);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
     L.running = o; o = up(o + 4 * J);
@@ -44,6 +52,9 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.total = o;
     return L;
 }
+
+// Events recorded around the grid-sweep kernel (profiling aid), or null.
+extern hipEvent_t g_sweep_start, g_sweep_stop;
 
 int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
