@@ -14,6 +14,7 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     "-ffp-contract=off",                      # multiply-add is fused only where the code says fma()
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    "-mllvm", "-disable-machine-licm",        # hoisted constants otherwise spill scalar registers in the sweep
     "-Wall", "-Wno-unused-command-line-argument",
 ]
 

@@ -5,15 +5,20 @@
 // Sec. 4.1 (Eq. 13), SPEEDUP / FITNESS_p, re-allocation penalty and
 // interference avoidance Sec. 4.2 (Eq. 14-15).
 //
-// Kernels
-//   tables_kernel     per job and grid point: T_grad(m) (Eq. 8) and ln T_grad;
-//                     reciprocals 1/(s+1); clears the status word
-//   jobs_kernel       per job (one wavefront): parameter checks, restart
-//                     factor, fair-share goodput (denominator of Eq. 15)
-//   pairs_kernel      per (candidate, job) (one wavefront): row reduce, sweep
-//                     of the (m, s) grid, argmax, SPEEDUP
-//   candidates_kernel per candidate (one workgroup): constraint check and the
-//                     generalized mean
+// Kernels (one call = five launches on the caller's stream)
+//   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), ln T_grad, phi/m and
+//                     the feasibility bounds; reciprocals; clears the status word
+//   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
+//                     per row): T_sync (Eq. 9) and, for every batch size of the grid,
+//                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
+//                     term depends on the allocation only through K and on whether
+//                     the job sits on one node, so it is shared by the population
+//   jobs_kernel       per job (one wavefront): parameter checks, restart factor,
+//                     fair-share goodput (denominator of Eq. 15)
+//   pairs_kernel      per (candidate, job) (one wavefront): row reduce, sweep of the
+//                     (m, s) grid, argmax
+//   candidates_kernel per candidate (one workgroup): SPEEDUP, penalty, constraint
+//                     check and the generalized mean
 //
 // How one wavefront sweeps the grid of a (candidate, job) pair.  Lane l owns
 // the batch sizes m_i, i = l, l+64, ...; it walks s = 0..Gs-1.  Dividing Eq. 4
@@ -62,13 +67,16 @@ struct FitnessArgs {
     double p, delta;
     // workspace
     int32_t *status;
-    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *denom, *factor, *S;
-    int32_t *running, *nodes;
+    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    int32_t *running, *meta;
     // outputs
     double *fitness, *best_goodput, *speedup;
     int32_t *best_m, *best_s, *violations;
 };
 
+constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
+
+// Parameters of one job that the sweep needs (uniform across the wavefront).
 struct Job {
     double alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma, phi, a;
 };
@@ -109,7 +117,7 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
         const double m = (double)mi;
         const double tg = a.job_params[(size_t)PX_ALPHA_G * a.J + j] + a.job_params[(size_t)PX_BETA_G * a.J + j] * m;   // Eq. 8
         a.tg[t] = tg;
-        a.lntg[t] = log(tg);
+        a.lntg[t] = px_log(tg);
         double qh = -1.5, ql = 1.0;
         if (mi > 0) {
             const double Mmax = a.job_params[(size_t)PX_MMAX * a.J + j], M0 = a.job_params[(size_t)PX_M0 * a.J + j];
@@ -128,6 +136,53 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
     }
 }
 
+// ---- T_sync and the last pass of Eq. 10 ------------------------------------------
+
+// Eq. 9: no synchronisation for one GPU, the "local" pair on one node, the "node" pair otherwise.
+__device__ __forceinline__ double t_sync(const Job &q, int K, bool one_node)
+{
+    if (K <= 1) return 0.0;
+    return one_node ? q.alpha_sl + q.beta_sl * (double)(K - 2) : q.alpha_sn + q.beta_sn * (double)(K - 2);
+}
+
+struct SyncTerm {
+    double ts, lnts;
+    int mode;           // 0: T_sync = 0 (last pass = T_grad); 1: gamma = 1 (plain sum); 2: general
+};
+
+__device__ __forceinline__ SyncTerm sync_term(const Job &q, int K, bool one_node)
+{
+    SyncTerm t;
+    t.ts = t_sync(q, K, one_node);
+    t.mode = (t.ts == 0.0) ? 0 : (q.gamma == 1.0 ? 1 : 2);
+    t.lnts = (t.mode == 2) ? px_log(t.ts) : 0.0;
+    return t;
+}
+
+__device__ __forceinline__ double last_pass(const Job &q, const SyncTerm &t, double tg, double lntg)
+{
+    if (t.mode == 0) return tg;
+    if (t.mode == 1) return tg + t.ts;
+    const double e = px_exp(-q.gamma * fabs(lntg - t.lnts));
+    return fmax(tg, t.ts) * px_exp(px_log1p_unit(e) * q.inv_gamma);
+}
+
+// One wavefront per row (job, placement class, K): lt[row][i] for every grid point i.
+// Row index ((j * 2 + one_node) * kTableK + (K - 1)).
+__global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long row = (long long)blockIdx.x * kWavesPerBlock + wave;
+    if (row >= (long long)a.J * 2 * kTableK) return;
+    const int K = (int)(row % kTableK) + 1;
+    const bool one_node = ((row / kTableK) & 1) != 0;
+    const int j = (int)(row / (2 * kTableK));
+    const Job q = load_job(a.job_params, a.J, j);
+    const SyncTerm t = sync_term(q, K, one_node);
+    const size_t o = (size_t)j * a.Gm;
+    for (int i = lane_id(); i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(q, t, a.tg[o + i], a.lntg[o + i]);
+}
+
 // ---- the sweep of one (job, K, nodes) ----------------------------------------
 
 struct Best {
@@ -138,6 +193,7 @@ struct Best {
 struct JobTables {
     const int32_t *__restrict__ m;
     const double *__restrict__ tg, *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
+    const double *__restrict__ lt;    // rows of this job in the last-pass table
 };
 
 __device__ __forceinline__ double vmin(double a, double b)
@@ -246,31 +302,24 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
     const int lane = lane_id();
     const double Kd = (double)K;
     const double rK = K < kRecipTable ? rk[K] : 1.0 / Kd;
-    // Eq. 9
-    double ts = 0.0;
-    if (K > 1) ts = (nodes == 1) ? q.alpha_sl + q.beta_sl * (double)(K - 2) : q.alpha_sn + q.beta_sn * (double)(K - 2);
-    const int mode = (ts == 0.0) ? 0 : (q.gamma == 1.0 ? 1 : 2);
-    const double lnts = (mode == 2) ? px_log(ts) : 0.0;
-    const double neg_gamma = -q.gamma;
+    const bool one_node = nodes == 1;
+    // the last pass of Eq. 10 comes from the job's table when K is in its range, else it is computed here
+    const bool tabled = K <= kTableK;
+    const double *__restrict__ lrow = tb.lt + ((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(tabled ? K - 1 : 0)) * Gm;
+    SyncTerm st = {0.0, 0.0, 0};
+    if (!tabled) st = sync_term(q, K, one_node);
+    const int s_chunks = (Gs + CH - 1) / CH;
 
     double kbest = __builtin_inf();   // smallest key seen by this lane
-    int ibest = -1, s0best = 0;
-    double last_best = 0.0, tg_best = 0.0;
+    int code = -1;                    // (m chunk) * s_chunks + (s chunk) of kbest
 
+    int code_now = 0;
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
         const int i = i0 + lane;
         const bool active = i < Gm;
         const int il = active ? i : Gm - 1;
         const double tg = tb.tg[il];
-        double last;                                             // last pass of Eq. 10
-        if (mode == 0) {
-            last = tg;
-        } else if (mode == 1) {
-            last = tg + ts;
-        } else {
-            const double e = px_exp(neg_gamma * fabs(tb.lntg[il] - lnts));
-            last = vmax(tg, ts) * px_exp(px_log1p_unit(e) * q.inv_gamma);
-        }
+        const double last = tabled ? lrow[il] : last_pass(q, st, tg, tb.lntg[il]);
         const double u = tb.pu[il] * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
@@ -279,7 +328,7 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
         s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
         if (!active) s_hi = -1;
 
-        for (int s0 = 0; s0 < Gs; s0 += CH) {
+        for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
             // bit b of `bad` is set when s = s0 + b is infeasible for this lane
             int first = s_lo - s0, lastb = s_hi - s0;
             first = first < 0 ? 0 : first;
@@ -288,10 +337,7 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
             const double kmin = sweep_chunk<CH>(tg, A0, B0, (int)~ok, s0, rs);
             if (kmin < kbest) {
                 kbest = kmin;
-                ibest = i;
-                s0best = s0;
-                last_best = last;
-                tg_best = tg;
+                code = code_now;
             }
         }
     }
@@ -299,10 +345,13 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
     // the elected point of each lane, evaluated in the paper's order of operations
     double g = -1.0;
     int flat = 0x7FFFFFFF, m_best = -1, sbest = -1;
-    if (ibest >= 0) {
-        sbest = s0best + (__double2loint(kbest) & 31);
+    if (code >= 0) {
+        const int ibest = (code / s_chunks) * kWave + lane;
+        sbest = (code % s_chunks) * CH + (__double2loint(kbest) & 31);
         m_best = tb.m[ibest];
-        g = goodput_point(q, Kd * (double)m_best, tg_best, last_best, sbest);
+        const double tg = tb.tg[ibest];
+        const double last = tabled ? lrow[ibest] : last_pass(q, st, tg, tb.lntg[ibest]);
+        g = goodput_point(q, Kd * (double)m_best, tg, last, sbest);
         flat = ibest * Gs + sbest;
     }
     const double gmax = wave_vmax(g);
@@ -319,7 +368,8 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
 __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 {
     const size_t o = (size_t)j * a.Gm;
-    return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o};
+    return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
+                     a.lt + (size_t)j * 2 * kTableK * a.Gm};
 }
 
 // ---- per job -----------------------------------------------------------------
@@ -361,7 +411,7 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     if (!(fair.goodput > 0.0)) st |= PX_ST_ZERO_FAIR;
     if (lane == 0) {
         a.denom[j] = fair.goodput;
-        a.factor[j] = factor;
+        a.factor[j] = (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && total > 0) ? factor : 1.0;
         a.running[j] = total > 0;
         if (st) atomicOr(a.status, st);
     }
@@ -385,8 +435,6 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
     const Job q = load_job(a.job_params, a.J, j);
     const JobTables tb = job_tables(a, j);
     const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
-    const double denom = a.denom[j];
-    const double factor = (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && a.running[j]) ? a.factor[j] : 1.0;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
 
     for (int r = 0; r < a.cand_per_wave; ++r) {
@@ -427,15 +475,11 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
 
         const Best best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
         if (lane == 0) {
-            // Eq. 15 and the re-allocation penalty
-            double s_j = denom > 0.0 ? best.goodput / denom : 0.0;
-            if (changed) s_j = s_j * factor;
-            a.S[pair] = s_j;
-            a.nodes[pair] = nodes;
+            a.G[pair] = best.goodput;
+            a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
             a.best_m[pair] = best.m;
             a.best_s[pair] = best.s;
             if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-            if (a.speedup) a.speedup[pair] = s_j;
             if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
         }
     }
@@ -458,13 +502,19 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     __shared__ long long red_v[kCandThreads];
     const int c = blockIdx.x;
     const int t = threadIdx.x;
-    const double *__restrict__ S = a.S + (size_t)c * a.J;
+    const double *__restrict__ G = a.G + (size_t)c * a.J;
+    const int32_t *__restrict__ meta = a.meta + (size_t)c * a.J;
     const double *__restrict__ wt = a.job_params + (size_t)PX_WEIGHT * a.J;
 
-    // generalized mean, Eq. 14: each thread sums its jobs in ascending order, then a fixed tree
+    // SPEEDUP (Eq. 15) with the re-allocation penalty, then the generalized mean (Eq. 14):
+    // each thread sums its jobs in ascending order, then a fixed tree
     double acc = 0.0, wsum = 0.0;
     for (int j = t; j < a.J; j += kCandThreads) {
-        acc += pmean_term(S[j], wt[j], a.p);
+        const double d = a.denom[j];
+        double s_j = d > 0.0 ? G[j] / d : 0.0;
+        if (meta[j] & kMetaChanged) s_j = s_j * a.factor[j];
+        if (a.speedup) a.speedup[(size_t)c * a.J + j] = s_j;
+        acc += pmean_term(s_j, wt[j], a.p);
         wsum += wt[j];
     }
     red_acc[t] = acc;
@@ -475,14 +525,13 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     const bool need_v = a.violations != nullptr || !(a.flags & PX_FLAG_NO_CONSTRAINT_CHECK);
     if (need_v) {
         const int32_t *__restrict__ A = a.population + (size_t)c * a.J * a.N;
-        const int32_t *__restrict__ nodes = a.nodes + (size_t)c * a.J;
         for (int n = t; n < a.N; n += kCandThreads) {
             long long total = 0;
             int distributed = 0;
             for (int j = 0; j < a.J; ++j) {
                 const int x = A[(size_t)j * a.N + n];
                 total += x;
-                distributed += (x > 0 && nodes[j] >= 2);
+                distributed += (x > 0 && (meta[j] & (kMetaChanged - 1)) >= 2);
             }
             if (distributed > 1) v += distributed - 1;
             const long long over = total - (long long)a.node_capacity[n];
@@ -535,11 +584,12 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.pu = (double *)(ws + L.pu);
     a.qh5 = (double *)(ws + L.qh5);
     a.ql5 = (double *)(ws + L.ql5);
+    a.lt = (double *)(ws + L.lt);
     a.denom = (double *)(ws + L.denom);
     a.factor = (double *)(ws + L.factor);
     a.running = (int32_t *)(ws + L.running);
-    a.S = (double *)(ws + L.S);
-    a.nodes = (int32_t *)(ws + L.nodes);
+    a.G = (double *)(ws + L.G);
+    a.meta = (int32_t *)(ws + L.meta);
     a.fitness = fitness; a.best_goodput = best_goodput; a.speedup = speedup;
     a.best_m = best_m; a.best_s = best_s; a.violations = violations;
 
@@ -557,6 +607,8 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
     if (table_items < kRecipTable) table_items = kRecipTable;
     hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+    const long long lt_rows = (long long)d->J * 2 * kTableK;
+    hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
     const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
     if (ch == 8) hipLaunchKernelGGL(jobs_kernel<8>, job_grid, dim3(256), 0, stream, a);
     else if (ch == 16) hipLaunchKernelGGL(jobs_kernel<16>, job_grid, dim3(256), 0, stream, a);

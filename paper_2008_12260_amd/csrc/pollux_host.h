@@ -10,6 +10,9 @@
 
 namespace px {
 
+// The last pass of Eq. 10 is tabled for GPU counts K = 1..kTableK; larger K are computed in place.
+constexpr int kTableK = 64;
+
 // Byte offsets of the sections of the caller's workspace (each 256-byte aligned).
 struct WorkspaceLayout {
     size_t status;    // int32 status word
@@ -20,11 +23,12 @@ struct WorkspaceLayout {
     size_t pu;        // double [J,Gm]    phi / m_i
     size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
     size_t ql5;       // double [J,Gm]    ceil(M0 / m_i) - 1/2
+    size_t lt;        // double [J,2,kTableK,Gm]  last pass of Eq. 10 by (job, one node?, K)
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
     size_t running;   // int32  [J]       job holds GPUs in current_alloc
-    size_t S;         // double [P,J]     SPEEDUP after the penalty
-    size_t nodes;     // int32  [P,J]     nodes occupied by the row
+    size_t G;         // double [P,J]     best goodput of the pair
+    size_t meta;      // int32  [P,J]     nodes occupied by the row | changed flag
     size_t order;     // int32  [P]       candidates by rank (search step)
     size_t total;
 };
@@ -43,11 +47,12 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.pu = o;      o = up(o + 8 * J * Gm);
     L.qh5 = o;     o = up(o + 8 * J * Gm);
     L.ql5 = o;     o = up(o + 8 * J * Gm);
+    L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
     L.running = o; o = up(o + 4 * J);
-    L.S = o;       o = up(o + 8 * P * J);
-    L.nodes = o;   o = up(o + 4 * P * J);
+    L.G = o;       o = up(o + 8 * P * J);
+    L.meta = o;    o = up(o + 4 * P * J);
     L.order = o;   o = up(o + 4 * P);
     L.total = o;
     return L;
