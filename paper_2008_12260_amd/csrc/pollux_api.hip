@@ -40,6 +40,7 @@ bool dims_ok(const pollux_dims *d, bool need_grid)
     // flat indices of (candidate, job) pairs and of grid points are kept in 32 bits
     if ((long long)d->P * d->J > 0x7FFFFFFFll) return false;
     if (need_grid && (long long)d->Gm * d->Gs > 0x7FFFFFFFll) return false;
+    if (need_grid && (d->Gm > (1 << 20) || d->Gs > (1 << 14))) return false;   // chunk ids are packed into one word
     if (need_grid && (long long)d->J * d->Gm > 0x7FFFFFFFll) return false;
     return true;
 }

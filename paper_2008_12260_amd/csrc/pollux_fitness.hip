@@ -76,23 +76,37 @@ struct FitnessArgs {
 
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
-// Parameters of one job that the sweep needs (uniform across the wavefront).
+// Parameters of one job (uniform across the wavefront).  The sweep itself needs only
+// phi and a = phi + M0; the synchronisation parameters are read where T_sync is formed.
 struct Job {
-    double alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma, phi, a;
+    const double *__restrict__ jp;   // job_params
+    int J, j;
+    double phi, a;
+};
+
+struct SyncParams {
+    double alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma;
 };
 
 __device__ __forceinline__ Job load_job(const double *__restrict__ jp, int J, int j)
 {
     Job q;
-    q.alpha_sl = jp[(size_t)PX_ALPHA_SL * J + j];
-    q.beta_sl = jp[(size_t)PX_BETA_SL * J + j];
-    q.alpha_sn = jp[(size_t)PX_ALPHA_SN * J + j];
-    q.beta_sn = jp[(size_t)PX_BETA_SN * J + j];
-    q.gamma = jp[(size_t)PX_GAMMA * J + j];
-    q.inv_gamma = 1.0 / q.gamma;
+    q.jp = jp; q.J = J; q.j = j;
     q.phi = jp[(size_t)PX_PHI * J + j];
     q.a = q.phi + jp[(size_t)PX_M0 * J + j];
     return q;
+}
+
+__device__ __forceinline__ SyncParams load_sync(const Job &q)
+{
+    SyncParams y;
+    y.alpha_sl = q.jp[(size_t)PX_ALPHA_SL * q.J + q.j];
+    y.beta_sl = q.jp[(size_t)PX_BETA_SL * q.J + q.j];
+    y.alpha_sn = q.jp[(size_t)PX_ALPHA_SN * q.J + q.j];
+    y.beta_sn = q.jp[(size_t)PX_BETA_SN * q.J + q.j];
+    y.gamma = q.jp[(size_t)PX_GAMMA * q.J + q.j];
+    y.inv_gamma = 1.0 / y.gamma;
+    return y;
 }
 
 // ---- tables ------------------------------------------------------------------
@@ -139,32 +153,35 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 // ---- T_sync and the last pass of Eq. 10 ------------------------------------------
 
 // Eq. 9: no synchronisation for one GPU, the "local" pair on one node, the "node" pair otherwise.
-__device__ __forceinline__ double t_sync(const Job &q, int K, bool one_node)
+__device__ __forceinline__ double t_sync(const SyncParams &y, int K, bool one_node)
 {
     if (K <= 1) return 0.0;
-    return one_node ? q.alpha_sl + q.beta_sl * (double)(K - 2) : q.alpha_sn + q.beta_sn * (double)(K - 2);
+    return one_node ? y.alpha_sl + y.beta_sl * (double)(K - 2) : y.alpha_sn + y.beta_sn * (double)(K - 2);
 }
 
 struct SyncTerm {
-    double ts, lnts;
+    double ts, lnts, gamma, inv_gamma;
     int mode;           // 0: T_sync = 0 (last pass = T_grad); 1: gamma = 1 (plain sum); 2: general
 };
 
 __device__ __forceinline__ SyncTerm sync_term(const Job &q, int K, bool one_node)
 {
+    const SyncParams y = load_sync(q);
     SyncTerm t;
-    t.ts = t_sync(q, K, one_node);
-    t.mode = (t.ts == 0.0) ? 0 : (q.gamma == 1.0 ? 1 : 2);
+    t.ts = t_sync(y, K, one_node);
+    t.gamma = y.gamma;
+    t.inv_gamma = y.inv_gamma;
+    t.mode = (t.ts == 0.0) ? 0 : (y.gamma == 1.0 ? 1 : 2);
     t.lnts = (t.mode == 2) ? px_log(t.ts) : 0.0;
     return t;
 }
 
-__device__ __forceinline__ double last_pass(const Job &q, const SyncTerm &t, double tg, double lntg)
+__device__ __forceinline__ double last_pass(const SyncTerm &t, double tg, double lntg)
 {
     if (t.mode == 0) return tg;
     if (t.mode == 1) return tg + t.ts;
-    const double e = px_exp(-q.gamma * fabs(lntg - t.lnts));
-    return fmax(tg, t.ts) * px_exp(px_log1p_unit(e) * q.inv_gamma);
+    const double e = px_exp(-t.gamma * fabs(lntg - t.lnts));
+    return fmax(tg, t.ts) * px_exp(px_log1p_unit(e) * t.inv_gamma);
 }
 
 // One wavefront per row (job, placement class, K): lt[row][i] for every grid point i.
@@ -180,7 +197,7 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
     const Job q = load_job(a.job_params, a.J, j);
     const SyncTerm t = sync_term(q, K, one_node);
     const size_t o = (size_t)j * a.Gm;
-    for (int i = lane_id(); i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(q, t, a.tg[o + i], a.lntg[o + i]);
+    for (int i = lane_id(); i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i], a.lntg[o + i]);
 }
 
 // ---- the sweep of one (job, K, nodes) ----------------------------------------
@@ -293,33 +310,31 @@ __device__ __forceinline__ double sweep_chunk(double tg, double A0, double B0, i
 }
 
 // All 64 lanes call this with the same (job, K, nodes).  Every lane returns the same result.
-template <int CH>
-__device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const double *__restrict__ rs,
-                                      const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
+// TABLED: the last pass of Eq. 10 comes from the job's table (K <= kTableK), else it is computed here.
+template <int CH, bool TABLED>
+__device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+                                           const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
     Best out = {0.0, -1, -1};
-    if (K <= 0) return out;
     const int lane = lane_id();
     const double Kd = (double)K;
     const double rK = K < kRecipTable ? rk[K] : 1.0 / Kd;
     const bool one_node = nodes == 1;
-    // the last pass of Eq. 10 comes from the job's table when K is in its range, else it is computed here
-    const bool tabled = K <= kTableK;
-    const double *__restrict__ lrow = tb.lt + ((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(tabled ? K - 1 : 0)) * Gm;
-    SyncTerm st = {0.0, 0.0, 0};
-    if (!tabled) st = sync_term(q, K, one_node);
-    const int s_chunks = (Gs + CH - 1) / CH;
+    const double *__restrict__ lrow = tb.lt + ((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(TABLED ? K - 1 : 0)) * Gm;
+    SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
+    if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
     double kbest = __builtin_inf();   // smallest key seen by this lane
-    int code = -1;                    // (m chunk) * s_chunks + (s chunk) of kbest
+    int code = -1;                    // (first grid index of the m chunk) << 10 | (s chunk) of kbest
 
-    int code_now = 0;
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
         const int i = i0 + lane;
         const bool active = i < Gm;
         const int il = active ? i : Gm - 1;
         const double tg = tb.tg[il];
-        const double last = tabled ? lrow[il] : last_pass(q, st, tg, tb.lntg[il]);
+        double last;
+        if constexpr (TABLED) last = lrow[il];
+        else last = last_pass(st, tg, tb.lntg[il]);
         const double u = tb.pu[il] * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
@@ -328,6 +343,7 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
         s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
         if (!active) s_hi = -1;
 
+        int code_now = i0 << 10;
         for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
             // bit b of `bad` is set when s = s0 + b is infeasible for this lane
             int first = s_lo - s0, lastb = s_hi - s0;
@@ -346,11 +362,13 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
     double g = -1.0;
     int flat = 0x7FFFFFFF, m_best = -1, sbest = -1;
     if (code >= 0) {
-        const int ibest = (code / s_chunks) * kWave + lane;
-        sbest = (code % s_chunks) * CH + (__double2loint(kbest) & 31);
+        const int ibest = (code >> 10) + lane;
+        sbest = (code & 1023) * CH + (__double2loint(kbest) & 31);
         m_best = tb.m[ibest];
         const double tg = tb.tg[ibest];
-        const double last = tabled ? lrow[ibest] : last_pass(q, st, tg, tb.lntg[ibest]);
+        double last;
+        if constexpr (TABLED) last = lrow[ibest];
+        else last = last_pass(st, tg, tb.lntg[ibest]);
         g = goodput_point(q, Kd * (double)m_best, tg, last, sbest);
         flat = ibest * Gs + sbest;
     }
@@ -363,6 +381,15 @@ __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const d
     out.m = __builtin_amdgcn_readlane(m_best, wl);
     out.s = __builtin_amdgcn_readlane(sbest, wl);
     return out;
+}
+
+template <int CH>
+__device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+                                      const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
+{
+    if (K <= 0) return Best{0.0, -1, -1};
+    if (K <= kTableK) return sweep_impl<CH, true>(q, tb, rs, rk, Gm, Gs, K, nodes);
+    return sweep_impl<CH, false>(q, tb, rs, rk, Gm, Gs, K, nodes);
 }
 
 __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
@@ -382,6 +409,7 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     if (j >= a.J) return;
     const int lane = lane_id();
     const Job q = load_job(a.job_params, a.J, j);
+    const SyncParams y = load_sync(q);
     const double *__restrict__ jp = a.job_params;
     const double alpha_g = jp[(size_t)PX_ALPHA_G * a.J + j], beta_g = jp[(size_t)PX_BETA_G * a.J + j];
     const double M0 = jp[(size_t)PX_M0 * a.J + j], Mmax = jp[(size_t)PX_MMAX * a.J + j];
@@ -389,8 +417,8 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     const double T = jp[(size_t)PX_AGE_T * a.J + j];
     const double R = jp[(size_t)PX_RESTARTS_R * a.J + j];
     int st = 0;
-    if (!(q.gamma >= 1.0 && q.gamma <= 10.0) || !(alpha_g >= 0.0) || !(beta_g >= 0.0) || !(q.alpha_sl >= 0.0) ||
-        !(q.beta_sl >= 0.0) || !(q.alpha_sn >= 0.0) || !(q.beta_sn >= 0.0) || !(q.phi > 0.0) || !(M0 >= 1.0) ||
+    if (!(y.gamma >= 1.0 && y.gamma <= 10.0) || !(alpha_g >= 0.0) || !(beta_g >= 0.0) || !(y.alpha_sl >= 0.0) ||
+        !(y.beta_sl >= 0.0) || !(y.alpha_sn >= 0.0) || !(y.beta_sn >= 0.0) || !(q.phi > 0.0) || !(M0 >= 1.0) ||
         !(Mmax >= M0) || !(w >= 0.0) || !(Mmax <= 4503599627370496.0) || !(alpha_g + beta_g > 0.0))
         st |= PX_ST_BAD_PARAM;
     // re-allocation penalty factor of Sec. 4.2
