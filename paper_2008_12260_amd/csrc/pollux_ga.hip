@@ -6,11 +6,9 @@
 //
 // Kernels
 //   rank_kernel                 order[] = candidates by (fitness desc, index asc)
-//   children_kernel             one workgroup per child, one wavefront per row:
-//                               elite copy, or row-wise crossover + mutation
-//   repair_capacity_kernel      one workgroup per child, one thread per node
-//   repair_interference_kernel  one workgroup per child: nodes in order, jobs in
-//                               parallel, integer LDS atomics (order independent)
+//   generation_kernel           one workgroup per child: elite copy, or row-wise
+//                               crossover + mutation, then both repairs, with the
+//                               per-node bookkeeping in LDS
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -69,25 +67,82 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
     a.order[before] = c;
 }
 
-// ---- children ------------------------------------------------------------------
-__global__ void __launch_bounds__(256) children_kernel(GaArgs a)
+// ---- one child per workgroup: build, repair capacity, repair interference ---------
+//
+// LDS (dynamic): nodes_of[J] nodes occupied by each row; colsum[N] GPUs asked per
+// node (64-bit); colcnt[N] multi-node jobs present per node, counted while the rows
+// are built (an over-estimate once repairs remove entries, which is all that is
+// needed to know which nodes can hold a conflict); dist[J] indices of multi-node jobs.
+//
+// Step A  one wavefront per row: crossover source, mutation, write the row, count its
+//         nodes, add its non-zero entries to colsum / colcnt with LDS atomics (rows are
+//         sparse: a job sits on a few of the N nodes).
+// Step B  one thread per node over capacity: walk the jobs cyclically from the drawn
+//         start and take GPUs away.
+// Step C  nodes in ascending order, skipping those that never held two multi-node
+//         jobs: count the multi-node jobs present and find the largest holder with
+//         integer LDS atomics (order independent), then zero the others there.
+//
+// A workgroup re-reads global memory written by its own wavefronts; __syncthreads()
+// orders those accesses (all wavefronts of a workgroup share one CU and its L1).
+
+constexpr int kGaThreads = 256;
+
+struct GaShared {
+    int32_t *nodes_of;
+    unsigned long long *colsum;
+    int32_t *colcnt;
+    int32_t *dist;
+};
+
+__device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N)
 {
+    GaShared sh;
+    sh.colsum = (unsigned long long *)base;                         // 8-byte aligned first
+    sh.nodes_of = (int32_t *)(sh.colsum + N);
+    sh.colcnt = sh.nodes_of + J;
+    sh.dist = sh.colcnt + N;
+    return sh;
+}
+
+inline size_t ga_shared_bytes(int J, int N) { return 8 * (size_t)N + 4 * (size_t)J + 4 * (size_t)N + 4 * (size_t)J; }
+
+__global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
+{
+    extern __shared__ __align__(16) unsigned char ga_lds[];
+    __shared__ int count, n_dist;
+    __shared__ unsigned long long keep;     // (GPUs there) << 32 | ~job: maximum = most GPUs, lowest job
+
     const int c = blockIdx.x;
+    const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int waves = blockDim.x >> 6;
+    const int waves = kGaThreads >> 6;
     const int lane = lane_id();
     const size_t JN = (size_t)a.J * a.N;
     int32_t *__restrict__ child = a.children + (size_t)c * JN;
 
     if ((uint32_t)c < a.elite_k) {
+        // survivors are copied verbatim, in rank order
         const int32_t *__restrict__ src = a.parents + (size_t)a.order[c] * JN;
-        for (size_t e = threadIdx.x; e < JN; e += blockDim.x) child[e] = src[e];
+        if ((JN & 3) == 0 && (((uintptr_t)src | (uintptr_t)child) & 15) == 0) {
+            const int4 *__restrict__ s4 = (const int4 *)src;
+            int4 *__restrict__ d4 = (int4 *)child;
+            for (size_t e = tid; e < (JN >> 2); e += kGaThreads) d4[e] = s4[e];
+        } else {
+            for (size_t e = tid; e < JN; e += kGaThreads) child[e] = src[e];
+        }
         return;
     }
+
+    const GaShared sh = carve_shared(ga_lds, a.J, a.N);
+    for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; }
+    if (tid == 0) { count = 0; n_dist = 0; keep = 0ull; }
+    __syncthreads();
+
+    // ---- step A ----
     const U4 pr = philox4x32_10(a.generation, (uint32_t)c, 0u, kTagParent, a.key0, a.key1);
     const int32_t *__restrict__ pa = a.parents + (size_t)a.order[below(pr.x, a.elite_k)] * JN;
     const int32_t *__restrict__ pb = a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
-
     for (int j = wave; j < a.J; j += waves) {
         const U4 cr = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagCross, a.key0, a.key1);
         const int32_t *__restrict__ src = ((cr.x & 1u) ? pb : pa) + (size_t)j * a.N;
@@ -99,6 +154,7 @@ __global__ void __launch_bounds__(256) children_kernel(GaArgs a)
             move = (int)(ma.x % 3u);
             target = (int)below(ma.y, (uint32_t)a.N);
         }
+        int32_t put = 0;
         if (move == 2) {
             // re-pack: the whole row goes to one node, as far as that node's capacity allows
             long long k = 0;
@@ -106,70 +162,63 @@ __global__ void __launch_bounds__(256) children_kernel(GaArgs a)
             k = wave_sum(k);
             if (k < 0) k = 0;
             const long long cap = a.node_capacity[target];
-            const int32_t put = (int32_t)(k < cap ? k : cap);
-            for (int n = lane; n < a.N; n += kWave) dst[n] = (n == target) ? put : 0;
-        } else {
-            for (int n = lane; n < a.N; n += kWave) {
-                int32_t v = src[n];
-                if (n == target) {
-                    if (move == 0) v += 1;
-                    else if (v > 0) v -= 1;     // move == 1
+            put = (int32_t)(k < cap ? k : cap);
+        }
+        int nodes = 0;
+        for (int n0 = 0; n0 < a.N; n0 += kWave) {
+            const int n = n0 + lane;
+            int32_t v = 0;
+            if (n < a.N) {
+                if (move == 2) {
+                    v = (n == target) ? put : 0;
+                } else {
+                    v = src[n];
+                    if (n == target) {
+                        if (move == 0) v += 1;
+                        else if (v > 0) v -= 1;     // move == 1
+                    }
                 }
                 dst[n] = v;
+                if (v != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
             }
+            nodes += __popcll(__ballot(v > 0));
+        }
+        if (lane == 0) sh.nodes_of[j] = nodes;
+        if (nodes >= 2) {
+            if (lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
+            for (int n = lane; n < a.N; n += kWave)
+                if (dst[n] > 0) atomicAdd(&sh.colcnt[n], 1);
         }
     }
-}
+    __syncthreads();
 
-// ---- repair: node capacity -------------------------------------------------------
-__global__ void __launch_bounds__(256) repair_capacity_kernel(GaArgs a)
-{
-    const int c = blockIdx.x + (int)a.elite_k;      // elites are kept verbatim
-    int32_t *__restrict__ A = a.children + (size_t)c * a.J * a.N;
-    for (int n = threadIdx.x; n < a.N; n += blockDim.x) {
-        long long total = 0;
-        for (int j = 0; j < a.J; ++j) total += A[(size_t)j * a.N + n];
-        long long excess = total - (long long)a.node_capacity[n];
+    // ---- step B: node capacity ----
+    for (int n = tid; n < a.N; n += kGaThreads) {
+        long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
         if (excess <= 0) continue;
         const U4 r = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)n, kTagRepair, a.key0, a.key1);
         int j = (int)below(r.x, (uint32_t)a.J);
         for (int t = 0; t < a.J && excess > 0; ++t) {
-            const long long have = A[(size_t)j * a.N + n];
+            const long long have = child[(size_t)j * a.N + n];
             if (have > 0) {
                 const long long take = have < excess ? have : excess;
-                A[(size_t)j * a.N + n] = (int32_t)(have - take);
+                child[(size_t)j * a.N + n] = (int32_t)(have - take);
                 excess -= take;
+                if (take == have) atomicSub(&sh.nodes_of[j], 1);
             }
             j = (j + 1 == a.J) ? 0 : j + 1;
         }
     }
-}
-
-// ---- repair: at most one multi-node job per node ------------------------------------
-__global__ void __launch_bounds__(256) repair_interference_kernel(GaArgs a)
-{
-    extern __shared__ int32_t nodes_of[];           // [J] nodes occupied by each job
-    __shared__ int count;                           // multi-node jobs present on the current node
-    __shared__ unsigned long long keep;             // (GPUs there) << 32 | ~job: maximum = most GPUs, lowest job
-    const int c = blockIdx.x + (int)a.elite_k;
-    int32_t *__restrict__ A = a.children + (size_t)c * a.J * a.N;
-    const int wave = threadIdx.x >> 6, waves = blockDim.x >> 6, lane = lane_id();
-
-    for (int j = wave; j < a.J; j += waves) {
-        int cnt = 0;
-        for (int n0 = 0; n0 < a.N; n0 += kWave) {
-            const int n = n0 + lane;
-            cnt += __popcll(__ballot(n < a.N && A[(size_t)j * a.N + n] > 0));
-        }
-        if (lane == 0) nodes_of[j] = cnt;
-    }
-    if (threadIdx.x == 0) { count = 0; keep = 0ull; }
     __syncthreads();
 
+    // ---- step C: at most one multi-node job per node ----
+    const int nd = n_dist;
     for (int n = 0; n < a.N; ++n) {
-        for (int j = threadIdx.x; j < a.J; j += blockDim.x) {
-            const int32_t v = A[(size_t)j * a.N + n];
-            if (v > 0 && nodes_of[j] >= 2) {
+        if (__builtin_amdgcn_readfirstlane(sh.colcnt[n]) <= 1) continue;
+        for (int k = tid; k < nd; k += kGaThreads) {
+            const int j = sh.dist[k];
+            const int32_t v = child[(size_t)j * a.N + n];
+            if (v > 0 && sh.nodes_of[j] >= 2) {
                 atomicAdd(&count, 1);
                 atomicMax(&keep, ((unsigned long long)(uint32_t)v << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)j));
             }
@@ -179,15 +228,16 @@ __global__ void __launch_bounds__(256) repair_interference_kernel(GaArgs a)
         const int keeper = (int)(0xFFFFFFFFu - (uint32_t)(keep & 0xFFFFFFFFull));
         __syncthreads();
         if (cnt > 1) {
-            for (int j = threadIdx.x; j < a.J; j += blockDim.x) {
+            for (int k = tid; k < nd; k += kGaThreads) {
+                const int j = sh.dist[k];
                 if (j == keeper) continue;
-                if (A[(size_t)j * a.N + n] > 0 && nodes_of[j] >= 2) {
-                    A[(size_t)j * a.N + n] = 0;
-                    nodes_of[j] -= 1;
+                if (child[(size_t)j * a.N + n] > 0 && sh.nodes_of[j] >= 2) {
+                    child[(size_t)j * a.N + n] = 0;
+                    sh.nodes_of[j] -= 1;
                 }
             }
         }
-        if (threadIdx.x == 0) { count = 0; keep = 0ull; }
+        if (tid == 0) { count = 0; keep = 0ull; }
         __syncthreads();
     }
 }
@@ -206,13 +256,13 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.generation = ga->generation; a.elite_k = ga->elite_k; a.mut_threshold = ga->mut_threshold;
 
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 255) / 256)), dim3(256), 0, stream, a);
-    hipLaunchKernelGGL(children_kernel, dim3((unsigned)d->P), dim3(256), 0, stream, a);
-    const int bred = d->P - (int)ga->elite_k;
-    if (bred > 0) {
-        hipLaunchKernelGGL(repair_capacity_kernel, dim3((unsigned)bred), dim3(256), 0, stream, a);
-        hipLaunchKernelGGL(repair_interference_kernel, dim3((unsigned)bred), dim3(256), sizeof(int32_t) * (size_t)d->J,
-                           stream, a);
+    const size_t lds = ga_shared_bytes(d->J, d->N);
+    if (lds > 48 * 1024) {
+        if (hipFuncSetAttribute((const void *)generation_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+            hipSuccess)
+            return PX_E_HIP;
     }
+    hipLaunchKernelGGL(generation_kernel, dim3((unsigned)d->P), dim3(kGaThreads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 
