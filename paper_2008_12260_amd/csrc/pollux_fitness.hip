@@ -5,7 +5,7 @@
 // Sec. 4.1 (Eq. 13), SPEEDUP / FITNESS_p, re-allocation penalty and
 // interference avoidance Sec. 4.2 (Eq. 14-15).
 //
-// Kernels (one call = five launches on the caller's stream)
+// Kernels (one call = six launches on the caller's stream)
 //   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), ln T_grad, phi/m and
 //                     the feasibility bounds; reciprocals; clears the status word
 //   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
@@ -16,9 +16,10 @@
 //   jobs_kernel       per job (one wavefront): parameter checks, restart factor,
 //                     fair-share goodput (denominator of Eq. 15)
 //   pairs_kernel      per (candidate, job) (one wavefront): row reduce, sweep of the
-//                     (m, s) grid, argmax
+//                     (m, s) grid, argmax; the row's non-zero entries are added to
+//                     per-candidate, per-node counters with integer atomics
 //   candidates_kernel per candidate (one workgroup): SPEEDUP, penalty, constraint
-//                     check and the generalized mean
+//                     check from those counters and the generalized mean
 //
 // How one wavefront sweeps the grid of a (candidate, job) pair.  Lane l owns
 // the batch sizes m_i, i = l, l+64, ...; it walks s = 0..Gs-1.  Dividing Eq. 4
@@ -69,11 +70,14 @@ struct FitnessArgs {
     int32_t *status;
     double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
     int32_t *running, *meta;
+    unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
+    int need_constraints;
     // outputs
     double *fitness, *best_goodput, *speedup;
     int32_t *best_m, *best_s, *violations;
 };
 
+constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
 // Parameters of one job (uniform across the wavefront).  The sweep itself needs only
@@ -147,6 +151,15 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
         a.pu[t] = mi > 0 ? a.job_params[(size_t)PX_PHI * a.J + j] / m : 0.0;
         a.qh5[t] = qh + 0.5;
         a.ql5[t] = ql - 0.5;
+    }
+}
+
+// Clears the per-candidate, per-node counters of the constraint check.
+__global__ void __launch_bounds__(256) zero_counters_kernel(FitnessArgs a)
+{
+    const size_t n = (size_t)a.P * a.N;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
+        a.colpack[i] = 0ull;
     }
 }
 
@@ -473,6 +486,7 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
         const int32_t *__restrict__ row = a.population + pair * a.N;
         int ksum = 0, nodes = 0;
         bool changed = false, neg = false;
+        int4 v0 = {0, 0, 0, 0};       // the lane's first four entries (the whole row when N <= 256)
         if (vec4) {
             const int4 *__restrict__ row4 = (const int4 *)row;
             const int4 *__restrict__ cur4 = (const int4 *)cur;
@@ -482,6 +496,7 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
                 const int4 z = {0, 0, 0, 0};
                 const int4 v = n < n4 ? row4[n] : z;
                 const int4 cv = n < n4 ? cur4[n] : z;
+                if (n0 == 0) v0 = v;
                 ksum += (v.x + v.y) + (v.z + v.w);
                 nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
                          __popcll(__ballot(v.w > 0));
@@ -500,6 +515,27 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
             }
         }
         const int K = __builtin_amdgcn_readfirstlane(wave_sum(ksum));
+
+        // constraint check, part one: the row's non-zero entries (a job sits on few nodes) go to the
+        // candidate's per-node counters; a multi-node job also counts once on each of its nodes.
+        // One 64-bit integer atomic per entry: the result does not depend on the order of arrival.
+        if (a.need_constraints) {
+            unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
+            const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
+            if (vec4 && a.N <= 4 * kWave && !neg) {
+                // the row is still in registers and has no negative entry
+                const int nb = lane * 4;
+                if (v0.x > 0) atomicAdd(&cp[nb + 0], (unsigned long long)v0.x + one_job);
+                if (v0.y > 0) atomicAdd(&cp[nb + 1], (unsigned long long)v0.y + one_job);
+                if (v0.z > 0) atomicAdd(&cp[nb + 2], (unsigned long long)v0.z + one_job);
+                if (v0.w > 0) atomicAdd(&cp[nb + 3], (unsigned long long)v0.w + one_job);
+            } else {
+                for (int n = lane; n < a.N; n += kWave) {
+                    const int v = row[n];
+                    if (v != 0) atomicAdd(&cp[n], (unsigned long long)(long long)v + (v > 0 ? one_job : 0ull));
+                }
+            }
+        }
 
         const Best best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
         if (lane == 0) {
@@ -548,21 +584,16 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     red_acc[t] = acc;
     red_w[t] = wsum;
 
-    // constraint check: thread <-> node, walk the jobs
+    // constraint check, part two: per node, multi-node jobs beyond the first and GPUs beyond capacity
     long long v = 0;
-    const bool need_v = a.violations != nullptr || !(a.flags & PX_FLAG_NO_CONSTRAINT_CHECK);
-    if (need_v) {
-        const int32_t *__restrict__ A = a.population + (size_t)c * a.J * a.N;
+    if (a.need_constraints) {
+        const unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
         for (int n = t; n < a.N; n += kCandThreads) {
-            long long total = 0;
-            int distributed = 0;
-            for (int j = 0; j < a.J; ++j) {
-                const int x = A[(size_t)j * a.N + n];
-                total += x;
-                distributed += (x > 0 && (meta[j] & (kMetaChanged - 1)) >= 2);
-            }
+            const long long x = (long long)cp[n];
+            const long long asked = (x << 24) >> 24;              // low 40 bits, sign-extended
+            const long long distributed = (x - asked) >> 40;
             if (distributed > 1) v += distributed - 1;
-            const long long over = total - (long long)a.node_capacity[n];
+            const long long over = asked - (long long)a.node_capacity[n];
             if (over > 0) v += over;
         }
     }
@@ -618,6 +649,8 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.running = (int32_t *)(ws + L.running);
     a.G = (double *)(ws + L.G);
     a.meta = (int32_t *)(ws + L.meta);
+    a.colpack = (unsigned long long *)(ws + L.colpack);
+    a.need_constraints = (violations != nullptr || !(d->flags & PX_FLAG_NO_CONSTRAINT_CHECK)) ? 1 : 0;
     a.fitness = fitness; a.best_goodput = best_goodput; a.speedup = speedup;
     a.best_m = best_m; a.best_s = best_s; a.violations = violations;
 
@@ -635,6 +668,10 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
     if (table_items < kRecipTable) table_items = kRecipTable;
     hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+    if (a.need_constraints) {
+        long long zb = ((long long)d->P * d->N + 255) / 256;
+        hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
+    }
     const long long lt_rows = (long long)d->J * 2 * kTableK;
     hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
     const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
