@@ -72,9 +72,11 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 // LDS (dynamic): nodes_of[J] nodes occupied by each row; colsum[N] GPUs asked per
 // node (64-bit); colcnt[N] multi-node jobs present per node, counted while the rows
 // are built (an over-estimate once repairs remove entries, which is all that is
-// needed to know which nodes can hold a conflict); dist[J] indices of multi-node jobs.
+// needed to know which nodes can hold a conflict); dist[J] indices of multi-node jobs;
+// dec[J] the drawn decisions of each row.
 //
-// Step A  one wavefront per row: crossover source, mutation, write the row, count its
+// Step A  one thread per job draws the row's decisions (Philox), then one wavefront
+//         per row: crossover source, mutation, write the row, count its
 //         nodes, add its non-zero entries to colsum / colcnt with LDS atomics (rows are
 //         sparse: a job sits on a few of the N nodes).
 // Step B  one thread per node over capacity: walk the jobs cyclically from the drawn
@@ -93,6 +95,7 @@ struct GaShared {
     unsigned long long *colsum;
     int32_t *colcnt;
     int32_t *dist;
+    int32_t *dec;
 };
 
 __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N)
@@ -102,10 +105,11 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.nodes_of = (int32_t *)(sh.colsum + N);
     sh.colcnt = sh.nodes_of + J;
     sh.dist = sh.colcnt + N;
+    sh.dec = sh.dist + J;
     return sh;
 }
 
-inline size_t ga_shared_bytes(int J, int N) { return 8 * (size_t)N + 4 * (size_t)J + 4 * (size_t)N + 4 * (size_t)J; }
+inline size_t ga_shared_bytes(int J, int N) { return 12 * (size_t)N + 12 * (size_t)J; }
 
 __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
 {
@@ -140,20 +144,29 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     __syncthreads();
 
     // ---- step A ----
+    // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1 | target << 3
+    for (int j = tid; j < a.J; j += kGaThreads) {
+        const U4 cr = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagCross, a.key0, a.key1);
+        const U4 md = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutDecide, a.key0, a.key1);
+        int d = (int)(cr.x & 1u);
+        if (md.x < a.mut_threshold) {
+            const U4 ma = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutArgs, a.key0, a.key1);
+            d |= (int)((ma.x % 3u) + 1u) << 1;
+            d |= (int)below(ma.y, (uint32_t)a.N) << 3;
+        }
+        sh.dec[j] = d;
+    }
     const U4 pr = philox4x32_10(a.generation, (uint32_t)c, 0u, kTagParent, a.key0, a.key1);
     const int32_t *__restrict__ pa = a.parents + (size_t)a.order[below(pr.x, a.elite_k)] * JN;
     const int32_t *__restrict__ pb = a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
+    const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
+    __syncthreads();
+
     for (int j = wave; j < a.J; j += waves) {
-        const U4 cr = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagCross, a.key0, a.key1);
-        const int32_t *__restrict__ src = ((cr.x & 1u) ? pb : pa) + (size_t)j * a.N;
+        const int d = __builtin_amdgcn_readfirstlane(sh.dec[j]);
+        const int32_t *__restrict__ src = ((d & 1) ? pb : pa) + (size_t)j * a.N;
         int32_t *__restrict__ dst = child + (size_t)j * a.N;
-        const U4 md = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutDecide, a.key0, a.key1);
-        int move = -1, target = -1;
-        if (md.x < a.mut_threshold) {
-            const U4 ma = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutArgs, a.key0, a.key1);
-            move = (int)(ma.x % 3u);
-            target = (int)below(ma.y, (uint32_t)a.N);
-        }
+        const int move = ((d >> 1) & 3) - 1, target = move >= 0 ? (d >> 3) : -1;
         int32_t put = 0;
         if (move == 2) {
             // re-pack: the whole row goes to one node, as far as that node's capacity allows
@@ -164,24 +177,47 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
             const long long cap = a.node_capacity[target];
             put = (int32_t)(k < cap ? k : cap);
         }
-        int nodes = 0;
-        for (int n0 = 0; n0 < a.N; n0 += kWave) {
-            const int n = n0 + lane;
-            int32_t v = 0;
-            if (n < a.N) {
-                if (move == 2) {
-                    v = (n == target) ? put : 0;
-                } else {
-                    v = src[n];
-                    if (n == target) {
-                        if (move == 0) v += 1;
-                        else if (v > 0) v -= 1;     // move == 1
-                    }
-                }
-                dst[n] = v;
-                if (v != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
+        // the entry of node n after the move
+        auto moved = [&](int n, int32_t v) -> int32_t {
+            if (move == 2) return (n == target) ? put : 0;
+            if (n == target) {
+                if (move == 0) return v + 1;
+                if (v > 0) return v - 1;     // move == 1
             }
-            nodes += __popcll(__ballot(v > 0));
+            return v;
+        };
+        int nodes = 0;
+        if (vec4) {
+            const int4 *__restrict__ s4 = (const int4 *)src;
+            int4 *__restrict__ d4 = (int4 *)dst;
+            const int n4 = a.N >> 2;
+            for (int q0 = 0; q0 < n4; q0 += kWave) {
+                const int q = q0 + lane;
+                int4 v = {0, 0, 0, 0};
+                if (q < n4) {
+                    v = s4[q];
+                    const int n = q * 4;
+                    v.x = moved(n, v.x); v.y = moved(n + 1, v.y); v.z = moved(n + 2, v.z); v.w = moved(n + 3, v.w);
+                    d4[q] = v;
+                    if (v.x != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v.x);
+                    if (v.y != 0) atomicAdd(&sh.colsum[n + 1], (unsigned long long)(long long)v.y);
+                    if (v.z != 0) atomicAdd(&sh.colsum[n + 2], (unsigned long long)(long long)v.z);
+                    if (v.w != 0) atomicAdd(&sh.colsum[n + 3], (unsigned long long)(long long)v.w);
+                }
+                nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
+                         __popcll(__ballot(v.w > 0));
+            }
+        } else {
+            for (int n0 = 0; n0 < a.N; n0 += kWave) {
+                const int n = n0 + lane;
+                int32_t v = 0;
+                if (n < a.N) {
+                    v = moved(n, src[n]);
+                    dst[n] = v;
+                    if (v != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
+                }
+                nodes += __popcll(__ballot(v > 0));
+            }
         }
         if (lane == 0) sh.nodes_of[j] = nodes;
         if (nodes >= 2) {
