@@ -65,6 +65,9 @@ def main():
     ap.add_argument("--workload", default="large", choices=["large", "mid", "physical", "tiny"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ga-loop", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="after the timed region, copy the population device-to-device twice (a plain copy of known "
+                         "size against which HBM byte counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; a population would shard over candidates, "
@@ -118,6 +121,11 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     px.pollux_set_sweep_events(None, None)
+
+    if args.calibration_copy:
+        for _ in range(2):
+            b.copy_(a)
+        torch.cuda.synchronize()
 
     status = call.status()
     best_fitness = float(call.fitness.max().item())

@@ -54,48 +54,55 @@ struct GaArgs {
 // order[rank(c)] = c is a permutation.
 __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 {
-    const int c = blockIdx.x * blockDim.x + threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int c = blockIdx.x * 4 + wave;           // one wavefront per candidate, lanes over the others
     if (c >= a.P) return;
+    const int lane = lane_id();
     double f = a.fitness[c];
     if (!(f == f)) f = -__builtin_inf();
     int before = 0;
-    for (int o = 0; o < a.P; ++o) {
-        double g = a.fitness[o];
+    for (int o0 = 0; o0 < a.P; o0 += kWave) {
+        const int o = o0 + lane;
+        double g = o < a.P ? a.fitness[o] : -__builtin_inf();
         if (!(g == g)) g = -__builtin_inf();
-        before += (g > f) || (g == f && o < c);
+        before += __popcll(__ballot(o < a.P && ((g > f) || (g == f && o < c))));
     }
-    a.order[before] = c;
+    if (lane == 0) a.order[before] = c;
 }
 
 // ---- one child per workgroup: build, repair capacity, repair interference ---------
 //
-// LDS (dynamic): nodes_of[J] nodes occupied by each row; colsum[N] GPUs asked per
-// node (64-bit); colcnt[N] multi-node jobs present per node, counted while the rows
-// are built (an over-estimate once repairs remove entries, which is all that is
-// needed to know which nodes can hold a conflict); dist[J] indices of multi-node jobs;
-// dec[J] the drawn decisions of each row.
+// Allocation matrices are sparse (a job sits on a few of the N nodes), so while the
+// rows are built every positive entry is also threaded into a per-node list in LDS:
+// entry e = (job, GPUs, next entry of the same node).  Both repairs then work on those
+// lists and touch global memory only to write the entries they change.
+//
+// LDS (dynamic): colsum[N] GPUs asked per node (64-bit); nodes_of[J] nodes occupied by
+// each row; colcnt[N] multi-node jobs per node; dist[J] indices of multi-node jobs;
+// dec[J] the drawn decisions of each row; head[N] and the entry arrays.
 //
 // Step A  one thread per job draws the row's decisions (Philox), then one wavefront
-//         per row: crossover source, mutation, write the row, count its
-//         nodes, add its non-zero entries to colsum / colcnt with LDS atomics (rows are
-//         sparse: a job sits on a few of the N nodes).
-// Step B  one thread per node over capacity: walk the jobs cyclically from the drawn
-//         start and take GPUs away.
-// Step C  nodes in ascending order, skipping those that never held two multi-node
-//         jobs: count the multi-node jobs present and find the largest holder with
-//         integer LDS atomics (order independent), then zero the others there.
+//         per row: crossover source, mutation, write the row, count its nodes, add
+//         its entries to colsum and to the node lists.
+// Step B  one thread per node over capacity: visit the jobs present in cyclic order
+//         from the drawn start and take GPUs away until the node fits.
+// Step C  one thread walks the nodes in ascending order: among the multi-node jobs
+//         present it keeps the largest holder (lowest job on ties) and zeroes the
+//         others there.  Sequential by definition: a job that loses a node may stop
+//         being multi-node, which later nodes must see.
+// When a matrix has more positive entries than the lists hold (dense matrices) steps
+// B and C run the same rules on columns read from memory instead.
 //
-// A workgroup re-reads global memory written by its own wavefronts; __syncthreads()
-// orders those accesses (all wavefronts of a workgroup share one CU and its L1).
+// A workgroup re-reads global memory written by its own wavefronts only in that
+// fallback; __syncthreads() orders those accesses (one CU, one L1).
 
 constexpr int kGaThreads = 256;
+constexpr int kGaMaxEntries = 3072;
 
 struct GaShared {
-    int32_t *nodes_of;
     unsigned long long *colsum;
-    int32_t *colcnt;
-    int32_t *dist;
-    int32_t *dec;
+    int32_t *nodes_of, *colcnt, *dist, *dec, *head;
+    int32_t *ent_j, *ent_v, *ent_next;
 };
 
 __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N)
@@ -106,16 +113,26 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.colcnt = sh.nodes_of + J;
     sh.dist = sh.colcnt + N;
     sh.dec = sh.dist + J;
+    sh.head = sh.dec + J;
+    sh.ent_j = sh.head + N;
+    sh.ent_v = sh.ent_j + kGaMaxEntries;
+    sh.ent_next = sh.ent_v + kGaMaxEntries;
     return sh;
 }
 
-inline size_t ga_shared_bytes(int J, int N) { return 12 * (size_t)N + 12 * (size_t)J; }
+inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 12 * (size_t)J + 12 * (size_t)kGaMaxEntries; }
+
+// (GPUs there) << 32 | ~job: the maximum is the largest holder, lowest job index on ties
+__device__ __forceinline__ unsigned long long holder_key(int32_t v, int j)
+{
+    return ((unsigned long long)(uint32_t)v << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)j);
+}
 
 __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
 {
     extern __shared__ __align__(16) unsigned char ga_lds[];
-    __shared__ int count, n_dist;
-    __shared__ unsigned long long keep;     // (GPUs there) << 32 | ~job: maximum = most GPUs, lowest job
+    __shared__ int count, n_dist, n_ent;
+    __shared__ unsigned long long keep;
 
     const int c = blockIdx.x;
     const int tid = threadIdx.x;
@@ -139,9 +156,8 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     }
 
     const GaShared sh = carve_shared(ga_lds, a.J, a.N);
-    for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; }
-    if (tid == 0) { count = 0; n_dist = 0; keep = 0ull; }
-    __syncthreads();
+    for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1; }
+    if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; }
 
     // ---- step A ----
     // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1 | target << 3
@@ -161,6 +177,19 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     const int32_t *__restrict__ pb = a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
     __syncthreads();
+
+    // a positive entry of the child: per-node total and node list
+    auto record = [&](int j, int n, int32_t v) {
+        atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
+        if (v > 0) {
+            const int e = atomicAdd(&n_ent, 1);
+            if (e < kGaMaxEntries) {
+                sh.ent_j[e] = j;
+                sh.ent_v[e] = v;
+                sh.ent_next[e] = atomicExch(&sh.head[n], e);
+            }
+        }
+    };
 
     for (int j = wave; j < a.J; j += waves) {
         const int d = __builtin_amdgcn_readfirstlane(sh.dec[j]);
@@ -199,10 +228,10 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                     const int n = q * 4;
                     v.x = moved(n, v.x); v.y = moved(n + 1, v.y); v.z = moved(n + 2, v.z); v.w = moved(n + 3, v.w);
                     d4[q] = v;
-                    if (v.x != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v.x);
-                    if (v.y != 0) atomicAdd(&sh.colsum[n + 1], (unsigned long long)(long long)v.y);
-                    if (v.z != 0) atomicAdd(&sh.colsum[n + 2], (unsigned long long)(long long)v.z);
-                    if (v.w != 0) atomicAdd(&sh.colsum[n + 3], (unsigned long long)(long long)v.w);
+                    if (v.x != 0) record(j, n, v.x);
+                    if (v.y != 0) record(j, n + 1, v.y);
+                    if (v.z != 0) record(j, n + 2, v.z);
+                    if (v.w != 0) record(j, n + 3, v.w);
                 }
                 nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
                          __popcll(__ballot(v.w > 0));
@@ -214,21 +243,80 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                 if (n < a.N) {
                     v = moved(n, src[n]);
                     dst[n] = v;
-                    if (v != 0) atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
+                    if (v != 0) record(j, n, v);
                 }
                 nodes += __popcll(__ballot(v > 0));
             }
         }
         if (lane == 0) sh.nodes_of[j] = nodes;
-        if (nodes >= 2) {
-            if (lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
-            for (int n = lane; n < a.N; n += kWave)
-                if (dst[n] > 0) atomicAdd(&sh.colcnt[n], 1);
-        }
+        if (nodes >= 2 && lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
     }
     __syncthreads();
 
-    // ---- step B: node capacity ----
+    if (n_ent <= kGaMaxEntries) {
+        // ---- step B on the node lists ----
+        for (int n = tid; n < a.N; n += kGaThreads) {
+            long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
+            if (excess <= 0) continue;
+            const U4 r = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)n, kTagRepair, a.key0, a.key1);
+            const int j0 = (int)below(r.x, (uint32_t)a.J);
+            int last = -1;                                  // cyclic distance from j0 of the job visited last
+            while (excess > 0) {
+                int pick = -1, pick_dist = 0x7FFFFFFF;
+                for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                    if (sh.ent_v[e] <= 0) continue;
+                    const int j = sh.ent_j[e];
+                    const int dist = j >= j0 ? j - j0 : j - j0 + a.J;
+                    if (dist > last && dist < pick_dist) { pick = e; pick_dist = dist; }
+                }
+                if (pick < 0) break;
+                const long long have = sh.ent_v[pick];
+                const long long take = have < excess ? have : excess;
+                const int j = sh.ent_j[pick];
+                sh.ent_v[pick] = (int32_t)(have - take);
+                child[(size_t)j * a.N + n] = (int32_t)(have - take);
+                excess -= take;
+                if (take == have) atomicSub(&sh.nodes_of[j], 1);
+                last = pick_dist;
+            }
+        }
+        __syncthreads();
+        // ---- step C on the node lists ----
+        // which nodes hold two or more multi-node jobs now (later removals can only lower the count)
+        for (int n = tid; n < a.N; n += kGaThreads) {
+            int cnt = 0;
+            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e])
+                cnt += (sh.ent_v[e] > 0 && sh.nodes_of[sh.ent_j[e]] >= 2);
+            sh.colcnt[n] = cnt;
+        }
+        __syncthreads();
+        if (tid != 0) return;
+        for (int n = 0; n < a.N; ++n) {
+            if (sh.colcnt[n] <= 1) continue;
+            int cnt = 0;
+            unsigned long long best = 0ull;
+            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                const int j = sh.ent_j[e];
+                if (sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
+                    cnt++;
+                    const unsigned long long key = holder_key(sh.ent_v[e], j);
+                    best = key > best ? key : best;
+                }
+            }
+            if (cnt <= 1) continue;
+            const int keeper = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                const int j = sh.ent_j[e];
+                if (j != keeper && sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
+                    child[(size_t)j * a.N + n] = 0;
+                    sh.nodes_of[j] -= 1;
+                }
+            }
+        }
+        return;
+    }
+
+    // ---- dense fallback: step B on columns read from memory ----
     for (int n = tid; n < a.N; n += kGaThreads) {
         long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
         if (excess <= 0) continue;
@@ -246,9 +334,15 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         }
     }
     __syncthreads();
-
-    // ---- step C: at most one multi-node job per node ----
+    // ---- dense fallback: step C, integer LDS atomics (order independent) ----
     const int nd = n_dist;
+    for (int k = wave; k < nd; k += waves) {
+        const int j = sh.dist[k];
+        if (__builtin_amdgcn_readfirstlane(sh.nodes_of[j]) < 2) continue;      // capacity repair left it on one node
+        for (int n = lane; n < a.N; n += kWave)
+            if (child[(size_t)j * a.N + n] > 0) atomicAdd(&sh.colcnt[n], 1);
+    }
+    __syncthreads();
     for (int n = 0; n < a.N; ++n) {
         if (__builtin_amdgcn_readfirstlane(sh.colcnt[n]) <= 1) continue;
         for (int k = tid; k < nd; k += kGaThreads) {
@@ -256,7 +350,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
             const int32_t v = child[(size_t)j * a.N + n];
             if (v > 0 && sh.nodes_of[j] >= 2) {
                 atomicAdd(&count, 1);
-                atomicMax(&keep, ((unsigned long long)(uint32_t)v << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)j));
+                atomicMax(&keep, holder_key(v, j));
             }
         }
         __syncthreads();
@@ -291,7 +385,7 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.key1 = (uint32_t)(ga->seed >> 32);
     a.generation = ga->generation; a.elite_k = ga->elite_k; a.mut_threshold = ga->mut_threshold;
 
-    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 255) / 256)), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);
     if (lds > 48 * 1024) {
         if (hipFuncSetAttribute((const void *)generation_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
