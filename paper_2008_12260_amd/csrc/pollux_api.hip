@@ -87,7 +87,6 @@ int pollux_fitness(const pollux_dims *dims, const int32_t *population, const dou
         !best_m || !best_s)
         return PX_E_INVALID_ARG;
     if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
-    if (dims->precision != 0) return PX_E_INVALID_ARG;   // fp32 arithmetic: not built yet
     int rc = check_workspace(dims, workspace, workspace_bytes);
     if (rc != PX_OK) return rc;
     rc = check_device();

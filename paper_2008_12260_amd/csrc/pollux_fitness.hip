@@ -412,9 +412,82 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
                      a.lt + (size_t)j * 2 * kTableK * a.Gm};
 }
 
+// ---- fp32 variant of the sweep --------------------------------------------------
+// The same model with every parameter rounded to fp32 and all arithmetic of Eq. 4-11 in
+// fp32, written the plain way (two divisions per grid point, powf for Eq. 10).  The
+// feasibility interval M0 <= K m (s+1) <= M_max stays the exact integer test of the fp64
+// path.  Ties go to the lowest flat index.
+
+struct JobF32 {
+    float alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, inv_gamma, phi, a;
+};
+
+__device__ __forceinline__ JobF32 load_job_f32(const double *__restrict__ jp, int J, int j)
+{
+    JobF32 q;
+    q.alpha_g = (float)jp[(size_t)PX_ALPHA_G * J + j];
+    q.beta_g = (float)jp[(size_t)PX_BETA_G * J + j];
+    q.alpha_sl = (float)jp[(size_t)PX_ALPHA_SL * J + j];
+    q.beta_sl = (float)jp[(size_t)PX_BETA_SL * J + j];
+    q.alpha_sn = (float)jp[(size_t)PX_ALPHA_SN * J + j];
+    q.beta_sn = (float)jp[(size_t)PX_BETA_SN * J + j];
+    q.gamma = (float)jp[(size_t)PX_GAMMA * J + j];
+    q.inv_gamma = 1.0f / q.gamma;
+    q.phi = (float)jp[(size_t)PX_PHI * J + j];
+    q.a = q.phi + (float)jp[(size_t)PX_M0 * J + j];
+    return q;
+}
+
+__device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, const double *__restrict__ rk, int Gm,
+                                          int Gs, int K, int nodes)
+{
+    Best out = {0.0, -1, -1};
+    if (K <= 0) return out;
+    const int lane = lane_id();
+    const float Kf = (float)K;
+    const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
+    float ts = 0.0f;                                                          // Eq. 9
+    if (K > 1) ts = (nodes == 1) ? q.alpha_sl + q.beta_sl * (float)(K - 2) : q.alpha_sn + q.beta_sn * (float)(K - 2);
+    const float tsg = (ts != 0.0f && q.gamma != 1.0f) ? powf(ts, q.gamma) : 0.0f;
+
+    float gbest = -1.0f;
+    int flat = 0x7FFFFFFF, m_best = -1, s_best = -1;
+    for (int i0 = 0; i0 < Gm; i0 += kWave) {
+        const int i = i0 + lane;
+        if (i >= Gm) continue;
+        const int m = tb.m[i];
+        const float mf = (float)m;
+        const float tg = q.alpha_g + q.beta_g * mf;                           // Eq. 8
+        float last;                                                           // Eq. 10
+        if (ts == 0.0f) last = tg;
+        else if (q.gamma == 1.0f) last = tg + ts;
+        else last = powf(powf(tg, q.gamma) + tsg, q.inv_gamma);
+        const int s_lo = (int)(tb.ql5[i] * rK);
+        int s_hi = (int)(tb.qh5[i] * rK) - 1;
+        s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
+        const float Km = Kf * mf;
+        for (int sI = s_lo; sI <= s_hi; ++sI) {
+            const float M = Km * (float)(sI + 1);
+            const float t_iter = (float)sI * tg + last;                      // Eq. 11
+            const float g = (M / t_iter) * (q.a / (q.phi + M));              // Eq. 7 x Eq. 6
+            if (g > gbest) { gbest = g; flat = i * Gs + sI; m_best = m; s_best = sI; }
+        }
+    }
+    const double gd = (double)gbest;
+    const double gmax = wave_vmax(gd);
+    if (!(gmax > 0.0)) return out;
+    const int fmin_ = wave_min(gd == gmax ? flat : 0x7FFFFFFF);
+    const uint64_t wmask = __ballot((gd == gmax) && (flat == fmin_));
+    const int wl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)wmask) - 1);
+    out.goodput = gmax;
+    out.m = __builtin_amdgcn_readlane(m_best, wl);
+    out.s = __builtin_amdgcn_readlane(s_best, wl);
+    return out;
+}
+
 // ---- per job -----------------------------------------------------------------
 
-template <int CH>
+template <int CH, bool F32>
 __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -435,7 +508,8 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
         !(Mmax >= M0) || !(w >= 0.0) || !(Mmax <= 4503599627370496.0) || !(alpha_g + beta_g > 0.0))
         st |= PX_ST_BAD_PARAM;
     // re-allocation penalty factor of Sec. 4.2
-    const double factor = (T - R * a.delta) / (T + a.delta);
+    double factor = (T - R * a.delta) / (T + a.delta);
+    if constexpr (F32) factor = (double)(((float)T - (float)R * (float)a.delta) / ((float)T + (float)a.delta));
     if (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && !(T - R * a.delta > 0.0)) st |= PX_ST_BAD_RESTART;
     // does the job hold GPUs now?
     long long csum = 0;
@@ -448,7 +522,12 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     const long long total = wave_sum(csum);
     if (__ballot(neg) != 0) st |= PX_ST_NEG_ALLOC;
     // denominator of Eq. 15: the same sweep at the fair-share allocation
-    const Best fair = sweep<CH>(q, job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
+    Best fair;
+    if constexpr (F32)
+        fair = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, a.fair_share[2 * j],
+                         a.fair_share[2 * j + 1]);
+    else
+        fair = sweep<CH>(q, job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
     if (!(fair.goodput > 0.0)) st |= PX_ST_ZERO_FAIR;
     if (lane == 0) {
         a.denom[j] = fair.goodput;
@@ -464,7 +543,7 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
 // of one job then run on one XCD and its tables stay in that XCD's L2.  Each of the
 // four wavefronts walks cand_per_wave candidates of that job.
 
-template <int CH>
+template <int CH, bool F32>
 __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -474,6 +553,8 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const Job q = load_job(a.job_params, a.J, j);
+    JobF32 qf = {};
+    if constexpr (F32) qf = load_job_f32(a.job_params, a.J, j);
     const JobTables tb = job_tables(a, j);
     const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
@@ -537,7 +618,9 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
             }
         }
 
-        const Best best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        Best best;
+        if constexpr (F32) best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
+        else best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
         if (lane == 0) {
             a.G[pair] = best.goodput;
             a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
@@ -559,10 +642,21 @@ __device__ __forceinline__ double pmean_term(double s, double w, double p)
     return w * pow(s, p);                 // pow(0, p<0) = +inf
 }
 
+__device__ __forceinline__ float pmean_term(float s, float w, float p)
+{
+    if (p == 0.0f) return w * logf(s);
+    return w * powf(s, p);
+}
+
+__device__ __forceinline__ double pmean_finish(double mean, double p) { return p == 0.0 ? exp(mean) : pow(mean, 1.0 / p); }
+__device__ __forceinline__ float pmean_finish(float mean, float p) { return p == 0.0f ? expf(mean) : powf(mean, 1.0f / p); }
+
+// REAL = double, or float for the fp32 variant (SPEEDUP, the penalty and the mean are then formed in fp32).
+template <typename REAL>
 __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
 {
-    __shared__ double red_acc[kCandThreads];
-    __shared__ double red_w[kCandThreads];
+    __shared__ REAL red_acc[kCandThreads];
+    __shared__ REAL red_w[kCandThreads];
     __shared__ long long red_v[kCandThreads];
     const int c = blockIdx.x;
     const int t = threadIdx.x;
@@ -572,14 +666,15 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
 
     // SPEEDUP (Eq. 15) with the re-allocation penalty, then the generalized mean (Eq. 14):
     // each thread sums its jobs in ascending order, then a fixed tree
-    double acc = 0.0, wsum = 0.0;
+    REAL acc = 0, wsum = 0;
+    const REAL p = (REAL)a.p;
     for (int j = t; j < a.J; j += kCandThreads) {
-        const double d = a.denom[j];
-        double s_j = d > 0.0 ? G[j] / d : 0.0;
-        if (meta[j] & kMetaChanged) s_j = s_j * a.factor[j];
-        if (a.speedup) a.speedup[(size_t)c * a.J + j] = s_j;
-        acc += pmean_term(s_j, wt[j], a.p);
-        wsum += wt[j];
+        const REAL d = (REAL)a.denom[j];
+        REAL s_j = d > 0 ? (REAL)G[j] / d : (REAL)0;
+        if (meta[j] & kMetaChanged) s_j = s_j * (REAL)a.factor[j];
+        if (a.speedup) a.speedup[(size_t)c * a.J + j] = (double)s_j;
+        acc += pmean_term(s_j, (REAL)wt[j], p);
+        wsum += (REAL)wt[j];
     }
     red_acc[t] = acc;
     red_w[t] = wsum;
@@ -608,8 +703,8 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
         __syncthreads();
     }
     if (t == 0) {
-        const double mean = red_acc[0] / red_w[0];
-        double f = (a.p == 0.0) ? exp(mean) : pow(mean, 1.0 / a.p);
+        const REAL mean = red_acc[0] / red_w[0];
+        double f = (double)pmean_finish(mean, (REAL)a.p);
         const long long V = red_v[0];
         if (a.violations) a.violations[c] = (int32_t)(V > 0x7FFFFFFF ? 0x7FFFFFFF : V);
         if (V > 0 && !(a.flags & PX_FLAG_NO_CONSTRAINT_CHECK)) f = -(double)V;
@@ -673,17 +768,22 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
     }
     const long long lt_rows = (long long)d->J * 2 * kTableK;
-    hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+    if (d->precision == 0)
+        hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
     const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
-    if (ch == 8) hipLaunchKernelGGL(jobs_kernel<8>, job_grid, dim3(256), 0, stream, a);
-    else if (ch == 16) hipLaunchKernelGGL(jobs_kernel<16>, job_grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(jobs_kernel<32>, job_grid, dim3(256), 0, stream, a);
+    const bool f32 = d->precision == 1;
+    if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
+    else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
+    else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
-    if (ch == 8) hipLaunchKernelGGL(pairs_kernel<8>, dim3(pair_blocks), dim3(256), 0, stream, a);
-    else if (ch == 16) hipLaunchKernelGGL(pairs_kernel<16>, dim3(pair_blocks), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL(pairs_kernel<32>, dim3(pair_blocks), dim3(256), 0, stream, a);
+    if (f32) hipLaunchKernelGGL((pairs_kernel<8, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    else hipLaunchKernelGGL((pairs_kernel<32, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
     if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
-    hipLaunchKernelGGL(candidates_kernel, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
+    if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
+    else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 

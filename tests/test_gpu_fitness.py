@@ -136,3 +136,40 @@ def test_large_config_on_sampled_candidates():
     idx = [0, 1, 3, 7, 1000, 4095]
     sub = np.concatenate([W.candidates(cfg, i, 1) for i in idx])
     assert compare(wl, run_gpu(wl, population=sub), run_oracle(wl, population=sub), population=sub) == 0
+
+
+@pytest.mark.parametrize("p", [-1.0, 0.5, 1.0])
+def test_fp32_variant_on_the_mid_configuration(p):
+    """precision = 1: fp32 arithmetic checked against the fp64 oracle.  Goodput, SPEEDUP and fitness within
+    1e-5 relative; the GPU's (m, s) may differ from the oracle's where fp32 cannot separate two points, but
+    the oracle's goodput at the GPU's choice must be within 1e-5 of the oracle's maximum."""
+    import oracle as O
+    wl = W.make("mid")
+    sub = wl.population[:300]
+    g = run_gpu(wl, population=sub, p=p, precision=1)
+    r = run_oracle(wl, population=sub, p=p)
+    assert g["status"] == r["status"] and np.array_equal(g["violations"], r["violations"])
+    from parity import rel_err
+    for name in ("best_goodput", "speedup", "fitness"):
+        assert rel_err(g[name], r[name]).max() <= 1e-5, name
+    differ = np.argwhere((g["best_m"] != r["best_m"]) | (g["best_s"] != r["best_s"]))
+    agreement = 1.0 - len(differ) / g["best_m"].size
+    print(f"fp32 (m,s) agreement with the fp64 oracle at p={p}: {agreement:.6f} ({len(differ)} of {g['best_m'].size} differ)")
+    assert agreement > 0.99
+    for cand, j in differ[:500]:
+        K, nodes = int(sub[cand, j].sum()), int((sub[cand, j] > 0).sum())
+        at, ok = O.goodput(O.job_from_params(wl.job_params, j), K, nodes, int(g["best_m"][cand, j]), int(g["best_s"][cand, j]))
+        assert ok and abs(at - r["best_goodput"][cand, j]) <= 1e-5 * r["best_goodput"][cand, j]
+
+
+def test_fp32_variant_small_and_ragged():
+    from parity import rel_err
+    for cfg in (W.CONFIGS["tiny"], W.custom("ragged32", P=4, J=6, N=130, cap=3, Gm=129, Gs=33)):
+        wl = W.make(cfg)
+        g, r = run_gpu(wl, precision=1), run_oracle(wl)
+        assert np.array_equal(g["violations"], r["violations"])
+        for name in ("best_goodput", "speedup", "fitness"):
+            assert rel_err(g[name], r[name]).max() <= 1e-5, name
+    wl = W.make("tiny", current="fair")
+    g = run_gpu(wl, population=wl.population[:1], precision=1)
+    assert g["fitness"][0] == 1.0 and np.all(g["speedup"][0] == 1.0)
