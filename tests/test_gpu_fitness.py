@@ -173,3 +173,37 @@ def test_fp32_variant_small_and_ragged():
     wl = W.make("tiny", current="fair")
     g = run_gpu(wl, population=wl.population[:1], precision=1)
     assert g["fitness"][0] == 1.0 and np.all(g["speedup"][0] == 1.0)
+
+
+def test_large_config_full_population_in_the_benchmark_launch_shape():
+    """All 4096 candidates on the GPU (the launch configuration bench.py times: 64 000 workgroups, 16 candidates
+    per wavefront); the oracle recomputes a seeded sample of candidates one by one."""
+    import torch
+    import paper_2008_12260_amd as px
+    cfg = W.CONFIGS["large"]
+    wl = W.make(cfg, with_population=False)
+    pop = W.candidates(cfg, 0, cfg.P)
+    call = px.FitnessCall(cfg.P, cfg.J, cfg.N, cfg.Gm, cfg.Gs, wl.job_params, wl.m_grid, wl.fair_share,
+                          wl.current_alloc, wl.node_capacity, p=cfg.p, delta=cfg.delta)
+    dpop = torch.from_numpy(pop).cuda()
+    call.run(dpop)
+    g = call.results()
+    rng = np.random.default_rng(4)
+    idx = np.unique(np.concatenate([[0, 1, 3, 7, cfg.P - 1], rng.integers(0, cfg.P, 27)]))
+    sub = pop[idx]
+    r = run_oracle(wl, population=sub)
+    gs = {k: (v[idx] if isinstance(v, np.ndarray) else v) for k, v in g.items()}
+    assert compare(wl, gs, r, population=sub) == 0
+    # properties that hold at any size: infeasible candidates are exactly the spoiled slice and score -V;
+    # every feasible candidate has a finite fitness >= 0; the argmax respects the batch-size limits
+    bad = np.flatnonzero(g["violations"] > 0)
+    assert set(bad) <= {i for i in range(cfg.P) if i % 20 == 7}
+    assert np.array_equal(g["fitness"][bad], -g["violations"][bad].astype(np.float64))
+    good = g["violations"] == 0
+    assert np.all(np.isfinite(g["fitness"][good])) and np.all(g["fitness"][good] >= 0)
+    K = pop.sum(2)
+    have = g["best_m"] > 0
+    M = K * g["best_m"] * (g["best_s"] + 1)
+    assert np.all(M[have] >= wl.param("M0")[None].repeat(cfg.P, 0)[have])
+    assert np.all(M[have] <= wl.param("M_max")[None].repeat(cfg.P, 0)[have])
+    assert np.all((g["best_goodput"] > 0) == have)

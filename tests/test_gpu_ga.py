@@ -93,3 +93,24 @@ def test_rejects_aliasing_and_bad_elite():
         call.ga_step(a, torch.empty_like(a), SEED, 0, 0, 0)
     with pytest.raises(px.PolluxError):
         call.ga_step(a, torch.empty_like(a), SEED, 0, 17, 0)
+
+
+def test_large_config_one_generation_bit_exact():
+    """One search step on the full 4096 x 1000 x 256 population against the oracle (all 4.19 GB compared)."""
+    import torch
+    cfg = W.CONFIGS["large"]
+    wl = W.make(cfg, with_population=False)
+    pop = W.candidates(cfg, 0, cfg.P)
+    rng = np.random.default_rng(8)
+    fit = rng.uniform(0.2, 1.0, cfg.P)
+    fit[::20] = -3.0
+    fit[5] = fit[6] = fit[4000]                       # ties in the ranking
+    call = gpu_call(wl)
+    parents = torch.from_numpy(pop).cuda()
+    children = torch.empty_like(parents)
+    call.ga_step(parents, children, SEED, 3, cfg.P // 2, 1 << 29, fitness=torch.as_tensor(fit).cuda())
+    got = children.cpu().numpy()
+    del parents, children
+    want = O.ga_step(pop, fit, wl.node_capacity, SEED, 3, cfg.P // 2, 1 << 29)
+    for lo in range(0, cfg.P, 256):
+        assert np.array_equal(got[lo:lo + 256], want[lo:lo + 256]), f"children {lo}..{lo + 255}"
