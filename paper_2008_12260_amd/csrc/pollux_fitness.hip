@@ -255,6 +255,28 @@ __device__ __forceinline__ double wave_vmax(double v)
     return v;
 }
 
+// Wave-wide argmax of non-negative goodput values g (0 = the lane has no point): positive
+// doubles order like their bit patterns, so the maximum is found as two unsigned 32-bit
+// reductions (high words, then low words among the lanes that hold the highest high word),
+// and ties go to the lowest flat index.  Every lane returns the same result.
+__device__ __forceinline__ Best wave_argmax(double g, int flat, int m, int s)
+{
+    g = g > 0.0 ? g : 0.0;                                        // also drops a NaN
+    const unsigned hi = (unsigned)__double2hiint(g), lo = (unsigned)__double2loint(g);
+    const unsigned hmax = wave_max(hi);
+    const unsigned lmax = wave_max(hi == hmax ? lo : 0u);
+    if ((hmax | lmax) == 0u) return Best{0.0, -1, -1};
+    const bool top = hi == hmax && lo == lmax;
+    const int fmin_ = wave_min(top ? flat : 0x7FFFFFFF);
+    const uint64_t wmask = __ballot(top && flat == fmin_);
+    const int wl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)wmask) - 1);
+    Best out;
+    out.goodput = __hiloint2double((int)__builtin_amdgcn_readfirstlane((int)hmax), (int)__builtin_amdgcn_readfirstlane((int)lmax));
+    out.m = __builtin_amdgcn_readlane(m, wl);
+    out.s = __builtin_amdgcn_readlane(s, wl);
+    return out;
+}
+
 // Eq. 4 at one grid point, in the paper's order of operations (no contraction).
 __device__ __forceinline__ double goodput_point(const Job &q, double Km, double tg, double last, int s)
 {
@@ -328,7 +350,6 @@ template <int CH, bool TABLED>
 __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
-    Best out = {0.0, -1, -1};
     const int lane = lane_id();
     const double Kd = (double)K;
     const double rK = K < kRecipTable ? rk[K] : 1.0 / Kd;
@@ -372,7 +393,7 @@ __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, co
     }
 
     // the elected point of each lane, evaluated in the paper's order of operations
-    double g = -1.0;
+    double g = 0.0;
     int flat = 0x7FFFFFFF, m_best = -1, sbest = -1;
     if (code >= 0) {
         const int ibest = (code >> 10) + lane;
@@ -385,15 +406,7 @@ __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, co
         g = goodput_point(q, Kd * (double)m_best, tg, last, sbest);
         flat = ibest * Gs + sbest;
     }
-    const double gmax = wave_vmax(g);
-    if (!(gmax > 0.0)) return out;
-    const int fmin_ = wave_min(g == gmax ? flat : 0x7FFFFFFF);
-    const uint64_t wmask = __ballot((g == gmax) && (flat == fmin_));
-    const int wl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)wmask) - 1);
-    out.goodput = gmax;
-    out.m = __builtin_amdgcn_readlane(m_best, wl);
-    out.s = __builtin_amdgcn_readlane(sbest, wl);
-    return out;
+    return wave_argmax(g, flat, m_best, sbest);
 }
 
 template <int CH>
@@ -473,16 +486,7 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
             if (g > gbest) { gbest = g; flat = i * Gs + sI; m_best = m; s_best = sI; }
         }
     }
-    const double gd = (double)gbest;
-    const double gmax = wave_vmax(gd);
-    if (!(gmax > 0.0)) return out;
-    const int fmin_ = wave_min(gd == gmax ? flat : 0x7FFFFFFF);
-    const uint64_t wmask = __ballot((gd == gmax) && (flat == fmin_));
-    const int wl = __builtin_amdgcn_readfirstlane(__ffsll((unsigned long long)wmask) - 1);
-    out.goodput = gmax;
-    out.m = __builtin_amdgcn_readlane(m_best, wl);
-    out.s = __builtin_amdgcn_readlane(s_best, wl);
-    return out;
+    return wave_argmax((double)gbest, flat, m_best, s_best);
 }
 
 // ---- per job -----------------------------------------------------------------
