@@ -44,7 +44,10 @@ typedef struct {
 
 enum {
     PX_FLAG_NO_REALLOC_PENALTY = 1,   /* skip the re-allocation penalty of Sec. 4.2         */
-    PX_FLAG_NO_CONSTRAINT_CHECK = 2   /* fitness is Eq. 14 even for infeasible candidates  */
+    PX_FLAG_NO_CONSTRAINT_CHECK = 2,  /* fitness is Eq. 14 even for infeasible candidates  */
+    PX_FLAG_MEMOISE = 4               /* sweep the (m, s) grid once per (job, K, one node or several) instead of
+                                         once per (candidate, job): the goodput model (Eq. 4, 9) sees a row only
+                                         through those; identical results, the population pass becomes a gather */
 };
 
 /* Rows of job_params[PX_NPARAM][J] (structure of arrays, fp64).

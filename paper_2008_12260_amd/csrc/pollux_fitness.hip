@@ -60,6 +60,12 @@ namespace px {
 constexpr int kWavesPerBlock = 4;
 constexpr int kRecipTable = 256;      // 1/K is tabled for K below this
 
+// Result of the sweep for one (job, placement class, K); filled and used only in memoised mode.
+struct __align__(16) MemoEntry {
+    double goodput;
+    int32_t m, s;
+};
+
 struct FitnessArgs {
     int P, J, N, Gm, Gs, flags;
     int cand_per_wave, cand_groups;   // pairs kernel: candidates each wavefront walks, groups of 4 * cand_per_wave
@@ -70,6 +76,7 @@ struct FitnessArgs {
     int32_t *status;
     double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
     int32_t *running, *meta;
+    MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
     int need_constraints;
     // outputs
@@ -541,13 +548,38 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     }
 }
 
+// ---- memoised mode ---------------------------------------------------------------
+// The goodput model sees an allocation row only through K and through whether the job
+// sits on one node (Eq. 9), so the sweep of a pair equals the sweep of its (job, class, K).
+// One wavefront per (job, class, K <= kTableK) runs the sweep once; the population pass
+// then looks the result up (pairs_kernel with MEMO) and is bound by reading the
+// population.  Rows with K > kTableK are swept in place.  Results are identical.
+template <int CH, bool F32>
+__global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long row = (long long)blockIdx.x * kWavesPerBlock + wave;
+    if (row >= (long long)a.J * 2 * kTableK) return;
+    const int K = (int)(row % kTableK) + 1;
+    const int nodes = ((row / kTableK) & 1) ? 1 : 2;
+    const int j = (int)(row / (2 * kTableK));
+    Best best;
+    if constexpr (F32) best = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, K, nodes);
+    else best = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+    if (lane_id() == 0) {
+        MemoEntry e;
+        e.goodput = best.goodput; e.m = best.m; e.s = best.s;
+        a.memo[row] = e;
+    }
+}
+
 // ---- per (candidate, job) ------------------------------------------------------
 // Workgroup -> (job, group of candidates).  Workgroups are dealt to the eight XCDs
 // round-robin, so the job index is derived from (blockIdx % 8) first: all workgroups
 // of one job then run on one XCD and its tables stay in that XCD's L2.  Each of the
 // four wavefronts walks cand_per_wave candidates of that job.
 
-template <int CH, bool F32>
+template <int CH, bool F32, bool MEMO>
 __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -623,8 +655,14 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
         }
 
         Best best;
-        if constexpr (F32) best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
-        else best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        if (MEMO && K >= 1 && K <= kTableK) {
+            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
+            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+        } else if constexpr (F32) {
+            best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
+        } else {
+            best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        }
         if (lane == 0) {
             a.G[pair] = best.goodput;
             a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
@@ -748,6 +786,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.running = (int32_t *)(ws + L.running);
     a.G = (double *)(ws + L.G);
     a.meta = (int32_t *)(ws + L.meta);
+    a.memo = (MemoEntry *)(ws + L.memo);
     a.colpack = (unsigned long long *)(ws + L.colpack);
     a.need_constraints = (violations != nullptr || !(d->flags & PX_FLAG_NO_CONSTRAINT_CHECK)) ? 1 : 0;
     a.fitness = fitness; a.best_goodput = best_goodput; a.speedup = speedup;
@@ -780,11 +819,26 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
     else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
     else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
+    const bool memo = (d->flags & PX_FLAG_MEMOISE) != 0;
+    if (memo) {
+        const dim3 memo_grid((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock));
+        if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
+        else if (ch == 8) hipLaunchKernelGGL((memo_kernel<8, false>), memo_grid, dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL((memo_kernel<16, false>), memo_grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
+    }
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
-    if (f32) hipLaunchKernelGGL((pairs_kernel<8, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
-    else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-    else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL((pairs_kernel<32, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    if (memo) {
+        if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((pairs_kernel<32, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    } else {
+        if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((pairs_kernel<32, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    }
     if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);

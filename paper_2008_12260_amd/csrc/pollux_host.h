@@ -29,6 +29,7 @@ struct WorkspaceLayout {
     size_t running;   // int32  [J]       job holds GPUs in current_alloc
     size_t G;         // double [P,J]     best goodput of the pair
     size_t meta;      // int32  [P,J]     nodes occupied by the row | changed flag
+    size_t memo;      // 16 bytes [J,2,kTableK]  best point per (job, one node?, K) in memoised mode
     size_t colpack;   // uint64 [P,N]     per node of each candidate: GPUs asked + multi-node jobs << 40
     size_t order;     // int32  [P]       candidates by rank (search step)
     size_t total;
@@ -54,6 +55,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.running = o; o = up(o + 4 * J);
     L.G = o;       o = up(o + 8 * P * J);
     L.meta = o;    o = up(o + 4 * P * J);
+    L.memo = o;    o = up(o + 16 * J * 2 * kTableK);
     L.colpack = o; o = up(o + 8 * P * (size_t)d.N);
     L.order = o;   o = up(o + 4 * P);
     L.total = o;

@@ -207,3 +207,25 @@ def test_large_config_full_population_in_the_benchmark_launch_shape():
     assert np.all(M[have] >= wl.param("M0")[None].repeat(cfg.P, 0)[have])
     assert np.all(M[have] <= wl.param("M_max")[None].repeat(cfg.P, 0)[have])
     assert np.all((g["best_goodput"] > 0) == have)
+
+
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_memoised_mode_gives_the_same_results(name):
+    """PX_FLAG_MEMOISE: one sweep per (job, K, placement class), looked up per pair."""
+    wl = W.make(name)
+    g = run_gpu(wl, flags=4)
+    assert compare(wl, g, run_oracle(wl)) == 0
+    plain = run_gpu(wl)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations"):
+        assert np.array_equal(g[k], plain[k], equal_nan=True), k
+
+
+def test_memoised_mode_with_rows_beyond_the_table_and_in_fp32():
+    cfg = W.custom("bigK", P=6, J=40, N=9, cap=40, Gm=33, Gs=5)      # K up to 160: beyond the 64-entry table
+    wl = W.make(cfg)
+    assert wl.population.sum(2).max() > 64
+    assert compare(wl, run_gpu(wl, flags=4), run_oracle(wl)) == 0
+    wl = W.make("physical")
+    a, b = run_gpu(wl, flags=4, precision=1), run_gpu(wl, precision=1)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup"):
+        assert np.array_equal(a[k], b[k], equal_nan=True), k
