@@ -96,7 +96,7 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 // A workgroup re-reads global memory written by its own wavefronts only in that
 // fallback; __syncthreads() orders those accesses (one CU, one L1).
 
-constexpr int kGaThreads = 256;
+constexpr int kGaThreads = 512;     // eight wavefronts keep enough row loads in flight to approach copy bandwidth
 constexpr int kGaMaxEntries = 3072;
 
 struct GaShared {
