@@ -610,9 +610,9 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
             const int n4 = a.N >> 2;
             for (int n0 = 0; n0 < n4; n0 += kWave) {
                 const int n = n0 + lane;
-                const int4 z = {0, 0, 0, 0};
-                const int4 v = n < n4 ? row4[n] : z;
-                const int4 cv = n < n4 ? cur4[n] : z;
+                const int nc = n < n4 ? n : n4 - 1;           // one unconditional 16-byte load per lane
+                int4 v = row4[nc], cv = cur4[nc];
+                if (n >= n4) { v = int4{0, 0, 0, 0}; cv = v; }
                 if (n0 == 0) v0 = v;
                 ksum += (v.x + v.y) + (v.z + v.w);
                 nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
