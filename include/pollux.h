@@ -45,9 +45,15 @@ typedef struct {
 enum {
     PX_FLAG_NO_REALLOC_PENALTY = 1,   /* skip the re-allocation penalty of Sec. 4.2         */
     PX_FLAG_NO_CONSTRAINT_CHECK = 2,  /* fitness is Eq. 14 even for infeasible candidates  */
-    PX_FLAG_MEMOISE = 4               /* sweep the (m, s) grid once per (job, K, one node or several) instead of
+    PX_FLAG_MEMOISE = 4,              /* sweep the (m, s) grid once per (job, K, one node or several) instead of
                                          once per (candidate, job): the goodput model (Eq. 4, 9) sees a row only
                                          through those; identical results, the population pass becomes a gather */
+    PX_FLAG_KEEP_JOB_TABLES = 8       /* reuse what the previous pollux_fitness call on this workspace derived from
+                                         the jobs alone (tables, fair-share goodput, restart factors, memoised
+                                         sweeps): the caller guarantees that dims, job_params, m_grid, fair_share,
+                                         current_alloc, delta and the other flags are unchanged since that call,
+                                         as in the generations of one scheduling interval.  The status word is
+                                         then not cleared and keeps accumulating. */
 };
 
 /* Rows of job_params[PX_NPARAM][J] (structure of arrays, fp64).

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libpollux_hip.so")
 
 NPARAM = 13
 PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
-PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE = 1, 2, 4
+PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
@@ -160,9 +160,12 @@ class FitnessCall:
         self.speedup = torch.empty((P, J), dtype=torch.float64, device=dev)
         self.violations = torch.empty(P, dtype=torch.int32, device=dev)
 
-    def run(self, population, stream=None, outputs="all"):
+    def run(self, population, stream=None, outputs="all", keep_job_tables=False):
         full = outputs == "all"
-        pollux_fitness(self.dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
+        dims = self.dims
+        if keep_job_tables:
+            dims = Dims(dims.P, dims.J, dims.N, dims.Gm, dims.Gs, dims.precision, dims.flags | PX_FLAG_KEEP_JOB_TABLES)
+        pollux_fitness(dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
                        self.node_capacity, self.p, self.delta, self.workspace, self.fitness, self.best_m, self.best_s,
                        self.best_goodput if full else None, self.speedup if full else None, self.violations,
                        stream)

@@ -802,30 +802,33 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.cand_groups = (int)((d->P + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
     const unsigned pair_blocks = (unsigned)(8 * ((d->J + 7) / 8) * a.cand_groups);
 
-    long long table_items = (long long)d->J * d->Gm;
-    if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
-    if (table_items < kRecipTable) table_items = kRecipTable;
-    hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+    const long long lt_rows = (long long)d->J * 2 * kTableK;
+    const bool f32 = d->precision == 1;
+    const bool memo = (d->flags & PX_FLAG_MEMOISE) != 0;
     if (a.need_constraints) {
         long long zb = ((long long)d->P * d->N + 255) / 256;
         hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
     }
-    const long long lt_rows = (long long)d->J * 2 * kTableK;
-    if (d->precision == 0)
-        hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
-    const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
-    const bool f32 = d->precision == 1;
-    if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
-    else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
-    else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
-    else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
-    const bool memo = (d->flags & PX_FLAG_MEMOISE) != 0;
-    if (memo) {
-        const dim3 memo_grid((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock));
-        if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
-        else if (ch == 8) hipLaunchKernelGGL((memo_kernel<8, false>), memo_grid, dim3(256), 0, stream, a);
-        else if (ch == 16) hipLaunchKernelGGL((memo_kernel<16, false>), memo_grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
+    if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
+        // everything that depends on the jobs only (not on the population)
+        long long table_items = (long long)d->J * d->Gm;
+        if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
+        if (table_items < kRecipTable) table_items = kRecipTable;
+        hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+        if (!f32)
+            hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+        const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
+        if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
+        else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
+        if (memo) {
+            const dim3 memo_grid((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock));
+            if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
+            else if (ch == 8) hipLaunchKernelGGL((memo_kernel<8, false>), memo_grid, dim3(256), 0, stream, a);
+            else if (ch == 16) hipLaunchKernelGGL((memo_kernel<16, false>), memo_grid, dim3(256), 0, stream, a);
+            else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
+        }
     }
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (memo) {

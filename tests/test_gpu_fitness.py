@@ -229,3 +229,24 @@ def test_memoised_mode_with_rows_beyond_the_table_and_in_fp32():
     a, b = run_gpu(wl, flags=4, precision=1), run_gpu(wl, precision=1)
     for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup"):
         assert np.array_equal(a[k], b[k], equal_nan=True), k
+
+
+def test_keep_job_tables_reuses_the_job_level_work():
+    """PX_FLAG_KEEP_JOB_TABLES: a second call on the same workspace with another population skips the job-level
+    kernels and must give what a full call gives."""
+    import torch
+    import paper_2008_12260_amd as px
+    for flags in (0, px.PX_FLAG_MEMOISE):
+        wl = W.make("mid")
+        c = wl.cfg
+        call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                              wl.node_capacity, p=c.p, delta=c.delta, flags=flags)
+        first = torch.as_tensor(wl.population).cuda()
+        other = torch.as_tensor(np.ascontiguousarray(wl.population[::-1])).cuda()
+        call.run(first)
+        call.run(other, keep_job_tables=True)
+        kept = call.results()
+        call.run(other)
+        full = call.results()
+        for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations", "status"):
+            assert np.array_equal(kept[k], full[k], equal_nan=True), k
