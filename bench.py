@@ -25,7 +25,8 @@ if ROOT not in sys.path:
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 (FMA) x 2.4 GHz
 FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 divisions, each counted as one
 GA_SEED = 0x2008_1226_5EED_0001
-MUT_THRESHOLD = 1 << 29             # mutation probability 1/8 per job
+def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
+    return (1 << 32) // J
 
 
 def cpu_baseline(wl, cfg, target_seconds=15.0):
@@ -39,7 +40,7 @@ def cpu_baseline(wl, cfg, target_seconds=15.0):
         t0 = time.perf_counter()
         r = O.fitness(pop, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc, wl.node_capacity,
                       cfg.p, cfg.delta, cfg.Gs)
-        O.ga_step(pop, r["fitness"], wl.node_capacity, GA_SEED, 0, max(1, count // 2), MUT_THRESHOLD)
+        O.ga_step(pop, r["fitness"], wl.node_capacity, GA_SEED, 0, max(1, count // 2), mut_threshold(cfg.J))
         return time.perf_counter() - t0
 
     probe = 32
@@ -94,7 +95,7 @@ def main():
 
     def step(gen, a, b):
         call.run(a, stream=stream, outputs="fitness")
-        call.ga_step(a, b, GA_SEED, gen, elite, MUT_THRESHOLD, stream=stream)
+        call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
         return b, a
 
     gen = 0
@@ -115,7 +116,7 @@ def main():
         fit_ev[k][0].record(stream)
         call.run(a, stream=stream, outputs="fitness")      # full call every step: job-level kernels included
         fit_ev[k][1].record(stream)
-        call.ga_step(a, b, GA_SEED, gen, elite, MUT_THRESHOLD, stream=stream)
+        call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
         a, b = b, a
         gen += 1
     torch.cuda.synchronize()
@@ -173,13 +174,13 @@ def main():
         mb = torch.empty_like(ma)
         for g in range(5):
             mcall.run(ma, stream=stream, outputs="fitness")
-            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, MUT_THRESHOLD, stream=stream)
+            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream)
             ma, mb = mb, ma
         torch.cuda.synchronize()
         tg0 = time.perf_counter()
         for g in range(5, 105):
             mcall.run(ma, stream=stream, outputs="fitness", keep_job_tables=True)   # jobs do not change within an interval
-            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, MUT_THRESHOLD, stream=stream)
+            mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream)
             ma, mb = mb, ma
         torch.cuda.synchronize()
         tg1 = time.perf_counter()

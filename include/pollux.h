@@ -158,12 +158,16 @@ typedef struct {
  * noted, and below(r, n) = (r * n) >> 32:
  *   rank     candidates ordered by (fitness descending, index ascending), NaN last;
  *   c < elite_k   child c = the candidate of rank c, verbatim;
- *   c >= elite_k  parents a, b = ranks below(word0, elite_k), below(word1, elite_k)   (item 0, tag 0);
+ *   c >= elite_k  parents a, b = ranks below(word0, elite_k), below(word1, elite_k), and b = a when
+ *                 bit 0 of word2 is set (a child of one parent)                       (item 0, tag 0);
  *                 row j comes from b if bit 0 is set, else from a                     (item j, tag 1);
  *                 if word0 < mut_threshold                                             (item j, tag 2)
- *                   then with (word0 % 3, n = below(word1, N))                         (item j, tag 3):
- *                   0: row[n] += 1;  1: row[n] -= 1 if positive;
- *                   2: row := 0 except row[n] = min(sum of row, node_capacity[n]);
+ *                   then with move = word0 % 3 and x = word1                           (item j, tag 3),
+ *                   occ = number of nodes on which the row is positive:
+ *                   0 grow:   one more GPU on the below(x, occ)-th occupied node (ascending),
+ *                             or on node below(x, N) if the job holds none;
+ *                   1 shrink: one GPU less on the below(x, occ)-th occupied node (nothing if occ = 0);
+ *                   2 pack:   row := 0 except row[below(x, N)] = min(sum of row, that node's capacity);
  *                 repair capacity: for each node over capacity, walking jobs cyclically
  *                   from below(word0, J) (item n, tag 4), remove GPUs until it fits;
  *                 repair interference: nodes in ascending order; of the multi-node jobs

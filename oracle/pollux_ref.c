@@ -382,8 +382,8 @@ void pollux_ref_repair(int32_t *A, int J, int N, const int32_t *cap, const uint3
  * One generation of the population search (Sec. 4.3: perturb and combine
  * candidates, then modify them to satisfy the constraints).  The operators are
  * this project's own: the best elite_k candidates survive unchanged; every
- * other child takes each job's row from one of two drawn survivors, may move
- * one GPU / drop one GPU / re-pack a row, and is repaired.
+ * other child takes each job's row from one of two drawn survivors, may grow or
+ * shrink a row by one GPU on a node it occupies or re-pack it, and is repaired.
  */
 int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const double *fitness,
                        const int32_t *cap, const pollux_ref_ga_params *ga, int32_t *children)
@@ -407,7 +407,8 @@ int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const d
         uint32_t r[4];
         draw(key, ga->generation, (uint32_t)c, 0u, TAG_PARENT, r);
         const int32_t *pa = parents + (size_t)order[below(r[0], ga->elite_k)] * JN;
-        const int32_t *pb = parents + (size_t)order[below(r[1], ga->elite_k)] * JN;
+        /* half of the children have a single parent (mutation only) */
+        const int32_t *pb = (r[2] & 1u) ? pa : parents + (size_t)order[below(r[1], ga->elite_k)] * JN;
         for (int j = 0; j < J; ++j) {
             int32_t *row = child + (size_t)j * N;
             draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_CROSS, r);
@@ -416,16 +417,25 @@ int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const d
             if (!(r[0] < ga->mut_threshold)) continue;
             draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_MUT_ARGS, r);
             uint32_t move = r[0] % 3u;
-            int n = (int)below(r[1], (uint32_t)N);
-            if (move == 0u) {
-                row[n] += 1;
-            } else if (move == 1u) {
-                if (row[n] > 0) row[n] -= 1;
-            } else {
+            int occupied = 0;
+            for (int k = 0; k < N; ++k) occupied += row[k] > 0;
+            if (move == 2u) {
+                /* re-pack: the whole row goes to one drawn node, as far as its capacity allows */
+                int n = (int)below(r[1], (uint32_t)N);
                 long K = 0;
                 for (int k = 0; k < N; ++k) { K += row[k]; row[k] = 0; }
                 if (K < 0) K = 0;
                 row[n] = (int32_t)(K < cap[n] ? K : cap[n]);
+            } else if (occupied > 0) {
+                /* grow / shrink by one GPU on one of the nodes the job already occupies */
+                int pick = (int)below(r[1], (uint32_t)occupied), n = -1;
+                for (int k = 0; k < N; ++k) {
+                    if (row[k] > 0 && pick-- == 0) { n = k; break; }
+                }
+                row[n] += (move == 0u) ? 1 : -1;
+            } else if (move == 0u) {
+                /* a job without GPUs starts on a drawn node */
+                row[below(r[1], (uint32_t)N)] += 1;
             }
         }
         pollux_ref_repair(child, J, N, cap, key, ga->generation, (uint32_t)c);

@@ -103,7 +103,7 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (!dims_ok(dims, false)) return PX_E_INVALID_ARG;
     if (!parents || !fitness || !node_capacity || !params || !children) return PX_E_INVALID_ARG;
     if (params->elite_k < 1u || params->elite_k > (uint32_t)dims->P) return PX_E_INVALID_ARG;
-    if (12 * (size_t)dims->J + 16 * (size_t)dims->N > 120 * 1024) return PX_E_INVALID_ARG;   // per-job and per-node bookkeeping lives in LDS
+    if (16 * (size_t)dims->J + 16 * (size_t)dims->N > 120 * 1024) return PX_E_INVALID_ARG;   // per-job and per-node bookkeeping lives in LDS
     const size_t bytes = sizeof(int32_t) * (size_t)dims->P * dims->J * dims->N;
     const char *a = (const char *)parents, *b = (const char *)children;
     if (a < b + bytes && b < a + bytes) return PX_E_INVALID_ARG;

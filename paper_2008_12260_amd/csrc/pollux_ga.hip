@@ -79,7 +79,7 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 //
 // LDS (dynamic): colsum[N] GPUs asked per node (64-bit); nodes_of[J] nodes occupied by
 // each row; colcnt[N] multi-node jobs per node; dist[J] indices of multi-node jobs;
-// dec[J] the drawn decisions of each row; head[N] and the entry arrays.
+// dec[J], decx[J] the drawn decisions of each row; head[N] and the entry arrays.
 //
 // Step A  one thread per job draws the row's decisions (Philox), then one wavefront
 //         per row: crossover source, mutation, write the row, count its nodes, add
@@ -101,7 +101,7 @@ constexpr int kGaMaxEntries = 3072;
 
 struct GaShared {
     unsigned long long *colsum;
-    int32_t *nodes_of, *colcnt, *dist, *dec, *head;
+    int32_t *nodes_of, *colcnt, *dist, *dec, *decx, *head;
     int32_t *ent_j, *ent_v, *ent_next;
 };
 
@@ -113,14 +113,43 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.colcnt = sh.nodes_of + J;
     sh.dist = sh.colcnt + N;
     sh.dec = sh.dist + J;
-    sh.head = sh.dec + J;
+    sh.decx = sh.dec + J;
+    sh.head = sh.decx + J;
     sh.ent_j = sh.head + N;
     sh.ent_v = sh.ent_j + kGaMaxEntries;
     sh.ent_next = sh.ent_v + kGaMaxEntries;
     return sh;
 }
 
-inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 12 * (size_t)J + 12 * (size_t)kGaMaxEntries; }
+inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)kGaMaxEntries; }
+
+// Number of positive entries of a row; every lane returns the same value.
+__device__ __forceinline__ int count_occupied(const int32_t *__restrict__ row, int N, int lane)
+{
+    int occupied = 0;
+    for (int n0 = 0; n0 < N; n0 += kWave) {
+        const int n = n0 + lane;
+        occupied += __popcll(__ballot(n < N && row[n] > 0));
+    }
+    return occupied;
+}
+
+// Index of the pick-th positive entry of a row in ascending order (pick < number of positive entries).
+__device__ __forceinline__ int kth_occupied(const int32_t *__restrict__ row, int N, int lane, int pick)
+{
+    int seen = 0;
+    for (int n0 = 0; n0 < N; n0 += kWave) {
+        const int n = n0 + lane;
+        unsigned long long mask = __ballot(n < N && row[n] > 0);
+        const int here = __popcll(mask);
+        if (pick < seen + here) {
+            for (int t = pick - seen; t > 0; --t) mask &= mask - 1;       // drop the lower set bits
+            return n0 + (__ffsll(mask) - 1);
+        }
+        seen += here;
+    }
+    return -1;
+}
 
 // (GPUs there) << 32 | ~job: the maximum is the largest holder, lowest job index on ties
 __device__ __forceinline__ unsigned long long holder_key(int32_t v, int j)
@@ -160,21 +189,25 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; }
 
     // ---- step A ----
-    // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1 | target << 3
+    // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1, decx[j] = the
+    // second word of the mutation draw (which node)
     for (int j = tid; j < a.J; j += kGaThreads) {
         const U4 cr = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagCross, a.key0, a.key1);
         const U4 md = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutDecide, a.key0, a.key1);
         int d = (int)(cr.x & 1u);
+        uint32_t x = 0u;
         if (md.x < a.mut_threshold) {
             const U4 ma = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)j, kTagMutArgs, a.key0, a.key1);
             d |= (int)((ma.x % 3u) + 1u) << 1;
-            d |= (int)below(ma.y, (uint32_t)a.N) << 3;
+            x = ma.y;
         }
         sh.dec[j] = d;
+        sh.decx[j] = (int32_t)x;
     }
     const U4 pr = philox4x32_10(a.generation, (uint32_t)c, 0u, kTagParent, a.key0, a.key1);
     const int32_t *__restrict__ pa = a.parents + (size_t)a.order[below(pr.x, a.elite_k)] * JN;
-    const int32_t *__restrict__ pb = a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
+    // half of the children have a single parent (mutation only)
+    const int32_t *__restrict__ pb = (pr.z & 1u) ? pa : a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
     __syncthreads();
 
@@ -195,25 +228,34 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         const int d = __builtin_amdgcn_readfirstlane(sh.dec[j]);
         const int32_t *__restrict__ src = ((d & 1) ? pb : pa) + (size_t)j * a.N;
         int32_t *__restrict__ dst = child + (size_t)j * a.N;
-        const int move = ((d >> 1) & 3) - 1, target = move >= 0 ? (d >> 3) : -1;
+        const int move = ((d >> 1) & 3) - 1;
+        int target = -1, delta = 0;
         int32_t put = 0;
         if (move == 2) {
-            // re-pack: the whole row goes to one node, as far as that node's capacity allows
+            // re-pack: the whole row goes to one drawn node, as far as that node's capacity allows
+            target = (int)below((uint32_t)__builtin_amdgcn_readfirstlane(sh.decx[j]), (uint32_t)a.N);
             long long k = 0;
             for (int n = lane; n < a.N; n += kWave) k += src[n];
             k = wave_sum(k);
             if (k < 0) k = 0;
             const long long cap = a.node_capacity[target];
             put = (int32_t)(k < cap ? k : cap);
+        } else if (move >= 0) {
+            // grow / shrink by one GPU on one of the nodes the job occupies (a job without GPUs grows on a drawn node)
+            const uint32_t x = (uint32_t)__builtin_amdgcn_readfirstlane(sh.decx[j]);
+            const int occupied = count_occupied(src, a.N, lane);
+            if (occupied > 0) {
+                target = kth_occupied(src, a.N, lane, (int)below(x, (uint32_t)occupied));
+                delta = move == 0 ? 1 : -1;
+            } else if (move == 0) {
+                target = (int)below(x, (uint32_t)a.N);
+                delta = 1;
+            }
         }
         // the entry of node n after the move
         auto moved = [&](int n, int32_t v) -> int32_t {
             if (move == 2) return (n == target) ? put : 0;
-            if (n == target) {
-                if (move == 0) return v + 1;
-                if (v > 0) return v - 1;     // move == 1
-            }
-            return v;
+            return n == target ? v + delta : v;
         };
         int nodes = 0;
         if (vec4) {

@@ -136,6 +136,8 @@ def test_ga_step_without_mutation_takes_every_row_from_one_of_two_survivors():
     for cidx in range(elite, c.P):
         r = O.philox4x32_10([2, cidx, 0, 0], [SEED & 0xFFFFFFFF, SEED >> 32])
         a, b = order[(int(r[0]) * elite) >> 32], order[(int(r[1]) * elite) >> 32]
+        if int(r[2]) & 1:
+            b = a                                  # a child of one parent
         for j in range(c.J):
             bit = int(O.philox4x32_10([2, cidx, j, 1], [SEED & 0xFFFFFFFF, SEED >> 32])[0]) & 1
             src = wl.population[b if bit else a][j]
@@ -188,9 +190,8 @@ def test_ga_search_improves_the_best_fitness():
 
 def test_mutation_moves():
     # one job, several nodes, mutation certain: the child differs from the parent by exactly one move
-    cfg = W.custom("mut", P=8, J=1, N=5, cap=8, Gm=2, Gs=1)
     parents = np.zeros((8, 1, 5), np.int32)
-    parents[:, 0, :] = [2, 0, 1, 0, 0]
+    parents[:, 0, :] = [2, 0, 1, 0, 0]          # occupies nodes 0 and 2
     cap = np.full(5, 8, np.int32)
     fit = np.ones(8)
     seen = set()
@@ -198,16 +199,45 @@ def test_mutation_moves():
         kids = O.ga_step(parents, fit, cap, SEED, gen, 1, 0xFFFFFFFF)
         for cidx in range(1, 8):
             r = O.philox4x32_10([gen, cidx, 0, 3], [SEED & 0xFFFFFFFF, SEED >> 32])
-            move, n = int(r[0]) % 3, (int(r[1]) * 5) >> 32
+            move, x = int(r[0]) % 3, int(r[1])
             want = np.array([2, 0, 1, 0, 0])
-            if move == 0:
-                want[n] += 1
-            elif move == 1:
-                want[n] = max(0, want[n] - 1)
-            else:
+            if move == 2:
                 want[:] = 0
-                want[n] = 3
+                want[(x * 5) >> 32] = 3
+            else:
+                n = [0, 2][(x * 2) >> 32]       # the drawn one of the two occupied nodes
+                want[n] += 1 if move == 0 else -1
             # single job: interference repair cannot trigger, capacity 8 never exceeded
             assert np.array_equal(kids[cidx, 0], want)
             seen.add(move)
     assert seen == {0, 1, 2}
+    # a job without GPUs: grow starts it on a drawn node, shrink leaves it alone
+    parents[:] = 0
+    for gen in range(20):
+        kids = O.ga_step(parents, fit, cap, SEED, gen, 1, 0xFFFFFFFF)
+        for cidx in range(1, 8):
+            r = O.philox4x32_10([gen, cidx, 0, 3], [SEED & 0xFFFFFFFF, SEED >> 32])
+            move, x = int(r[0]) % 3, int(r[1])
+            want = np.zeros(5, np.int64)
+            if move == 0:
+                want[(x * 5) >> 32] = 1
+            assert np.array_equal(kids[cidx, 0], want)
+
+
+def test_search_finds_better_allocations_than_the_fair_share():
+    """With spare GPUs in the cluster (64 GPUs, 30 jobs at 2 each) and about one mutation per child, the search
+    must beat candidate 0, which keeps every job at its fair share and scores exactly 1."""
+    wl = W.make("physical", current="fair")
+    c = wl.cfg
+
+    def fitness_of(pop):
+        return O.fitness(pop, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc, wl.node_capacity,
+                         c.p, c.delta, c.Gs)["fitness"]
+
+    pop = wl.population
+    assert fitness_of(pop).max() == 1.0
+    for g in range(40):
+        pop = O.ga_step(pop, fitness_of(pop), wl.node_capacity, SEED, g, c.P // 2, (1 << 32) // c.J)
+    f = fitness_of(pop)
+    assert f.max() > 1.01
+    assert np.all(constraint_violations(pop[np.argsort(-f)[:10]], wl.node_capacity) == 0)
