@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define POLLUX_VERSION 100
+#define POLLUX_VERSION 101
 
 typedef struct {
     int32_t P;         /* candidates in the population                          */
@@ -48,12 +48,16 @@ enum {
     PX_FLAG_MEMOISE = 4,              /* sweep the (m, s) grid once per (job, K, one node or several) instead of
                                          once per (candidate, job): the goodput model (Eq. 4, 9) sees a row only
                                          through those; identical results, the population pass becomes a gather */
-    PX_FLAG_KEEP_JOB_TABLES = 8       /* reuse what the previous pollux_fitness call on this workspace derived from
+    PX_FLAG_KEEP_JOB_TABLES = 8,      /* reuse what the previous pollux_fitness call on this workspace derived from
                                          the jobs alone (tables, fair-share goodput, restart factors, memoised
                                          sweeps): the caller guarantees that dims, job_params, m_grid, fair_share,
                                          current_alloc, delta and the other flags are unchanged since that call,
                                          as in the generations of one scheduling interval.  The status word is
                                          then not cleared and keeps accumulating. */
+    PX_FLAG_SAMPLE_M = 16             /* the argmax of Eq. 13 by the sampling procedure of Sec. 4.3 instead of the
+                                         dense grid: m_grid[j,*] then holds candidate TOTAL batch sizes M, and for
+                                         each one s is the smallest count with which the per-GPU batch fits
+                                         PX_M_MEM; see pollux_fitness.  fp64 only. */
 };
 
 /* Rows of job_params[PX_NPARAM][J] (structure of arrays, fp64).
@@ -73,6 +77,8 @@ enum {
     PX_WEIGHT,        /* weight of the job in the generalized mean, >= 0        */
     PX_AGE_T,         /* age T_j of the job [s] (Sec. 4.2, re-allocation penalty) */
     PX_RESTARTS_R,    /* re-allocations R_j so far                               */
+    PX_M_MEM,         /* largest per-GPU batch size that fits GPU memory (Sec. 4.3), 1..2^31-1;
+                         read only with PX_FLAG_SAMPLE_M                         */
     PX_NPARAM
 };
 
@@ -118,6 +124,16 @@ int pollux_workspace_size(const pollux_dims *dims, size_t *bytes /* host, out */
  * V = sum_n max(0, d_n - 1) + sum_n max(0, sum_j A[c,j,n] - node_capacity[n]),
  * d_n = number of jobs with nodes >= 2 and A[c,j,n] > 0; when V > 0 the
  * fitness is replaced by -V unless PX_FLAG_NO_CONSTRAINT_CHECK is set.
+ *
+ * With PX_FLAG_SAMPLE_M the maximum of Eq. 13 is taken the way Sec. 4.3
+ * describes instead: for each candidate total batch size M = m_grid[j,i] > 0,
+ * s = ceil(M / (K * m_mem)) - 1 is the smallest accumulation count whose per-GPU
+ * batch m = ceil(M / (K * (s+1))) does not exceed m_mem = trunc(PX_M_MEM); the
+ * point is skipped when s > Gs-1 or when the batch actually run, K*m*(s+1)
+ * (M rounded up to a multiple of K*(s+1)), falls outside [M0, M_max]; the best
+ * of the remaining points is reported (best_m = m, best_s = s), ties to the
+ * lowest i.  The fair-share goodput is found the same way.  Everything else is
+ * unchanged.  Not available with precision 1 (PX_E_INVALID_ARG).
  *
  * fp64 (precision 0): best_goodput, speedup and fitness agree with a plain
  * fp64 evaluation of the formulas to a few units in the last place.

@@ -16,9 +16,9 @@ _SRC = os.path.join(_HERE, "pollux_ref.c")
 _HDR = os.path.join(_HERE, "pollux_ref.h")
 _LIB = os.path.join(_HERE, "libpollux_ref.so")
 
-NPARAM = 13
+NPARAM = 14
 ST_BAD_PARAM, ST_ZERO_FAIR, ST_BAD_RESTART, ST_NEG_ALLOC = 1, 2, 4, 8
-FLAG_NO_PENALTY, FLAG_NO_CHECK = 1, 2
+FLAG_NO_PENALTY, FLAG_NO_CHECK, FLAG_SAMPLE_M = 1, 2, 16
 
 
 def build(force: bool = False) -> str:
@@ -37,7 +37,7 @@ class Dims(ctypes.Structure):
 
 class Job(ctypes.Structure):
     _fields_ = [(n, ctypes.c_double) for n in
-                ("alpha_g", "beta_g", "alpha_sl", "beta_sl", "alpha_sn", "beta_sn", "gamma", "phi", "M0", "Mmax")]
+                ("alpha_g", "beta_g", "alpha_sl", "beta_sl", "alpha_sn", "beta_sn", "gamma", "phi", "M0", "Mmax", "m_mem")]
 
 
 class GaParams(ctypes.Structure):
@@ -67,6 +67,9 @@ def lib():
         L.pollux_ref_best_goodput.restype = d
         L.pollux_ref_best_goodput.argtypes = [ctypes.POINTER(Job), vp, i, i, i, i,
                                               ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
+        L.pollux_ref_best_goodput_sampled.restype = d
+        L.pollux_ref_best_goodput_sampled.argtypes = [ctypes.POINTER(Job), vp, i, i, i, i,
+                                                      ctypes.POINTER(ctypes.c_int), ctypes.POINTER(ctypes.c_int)]
         L.pollux_ref_argmax_gap.restype = d
         L.pollux_ref_argmax_gap.argtypes = [ctypes.POINTER(Job), vp, i, i, i, i]
         L.pollux_ref_realloc_factor.restype = d
@@ -98,12 +101,12 @@ def _c(a, dtype):
     return a
 
 
-def job(alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, Mmax) -> Job:
-    return Job(alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, Mmax)
+def job(alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, Mmax, m_mem=0.0) -> Job:
+    return Job(alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, Mmax, m_mem)
 
 
 def job_from_params(job_params: np.ndarray, j: int) -> Job:
-    return Job(*[float(job_params[k, j]) for k in range(10)])
+    return Job(*[float(job_params[k, j]) for k in range(10)], float(job_params[13, j]))
 
 
 def threads() -> int:
@@ -138,6 +141,15 @@ def best_goodput(jb: Job, m_grid, Gs, K, nodes):
     g = lib().pollux_ref_best_goodput(ctypes.byref(jb), _p(mg), mg.size, Gs, K, nodes,
                                       ctypes.byref(im), ctypes.byref(is_))
     return g, im.value, is_.value
+
+
+def best_goodput_sampled(jb: Job, M_list, s_max, K, nodes):
+    """Sec. 4.3 procedure: returns (goodput, m, s)."""
+    ml = _c(M_list, np.int32)
+    m, s = ctypes.c_int(0), ctypes.c_int(0)
+    g = lib().pollux_ref_best_goodput_sampled(ctypes.byref(jb), _p(ml), ml.size, s_max, K, nodes,
+                                              ctypes.byref(m), ctypes.byref(s))
+    return g, m.value, s.value
 
 
 def argmax_gap(jb: Job, m_grid, Gs, K, nodes):

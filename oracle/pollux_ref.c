@@ -99,6 +99,33 @@ double pollux_ref_best_goodput(const pollux_ref_job *job, const int32_t *m_grid,
     return best;
 }
 
+/* Sec. 4.3: sample total batch sizes, derive (m, s) from the memory bound, keep the best.
+ * The text's "m = ceil(M / s)" is read as m = ceil(M / (K (s+1))), consistent with
+ * M = SUM(a) * m * (s+1) of Sec. 3. */
+double pollux_ref_best_goodput_sampled(const pollux_ref_job *job, const int32_t *M_list, int count, int s_max,
+                                       int K, int nodes, int *m_out, int *s_out)
+{
+    double best = 0.0;
+    int bm = -1, bs = -1;
+    if (K > 0 && job->m_mem >= 1.0) {
+        for (int i = 0; i < count; ++i) {
+            long long M = M_list[i];
+            if (M <= 0) continue;
+            long long per_step = (long long)K * (long long)job->m_mem;          /* examples one pass can hold */
+            long long s = (M + per_step - 1) / per_step - 1;                     /* smallest s that fits */
+            if (s > s_max) continue;
+            long long m = (M + (long long)K * (s + 1) - 1) / ((long long)K * (s + 1));
+            if (m > 2147483647LL) continue;
+            int ok;
+            double g = pollux_ref_goodput(job, K, nodes, (int)m, (int)s, &ok);
+            if (ok && g > best) { best = g; bm = (int)m; bs = (int)s; }
+        }
+    }
+    if (m_out) *m_out = bm;
+    if (s_out) *s_out = bs;
+    return best;
+}
+
 double pollux_ref_argmax_gap(const pollux_ref_job *job, const int32_t *m_grid, int Gm, int Gs,
                              int K, int nodes)
 {
@@ -162,6 +189,7 @@ static void load_job(const double *jp, int J, int j, pollux_ref_job *job)
     job->phi = jp[(size_t)PXR_PHI * J + j];
     job->M0 = jp[(size_t)PXR_M0 * J + j];
     job->Mmax = jp[(size_t)PXR_MMAX * J + j];
+    job->m_mem = jp[(size_t)PXR_M_MEM * J + j];
 }
 
 static int job_is_bad(const pollux_ref_job *job, double weight)
@@ -184,7 +212,7 @@ int pollux_fitness_ref(const pollux_ref_dims *d, const int32_t *population, cons
     const int P = d->P, J = d->J, N = d->N, Gm = d->Gm, Gs = d->Gs;
     if (P <= 0 || J <= 0 || N <= 0 || Gm <= 0 || Gs <= 0 || !isfinite(p) || !isfinite(delta) || delta < 0.0)
         return -1;
-    const int use_penalty = !(d->flags & 1), use_check = !(d->flags & 2);
+    const int use_penalty = !(d->flags & 1), use_check = !(d->flags & 2), sampled = (d->flags & 16) != 0;
     int st = 0;
 
     /* per job: fair-share denominator of Eq. 15, restart factor, "has a current allocation" */
@@ -196,9 +224,12 @@ int pollux_fitness_ref(const pollux_ref_dims *d, const int32_t *population, cons
         pollux_ref_job job;
         load_job(job_params, J, j, &job);
         double w = job_params[(size_t)PXR_WEIGHT * J + j];
-        if (job_is_bad(&job, w)) st |= PXR_ST_BAD_PARAM;
-        denom[j] = pollux_ref_best_goodput(&job, m_grid + (size_t)j * Gm, Gm, Gs, fair_share[2 * j],
-                                           fair_share[2 * j + 1], NULL, NULL);
+        if (job_is_bad(&job, w) || (sampled && !(job.m_mem >= 1.0 && job.m_mem <= 2147483647.0))) st |= PXR_ST_BAD_PARAM;
+        denom[j] = sampled
+                       ? pollux_ref_best_goodput_sampled(&job, m_grid + (size_t)j * Gm, Gm, Gs - 1, fair_share[2 * j],
+                                                         fair_share[2 * j + 1], NULL, NULL)
+                       : pollux_ref_best_goodput(&job, m_grid + (size_t)j * Gm, Gm, Gs, fair_share[2 * j],
+                                                 fair_share[2 * j + 1], NULL, NULL);
         if (!(denom[j] > 0.0)) st |= PXR_ST_ZERO_FAIR;
         double T = job_params[(size_t)PXR_AGE_T * J + j], R = job_params[(size_t)PXR_RESTARTS_R * J + j];
         factor[j] = pollux_ref_realloc_factor(T, R, delta);
@@ -229,11 +260,16 @@ int pollux_fitness_ref(const pollux_ref_dims *d, const int32_t *population, cons
             nodes_of[j] = nodes;
             pollux_ref_job job;
             load_job(job_params, J, j, &job);
-            int im = -1, is = -1;
+            int im = -1, is = -1, m_star = -1;
             double g = 0.0;
-            if (K > 0) g = pollux_ref_best_goodput(&job, m_grid + (size_t)j * Gm, Gm, Gs, (int)K, nodes, &im, &is);
+            if (K > 0 && sampled) {
+                g = pollux_ref_best_goodput_sampled(&job, m_grid + (size_t)j * Gm, Gm, Gs - 1, (int)K, nodes, &m_star, &is);
+            } else if (K > 0) {
+                g = pollux_ref_best_goodput(&job, m_grid + (size_t)j * Gm, Gm, Gs, (int)K, nodes, &im, &is);
+                m_star = im >= 0 ? m_grid[(size_t)j * Gm + im] : -1;
+            }
             size_t o = (size_t)c * J + j;
-            best_m[o] = im >= 0 ? m_grid[(size_t)j * Gm + im] : -1;
+            best_m[o] = m_star;
             best_s[o] = is;
             if (best_goodput) best_goodput[o] = g;
             /* Eq. 15, then the re-allocation penalty for a job whose row differs

@@ -32,13 +32,14 @@ extern "C" {
 typedef struct {
     int32_t P, J, N, Gm, Gs;
     int32_t precision; /* ignored: the oracle is always fp64 */
-    int32_t flags;     /* bit0: no re-allocation penalty; bit1: no constraint check */
+    int32_t flags;     /* bit0: no re-allocation penalty; bit1: no constraint check;
+                          bit4 (16): Eq. 13 by sampling total batch sizes (Sec. 4.3) instead of the (m,s) grid */
 } pollux_ref_dims;
 
 /* rows of job_params[NPARAM][J] */
 enum {
     PXR_ALPHA_G, PXR_BETA_G, PXR_ALPHA_SL, PXR_BETA_SL, PXR_ALPHA_SN, PXR_BETA_SN,
-    PXR_GAMMA, PXR_PHI, PXR_M0, PXR_MMAX, PXR_WEIGHT, PXR_AGE_T, PXR_RESTARTS_R, PXR_NPARAM
+    PXR_GAMMA, PXR_PHI, PXR_M0, PXR_MMAX, PXR_WEIGHT, PXR_AGE_T, PXR_RESTARTS_R, PXR_M_MEM, PXR_NPARAM
 };
 
 /* data-dependent conditions, OR-ed into *status */
@@ -52,6 +53,7 @@ enum {
 
 typedef struct {
     double alpha_g, beta_g, alpha_sl, beta_sl, alpha_sn, beta_sn, gamma, phi, M0, Mmax;
+    double m_mem;      /* largest per-GPU batch size that fits GPU memory (sampling mode only) */
 } pollux_ref_job;
 
 /* --- pieces of the model, exposed so that each can be pinned on its own --- */
@@ -65,6 +67,12 @@ double pollux_ref_goodput(const pollux_ref_job *job, int K, int nodes, int m, in
  * Returns the best goodput (0 when nothing is feasible; then *im = *is = -1). */
 double pollux_ref_best_goodput(const pollux_ref_job *job, const int32_t *m_grid, int Gm, int Gs,
                                int K, int nodes, int *im, int *is);
+/* Eq. 13 the way Sec. 4.3 describes it: for each candidate total batch size M_i the
+ * smallest s whose per-GPU batch size m = ceil(M_i / (K (s+1))) fits GPU memory
+ * (m <= m_mem, s <= s_max), then the best GOODPUT among those configurations; ties ->
+ * lowest i.  *m and *s receive the chosen configuration (-1/-1 if none is feasible). */
+double pollux_ref_best_goodput_sampled(const pollux_ref_job *job, const int32_t *M_list, int count, int s_max,
+                                       int K, int nodes, int *m, int *s);
 /* Same sweep in long double: relative gap between the best value and the best
  * strictly smaller value (1.0 when there is no runner-up).  Used to tell a
  * genuine mismatch from a tie below fp64 resolution. */

@@ -12,9 +12,10 @@ import os
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpollux_hip.so")
 
-NPARAM = 13
+NPARAM = 14
 PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
 PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
+PX_FLAG_SAMPLE_M = 16
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",

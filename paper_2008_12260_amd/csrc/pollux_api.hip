@@ -36,6 +36,7 @@ bool dims_ok(const pollux_dims *d, bool need_grid)
     if (d->P <= 0 || d->J <= 0 || d->N <= 0) return false;
     if (need_grid && (d->Gm <= 0 || d->Gs <= 0)) return false;
     if (d->precision != 0 && d->precision != 1) return false;
+    if ((d->flags & PX_FLAG_SAMPLE_M) && d->precision != 0) return false;   // the sampling argmax exists in fp64 only
     if (d->N >= (1 << 30)) return false;   // node counts share a 32-bit word with a flag
     // flat indices of (candidate, job) pairs and of grid points are kept in 32 bits
     if ((long long)d->P * d->J > 0x7FFFFFFFll) return false;

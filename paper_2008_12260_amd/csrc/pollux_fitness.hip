@@ -20,6 +20,8 @@
 //                     per-candidate, per-node counters with integer atomics
 //   candidates_kernel per candidate (one workgroup): SPEEDUP, penalty, constraint
 //                     check from those counters and the generalized mean
+// With PX_FLAG_SAMPLE_M the sweep is replaced by sweep_sampled (Sec. 4.3), the kernels
+// instantiated with CH = 0, and last_kernel is not launched.
 //
 // How one wavefront sweeps the grid of a (candidate, job) pair.  Lane l owns
 // the batch sizes m_i, i = l, l+64, ...; it walks s = 0..Gs-1.  Dividing Eq. 4
@@ -432,6 +434,48 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
                      a.lt + (size_t)j * 2 * kTableK * a.Gm};
 }
 
+// ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
+// The grid row of the job holds candidate total batch sizes M_i.  Lane l takes
+// i = l, l+64, ...: s is the smallest accumulation count whose per-GPU batch
+// m = ceil(M / (K (s+1))) stays within the memory bound, found with integer
+// arithmetic; the point is then priced with Eq. 4 in the paper's order of operations
+// (T_grad, its logarithm and the last pass of Eq. 10 are formed here, m is not on a grid).
+// Gm evaluations per call instead of Gm * Gs.  Ties go to the lowest i.
+__device__ __forceinline__ Best sweep_sampled(const Job &q, const int32_t *__restrict__ M_list, int Gm, int Gs, int K,
+                                              int nodes)
+{
+    if (K <= 0) return Best{0.0, -1, -1};
+    const int lane = lane_id();
+    const double alpha_g = q.jp[(size_t)PX_ALPHA_G * q.J + q.j], beta_g = q.jp[(size_t)PX_BETA_G * q.J + q.j];
+    const double M0 = q.jp[(size_t)PX_M0 * q.J + q.j], Mmax = q.jp[(size_t)PX_MMAX * q.J + q.j];
+    const double m_mem_d = q.jp[(size_t)PX_M_MEM * q.J + q.j];
+    if (!(m_mem_d >= 1.0 && m_mem_d <= 2147483647.0)) return Best{0.0, -1, -1};
+    const long long per_pass = (long long)K * (long long)m_mem_d;     // examples one pass over K GPUs can hold
+    const SyncTerm st = sync_term(q, K, nodes == 1);
+    const double Kd = (double)K;
+
+    double gbest = 0.0;
+    int ibest = 0x7FFFFFFF, m_best = -1, s_best = -1;
+    for (int i0 = 0; i0 < Gm; i0 += kWave) {
+        const int i = i0 + lane;
+        if (i >= Gm) continue;
+        const long long M = M_list[i];
+        if (M <= 0) continue;
+        const long long s = (M + per_pass - 1) / per_pass - 1;
+        if (s > (long long)(Gs - 1)) continue;
+        const long long ks = (long long)K * (s + 1);
+        const long long m = (M + ks - 1) / ks;                         // 1 <= m <= m_mem
+        const double Km = Kd * (double)m;
+        const double Mrun = Km * (double)(s + 1);
+        if (Mrun < M0 || Mrun > Mmax) continue;
+        const double tg = alpha_g + beta_g * (double)m;                // Eq. 8
+        const double last = last_pass(st, tg, st.mode == 2 ? px_log(tg) : 0.0);
+        const double g = goodput_point(q, Km, tg, last, (int)s);
+        if (g > gbest) { gbest = g; ibest = i; m_best = (int)m; s_best = (int)s; }
+    }
+    return wave_argmax(gbest, ibest, m_best, s_best);
+}
+
 // ---- fp32 variant of the sweep --------------------------------------------------
 // The same model with every parameter rounded to fp32 and all arithmetic of Eq. 4-11 in
 // fp32, written the plain way (two divisions per grid point, powf for Eq. 10).  The
@@ -518,6 +562,10 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
         !(y.beta_sl >= 0.0) || !(y.alpha_sn >= 0.0) || !(y.beta_sn >= 0.0) || !(q.phi > 0.0) || !(M0 >= 1.0) ||
         !(Mmax >= M0) || !(w >= 0.0) || !(Mmax <= 4503599627370496.0) || !(alpha_g + beta_g > 0.0))
         st |= PX_ST_BAD_PARAM;
+    if constexpr (CH == 0) {
+        const double m_mem = jp[(size_t)PX_M_MEM * a.J + j];
+        if (!(m_mem >= 1.0 && m_mem <= 2147483647.0)) st |= PX_ST_BAD_PARAM;
+    }
     // re-allocation penalty factor of Sec. 4.2
     double factor = (T - R * a.delta) / (T + a.delta);
     if constexpr (F32) factor = (double)(((float)T - (float)R * (float)a.delta) / ((float)T + (float)a.delta));
@@ -534,7 +582,9 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     if (__ballot(neg) != 0) st |= PX_ST_NEG_ALLOC;
     // denominator of Eq. 15: the same sweep at the fair-share allocation
     Best fair;
-    if constexpr (F32)
+    if constexpr (CH == 0)
+        fair = sweep_sampled(q, a.m_grid + (size_t)j * a.Gm, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
+    else if constexpr (F32)
         fair = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, a.fair_share[2 * j],
                          a.fair_share[2 * j + 1]);
     else
@@ -564,7 +614,8 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
     const int nodes = ((row / kTableK) & 1) ? 1 : 2;
     const int j = (int)(row / (2 * kTableK));
     Best best;
-    if constexpr (F32) best = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, K, nodes);
+    if constexpr (CH == 0) best = sweep_sampled(load_job(a.job_params, a.J, j), a.m_grid + (size_t)j * a.Gm, a.Gm, a.Gs, K, nodes);
+    else if constexpr (F32) best = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, K, nodes);
     else best = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
     if (lane_id() == 0) {
         MemoEntry e;
@@ -658,6 +709,8 @@ __global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
         if (MEMO && K >= 1 && K <= kTableK) {
             const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
             best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+        } else if constexpr (CH == 0) {
+            best = sweep_sampled(q, tb.m, a.Gm, a.Gs, K, nodes);
         } else if constexpr (F32) {
             best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
         } else {
@@ -805,6 +858,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const long long lt_rows = (long long)d->J * 2 * kTableK;
     const bool f32 = d->precision == 1;
     const bool memo = (d->flags & PX_FLAG_MEMOISE) != 0;
+    const bool sampled = (d->flags & PX_FLAG_SAMPLE_M) != 0;       // fp64 only (checked by the caller)
     if (a.need_constraints) {
         long long zb = ((long long)d->P * d->N + 255) / 256;
         hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
@@ -815,16 +869,18 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
         if (table_items < kRecipTable) table_items = kRecipTable;
         hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
-        if (!f32)
+        if (!f32 && !sampled)
             hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
         const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
-        if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
+        if (sampled) hipLaunchKernelGGL((jobs_kernel<0, false>), job_grid, dim3(256), 0, stream, a);
+        else if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
         else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
         else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
         if (memo) {
             const dim3 memo_grid((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock));
-            if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
+            if (sampled) hipLaunchKernelGGL((memo_kernel<0, false>), memo_grid, dim3(256), 0, stream, a);
+            else if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
             else if (ch == 8) hipLaunchKernelGGL((memo_kernel<8, false>), memo_grid, dim3(256), 0, stream, a);
             else if (ch == 16) hipLaunchKernelGGL((memo_kernel<16, false>), memo_grid, dim3(256), 0, stream, a);
             else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
@@ -832,12 +888,14 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     if (memo) {
-        if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        if (sampled) hipLaunchKernelGGL((pairs_kernel<0, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((pairs_kernel<32, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
     } else {
-        if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        if (sampled) hipLaunchKernelGGL((pairs_kernel<0, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        else if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((pairs_kernel<32, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);

@@ -250,3 +250,58 @@ def test_keep_job_tables_reuses_the_job_level_work():
         full = call.results()
         for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations", "status"):
             assert np.array_equal(kept[k], full[k], equal_nan=True), k
+
+
+# ---- the sampling argmax of Sec. 4.3 (PX_FLAG_SAMPLE_M) -------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_sampling_argmax_matches_oracle(name):
+    wl = W.sampled(W.make(name))
+    pop = wl.population[:300]
+    ref = run_oracle(wl, population=pop, flags=16)
+    assert (ref["best_m"] > 0).mean() > 0.5                      # the workload exercises the procedure
+    assert compare(wl, run_gpu(wl, population=pop, flags=16), ref, population=pop, sampled=True) == 0
+
+
+@pytest.mark.parametrize("shape", [
+    dict(P=3, J=1, N=1, cap=8, Gm=1, Gs=1),
+    dict(P=9, J=13, N=67, cap=2, Gm=70, Gs=5),
+    dict(P=4, J=6, N=130, cap=3, Gm=129, Gs=33),
+    dict(P=6, J=40, N=9, cap=40, Gm=33, Gs=5),                   # K beyond the memo table
+])
+def test_sampling_argmax_on_ragged_shapes_plain_and_memoised(shape):
+    wl = W.sampled(W.make(W.custom("ragged_sampled", **shape)))
+    ref = run_oracle(wl, flags=16)
+    plain = run_gpu(wl, flags=16)
+    assert compare(wl, plain, ref, sampled=True) == 0
+    memo = run_gpu(wl, flags=16 | 4)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations", "status"):
+        assert np.array_equal(memo[k], plain[k], equal_nan=True), k
+
+
+def test_sampling_argmax_flags_a_bad_memory_bound_and_rejects_fp32():
+    import paper_2008_12260_amd as px
+    wl = W.sampled(W.make("tiny"))
+    jp = wl.job_params.copy()
+    jp[W.PARAM_INDEX["m_mem"], 2] = 0.0
+    g, ref = run_gpu(wl, flags=16, job_params=jp), run_oracle(wl, flags=16, job_params=jp)
+    assert g["status"] == ref["status"] and g["status"] & 1
+    with pytest.raises(px.PolluxError):
+        run_gpu(wl, flags=16, precision=1)
+
+
+def test_non_adaptive_jobs_with_a_fixed_batch_size():
+    """M_max = M0 for every job (Sec. 4.1, jobs that do not adapt their batch size): only exact splits of M0 are
+    feasible and EFFICIENCY is 1; the grid lists the divisors."""
+    cfg = W.custom("fixed_batch", P=64, J=24, N=8, cap=4, Gm=16, Gs=8)
+    wl = W.make(cfg)
+    jp = wl.job_params.copy()
+    jp[W.PARAM_INDEX["M_max"]] = jp[W.PARAM_INDEX["M0"]]
+    wl.m_grid[:] = np.array([1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256], np.int32)
+    ref = run_oracle(wl, job_params=jp)
+    g = run_gpu(wl, job_params=jp)
+    assert compare(wl, g, ref, job_params=jp) == 0
+    have = g["best_m"] > 0
+    assert have.mean() > 0.3
+    K = wl.population.sum(2)
+    assert np.all((K * g["best_m"] * (g["best_s"] + 1))[have] == np.broadcast_to(jp[W.PARAM_INDEX["M0"]], K.shape)[have])

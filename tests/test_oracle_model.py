@@ -246,3 +246,90 @@ def test_argmax_gap_reports_distance_to_the_runner_up():
     gap = O.argmax_gap(jb, grid, 2, 2, 1)
     vals = sorted({brute_goodput(dict(HAND, gamma=2.0), 2, 1, int(m), s) for m in grid for s in range(2)} - {None})
     assert gap == pytest.approx((vals[-1] - vals[-2]) / vals[-1], rel=1e-9)
+
+
+# ------------------------------------------------------------ Sec. 4.3 sampling argmax
+def _sampled_brute(jb, m_mem, M_list, s_max, K, nodes):
+    """The procedure with nothing closed-form: try s = 0, 1, ... until the per-GPU share fits."""
+    best, bm, bs = 0.0, -1, -1
+    for M in M_list:
+        M = int(M)
+        if M <= 0:
+            continue
+        s = 0
+        while -(-M // (K * (s + 1))) > m_mem:
+            s += 1
+        if s > s_max:
+            continue
+        m = -(-M // (K * (s + 1)))
+        g, ok = O.goodput(jb, K, nodes, m, s)
+        if ok and g > best:
+            best, bm, bs = g, m, s
+    return best, bm, bs
+
+
+def test_sampling_argmax_against_brute_force():
+    rng = np.random.default_rng(43)
+    for _ in range(300):
+        m_mem = int(rng.integers(1, 200))
+        M0 = float(rng.integers(1, 500))
+        jb = O.job(rng.uniform(0.01, 0.5), rng.uniform(1e-4, 1e-2), rng.uniform(0, 0.1), rng.uniform(0, 0.02),
+                   rng.uniform(0, 0.3), rng.uniform(0, 0.05), rng.uniform(1, 10), rng.uniform(10, 1e5), M0,
+                   M0 * rng.uniform(1, 64), float(m_mem))
+        K = int(rng.integers(1, 40))
+        nodes = 1 if K == 1 else int(rng.integers(1, 5))
+        Ms = rng.integers(-2, 20000, int(rng.integers(1, 40))).astype(np.int32)
+        s_max = int(rng.integers(0, 20))
+        assert O.best_goodput_sampled(jb, Ms, s_max, K, nodes) == _sampled_brute(jb, m_mem, Ms, s_max, K, nodes)
+
+
+def test_sampling_argmax_points_fit_memory_with_the_fewest_passes():
+    rng = np.random.default_rng(44)
+    jb = O.job(0.1, 0.001, 0.05, 0.01, 0.2, 0.02, 2.0, 1000.0, 1.0, 1e9, 37.0)
+    for _ in range(500):
+        K = int(rng.integers(1, 64))
+        M = int(rng.integers(1, 100000))
+        g, m, s = O.best_goodput_sampled(jb, np.array([M], np.int32), 10**6, K, 2)
+        assert g > 0 and 1 <= m <= 37
+        assert K * m * (s + 1) >= M > K * (m - 1) * (s + 1)          # m is the ceiling
+        assert s == 0 or K * 37 * s < M                               # one pass fewer would not hold M
+
+
+def test_sampling_argmax_without_a_memory_bound_is_the_dense_argmax_on_one_column():
+    """With room for any batch, s = 0 and m = ceil(M/K): the dense routine on that grid with Gs = 1 agrees."""
+    rng = np.random.default_rng(45)
+    for _ in range(100):
+        jb = O.job(0.05, 0.002, 0.03, 0.004, 0.1, 0.01, float(rng.uniform(1, 4)), 5000.0, 64.0, 8192.0, 2.0**31 - 1)
+        K = int(rng.integers(1, 33))
+        Ms = np.sort(rng.choice(np.arange(64, 8193), 24, replace=False)).astype(np.int32)
+        grid = (-(-Ms.astype(np.int64) // K)).astype(np.int32)
+        g0, im, is_ = O.best_goodput(jb, grid, 1, K, 2)
+        g1, m, s = O.best_goodput_sampled(jb, Ms, 7, K, 2)
+        assert g1 == g0 and s == is_ == 0 and m == grid[im]
+
+
+# ------------------------------------------------------------ non-adaptive jobs (Sec. 4.1: fixed batch size)
+def test_a_job_with_a_fixed_batch_size_has_efficiency_one_and_the_fastest_split_wins():
+    """M_max = M0 leaves only points with K m (s+1) = M0: Eq. 6 is exactly 1 there, so goodput is throughput
+    and the argmax is the split of M0 over GPUs and accumulation passes with the shortest iteration."""
+    rng = np.random.default_rng(46)
+    grid = np.array([1, 2, 3, 4, 6, 8, 12, 16, 24, 32, 48, 64, 96, 128, 192, 256], np.int32)
+    for _ in range(200):
+        M0 = float(rng.choice([32, 64, 96, 128, 256]))
+        jb = O.job(rng.uniform(0.01, 0.2), rng.uniform(1e-5, 1e-3), 0.02, 0.004, 0.1, 0.01, rng.uniform(1, 5),
+                   rng.uniform(1e2, 1e5), M0, M0)
+        K = int(rng.choice([1, 2, 3, 4, 6, 8, 16]))
+        nodes = 1 if K < 4 else 2
+        g, im, is_ = O.best_goodput(jb, grid, 8, K, nodes)
+        want = 0.0
+        for m in grid:
+            for s in range(8):
+                if K * int(m) * (s + 1) == int(M0):
+                    t = O.titer(O.tgrad(jb.alpha_g, jb.beta_g, float(m)), O.tsync(jb, K, nodes), jb.gamma, s)
+                    want = max(want, M0 / t)
+        if want == 0.0:
+            assert g == 0.0 and im == -1
+        else:
+            assert abs(g - want) <= 1e-15 * want
+            assert K * int(grid[im]) * (is_ + 1) == int(M0)
+            assert O.efficiency(jb.phi, M0, float(K * int(grid[im]) * (is_ + 1))) == 1.0

@@ -38,6 +38,12 @@ MUTANTS = [
     ("philox words crossed", "uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;", "uint32_t n0 = (uint32_t)(p0 >> 32) ^ c1 ^ k0;"),
     ("rank ascending", "if (x->f > y->f) return -1;\n    if (x->f < y->f) return 1;", "if (x->f > y->f) return 1;\n    if (x->f < y->f) return -1;"),
     ("capacity repair leaves one too many", "long excess = total - cap[n];", "long excess = total - cap[n] - 1;"),
+    ("sampling: s one too many", "long long s = (M + per_step - 1) / per_step - 1;", "long long s = (M + per_step - 1) / per_step;"),
+    ("sampling: memory bound ignores K", "long long per_step = (long long)K * (long long)job->m_mem;", "long long per_step = (long long)job->m_mem;"),
+    ("sampling: m ignores accumulation", "long long m = (M + (long long)K * (s + 1) - 1) / ((long long)K * (s + 1));", "long long m = (M + (long long)K - 1) / (long long)K;"),
+    ("sampling: m rounded down", "long long m = (M + (long long)K * (s + 1) - 1) / ((long long)K * (s + 1));", "long long m = M / ((long long)K * (s + 1));"),
+    ("sampling: s beyond the limit accepted", "if (s > s_max) continue;", "if (s > s_max + 100) continue;"),
+    ("sampling: fair share from the dense grid", "denom[j] = sampled\n", "denom[j] = !sampled\n"),
     ("interference repair keeps the smallest holder", "if (a > most) { most = a; keep = j; }", "if (keep < 0 || a < most) { most = a; keep = j; }"),
 ]
 
@@ -58,6 +64,9 @@ def load(path):
     L.pollux_ref_best_goodput.restype = d
     L.pollux_ref_best_goodput.argtypes = [ctypes.POINTER(O.Job), vp, i, i, i, i, ctypes.POINTER(ctypes.c_int),
                                           ctypes.POINTER(ctypes.c_int)]
+    L.pollux_ref_best_goodput_sampled.restype = d
+    L.pollux_ref_best_goodput_sampled.argtypes = [ctypes.POINTER(O.Job), vp, i, i, i, i, ctypes.POINTER(ctypes.c_int),
+                                                  ctypes.POINTER(ctypes.c_int)]
     L.pollux_ref_realloc_factor.restype = d
     L.pollux_ref_realloc_factor.argtypes = [d, d, d]
     L.pollux_ref_pmean.restype = d
@@ -112,6 +121,27 @@ def pin_suite(L):
     im, is_ = ctypes.c_int(0), ctypes.c_int(0)
     L.pollux_ref_best_goodput(ctypes.byref(jb2), ptr(grid), 3, 4, 1, 1, ctypes.byref(im), ctypes.byref(is_))
     check("ties to the lowest index", (im.value, is_.value) == (0, 0))
+    # Sec. 4.3 sampling, points worked out by hand for K = 2 GPUs and a memory bound of 64 per GPU:
+    #   M = 128 -> one pass holds it: s = 0, m = 64;  M = 129 -> s = 1, m = ceil(129/4) = 33;
+    #   M = 300 -> 128 per pass: s = 2, m = ceil(300/6) = 50;  M = 1000 -> s = 7, m = 63
+    jm = O.job(0.1, 0.001, 0.05, 0.01, 0.2, 0.02, 2.0, 1000.0, 100.0, 3200.0, 64.0)
+
+    def sampled(Ms, s_max, K=2, nodes=1):
+        arr = np.array(Ms, dtype=np.int32)
+        L.pollux_ref_best_goodput_sampled(ctypes.byref(jm), ptr(arr), len(Ms), s_max, K, nodes, ctypes.byref(im), ctypes.byref(is_))
+        return im.value, is_.value
+
+    check("sampling M=128", sampled([128], 15) == (64, 0))
+    check("sampling M=129", sampled([129], 15) == (33, 1))
+    check("sampling M=300", sampled([300], 15) == (50, 2))
+    check("sampling M=1000", sampled([1000], 15) == (63, 7))
+    check("sampling s limit", sampled([1000], 3) == (-1, -1))
+    check("sampling one GPU", sampled([300], 15, K=1) == (60, 4))
+    arr = np.array([128, 129, 300, 1000], dtype=np.int32)
+    gs = L.pollux_ref_best_goodput_sampled(ctypes.byref(jm), ptr(arr), 4, 15, 2, 1, ctypes.byref(im), ctypes.byref(is_))
+    pts = [(64, 0), (33, 1), (50, 2), (63, 7)]
+    vals = [gp(jm, 2, 1, m, s) for m, s in pts]
+    check("sampling takes the best point", gs == max(vals) and (im.value, is_.value) == pts[int(np.argmax(vals))])
     # restart factor, p-mean
     check("restart factor", close(L.pollux_ref_realloc_factor(3600.0, 2.0, 30.0), 3540.0 / 3630.0))
     S = np.array([1.0, 2.0, 0.5, 4.0])
@@ -143,7 +173,7 @@ def pin_suite(L):
     check("interference repair", B.tolist() == [[1, 0, 0], [0, 3, 1], [0, 2, 0]])
     # whole call: the fair-share candidate scores exactly 1; a changed row is penalised; violations
     J, N, Gm, Gs = 3, 3, 8, 3
-    jp = np.zeros((13, J))
+    jp = np.zeros((14, J))
     jp[0], jp[1], jp[2], jp[3], jp[4], jp[5] = 0.1, 0.001, 0.05, 0.01, 0.2, 0.02
     jp[6], jp[7], jp[8], jp[9], jp[10], jp[11], jp[12] = 2.0, 1000.0, 32.0, 1024.0, [1.0, 2.0, 1.0], 3600.0, 2.0
     mg = np.tile(np.array([8, 16, 32, 64, 96, 128, 192, 256], np.int32), (J, 1))
@@ -166,6 +196,18 @@ def pin_suite(L):
     check("violations", list(viol) == [0, 0, 2] and fit[2] == -2.0)
     S1 = sp[1]
     check("weighted harmonic mean in the call", close(fit[1], 4.0 / (1.0 / S1[0] + 2.0 / S1[1] + 1.0 / S1[2]), 1e-12))
+    # the same call with the sampling argmax: the grid row now lists total batch sizes; memory bound 40 per GPU
+    jp[13] = 40.0
+    Ml = np.tile(np.array([32, 64, 100, 160, 256, 400, 640, 1024], np.int32), (J, 1))
+    d16 = O.Dims(3, J, N, Gm, Gs, 0, 16)
+    L.pollux_fitness_ref(ctypes.byref(d16), ptr(pop), ptr(jp), ptr(Ml), ptr(fs), ptr(cur), ptr(capn), -1.0, 30.0,
+                         ptr(fit), ptr(bm), ptr(bs), ptr(bg), ptr(sp), ptr(viol), ptr(st))
+    # two GPUs, at most 3 passes of 80: M = 160 -> (40, 1); 256 -> s = 3 is beyond Gs-1 = 2; 100 -> (25, 1); 64 -> (32, 0)
+    jq = O.job(0.1, 0.001, 0.05, 0.01, 0.2, 0.02, 2.0, 1000.0, 32.0, 1024.0, 40.0)
+    cand = [(16, 0), (32, 0), (25, 1), (40, 1)]
+    vals = [gp(jq, 2, 1, m, s) for m, s in cand]
+    check("sampled call: fair share scores 1", fit[0] == 1.0 and np.all(sp[0] == 1.0))
+    check("sampled call: chosen point", (int(bm[0, 0]), int(bs[0, 0])) == cand[int(np.argmax(vals))] and bg[0, 0] == max(vals))
     return failed
 
 

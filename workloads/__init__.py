@@ -27,7 +27,7 @@ _SRC_PATH = os.path.join(_HERE, "popgen.c")
 PARAM_NAMES = (
     "alpha_grad", "beta_grad", "alpha_sync_local", "beta_sync_local",
     "alpha_sync_node", "beta_sync_node", "gamma", "phi",
-    "M0", "M_max", "weight", "age_T", "restarts_R",
+    "M0", "M_max", "weight", "age_T", "restarts_R", "m_mem",
 )
 NPARAM = len(PARAM_NAMES)
 PARAM_INDEX = {n: i for i, n in enumerate(PARAM_NAMES)}
@@ -113,6 +113,16 @@ def m_grid(m_max: np.ndarray, Gm: int, m_min: int = 8) -> np.ndarray:
     return g.astype(np.int32)
 
 
+def total_batch_grid(M0: np.ndarray, M_max: np.ndarray, Gm: int) -> np.ndarray:
+    """[J,Gm] int32 log-spaced candidate total batch sizes in [M0_j, M_max_j] (for the sampling form of Eq. 13)."""
+    M0, M_max = np.asarray(M0, np.float64), np.asarray(M_max, np.float64)
+    if Gm == 1:
+        return M0.astype(np.int32).reshape(-1, 1)
+    t = np.arange(Gm, dtype=np.float64) / (Gm - 1)
+    g = np.floor(M0[:, None] * (M_max[:, None] / M0[:, None]) ** t[None, :] + 0.5)
+    return np.clip(g, M0[:, None], M_max[:, None]).astype(np.int32)
+
+
 @dataclass
 class Workload:
     cfg: Config
@@ -156,6 +166,7 @@ def draw_job_params(cfg: Config, rng: np.random.Generator) -> tuple[np.ndarray, 
     age = logU(120.0, 8 * 3600.0)
     jp[PARAM_INDEX["age_T"]] = age
     jp[PARAM_INDEX["restarts_R"]] = np.floor(rng.uniform(0.0, 1.0, J) * age / 210.0)
+    jp[PARAM_INDEX["m_mem"]] = m_max.astype(np.float64)      # per-GPU batch size that still fits GPU memory
     return jp, m_max
 
 
@@ -191,6 +202,12 @@ def make(cfg: Config | str, with_population: bool = True, current: str = "random
     if with_population:
         wl.population = candidates(cfg, 0, cfg.P)
     return wl
+
+
+def sampled(wl: Workload) -> Workload:
+    """The same workload for the sampling form of Eq. 13 (Sec. 4.3): the grid rows list total batch sizes."""
+    import dataclasses
+    return dataclasses.replace(wl, m_grid=total_batch_grid(wl.param("M0"), wl.param("M_max"), wl.cfg.Gm))
 
 
 def custom(name: str, **kw) -> Config:
