@@ -24,7 +24,7 @@ def build(verbose: bool = False, save_temps: str | None = None) -> str:
     cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, s) for s in SOURCES] + ["-o", LIB]
     if save_temps:
         os.makedirs(save_temps, exist_ok=True)
-        cmd += ["-save-temps=obj"]
+        cmd += ["-save-temps=cwd"]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True, cwd=save_temps or HERE)

@@ -12,7 +12,8 @@
 //                     per row): T_sync (Eq. 9) and, for every batch size of the grid,
 //                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
 //                     term depends on the allocation only through K and on whether
-//                     the job sits on one node, so it is shared by the population
+//                     the job sits on one node, so it is shared by the population;
+//                     also the feasibility lane masks per (job, K, s)
 //   jobs_kernel       per job (one wavefront): parameter checks, restart factor,
 //                     fair-share goodput (denominator of Eq. 15)
 //   pairs_kernel      per (candidate, job) (one wavefront): row reduce, sweep of the
@@ -30,11 +31,12 @@
 // and with u = phi/(K m), last = (T_grad^g + T_sync^g)^(1/g):
 //     h(m, s) = (last + u T_grad) + s T_grad + (last - T_grad) u / (s + 1),
 // two fused multiply-adds per grid point with every term non-negative.  The
-// argmax of GOODPUT is the argmin of h over the feasible points.  The lane
-// keeps the minimum with one v_min_f64 per point: the low five mantissa bits of
-// h are replaced by s (so the minimum carries its own index and equal values
-// resolve to the smaller s), and infeasible points are turned into quiet NaNs,
-// which the minimum ignores.  The perturbation is 2^-47 relative; the point each lane
+// argmax of GOODPUT is the argmin of h over the feasible points.  Which lanes
+// hold a feasible batch size at a given s depends on (job, K) only, so those
+// 64-bit lane masks are tabled; the lane keeps its minimum with one v_min_f64
+// per point, executed with only the feasible lanes enabled, and the low five
+// mantissa bits of h are replaced by s (so the minimum carries its own index and
+// equal values resolve to the smaller s).  The perturbation is 2^-47 relative; the point each lane
 // elects is then evaluated again with the formulas in the paper's own order
 // (separate multiply and add, IEEE division), and the wave-wide argmax is taken
 // over those values with ties going to the lowest flat index, so the reported
@@ -76,7 +78,9 @@ struct FitnessArgs {
     double p, delta;
     // workspace
     int32_t *status;
-    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    double *rs, *sv, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    unsigned long long *fmask;    // [J,kTableK,ni,gs_pad] feasibility lane masks (see last_kernel)
+    int ni, gs_pad;               // ceil(Gm / 64); Gs rounded up to a multiple of 32
     int32_t *running, *meta;
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
@@ -130,13 +134,16 @@ __device__ __forceinline__ SyncParams load_sync(const Job &q)
 // M0 <= K m (s+1) <= M_max holds exactly when ceil(M0/m) <= K (s+1) <= floor(M_max/m),
 // i.e. for s between trunc(ql5 / K) and trunc(qh5 / K) - 1; the halves keep the
 // quotients at least 1/(2K) away from an integer, so a rounded 1/K cannot move them
-// across one.  Also rs[s] = 1/(s+1), rk[K] = 1/K, and the status word is cleared.
+// across one.  Also rs[s] = 1/(s+1), sv[s] = s, rk[K] = 1/K, and the status word is cleared.
 __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) *a.status = 0;
     const int rs_len = ((a.Gs + 31) / 32) * 32;
-    if (t < rs_len) a.rs[t] = 1.0 / (double)(t + 1);
+    if (t < rs_len) {
+        a.rs[t] = 1.0 / (double)(t + 1);
+        a.sv[t] = (double)t;
+    }
     if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
     if (t < a.J * a.Gm) {
         const int j = t / a.Gm;
@@ -206,8 +213,19 @@ __device__ __forceinline__ double last_pass(const SyncTerm &t, double tg, double
     return fmax(tg, t.ts) * px_exp(px_log1p_unit(e) * t.inv_gamma);
 }
 
+// The feasible accumulation counts of grid point i with K GPUs: s_lo <= s <= s_hi
+// (empty when s_lo > s_hi), from the half-offset quotients of tables_kernel.
+__device__ __forceinline__ void feasible_range(double ql5, double qh5, double rK, int Gs, int &s_lo, int &s_hi)
+{
+    s_lo = (int)(ql5 * rK);
+    s_hi = (int)(qh5 * rK) - 1;
+    s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
+}
+
 // One wavefront per row (job, placement class, K): lt[row][i] for every grid point i.
-// Row index ((j * 2 + one_node) * kTableK + (K - 1)).
+// Row index ((j * 2 + one_node) * kTableK + (K - 1)).  The rows of the "several nodes"
+// class also write the feasibility masks of (job, K), which do not depend on the class:
+// fmask[j][K-1][g][s] has bit l set when grid point 64 g + l is feasible at s.
 __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -219,7 +237,20 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
     const Job q = load_job(a.job_params, a.J, j);
     const SyncTerm t = sync_term(q, K, one_node);
     const size_t o = (size_t)j * a.Gm;
-    for (int i = lane_id(); i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i], a.lntg[o + i]);
+    const int lane = lane_id();
+    for (int i = lane; i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i], a.lntg[o + i]);
+    if (one_node) return;
+    const double rK = a.rk[K];
+    unsigned long long *__restrict__ out = a.fmask + ((size_t)j * kTableK + (size_t)(K - 1)) * a.ni * a.gs_pad;
+    for (int g = 0; g < a.ni; ++g) {
+        const int i = g * kWave + lane;
+        int s_lo = 1, s_hi = 0;
+        if (i < a.Gm) feasible_range(a.ql5[o + i], a.qh5[o + i], rK, a.Gs, s_lo, s_hi);
+        for (int s = 0; s < a.gs_pad; ++s) {
+            const unsigned long long m = __ballot(s_lo <= s && s <= s_hi);
+            if (lane == (s & 63)) out[(size_t)g * a.gs_pad + s] = m;
+        }
+    }
 }
 
 // ---- the sweep of one (job, K, nodes) ----------------------------------------
@@ -233,6 +264,9 @@ struct JobTables {
     const int32_t *__restrict__ m;
     const double *__restrict__ tg, *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
     const double *__restrict__ lt;    // rows of this job in the last-pass table
+    const unsigned long long *__restrict__ fmask;   // feasibility masks of this job, [kTableK, ni, gs_pad]
+    const double *__restrict__ sv;    // sv[s] = s
+    int ni, gs_pad;
 };
 
 __device__ __forceinline__ double vmin(double a, double b)
@@ -254,6 +288,12 @@ __device__ __forceinline__ double uniform(double v)
 {
     return __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v)),
                             __builtin_amdgcn_readfirstlane(__double2loint(v)));
+}
+
+__device__ __forceinline__ unsigned long long uniform(unsigned long long v)
+{
+    return ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
+           (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(v & 0xFFFFFFFFull));
 }
 
 template <int STEP = 0>
@@ -296,61 +336,92 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
     return throughput * efficiency;                              // Eq. 4
 }
 
-// One grid point of the sweep, position B (a compile-time constant) inside a chunk.
-// Six VALU instructions, written out so that the constants sit where the encoding
-// allows them (one SGPR or literal-free inline constant per VOP3 instruction):
-//   x   = B * tg + A0              v_fma_f64, B as an SGPR pair
-//   h   = B0 * r + x               v_fma_f64, r = 1/(s+1) as an SGPR pair
-//   t   = sign-extended bit B of `bad`                       v_bfe_i32
-//   hi  = (t & quiet-NaN pattern) | hi(h)                    v_and_or_b32
-//   lo  = (31 & B) | (~31 & lo(h))                           v_bfi_b32
-//   kmin = min(kmin, key)                                    v_min_f64
+// ---- the sweep of one batch size per lane over CH accumulation counts ---------------
+// For point s the lanes whose batch size is feasible are known as a 64-bit lane mask in
+// scalar registers, tabled per (job, K) by last_kernel.  Per point and lane:
+//   x    = A0 + s tg         from a base per four points (advanced by 4 tg) plus 0, tg, 2 tg
+//                            or 3 tg: v_add_f64 / v_fma_f64 with inline constants, a few
+//                            roundings deep, far below the index perturbation
+//   h    = B0 * r + x        v_fma_f64, r = 1/(s+1) from scalar registers
+//   lo   = (31 & b) | (~31 & lo(h))                       v_bfi_b32
+//   kmin = min(kmin, key)    v_min_f64 with only the feasible lanes enabled
+// so the key carries its position b inside the chunk in the low five mantissa bits (equal
+// values resolve to the smaller s), and a lane never sees an infeasible point.  Four VALU
+// instructions per point; masks and reciprocals arrive through the scalar cache.
+typedef const double __attribute__((address_space(4))) *ScalarDoubles;
+typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
+
 template <int B>
-__device__ __forceinline__ double sweep_point(double kmin, double tg, double A0, double B0, int bad, double r)
+__device__ __forceinline__ double masked_min(double kmin, double x, double B0, double r, unsigned long long lanes)
 {
-    double x, h;
-    const double bd = (double)B;
-    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(x) : "s"(bd), "v"(tg), "v"(A0));
+    double h;
     asm("v_fma_f64 %0, %1, %2, %3" : "=v"(h) : "v"(B0), "s"(r), "v"(x));
-    int t, hh, hl;
-    asm("v_bfe_i32 %0, %1, %2, 1" : "=v"(t) : "v"(bad), "n"(B));
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(hh) : "v"(t), "s"(0x7FF80000), "v"(__double2hiint(h)));
+    int hl;
     asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(hl) : "n"(B), "v"(__double2loint(h)));
-    return vmin(kmin, __hiloint2double(hh, hl));
+    const double key = __hiloint2double(__double2hiint(h), hl);
+    unsigned long long saved;
+    asm volatile("s_and_saveexec_b64 %1, %3\n\t"
+                 "v_min_f64 %0, %0, %2\n\t"
+                 "s_mov_b64 exec, %1"
+                 : "+v"(kmin), "=&s"(saved)
+                 : "v"(key), "s"(lanes)
+                 : "scc");
+    return kmin;
 }
 
-template <int CH, int B = 0>
-__device__ __forceinline__ double sweep_points(double kmin, double tg, double A0, double B0, int bad,
-                                               const double *__restrict__ rs)
+// Four points at positions 4 G .. 4 G + 3 of the chunk (G a compile-time group index);
+// base = A0 + (s0 + 4 G) tg.  The empty volatile statement at the head of a group keeps the
+// scalar loads of the group behind the previous group's work (volatile statements keep
+// their order), so that only one group's masks and reciprocals occupy scalar registers.
+template <int G>
+__device__ __forceinline__ double masked_group(double kmin, double base, double tg, double B0, ScalarDoubles rs,
+                                               ScalarMasks lanes)
 {
-    if constexpr (B < CH) {
-        kmin = sweep_point<B>(kmin, tg, A0, B0, bad, uniform(rs[B]));
-        return sweep_points<CH, B + 1>(kmin, tg, A0, B0, bad, rs);
+    asm volatile("" : "+s"(rs), "+s"(lanes));
+    double x1, x2, x3;
+    asm("v_add_f64 %0, %1, %2" : "=v"(x1) : "v"(tg), "v"(base));
+    asm("v_fma_f64 %0, 2.0, %1, %2" : "=v"(x2) : "v"(tg), "v"(base));
+    asm("v_fma_f64 %0, 2.0, %1, %2" : "=v"(x3) : "v"(tg), "v"(x1));
+    kmin = masked_min<4 * G + 0>(kmin, base, B0, rs[4 * G + 0], lanes[4 * G + 0]);
+    kmin = masked_min<4 * G + 1>(kmin, x1, B0, rs[4 * G + 1], lanes[4 * G + 1]);
+    kmin = masked_min<4 * G + 2>(kmin, x2, B0, rs[4 * G + 2], lanes[4 * G + 2]);
+    kmin = masked_min<4 * G + 3>(kmin, x3, B0, rs[4 * G + 3], lanes[4 * G + 3]);
+    return kmin;
+}
+
+template <int CH, int G = 0>
+__device__ __forceinline__ double masked_groups(double kmin, double base, double tg, double tg4, double B0,
+                                                ScalarDoubles rs, ScalarMasks lanes)
+{
+    if constexpr (4 * G < CH) {
+        kmin = masked_group<G>(kmin, base, tg, B0, rs, lanes);
+        return masked_groups<CH, G + 1>(kmin, base + tg4, tg, tg4, B0, rs, lanes);
     }
     return kmin;
 }
 
-// The same with the reciprocals 1/(B+1) as compile-time constants (first chunk, s0 = 0).
-template <int CH, int B = 0>
-__device__ __forceinline__ double sweep_points_first(double kmin, double tg, double A0, double B0, int bad)
-{
-    if constexpr (B < CH) {
-        kmin = sweep_point<B>(kmin, tg, A0, B0, bad, 1.0 / (double)(B + 1));
-        return sweep_points_first<CH, B + 1>(kmin, tg, A0, B0, bad);
-    }
-    return kmin;
-}
-
-// CH grid points s = s0 .. s0+CH-1 of one batch size: key = h with the low five
-// mantissa bits replaced by the point's position b; an infeasible point becomes a
-// quiet NaN (v_min_f64 returns the other operand for a quiet NaN, so it never wins).
-// Returns the smallest key, +inf if no point is feasible.
+// CH points starting at accumulation count s0 (A0s = A0 + s0 tg); rs and lanes point at s0.
+// Returns the smallest key, +inf if no point is feasible for the lane.
 template <int CH>
-__device__ __forceinline__ double sweep_chunk(double tg, double A0, double B0, int bad, int s0,
-                                              const double *__restrict__ rs)
+__device__ __forceinline__ double sweep_chunk(double tg, double A0s, double B0, ScalarDoubles rs, ScalarMasks lanes)
 {
-    if (s0 == 0) return sweep_points_first<CH>(__builtin_inf(), tg, A0, B0, bad);
-    return sweep_points<CH>(__builtin_inf(), tg, px_fma((double)s0, tg, A0), B0, bad, rs + s0);
+    return masked_groups<CH>(__builtin_inf(), A0s, tg, 4.0 * tg, B0, rs, lanes);
+}
+
+// The same chunk for a GPU count beyond the tables, written as a plain loop (rare, so
+// compactness counts more than speed): the lane's feasible positions are first..last.
+template <int CH>
+__device__ __forceinline__ double sweep_chunk_plain(double tg, double A0s, double B0, const double *__restrict__ rs,
+                                                    int first, int last)
+{
+    double kmin = __builtin_inf();
+#pragma unroll 1
+    for (int b = 0; b < CH; ++b) {
+        const double h = px_fma(B0, rs[b], px_fma((double)b, tg, A0s));
+        const double key = __hiloint2double(__double2hiint(h), (__double2loint(h) & ~31) | b);
+        if (first <= b && b <= last && key < kmin) kmin = key;
+    }
+    return kmin;
 }
 
 // All 64 lanes call this with the same (job, K, nodes).  Every lane returns the same result.
@@ -369,6 +440,7 @@ __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, co
 
     double kbest = __builtin_inf();   // smallest key seen by this lane
     int code = -1;                    // (first grid index of the m chunk) << 10 | (s chunk) of kbest
+    const ScalarDoubles rsc = (ScalarDoubles)rs;
 
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
         const int i = i0 + lane;
@@ -381,19 +453,18 @@ __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, co
         const double u = tb.pu[il] * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
-        const int s_lo = (int)(tb.ql5[il] * rK);
-        int s_hi = (int)(tb.qh5[il] * rK) - 1;
-        s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
-        if (!active) s_hi = -1;
-
+        int s_lo = 1, s_hi = 0;
+        if constexpr (!TABLED) {
+            feasible_range(tb.ql5[il], tb.qh5[il], rK, Gs, s_lo, s_hi);
+            if (!active) s_hi = -1;
+        }
+        const ScalarMasks lanes = (ScalarMasks)(tb.fmask + ((size_t)(TABLED ? K - 1 : 0) * tb.ni + (size_t)(i0 >> 6)) * tb.gs_pad);
         int code_now = i0 << 10;
         for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
-            // bit b of `bad` is set when s = s0 + b is infeasible for this lane
-            int first = s_lo - s0, lastb = s_hi - s0;
-            first = first < 0 ? 0 : first;
-            lastb = lastb > CH - 1 ? CH - 1 : lastb;
-            const uint32_t ok = (first <= lastb) ? ((0xFFFFFFFFu >> (31 - lastb)) & (0xFFFFFFFFu << first)) : 0u;
-            const double kmin = sweep_chunk<CH>(tg, A0, B0, (int)~ok, s0, rs);
+            const double A0s = s0 == 0 ? A0 : px_fma((double)s0, tg, A0);
+            double kmin;
+            if constexpr (TABLED) kmin = sweep_chunk<CH>(tg, A0s, B0, rsc + s0, lanes + s0);
+            else kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
             if (kmin < kbest) {
                 kbest = kmin;
                 code = code_now;
@@ -431,7 +502,7 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 {
     const size_t o = (size_t)j * a.Gm;
     return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
-                     a.lt + (size_t)j * 2 * kTableK * a.Gm};
+                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.fmask + (size_t)j * kTableK * a.ni * a.gs_pad, a.sv, a.ni, a.gs_pad};
 }
 
 // ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
@@ -631,7 +702,7 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // four wavefronts walks cand_per_wave candidates of that job.
 
 template <int CH, bool F32, bool MEMO>
-__global__ void __launch_bounds__(256) pairs_kernel(FitnessArgs a)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int j = (slot / a.cand_groups) * 8 + xcd;
@@ -827,6 +898,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.p = p; a.delta = delta;
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
+    a.sv = (double *)(ws + L.sv);
     a.rk = (double *)(ws + L.rk);
     a.tg = (double *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);
@@ -834,6 +906,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.qh5 = (double *)(ws + L.qh5);
     a.ql5 = (double *)(ws + L.ql5);
     a.lt = (double *)(ws + L.lt);
+    a.fmask = (unsigned long long *)(ws + L.fmask);
+    a.ni = (d->Gm + 63) / 64;
+    a.gs_pad = ((d->Gs + 31) / 32) * 32;
     a.denom = (double *)(ws + L.denom);
     a.factor = (double *)(ws + L.factor);
     a.running = (int32_t *)(ws + L.running);

@@ -17,6 +17,7 @@ constexpr int kTableK = 64;
 struct WorkspaceLayout {
     size_t status;    // int32 status word
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
+    size_t sv;        // double [as rs]   s as a double
     size_t rk;        // double [256]     1/K
     size_t tg;        // double [J,Gm]    T_grad(m_i)
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
@@ -24,6 +25,8 @@ struct WorkspaceLayout {
     size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
     size_t ql5;       // double [J,Gm]    ceil(M0 / m_i) - 1/2
     size_t lt;        // double [J,2,kTableK,Gm]  last pass of Eq. 10 by (job, one node?, K)
+    size_t fmask;     // uint64 [J,kTableK,ceil(Gm/64),Gs up to a multiple of 32]  lanes whose batch size is
+                      //                  feasible at accumulation count s, by (job, K, group of 64 grid points)
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
     size_t running;   // int32  [J]       job holds GPUs in current_alloc
@@ -43,6 +46,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
+    L.sv = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
     L.rk = o;      o = up(o + 8 * 256);
     L.tg = o;      o = up(o + 8 * J * Gm);
     L.lntg = o;    o = up(o + 8 * J * Gm);
@@ -50,6 +54,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.qh5 = o;     o = up(o + 8 * J * Gm);
     L.ql5 = o;     o = up(o + 8 * J * Gm);
     L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
+    L.fmask = o;   o = up(o + 8 * J * kTableK * ((Gm + 63) / 64) * (((Gs + 31) / 32) * 32));
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
     L.running = o; o = up(o + 4 * J);
