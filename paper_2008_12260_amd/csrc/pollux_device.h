@@ -78,6 +78,15 @@ __device__ __forceinline__ int wave_min(int v)
     return o < v ? o : v;
 }
 
+__device__ __forceinline__ unsigned wave_min(unsigned v)
+{
+    PX_DPP_STEPS("v_min_u32_dpp", v);
+    unsigned o = (unsigned)exchange<4>((int)v);
+    v = o < v ? o : v;
+    o = (unsigned)exchange<5>((int)v);
+    return o < v ? o : v;
+}
+
 __device__ __forceinline__ unsigned wave_max(unsigned v)
 {
     PX_DPP_STEPS("v_max_u32_dpp", v);

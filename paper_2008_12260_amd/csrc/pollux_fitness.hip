@@ -424,22 +424,29 @@ __device__ __forceinline__ double sweep_chunk_plain(double tg, double A0s, doubl
     return kmin;
 }
 
-// All 64 lanes call this with the same (job, K, nodes).  Every lane returns the same result.
-// TABLED: the last pass of Eq. 10 comes from the job's table (K <= kTableK), else it is computed here.
+// The grid point a sweep elects: index into the job's batch-size grid and accumulation
+// count; i = -1 when no point is feasible.
+struct Pick {
+    int i, s;
+};
+
+// All 64 lanes call this with the same (job, K >= 1, nodes).  Every lane returns the same result:
+// the point with the smallest key over the whole grid (equal keys, i.e. equal h and equal
+// position inside the chunk, resolve to the lowest flat index i * Gs + s).
+// TABLED: last pass and lane masks come from the job's tables (K <= kTableK), else they are formed here.
 template <int CH, bool TABLED>
-__device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+__device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
     const int lane = lane_id();
-    const double Kd = (double)K;
-    const double rK = K < kRecipTable ? rk[K] : 1.0 / Kd;
+    const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
     const double *__restrict__ lrow = tb.lt + ((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(TABLED ? K - 1 : 0)) * Gm;
     SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
     double kbest = __builtin_inf();   // smallest key seen by this lane
-    int code = -1;                    // (first grid index of the m chunk) << 10 | (s chunk) of kbest
+    int code = 0;                     // (first grid index of the m chunk) << 10 | (s chunk) of kbest
     const ScalarDoubles rsc = (ScalarDoubles)rs;
 
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
@@ -472,30 +479,53 @@ __device__ __forceinline__ Best sweep_impl(const Job &q, const JobTables &tb, co
         }
     }
 
-    // the elected point of each lane, evaluated in the paper's order of operations
-    double g = 0.0;
-    int flat = 0x7FFFFFFF, m_best = -1, sbest = -1;
-    if (code >= 0) {
-        const int ibest = (code >> 10) + lane;
-        sbest = (code & 1023) * CH + (__double2loint(kbest) & 31);
-        m_best = tb.m[ibest];
-        const double tg = tb.tg[ibest];
-        double last;
-        if constexpr (TABLED) last = lrow[ibest];
-        else last = last_pass(st, tg, tb.lntg[ibest]);
-        g = goodput_point(q, Kd * (double)m_best, tg, last, sbest);
-        flat = ibest * Gs + sbest;
+    // positive doubles order like their bit patterns: two unsigned 32-bit wave minima
+    const unsigned hi = (unsigned)__double2hiint(kbest), lo = (unsigned)__double2loint(kbest);
+    const unsigned hmin = wave_min(hi);
+    if (hmin >= 0x7FF00000u) return Pick{-1, -1};              // every lane still holds +inf
+    const unsigned lmin = wave_min(hi == hmin ? lo : 0xFFFFFFFFu);
+    const bool top = hi == hmin && lo == lmin;
+    const int ibest = (code >> 10) + lane;
+    const int sbest = (code & 1023) * CH + (int)(lo & 31u);
+    unsigned long long winners = __ballot(top);
+    if (__popcll(winners) > 1) {
+        const int flat = ibest * Gs + sbest;
+        const int first = wave_min(top ? flat : 0x7FFFFFFF);
+        winners = __ballot(top && flat == first);
     }
-    return wave_argmax(g, flat, m_best, sbest);
+    const int wl = __builtin_amdgcn_readfirstlane(__ffsll(winners) - 1);
+    return Pick{__builtin_amdgcn_readlane(ibest, wl), __builtin_amdgcn_readlane(sbest, wl)};
 }
 
+template <int CH>
+__device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+                                           const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
+{
+    if (K <= 0) return Pick{-1, -1};
+    if (K <= kTableK) return sweep_pick<CH, true>(q, tb, rs, rk, Gm, Gs, K, nodes);
+    return sweep_pick<CH, false>(q, tb, rs, rk, Gm, Gs, K, nodes);
+}
+
+// Eq. 4 at grid point (i, s) in the paper's order of operations.  Arguments may differ
+// from lane to lane.
+__device__ __forceinline__ Best price_point(const Job &q, const JobTables &tb, int Gm, int K, bool one_node, int i, int s)
+{
+    if (i < 0) return Best{0.0, -1, -1};
+    const int m = tb.m[i];
+    const double tg = tb.tg[i];
+    double last;
+    if (K <= kTableK) last = tb.lt[((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(K - 1)) * Gm + i];
+    else last = last_pass(sync_term(q, K, one_node), tg, tb.lntg[i]);
+    return Best{goodput_point(q, (double)K * (double)m, tg, last, s), m, s};
+}
+
+// Sweep and price: every lane returns the same result.
 template <int CH>
 __device__ __forceinline__ Best sweep(const Job &q, const JobTables &tb, const double *__restrict__ rs,
                                       const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
-    if (K <= 0) return Best{0.0, -1, -1};
-    if (K <= kTableK) return sweep_impl<CH, true>(q, tb, rs, rk, Gm, Gs, K, nodes);
-    return sweep_impl<CH, false>(q, tb, rs, rk, Gm, Gs, K, nodes);
+    const Pick pick = sweep_pick<CH>(q, tb, rs, rk, Gm, Gs, K, nodes);
+    return price_point(q, tb, Gm, K, nodes == 1, pick.i, pick.s);
 }
 
 __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
@@ -716,6 +746,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const JobTables tb = job_tables(a, j);
     const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
+    constexpr bool kDeferred = !F32 && CH != 0;
+    int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
+    bool any_neg = false;
 
     for (int r = 0; r < a.cand_per_wave; ++r) {
         const int c = (group * a.cand_per_wave + r) * kWavesPerBlock + wave;
@@ -776,25 +809,59 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             }
         }
 
-        Best best;
-        if (MEMO && K >= 1 && K <= kTableK) {
-            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
-            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
-        } else if constexpr (CH == 0) {
-            best = sweep_sampled(q, tb.m, a.Gm, a.Gs, K, nodes);
-        } else if constexpr (F32) {
-            best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
+        if constexpr (kDeferred) {
+            // fp64 grid sweep: elect the point now, price it after the loop (lane r keeps candidate r)
+            Pick pick = {-1, -1};
+            if (!(MEMO && K >= 1 && K <= kTableK)) pick = sweep_pick<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            if (lane == r) {
+                d_K = K;
+                d_meta = nodes | (changed ? kMetaChanged : 0);
+                d_i = pick.i;
+                d_s = pick.s;
+            }
+            any_neg |= neg;
         } else {
-            best = sweep<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            Best best;
+            if (MEMO && K >= 1 && K <= kTableK) {
+                const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
+                best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+            } else if constexpr (CH == 0) {
+                best = sweep_sampled(q, tb.m, a.Gm, a.Gs, K, nodes);
+            } else {
+                best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
+            }
+            if (lane == 0) {
+                a.G[pair] = best.goodput;
+                a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
+                a.best_m[pair] = best.m;
+                a.best_s[pair] = best.s;
+                if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+                if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
+            }
         }
-        if (lane == 0) {
+    }
+
+    if constexpr (kDeferred) {
+        // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
+        // Eq. 4 in the paper's order of operations (or looked up in memoised mode) and stored.
+        const int c = (group * a.cand_per_wave + lane) * kWavesPerBlock + wave;
+        if (lane < a.cand_per_wave && c < a.P) {
+            const size_t pair = (size_t)c * a.J + j;
+            const int nodes = d_meta & ~kMetaChanged;
+            Best best;
+            if (MEMO && d_K >= 1 && d_K <= kTableK) {
+                const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
+                best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+            } else {
+                best = price_point(q, tb, a.Gm, d_K, nodes == 1, d_i, d_s);
+            }
             a.G[pair] = best.goodput;
-            a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
+            a.meta[pair] = d_meta;
             a.best_m[pair] = best.m;
             a.best_s[pair] = best.s;
             if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-            if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
         }
+        if (any_neg && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
     }
 }
 
