@@ -91,6 +91,7 @@ struct FitnessArgs {
 };
 
 constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
+constexpr int kPending = -2;             // pairs kernel: grid index of a row whose sweep is still to be done
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
 // Parameters of one job (uniform across the wavefront).  The sweep itself needs only
@@ -746,6 +747,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const JobTables tb = job_tables(a, j);
     const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
+    const int n4 = a.N >> 2;
+    int4 cur0 = {0, 0, 0, 0};                         // the lane's share of the job's current row (its first 256 entries)
+    if (vec4) cur0 = ((const int4 *)cur)[lane < n4 ? lane : n4 - 1];
     constexpr bool kDeferred = !F32 && CH != 0;
     int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
     bool any_neg = false;
@@ -762,18 +766,20 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         if (vec4) {
             const int4 *__restrict__ row4 = (const int4 *)row;
             const int4 *__restrict__ cur4 = (const int4 *)cur;
-            const int n4 = a.N >> 2;
             for (int n0 = 0; n0 < n4; n0 += kWave) {
+                // lanes past the end of the row load its last 16 bytes again and are masked out of the ballots
                 const int n = n0 + lane;
-                const int nc = n < n4 ? n : n4 - 1;           // one unconditional 16-byte load per lane
-                int4 v = row4[nc], cv = cur4[nc];
-                if (n >= n4) { v = int4{0, 0, 0, 0}; cv = v; }
+                const int nc = n < n4 ? n : n4 - 1;
+                const int4 v = row4[nc];
+                const int4 cv = n0 == 0 ? cur0 : cur4[nc];
+                const unsigned long long valid = __ballot(n < n4);
                 if (n0 == 0) v0 = v;
-                ksum += (v.x + v.y) + (v.z + v.w);
-                nodes += __popcll(__ballot(v.x > 0)) + __popcll(__ballot(v.y > 0)) + __popcll(__ballot(v.z > 0)) +
-                         __popcll(__ballot(v.w > 0));
-                changed |= __ballot(((v.x ^ cv.x) | (v.y ^ cv.y) | (v.z ^ cv.z) | (v.w ^ cv.w)) != 0) != 0;
-                neg |= __ballot((v.x | v.y | v.z | v.w) < 0) != 0;
+                const int part = (v.x + v.y) + (v.z + v.w);
+                ksum += n < n4 ? part : 0;
+                nodes += __popcll(__ballot(v.x > 0) & valid) + __popcll(__ballot(v.y > 0) & valid) +
+                         __popcll(__ballot(v.z > 0) & valid) + __popcll(__ballot(v.w > 0) & valid);
+                changed |= ((__ballot(v.x != cv.x) | __ballot(v.y != cv.y) | __ballot(v.z != cv.z) | __ballot(v.w != cv.w)) & valid) != 0;
+                neg |= (__ballot((v.x | v.y | v.z | v.w) < 0) & valid) != 0;
             }
         } else {
             for (int n0 = 0; n0 < a.N; n0 += kWave) {
@@ -797,10 +803,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             if (vec4 && a.N <= 4 * kWave && !neg) {
                 // the row is still in registers and has no negative entry
                 const int nb = lane * 4;
-                if (v0.x > 0) atomicAdd(&cp[nb + 0], (unsigned long long)v0.x + one_job);
-                if (v0.y > 0) atomicAdd(&cp[nb + 1], (unsigned long long)v0.y + one_job);
-                if (v0.z > 0) atomicAdd(&cp[nb + 2], (unsigned long long)v0.z + one_job);
-                if (v0.w > 0) atomicAdd(&cp[nb + 3], (unsigned long long)v0.w + one_job);
+                if (lane < n4) {
+                    if (v0.x > 0) atomicAdd(&cp[nb + 0], (unsigned long long)v0.x + one_job);
+                    if (v0.y > 0) atomicAdd(&cp[nb + 1], (unsigned long long)v0.y + one_job);
+                    if (v0.z > 0) atomicAdd(&cp[nb + 2], (unsigned long long)v0.z + one_job);
+                    if (v0.w > 0) atomicAdd(&cp[nb + 3], (unsigned long long)v0.w + one_job);
+                }
             } else {
                 for (int n = lane; n < a.N; n += kWave) {
                     const int v = row[n];
@@ -812,7 +820,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         if constexpr (kDeferred) {
             // fp64 grid sweep: elect the point now, price it after the loop (lane r keeps candidate r)
             Pick pick = {-1, -1};
-            if (!(MEMO && K >= 1 && K <= kTableK)) pick = sweep_pick<CH>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
+            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
             if (lane == r) {
                 d_K = K;
                 d_meta = nodes | (changed ? kMetaChanged : 0);
@@ -842,6 +851,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     }
 
     if constexpr (kDeferred) {
+        // rows with more GPUs than the tables cover: the whole wavefront sweeps them one by one
+        unsigned long long pending = __ballot(d_i == kPending);
+        while (pending) {
+            const int l = __ffsll(pending) - 1;
+            pending &= pending - 1;
+            const int K = __builtin_amdgcn_readlane(d_K, l);
+            const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
+            const Pick pick = sweep_pick<CH, false>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            if (lane == l) {
+                d_i = pick.i;
+                d_s = pick.s;
+            }
+        }
         // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
         // Eq. 4 in the paper's order of operations (or looked up in memoised mode) and stored.
         const int c = (group * a.cand_per_wave + lane) * kWavesPerBlock + wave;
