@@ -732,7 +732,9 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // of one job then run on one XCD and its tables stay in that XCD's L2.  Each of the
 // four wavefronts walks cand_per_wave candidates of that job.
 
-template <int CH, bool F32, bool MEMO>
+// ROW1: the host has checked that a row is at most 256 entries, a multiple of four, and that
+// population and current_alloc are 16-byte aligned, so one 16-byte load per lane covers a row.
+template <int CH, bool F32, bool MEMO, bool ROW1>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -746,24 +748,41 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     if constexpr (F32) qf = load_job_f32(a.job_params, a.J, j);
     const JobTables tb = job_tables(a, j);
     const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
-    const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0;
+    const bool vec4 = ROW1 || ((a.N & 3) == 0 && (((uintptr_t)a.population | (uintptr_t)a.current_alloc) & 15) == 0);
     const int n4 = a.N >> 2;
     int4 cur0 = {0, 0, 0, 0};                         // the lane's share of the job's current row (its first 256 entries)
     if (vec4) cur0 = ((const int4 *)cur)[lane < n4 ? lane : n4 - 1];
+    const int lane4 = lane < n4 ? lane : n4 - 1;      // ROW1: lanes past the end of the row load its last 16 bytes again
+    const unsigned long long in_row = __ballot(lane < n4);
     constexpr bool kDeferred = !F32 && CH != 0;
     int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
     bool any_neg = false;
 
+    // candidate c = c0 + kWavesPerBlock * r; its row of job j and its counters are reached by stepping pointers
+    const int c0 = group * a.cand_per_wave * kWavesPerBlock + wave;
+    const size_t row_step = (size_t)kWavesPerBlock * a.J * a.N;
+    const int32_t *__restrict__ row = a.population + ((size_t)c0 * a.J + j) * a.N - row_step;
+    unsigned long long *__restrict__ cp = a.colpack + (size_t)c0 * a.N - (size_t)kWavesPerBlock * a.N;
+
     for (int r = 0; r < a.cand_per_wave; ++r) {
-        const int c = (group * a.cand_per_wave + r) * kWavesPerBlock + wave;
+        const int c = c0 + kWavesPerBlock * r;
         if (c >= a.P) break;
-        const size_t pair = (size_t)c * a.J + j;
+        row += row_step;
+        cp += (size_t)kWavesPerBlock * a.N;
         // row reduce: K = sum, nodes = #positive, changed = differs from the current row
-        const int32_t *__restrict__ row = a.population + pair * a.N;
         int ksum = 0, nodes = 0;
         bool changed = false, neg = false;
         int4 v0 = {0, 0, 0, 0};       // the lane's first four entries (the whole row when N <= 256)
-        if (vec4) {
+        if constexpr (ROW1) {
+            const int4 v = ((const int4 *)row)[lane4];
+            v0 = v;
+            const int part = (v.x + v.y) + (v.z + v.w);
+            ksum = lane < n4 ? part : 0;
+            nodes = __popcll(__ballot(v.x > 0) & in_row) + __popcll(__ballot(v.y > 0) & in_row) +
+                    __popcll(__ballot(v.z > 0) & in_row) + __popcll(__ballot(v.w > 0) & in_row);
+            changed = ((__ballot(v.x != cur0.x) | __ballot(v.y != cur0.y) | __ballot(v.z != cur0.z) | __ballot(v.w != cur0.w)) & in_row) != 0;
+            neg = (__ballot((v.x | v.y | v.z | v.w) < 0) & in_row) != 0;
+        } else if (vec4) {
             const int4 *__restrict__ row4 = (const int4 *)row;
             const int4 *__restrict__ cur4 = (const int4 *)cur;
             for (int n0 = 0; n0 < n4; n0 += kWave) {
@@ -798,9 +817,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         // candidate's per-node counters; a multi-node job also counts once on each of its nodes.
         // One 64-bit integer atomic per entry: the result does not depend on the order of arrival.
         if (a.need_constraints) {
-            unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
             const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
-            if (vec4 && a.N <= 4 * kWave && !neg) {
+            if ((ROW1 || (vec4 && a.N <= 4 * kWave)) && !neg) {
                 // the row is still in registers and has no negative entry
                 const int nb = lane * 4;
                 if (lane < n4) {
@@ -840,6 +858,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
             }
             if (lane == 0) {
+                const size_t pair = (size_t)c * a.J + j;
                 a.G[pair] = best.goodput;
                 a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
                 a.best_m[pair] = best.m;
@@ -851,6 +870,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     }
 
     if constexpr (kDeferred) {
+        // What follows needs pointers the loop above never touches (outputs, the tables of the
+        // untabled path).  They are read from the kernel-argument segment again here, behind a
+        // volatile statement, instead of occupying scalar registers throughout the loop.
+        typedef const FitnessArgs __attribute__((address_space(4))) *KernelArgs;
+        KernelArgs again = (KernelArgs)__builtin_amdgcn_kernarg_segment_ptr();
+        asm volatile("" : "+s"(again));
+        const FitnessArgs b = *(const FitnessArgs *)again;
+        const Job qb = load_job(b.job_params, b.J, j);
+        const JobTables tbb = job_tables(b, j);
+
         // rows with more GPUs than the tables cover: the whole wavefront sweeps them one by one
         unsigned long long pending = __ballot(d_i == kPending);
         while (pending) {
@@ -858,7 +887,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             pending &= pending - 1;
             const int K = __builtin_amdgcn_readlane(d_K, l);
             const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
-            const Pick pick = sweep_pick<CH, false>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            const Pick pick = sweep_pick<CH, false>(qb, tbb, b.rs, b.rk, b.Gm, b.Gs, K, nodes);
             if (lane == l) {
                 d_i = pick.i;
                 d_s = pick.s;
@@ -866,24 +895,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         }
         // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
         // Eq. 4 in the paper's order of operations (or looked up in memoised mode) and stored.
-        const int c = (group * a.cand_per_wave + lane) * kWavesPerBlock + wave;
-        if (lane < a.cand_per_wave && c < a.P) {
-            const size_t pair = (size_t)c * a.J + j;
+        const int c = (group * b.cand_per_wave + lane) * kWavesPerBlock + wave;
+        if (lane < b.cand_per_wave && c < b.P) {
+            const size_t pair = (size_t)c * b.J + j;
             const int nodes = d_meta & ~kMetaChanged;
             Best best;
             if (MEMO && d_K >= 1 && d_K <= kTableK) {
-                const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
+                const MemoEntry e = b.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
             } else {
-                best = price_point(q, tb, a.Gm, d_K, nodes == 1, d_i, d_s);
+                best = price_point(qb, tbb, b.Gm, d_K, nodes == 1, d_i, d_s);
             }
-            a.G[pair] = best.goodput;
-            a.meta[pair] = d_meta;
-            a.best_m[pair] = best.m;
-            a.best_s[pair] = best.s;
-            if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+            b.G[pair] = best.goodput;
+            b.meta[pair] = d_meta;
+            b.best_m[pair] = best.m;
+            b.best_s[pair] = best.s;
+            if (b.best_goodput) b.best_goodput[pair] = best.goodput;
         }
-        if (any_neg && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
+        if (any_neg && lane == 0) atomicOr(b.status, PX_ST_NEG_ALLOC);
     }
 }
 
@@ -1051,19 +1080,31 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         }
     }
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
-    if (memo) {
-        if (sampled) hipLaunchKernelGGL((pairs_kernel<0, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((pairs_kernel<32, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a);
+    const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
+#define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1) \
+    hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1>), dim3(pair_blocks), dim3(256), 0, stream, a)
+#define PX_LAUNCH_PAIRS_FP64(CH)                                   \
+    do {                                                           \
+        if (memo && row1) PX_LAUNCH_PAIRS(CH, false, true, true);  \
+        else if (memo) PX_LAUNCH_PAIRS(CH, false, true, false);    \
+        else if (row1) PX_LAUNCH_PAIRS(CH, false, false, true);    \
+        else PX_LAUNCH_PAIRS(CH, false, false, false);             \
+    } while (0)
+    if (sampled) {
+        if (memo) PX_LAUNCH_PAIRS(0, false, true, false);
+        else PX_LAUNCH_PAIRS(0, false, false, false);
+    } else if (f32) {
+        if (memo) PX_LAUNCH_PAIRS(8, true, true, false);
+        else PX_LAUNCH_PAIRS(8, true, false, false);
+    } else if (ch == 8) {
+        PX_LAUNCH_PAIRS_FP64(8);
+    } else if (ch == 16) {
+        PX_LAUNCH_PAIRS_FP64(16);
     } else {
-        if (sampled) hipLaunchKernelGGL((pairs_kernel<0, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (f32) hipLaunchKernelGGL((pairs_kernel<8, true, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (ch == 8) hipLaunchKernelGGL((pairs_kernel<8, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else if (ch == 16) hipLaunchKernelGGL((pairs_kernel<16, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((pairs_kernel<32, false, false>), dim3(pair_blocks), dim3(256), 0, stream, a);
+        PX_LAUNCH_PAIRS_FP64(32);
     }
+#undef PX_LAUNCH_PAIRS_FP64
+#undef PX_LAUNCH_PAIRS
     if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
     if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
