@@ -3,7 +3,8 @@
 
 A step is one generation on the large configuration (4096 candidates, 1000
 jobs, 256 nodes x 8 GPUs, 128 x 32 grid): pollux_fitness on the current
-population followed by pollux_ga_step into the other buffer.  The reported
+population followed by pollux_ga_step in place (children overwrite the candidates
+that did not survive).  The reported
 value counts the (m, s) grid points the fitness call sweeps
 (P * J * Gm * Gs per step) over the wall time of the whole step.
 
@@ -40,7 +41,8 @@ def cpu_baseline(wl, cfg, target_seconds=15.0):
         t0 = time.perf_counter()
         r = O.fitness(pop, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc, wl.node_capacity,
                       cfg.p, cfg.delta, cfg.Gs)
-        O.ga_step(pop, r["fitness"], wl.node_capacity, GA_SEED, 0, max(1, count // 2), mut_threshold(cfg.J))
+        O.ga_step(pop, r["fitness"], wl.node_capacity, GA_SEED, 0, max(1, count // 2), mut_threshold(cfg.J),
+                  flags=O.GA_IN_PLACE)
         return time.perf_counter() - t0
 
     probe = 32
@@ -71,7 +73,7 @@ def main():
                          "size against which HBM byte counters are scaled)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU; a population would shard over candidates, "
+        sys.exit("bench.py: this library runs on one GPU; a population would shard over candidates, "
                  "but no multi-GPU path exists. Use --gpus 1.")
 
     import numpy as np
@@ -89,18 +91,13 @@ def main():
                           wl.current_alloc, wl.node_capacity, p=cfg.p, delta=cfg.delta, device=dev)
     a = torch.from_numpy(host_pop).to(dev)
     del host_pop
-    b = torch.empty_like(a)
     stream = torch.cuda.current_stream()
     elite = cfg.P // 2
 
-    def step(gen, a, b):
-        call.run(a, stream=stream, outputs="fitness")
-        call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
-        return b, a
-
     gen = 0
     for _ in range(args.warmup):
-        a, b = step(gen, a, b)
+        call.run(a, stream=stream, outputs="fitness")
+        call.ga_step(a, a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, flags=px.PX_GA_IN_PLACE)
         gen += 1
     torch.cuda.synchronize()
 
@@ -116,17 +113,28 @@ def main():
         fit_ev[k][0].record(stream)
         call.run(a, stream=stream, outputs="fitness")      # full call every step: job-level kernels included
         fit_ev[k][1].record(stream)
-        call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
-        a, b = b, a
+        call.ga_step(a, a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, flags=px.PX_GA_IN_PLACE)
         gen += 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     px.pollux_set_sweep_events(None, None)
 
+    # the same search step out of place (survivors copied into a second buffer), for comparison
+    b = torch.empty_like(a)
+    o0, o1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
+    o0.record(stream)
+    for k in range(3):
+        call.ga_step(a, b, GA_SEED, gen + k, elite, mut_threshold(cfg.J), stream=stream)
+    o1.record(stream)
+    torch.cuda.synchronize()
+    ga_out_of_place_ms = o0.elapsed_time(o1) / 3
+
     if args.calibration_copy:
         for _ in range(2):
             b.copy_(a)
         torch.cuda.synchronize()
+    del b
 
     status = call.status()
     best_fitness = float(call.fitness.max().item())
@@ -141,6 +149,7 @@ def main():
         "fitness_call_ms": sum(fit_ms) / len(fit_ms),
         "sweep_kernel_ms": sweep_avg_ms,
         "ga_step_ms": elapsed * 1e3 / args.steps - sum(fit_ms) / len(fit_ms),
+        "ga_step_out_of_place_ms": ga_out_of_place_ms,
         "fitness_only_evals_per_s": evals_per_step / (sum(fit_ms) / len(fit_ms) * 1e-3),
         "sweep_kernel_evals_per_s": evals_per_step / (sweep_avg_ms * 1e-3),
         "population_bytes_per_s_in_sweep": 4.0 * cfg.P * cfg.J * cfg.N / (sweep_avg_ms * 1e-3),
@@ -175,17 +184,16 @@ def main():
                                    mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta,
                                    flags=flags, device=dev)
             ma = torch.from_numpy(mwl.population).to(dev)
-            mb = torch.empty_like(ma)
             for g in range(5):
                 mcall.run(ma, stream=stream, outputs="fitness")
-                mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream)
-                ma, mb = mb, ma
+                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream,
+                              flags=px.PX_GA_IN_PLACE)
             torch.cuda.synchronize()
             tg0 = time.perf_counter()
             for g in range(5, 105):
                 mcall.run(ma, stream=stream, outputs="fitness", keep_job_tables=True)
-                mcall.ga_step(ma, mb, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream)
-                ma, mb = mb, ma
+                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream,
+                              flags=px.PX_GA_IN_PLACE)
             torch.cuda.synchronize()
             tg1 = time.perf_counter()
             extra[label + "_generations_per_s"] = 100.0 / (tg1 - tg0)
@@ -202,7 +210,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: P={cfg.P} candidates, J={cfg.J} jobs, {cfg.N} nodes x {cfg.cap} GPUs, "
-                               f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step per step",
+                               f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step (in place) per step",
                    "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed},
         "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,

@@ -162,8 +162,15 @@ typedef struct {
     uint32_t generation;     /* counter word 0 */
     uint32_t elite_k;        /* survivors, 1..P: the best elite_k candidates are copied unchanged */
     uint32_t mut_threshold;  /* per-job mutation probability * 2^32, rounded down */
-    uint32_t flags;          /* reserved, 0 */
+    uint32_t flags;          /* PX_GA_* */
 } pollux_ga_params;
+
+enum {
+    PX_GA_IN_PLACE = 1   /* children == parents: child c (c >= elite_k) overwrites the candidate of rank c, which
+                            did not survive, and the survivors stay where they are.  The new population holds the
+                            same matrices as the out-of-place call, child c in slot order[c] instead of slot c,
+                            and half of the traffic: survivors are neither read nor written. */
+};
 
 /*
  * One generation of the population search (Sec. 4.3: candidates are perturbed
@@ -197,7 +204,8 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; Gm, Gs, precis
                    const int32_t *node_capacity,         /* [N] */
                    const pollux_ga_params *params,       /* host */
                    void *workspace, size_t workspace_bytes,
-                   int32_t *children,                    /* [P,J,N] out, must not overlap parents */
+                   int32_t *children,                    /* [P,J,N] out, must not overlap parents; with
+                                                            PX_GA_IN_PLACE it must equal parents */
                    void *hip_stream);
 
 /* Copies the status word of the last pollux_fitness call that used `workspace`

@@ -201,15 +201,19 @@ def fitness(population, job_params, m_grid, fair_share, current_alloc, node_capa
     return out
 
 
-def ga_step(parents, fitness_values, node_capacity, seed, generation, elite_k, mut_threshold):
+GA_IN_PLACE = 1
+
+
+def ga_step(parents, fitness_values, node_capacity, seed, generation, elite_k, mut_threshold, flags=0):
+    """One generation; with GA_IN_PLACE the result has child c in the slot of the candidate of rank c."""
     A = _c(parents, np.int32)
     P, J, N = A.shape
     f = _c(fitness_values, np.float64)
     cap = _c(node_capacity, np.int32)
     d = Dims(P, J, N, 1, 1, 0, 0)
-    ga = GaParams(seed, generation, elite_k, mut_threshold, 0)
-    out = np.empty_like(A)
-    rc = lib().pollux_ga_step_ref(ctypes.byref(d), _p(A), _p(f), _p(cap), ctypes.byref(ga), _p(out))
+    ga = GaParams(seed, generation, elite_k, mut_threshold, flags)
+    out = A.copy() if flags & GA_IN_PLACE else np.empty_like(A)
+    rc = lib().pollux_ga_step_ref(ctypes.byref(d), _p(out if flags & GA_IN_PLACE else A), _p(f), _p(cap), ctypes.byref(ga), _p(out))
     if rc != 0:
         raise ValueError(f"pollux_ga_step_ref returned {rc}")
     return out

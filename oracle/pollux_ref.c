@@ -432,10 +432,18 @@ int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const d
     if (!order) return -2;
     pollux_ref_rank(fitness, P, order);
     const size_t JN = (size_t)J * N;
+    /* in place (flags bit 0): the new generation is formed in a scratch copy exactly as below and
+     * child c is then stored in the slot of the candidate of rank c, so survivors do not move */
+    const int in_place = (ga->flags & 1u) != 0;
+    int32_t *out = children;
+    if (in_place) {
+        out = (int32_t *)malloc(sizeof(int32_t) * JN * (size_t)P);
+        if (!out) { free(order); return -2; }
+    }
 
     #pragma omp parallel for schedule(dynamic, 1)
     for (int c = 0; c < P; ++c) {
-        int32_t *child = children + (size_t)c * JN;
+        int32_t *child = out + (size_t)c * JN;
         if ((uint32_t)c < ga->elite_k) {
             memcpy(child, parents + (size_t)order[c] * JN, sizeof(int32_t) * JN);
             continue;
@@ -475,6 +483,10 @@ int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const d
             }
         }
         pollux_ref_repair(child, J, N, cap, key, ga->generation, (uint32_t)c);
+    }
+    if (in_place) {
+        for (int c = 0; c < P; ++c) memcpy(children + (size_t)order[c] * JN, out + (size_t)c * JN, sizeof(int32_t) * JN);
+        free(out);
     }
     free(order);
     return 0;

@@ -16,6 +16,7 @@ NPARAM = 14
 PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
 PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
 PX_FLAG_SAMPLE_M = 16
+PX_GA_IN_PLACE = 1
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
@@ -174,8 +175,9 @@ class FitnessCall:
     def status(self, stream=None) -> int:
         return pollux_last_status(self.workspace, stream)
 
-    def ga_step(self, parents, children, seed, generation, elite_k, mut_threshold, fitness=None, stream=None):
-        ga = GaParams(seed, generation, elite_k, mut_threshold, 0)
+    def ga_step(self, parents, children, seed, generation, elite_k, mut_threshold, fitness=None, stream=None,
+                flags=0):
+        ga = GaParams(seed, generation, elite_k, mut_threshold, flags)
         pollux_ga_step(self.dims, parents, self.fitness if fitness is None else fitness, self.node_capacity, ga,
                        self.workspace, children, stream)
 

@@ -107,7 +107,12 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (16 * (size_t)dims->J + 16 * (size_t)dims->N > 120 * 1024) return PX_E_INVALID_ARG;   // per-job and per-node bookkeeping lives in LDS
     const size_t bytes = sizeof(int32_t) * (size_t)dims->P * dims->J * dims->N;
     const char *a = (const char *)parents, *b = (const char *)children;
-    if (a < b + bytes && b < a + bytes) return PX_E_INVALID_ARG;
+    if (params->flags & ~(uint32_t)PX_GA_IN_PLACE) return PX_E_INVALID_ARG;
+    if (params->flags & PX_GA_IN_PLACE) {
+        if (a != b) return PX_E_INVALID_ARG;
+    } else if (a < b + bytes && b < a + bytes) {
+        return PX_E_INVALID_ARG;
+    }
     int rc = check_workspace(dims, workspace, workspace_bytes);
     if (rc != PX_OK) return rc;
     rc = check_device();

@@ -47,6 +47,7 @@ struct GaArgs {
     const double *fitness;
     int32_t *children, *order;
     uint32_t key0, key1, generation, elite_k, mut_threshold;
+    int in_place;      // children == parents: only children c >= elite_k are formed, child c goes to slot order[c]
 };
 
 // ---- rank ----------------------------------------------------------------------
@@ -163,13 +164,13 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     __shared__ int count, n_dist, n_ent;
     __shared__ unsigned long long keep;
 
-    const int c = blockIdx.x;
+    const int c = a.in_place ? (int)(blockIdx.x + a.elite_k) : (int)blockIdx.x;
     const int tid = threadIdx.x;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int waves = kGaThreads >> 6;
     const int lane = lane_id();
     const size_t JN = (size_t)a.J * a.N;
-    int32_t *__restrict__ child = a.children + (size_t)c * JN;
+    int32_t *__restrict__ child = a.children + (size_t)(a.in_place ? a.order[c] : c) * JN;
 
     if ((uint32_t)c < a.elite_k) {
         // survivors are copied verbatim, in rank order
@@ -426,6 +427,7 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.key0 = (uint32_t)(ga->seed & 0xFFFFFFFFull);
     a.key1 = (uint32_t)(ga->seed >> 32);
     a.generation = ga->generation; a.elite_k = ga->elite_k; a.mut_threshold = ga->mut_threshold;
+    a.in_place = (ga->flags & PX_GA_IN_PLACE) ? 1 : 0;
 
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);
@@ -434,7 +436,8 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
             hipSuccess)
             return PX_E_HIP;
     }
-    hipLaunchKernelGGL(generation_kernel, dim3((unsigned)d->P), dim3(kGaThreads), lds, stream, a);
+    const unsigned children_formed = a.in_place ? (unsigned)d->P - ga->elite_k : (unsigned)d->P;
+    if (children_formed > 0) hipLaunchKernelGGL(generation_kernel, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 

@@ -114,3 +114,51 @@ def test_large_config_one_generation_bit_exact():
     want = O.ga_step(pop, fit, wl.node_capacity, SEED, 3, cfg.P // 2, 1 << 29)
     for lo in range(0, cfg.P, 256):
         assert np.array_equal(got[lo:lo + 256], want[lo:lo + 256]), f"children {lo}..{lo + 255}"
+
+
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_in_place_step_matches_oracle(name):
+    """PX_GA_IN_PLACE: children overwrite the slots of the candidates that did not survive."""
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make(name)
+    c = wl.cfg
+    fit = run_oracle(wl)["fitness"]
+    call = gpu_call(wl)
+    for elite in (1, c.P // 2, c.P):
+        pop = torch.as_tensor(wl.population).cuda()
+        call.ga_step(pop, pop, SEED, 4, elite, 1 << 29, fitness=torch.as_tensor(fit).cuda(), flags=px.PX_GA_IN_PLACE)
+        want = O.ga_step(wl.population, fit, wl.node_capacity, SEED, 4, elite, 1 << 29, flags=O.GA_IN_PLACE)
+        assert np.array_equal(pop.cpu().numpy(), want)
+
+
+def test_in_place_search_loop_matches_oracle_every_generation():
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("physical")
+    c = wl.cfg
+    call = gpu_call(wl)
+    host = wl.population.copy()
+    dev = torch.as_tensor(host).cuda()
+    for gen in range(25):
+        ref = run_oracle(wl, population=host)
+        call.run(dev)
+        got = call.results()
+        assert np.array_equal(got["best_m"], ref["best_m"]) and np.array_equal(got["violations"], ref["violations"])
+        # the step is driven by the oracle's fitness on both sides, so that one ulp never forks the two searches
+        host = O.ga_step(host, ref["fitness"], wl.node_capacity, SEED, gen, c.P // 2, (1 << 32) // c.J, flags=O.GA_IN_PLACE)
+        call.ga_step(dev, dev, SEED, gen, c.P // 2, (1 << 32) // c.J, fitness=torch.as_tensor(ref["fitness"]).cuda(),
+                     flags=px.PX_GA_IN_PLACE)
+        assert np.array_equal(dev.cpu().numpy(), host), f"generation {gen}"
+
+
+def test_in_place_flag_needs_the_same_buffer_and_unknown_flags_are_rejected():
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("tiny")
+    call = gpu_call(wl)
+    a = torch.as_tensor(wl.population).cuda()
+    with pytest.raises(px.PolluxError):
+        call.ga_step(a, torch.empty_like(a), SEED, 0, 8, 0, flags=px.PX_GA_IN_PLACE)
+    with pytest.raises(px.PolluxError):
+        call.ga_step(a, torch.empty_like(a), SEED, 0, 8, 0, flags=2)

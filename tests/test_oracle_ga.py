@@ -241,3 +241,17 @@ def test_search_finds_better_allocations_than_the_fair_share():
     f = fitness_of(pop)
     assert f.max() > 1.01
     assert np.all(constraint_violations(pop[np.argsort(-f)[:10]], wl.node_capacity) == 0)
+
+
+def test_in_place_step_is_the_out_of_place_step_with_children_in_the_slots_of_the_losers():
+    wl = W.make("physical")
+    c = wl.cfg
+    rng = np.random.default_rng(12)
+    fit = rng.uniform(0.1, 1.0, c.P)
+    fit[3] = fit[40] = fit[77]
+    order = O.rank(fit)
+    for elite in (1, c.P // 2, c.P):
+        out = O.ga_step(wl.population, fit, wl.node_capacity, 77, 2, elite, 1 << 29)
+        inp = O.ga_step(wl.population, fit, wl.node_capacity, 77, 2, elite, 1 << 29, flags=O.GA_IN_PLACE)
+        assert np.array_equal(inp[order], out)                                  # child c sits in slot order[c]
+        assert np.array_equal(inp[order[:elite]], wl.population[order[:elite]])  # survivors did not move
