@@ -25,6 +25,10 @@ if ROOT not in sys.path:
 
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 (FMA) x 2.4 GHz
 FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 divisions, each counted as one
+# HBM bytes one launch of the sweep kernel moves on the "large" workload: rocprofv3 FETCH_SIZE (2 077 094 KiB,
+# scaled by 2.0) + WRITE_SIZE (686 833 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
+# size in the same runs (profiles/pairs_kernel_large.md).  Valid for the kernel those counters were taken on.
+SWEEP_HBM_BYTES = {"large": 2077094 * 1024 * 2.0 + 686833 * 1024 * 1.0}
 GA_SEED = 0x2008_1226_5EED_0001
 def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
     return (1 << 32) // J
@@ -213,7 +217,7 @@ def main():
                                f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step (in place) per step",
                    "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed},
         "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": None,
+                     "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": SWEEP_HBM_BYTES.get(cfg.name),
                      "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL,
                      "avg_launch_ms": sweep_avg_ms},
         "extra": extra,
