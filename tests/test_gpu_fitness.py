@@ -305,3 +305,41 @@ def test_non_adaptive_jobs_with_a_fixed_batch_size():
     assert have.mean() > 0.3
     K = wl.population.sum(2)
     assert np.all((K * g["best_m"] * (g["best_s"] + 1))[have] == np.broadcast_to(jp[W.PARAM_INDEX["M0"]], K.shape)[have])
+
+
+# ---- launch-shape corners of the pairs kernel -----------------------------------------------------------------
+
+@pytest.mark.parametrize("shape", [
+    dict(P=5, J=7, N=260, cap=2, Gm=20, Gs=6),        # rows of 16-byte groups beyond one wavefront's single load
+    dict(P=3, J=4, N=512, cap=1, Gm=9, Gs=3),
+    dict(P=6, J=5, N=256, cap=2, Gm=64, Gs=32),       # exactly one load per lane, one full mask group
+    dict(P=6, J=5, N=252, cap=2, Gm=65, Gs=31),       # one lane short of it, grid one past it
+])
+def test_row_lengths_around_the_single_load_case(shape):
+    wl = W.make(W.custom("rows", **shape))
+    assert compare(wl, run_gpu(wl), run_oracle(wl)) == 0
+
+
+def test_several_candidates_per_wavefront_with_a_ragged_population():
+    """P * J large enough for several candidates per wavefront, P not a multiple of a workgroup's share."""
+    cfg = W.custom("ragged_population", P=1001, J=200, N=64, cap=8, Gm=64, Gs=16)
+    wl = W.make(cfg)
+    ref = run_oracle(wl)
+    for flags in (0, 4):
+        assert compare(wl, run_gpu(wl, flags=flags), ref) == 0
+
+
+def test_population_that_is_not_16_byte_aligned():
+    """A population view that starts 4 bytes into its allocation takes the scalar row path."""
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("physical")
+    c = wl.cfg
+    call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                          wl.node_capacity, p=c.p, delta=c.delta)
+    flat = torch.zeros(wl.population.size + 1, dtype=torch.int32, device="cuda")
+    view = flat[1:].view(c.P, c.J, c.N)
+    view.copy_(torch.as_tensor(wl.population))
+    assert view.data_ptr() % 16 == 4
+    call.run(view)
+    assert compare(wl, call.results(), run_oracle(wl)) == 0
