@@ -163,6 +163,8 @@ typedef struct {
     uint32_t elite_k;        /* survivors, 1..P: the best elite_k candidates are copied unchanged */
     uint32_t mut_threshold;  /* per-job mutation probability * 2^32, rounded down */
     uint32_t flags;          /* PX_GA_* */
+    const int32_t *job_gpu_cap; /* device, [J], or NULL: the most GPUs job j may hold in a child (Sec. 4.1:
+                                twice the most it has ever held); negative values count as 0 */
 } pollux_ga_params;
 
 enum {
@@ -191,6 +193,9 @@ enum {
  *                             or on node below(x, N) if the job holds none;
  *                   1 shrink: one GPU less on the below(x, occ)-th occupied node (nothing if occ = 0);
  *                   2 pack:   row := 0 except row[below(x, N)] = min(sum of row, that node's capacity);
+ *                 GPU limit (if job_gpu_cap is given, every row of a child, mutated or not): walking the
+ *                   nodes in ascending order the job keeps its GPUs until job_gpu_cap[j] are kept; the
+ *                   rest of the row is given back;
  *                 repair capacity: for each node over capacity, walking jobs cyclically
  *                   from below(word0, J) (item n, tag 4), remove GPUs until it fits;
  *                 repair interference: nodes in ascending order; of the multi-node jobs

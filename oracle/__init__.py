@@ -42,7 +42,7 @@ class Job(ctypes.Structure):
 
 class GaParams(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("generation", ctypes.c_uint32), ("elite_k", ctypes.c_uint32),
-                ("mut_threshold", ctypes.c_uint32), ("flags", ctypes.c_uint32)]
+                ("mut_threshold", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("job_gpu_cap", ctypes.c_void_p)]
 
 
 _lib = None
@@ -82,6 +82,8 @@ def lib():
         L.pollux_fitness_ref.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d] + [vp] * 7
         L.pollux_ga_step_ref.restype = i
         L.pollux_ga_step_ref.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp]
+        L.pollux_ref_cap_row.restype = None
+        L.pollux_ref_cap_row.argtypes = [vp, i, ctypes.c_int32]
         L.pollux_ref_repair.restype = None
         L.pollux_ref_repair.argtypes = [vp, i, i, vp, vp, ctypes.c_uint32, ctypes.c_uint32]
         L.pollux_ref_rank.restype = None
@@ -204,19 +206,27 @@ def fitness(population, job_params, m_grid, fair_share, current_alloc, node_capa
 GA_IN_PLACE = 1
 
 
-def ga_step(parents, fitness_values, node_capacity, seed, generation, elite_k, mut_threshold, flags=0):
-    """One generation; with GA_IN_PLACE the result has child c in the slot of the candidate of rank c."""
+def ga_step(parents, fitness_values, node_capacity, seed, generation, elite_k, mut_threshold, flags=0, job_gpu_cap=None):
+    """One generation; with GA_IN_PLACE the result has child c in the slot of the candidate of rank c.
+    job_gpu_cap: int32 [J], the most GPUs each job may hold in a child (None: no limit)."""
     A = _c(parents, np.int32)
     P, J, N = A.shape
     f = _c(fitness_values, np.float64)
     cap = _c(node_capacity, np.int32)
     d = Dims(P, J, N, 1, 1, 0, 0)
-    ga = GaParams(seed, generation, elite_k, mut_threshold, flags)
+    gcap = None if job_gpu_cap is None else _c(job_gpu_cap, np.int32)
+    ga = GaParams(seed, generation, elite_k, mut_threshold, flags, None if gcap is None else gcap.ctypes.data)
     out = A.copy() if flags & GA_IN_PLACE else np.empty_like(A)
     rc = lib().pollux_ga_step_ref(ctypes.byref(d), _p(out if flags & GA_IN_PLACE else A), _p(f), _p(cap), ctypes.byref(ga), _p(out))
     if rc != 0:
         raise ValueError(f"pollux_ga_step_ref returned {rc}")
     return out
+
+
+def cap_row(row, cap):
+    r = np.array(row, dtype=np.int32, order="C", copy=True)
+    lib().pollux_ref_cap_row(_p(r), r.size, int(cap))
+    return r
 
 
 def repair(A, node_capacity, seed, generation, child):

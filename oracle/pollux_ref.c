@@ -421,6 +421,20 @@ void pollux_ref_repair(int32_t *A, int J, int N, const int32_t *cap, const uint3
  * other child takes each job's row from one of two drawn survivors, may grow or
  * shrink a row by one GPU on a node it occupies or re-pack it, and is repaired.
  */
+/* Sec. 4.1 limits the GPUs a job may be given to twice the most it has ever held.  In the
+ * search this is a repair on the row: walking the nodes in ascending order, the job keeps its
+ * GPUs until `cap` of them are kept; what lies beyond is given back. */
+void pollux_ref_cap_row(int32_t *row, int N, int32_t cap)
+{
+    long kept = 0, limit = cap > 0 ? cap : 0;
+    for (int n = 0; n < N; ++n) {
+        if (row[n] <= 0) continue;
+        long room = limit - kept;
+        if (row[n] > room) row[n] = (int32_t)room;
+        kept += row[n];
+    }
+}
+
 int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const double *fitness,
                        const int32_t *cap, const pollux_ref_ga_params *ga, int32_t *children)
 {
@@ -458,29 +472,31 @@ int pollux_ga_step_ref(const pollux_ref_dims *d, const int32_t *parents, const d
             draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_CROSS, r);
             memcpy(row, ((r[0] & 1u) ? pb : pa) + (size_t)j * N, sizeof(int32_t) * (size_t)N);
             draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_MUT_DECIDE, r);
-            if (!(r[0] < ga->mut_threshold)) continue;
-            draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_MUT_ARGS, r);
-            uint32_t move = r[0] % 3u;
-            int occupied = 0;
-            for (int k = 0; k < N; ++k) occupied += row[k] > 0;
-            if (move == 2u) {
-                /* re-pack: the whole row goes to one drawn node, as far as its capacity allows */
-                int n = (int)below(r[1], (uint32_t)N);
-                long K = 0;
-                for (int k = 0; k < N; ++k) { K += row[k]; row[k] = 0; }
-                if (K < 0) K = 0;
-                row[n] = (int32_t)(K < cap[n] ? K : cap[n]);
-            } else if (occupied > 0) {
-                /* grow / shrink by one GPU on one of the nodes the job already occupies */
-                int pick = (int)below(r[1], (uint32_t)occupied), n = -1;
-                for (int k = 0; k < N; ++k) {
-                    if (row[k] > 0 && pick-- == 0) { n = k; break; }
+            if (r[0] < ga->mut_threshold) {
+                draw(key, ga->generation, (uint32_t)c, (uint32_t)j, TAG_MUT_ARGS, r);
+                uint32_t move = r[0] % 3u;
+                int occupied = 0;
+                for (int k = 0; k < N; ++k) occupied += row[k] > 0;
+                if (move == 2u) {
+                    /* re-pack: the whole row goes to one drawn node, as far as its capacity allows */
+                    int n = (int)below(r[1], (uint32_t)N);
+                    long K = 0;
+                    for (int k = 0; k < N; ++k) { K += row[k]; row[k] = 0; }
+                    if (K < 0) K = 0;
+                    row[n] = (int32_t)(K < cap[n] ? K : cap[n]);
+                } else if (occupied > 0) {
+                    /* grow / shrink by one GPU on one of the nodes the job already occupies */
+                    int pick = (int)below(r[1], (uint32_t)occupied), n = -1;
+                    for (int k = 0; k < N; ++k) {
+                        if (row[k] > 0 && pick-- == 0) { n = k; break; }
+                    }
+                    row[n] += (move == 0u) ? 1 : -1;
+                } else if (move == 0u) {
+                    /* a job without GPUs starts on a drawn node */
+                    row[below(r[1], (uint32_t)N)] += 1;
                 }
-                row[n] += (move == 0u) ? 1 : -1;
-            } else if (move == 0u) {
-                /* a job without GPUs starts on a drawn node */
-                row[below(r[1], (uint32_t)N)] += 1;
             }
+            if (ga->job_gpu_cap) pollux_ref_cap_row(row, N, ga->job_gpu_cap[j]);
         }
         pollux_ref_repair(child, J, N, cap, key, ga->generation, (uint32_t)c);
     }

@@ -109,12 +109,15 @@ typedef struct {
     uint32_t elite_k;
     uint32_t mut_threshold; /* floor(probability * 2^32) */
     uint32_t flags;
+    const int32_t *job_gpu_cap; /* [J] or NULL: most GPUs job j may hold in a child (Sec. 4.1: twice its lifetime maximum) */
 } pollux_ref_ga_params;
 
 int pollux_ga_step_ref(const pollux_ref_dims *dims, const int32_t *parents, const double *fitness,
                        const int32_t *node_capacity, const pollux_ref_ga_params *ga,
                        int32_t *children /* [P,J,N], must not alias parents */);
 
+/* the per-job GPU limit on one row, in place: GPUs are kept in ascending node order up to `cap` */
+void pollux_ref_cap_row(int32_t *row, int N, int32_t cap);
 /* repair alone (capacity, then interference) on one matrix A[J][N], in place */
 void pollux_ref_repair(int32_t *A, int J, int N, const int32_t *node_capacity,
                        const uint32_t key[2], uint32_t generation, uint32_t child);

@@ -35,7 +35,7 @@ class Dims(ctypes.Structure):
 
 class GaParams(ctypes.Structure):
     _fields_ = [("seed", ctypes.c_uint64), ("generation", ctypes.c_uint32), ("elite_k", ctypes.c_uint32),
-                ("mut_threshold", ctypes.c_uint32), ("flags", ctypes.c_uint32)]
+                ("mut_threshold", ctypes.c_uint32), ("flags", ctypes.c_uint32), ("job_gpu_cap", ctypes.c_void_p)]
 
 
 _lib = None
@@ -176,8 +176,11 @@ class FitnessCall:
         return pollux_last_status(self.workspace, stream)
 
     def ga_step(self, parents, children, seed, generation, elite_k, mut_threshold, fitness=None, stream=None,
-                flags=0):
-        ga = GaParams(seed, generation, elite_k, mut_threshold, flags)
+                flags=0, job_gpu_cap=None):
+        """job_gpu_cap: int32 device tensor [J] (the most GPUs each job may hold in a child) or None."""
+        if job_gpu_cap is not None:
+            assert job_gpu_cap.dtype == self.torch.int32 and job_gpu_cap.numel() == self.dims.J and job_gpu_cap.is_cuda
+        ga = GaParams(seed, generation, elite_k, mut_threshold, flags, None if job_gpu_cap is None else job_gpu_cap.data_ptr())
         pollux_ga_step(self.dims, parents, self.fitness if fitness is None else fitness, self.node_capacity, ga,
                        self.workspace, children, stream)
 

@@ -43,6 +43,13 @@ __device__ __forceinline__ long long exchange(long long v)
     return ((long long)exchange<STEP>(hi) << 32) | (long long)(unsigned)exchange<STEP>(lo);
 }
 
+// The value lane `src` holds (src the same in every lane).
+__device__ __forceinline__ long long wave_broadcast(long long v, int src)
+{
+    const int lo = __builtin_amdgcn_readlane((int)(v & 0xFFFFFFFFll), src), hi = __builtin_amdgcn_readlane((int)(v >> 32), src);
+    return ((long long)hi << 32) | (long long)(unsigned)lo;
+}
+
 template <int STEP = 0>
 __device__ __forceinline__ long long wave_sum(long long v)
 {

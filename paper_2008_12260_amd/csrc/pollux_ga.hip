@@ -44,6 +44,7 @@ __device__ __forceinline__ uint32_t below(uint32_t r, uint32_t n) { return __umu
 struct GaArgs {
     int P, J, N;
     const int32_t *parents, *node_capacity;
+    const int32_t *job_gpu_cap;    // [J] or null
     const double *fitness;
     int32_t *children, *order;
     uint32_t key0, key1, generation, elite_k, mut_threshold;
@@ -259,7 +260,43 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
             return n == target ? v + delta : v;
         };
         int nodes = 0;
-        if (vec4) {
+        // GPU limit of the job: needed only when the row after the move holds more than the limit (rare);
+        // that row is then written by the slower path below, which keeps GPUs in ascending node order.
+        bool over_limit = false;
+        long long limit = 0;
+        if (a.job_gpu_cap) {
+            limit = a.job_gpu_cap[j];
+            if (limit < 0) limit = 0;
+            long long k = 0;
+            for (int n = lane; n < a.N; n += kWave) {
+                const int32_t v = moved(n, src[n]);
+                k += v > 0 ? v : 0;
+            }
+            over_limit = wave_sum(k) > limit;
+        }
+        if (over_limit) {
+            long long kept = 0;                       // GPUs kept on the nodes before this group of 64
+            for (int n0 = 0; n0 < a.N; n0 += kWave) {
+                const int n = n0 + lane;
+                int32_t v = n < a.N ? moved(n, src[n]) : 0;
+                const long long pos = v > 0 ? v : 0;
+                long long before = kept;              // plus the positive entries of the lower lanes
+                for (int l = 0; l < kWave; ++l) {
+                    const long long other = wave_broadcast(pos, l);
+                    if (l < lane) before += other;
+                    kept += other;
+                }
+                if (n < a.N) {
+                    if (v > 0) {
+                        const long long room = limit - before;
+                        if (v > room) v = (int32_t)(room > 0 ? room : 0);
+                    }
+                    dst[n] = v;
+                    if (v != 0) record(j, n, v);
+                }
+                nodes += __popcll(__ballot(v > 0));
+            }
+        } else if (vec4) {
             const int4 *__restrict__ s4 = (const int4 *)src;
             int4 *__restrict__ d4 = (int4 *)dst;
             const int n4 = a.N >> 2;
@@ -423,6 +460,7 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.P = d->P; a.J = d->J; a.N = d->N;
     a.parents = parents; a.node_capacity = node_capacity; a.fitness = fitness;
     a.children = children;
+    a.job_gpu_cap = ga->job_gpu_cap;
     a.order = (int32_t *)((char *)workspace + L.order);
     a.key0 = (uint32_t)(ga->seed & 0xFFFFFFFFull);
     a.key1 = (uint32_t)(ga->seed >> 32);

@@ -162,3 +162,43 @@ def test_in_place_flag_needs_the_same_buffer_and_unknown_flags_are_rejected():
         call.ga_step(a, torch.empty_like(a), SEED, 0, 8, 0, flags=px.PX_GA_IN_PLACE)
     with pytest.raises(px.PolluxError):
         call.ga_step(a, torch.empty_like(a), SEED, 0, 8, 0, flags=2)
+
+
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_job_gpu_limits_match_oracle(name):
+    """pollux_ga_params.job_gpu_cap: rows of children are cut back to the job's limit before the repairs."""
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make(name)
+    c = wl.cfg
+    fit = run_oracle(wl)["fitness"]
+    limits = np.random.default_rng(9).integers(0, 6, c.J).astype(np.int32)
+    limits[::7] = 10**6
+    assert (wl.population.sum(2) > limits[None]).any()
+    call = gpu_call(wl)
+    dl = torch.as_tensor(limits).cuda()
+    dfit = torch.as_tensor(fit).cuda()
+    parents = torch.as_tensor(wl.population).cuda()
+    children = torch.empty_like(parents)
+    call.ga_step(parents, children, SEED, 2, c.P // 2, 1 << 30, fitness=dfit, job_gpu_cap=dl)
+    want = O.ga_step(wl.population, fit, wl.node_capacity, SEED, 2, c.P // 2, 1 << 30, job_gpu_cap=limits)
+    assert np.array_equal(children.cpu().numpy(), want)
+    call.ga_step(parents, parents, SEED, 2, c.P // 2, 1 << 30, fitness=dfit, job_gpu_cap=dl, flags=px.PX_GA_IN_PLACE)
+    want = O.ga_step(wl.population, fit, wl.node_capacity, SEED, 2, c.P // 2, 1 << 30, job_gpu_cap=limits, flags=O.GA_IN_PLACE)
+    assert np.array_equal(parents.cpu().numpy(), want)
+
+
+def test_job_gpu_limits_on_long_unaligned_rows():
+    import torch
+    cfg = W.custom("ga_limits", P=6, J=9, N=300, cap=3, Gm=2, Gs=1)
+    wl = W.make(cfg)
+    rng = np.random.default_rng(4)
+    pop = (wl.population + (rng.uniform(size=wl.population.shape) < 0.2)).astype(np.int32)
+    fit = rng.uniform(size=cfg.P)
+    limits = rng.integers(0, 30, cfg.J).astype(np.int32)
+    call = gpu_call(wl)
+    parents = torch.as_tensor(pop).cuda()
+    children = torch.empty_like(parents)
+    call.ga_step(parents, children, SEED, 1, 2, 1 << 31, fitness=torch.as_tensor(fit).cuda(), job_gpu_cap=torch.as_tensor(limits).cuda())
+    want = O.ga_step(pop, fit, wl.node_capacity, SEED, 1, 2, 1 << 31, job_gpu_cap=limits)
+    assert np.array_equal(children.cpu().numpy(), want)

@@ -255,3 +255,37 @@ def test_in_place_step_is_the_out_of_place_step_with_children_in_the_slots_of_th
         inp = O.ga_step(wl.population, fit, wl.node_capacity, 77, 2, elite, 1 << 29, flags=O.GA_IN_PLACE)
         assert np.array_equal(inp[order], out)                                  # child c sits in slot order[c]
         assert np.array_equal(inp[order[:elite]], wl.population[order[:elite]])  # survivors did not move
+
+
+def test_gpu_limit_on_a_row_keeps_gpus_in_ascending_node_order():
+    assert O.cap_row([3, 0, 2, 4], 4).tolist() == [3, 0, 1, 0]
+    assert O.cap_row([3, 0, 2, 4], 5).tolist() == [3, 0, 2, 0]
+    assert O.cap_row([3, 0, 2, 4], 9).tolist() == [3, 0, 2, 4]
+    assert O.cap_row([3, 0, 2, 4], 0).tolist() == [0, 0, 0, 0]
+    assert O.cap_row([3, 0, 2, 4], -5).tolist() == [0, 0, 0, 0]
+    assert O.cap_row([0, 0, 7], 2).tolist() == [0, 0, 2]
+    rng = np.random.default_rng(5)
+    for _ in range(200):
+        row = rng.integers(0, 5, 12).astype(np.int32) * (rng.uniform(size=12) < 0.4)
+        cap = int(rng.integers(0, 20))
+        got = O.cap_row(row, cap)
+        assert got.sum() == min(cap, row.sum()) and np.all(got <= row) and np.all(got >= 0)
+        nz = np.flatnonzero(got != row)                      # everything before the first cut is intact
+        if nz.size:
+            assert np.all(got[nz[0] + 1:] == 0)
+
+
+def test_ga_step_with_job_gpu_limits():
+    wl = W.make("physical")
+    c = wl.cfg
+    fit = np.linspace(1.0, 0.1, c.P)
+    base = O.ga_step(wl.population, fit, wl.node_capacity, 5, 1, c.P // 2, 1 << 30)
+    # a limit nobody reaches changes nothing
+    same = O.ga_step(wl.population, fit, wl.node_capacity, 5, 1, c.P // 2, 1 << 30, job_gpu_cap=np.full(c.J, 10**6, np.int32))
+    assert np.array_equal(base, same)
+    limits = np.random.default_rng(6).integers(0, 4, c.J).astype(np.int32)
+    capped = O.ga_step(wl.population, fit, wl.node_capacity, 5, 1, c.P // 2, 1 << 30, job_gpu_cap=limits)
+    assert (wl.population.sum(2) > limits[None]).any()                     # the parents do break the limits
+    assert np.all(capped[c.P // 2:].sum(2) <= limits[None])                # no child does
+    assert np.array_equal(capped[:c.P // 2], base[:c.P // 2])              # survivors are kept as they are
+    assert np.all(capped >= 0)

@@ -44,6 +44,8 @@ MUTANTS = [
     ("sampling: m rounded down", "long long m = (M + (long long)K * (s + 1) - 1) / ((long long)K * (s + 1));", "long long m = M / ((long long)K * (s + 1));"),
     ("sampling: s beyond the limit accepted", "if (s > s_max) continue;", "if (s > s_max + 100) continue;"),
     ("sampling: fair share from the dense grid", "denom[j] = sampled\n", "denom[j] = !sampled\n"),
+    ("GPU limit off by one", "long room = limit - kept;", "long room = limit - kept + 1;"),
+    ("GPU limit forgets what it kept", "kept += row[n];\n    }\n}", "kept += 0;\n    }\n}"),
     ("interference repair keeps the smallest holder", "if (a > most) { most = a; keep = j; }", "if (keep < 0 || a < most) { most = a; keep = j; }"),
 ]
 
@@ -75,6 +77,8 @@ def load(path):
     L.pollux_ref_philox4x32_10.argtypes = [vp, vp, vp]
     L.pollux_fitness_ref.restype = i
     L.pollux_fitness_ref.argtypes = [ctypes.POINTER(O.Dims)] + [vp] * 6 + [d, d] + [vp] * 7
+    L.pollux_ref_cap_row.restype = None
+    L.pollux_ref_cap_row.argtypes = [vp, i, ctypes.c_int32]
     L.pollux_ref_repair.restype = None
     L.pollux_ref_repair.argtypes = [vp, i, i, vp, vp, ctypes.c_uint32, ctypes.c_uint32]
     L.pollux_ref_rank.restype = None
@@ -171,6 +175,13 @@ def pin_suite(L):
     B = np.array([[1, 2, 0], [0, 3, 1], [0, 2, 0]], np.int32)
     L.pollux_ref_repair(ptr(B), 3, 3, ptr(cap3), ptr(key), 0, 0)
     check("interference repair", B.tolist() == [[1, 0, 0], [0, 3, 1], [0, 2, 0]])
+    # per-job GPU limit: kept in ascending node order
+    row = np.array([3, 0, 2, 4], np.int32)
+    L.pollux_ref_cap_row(ptr(row), 4, 4)
+    check("GPU limit 4 on (3,0,2,4)", row.tolist() == [3, 0, 1, 0])
+    row = np.array([3, 0, 2, 4], np.int32)
+    L.pollux_ref_cap_row(ptr(row), 4, 9)
+    check("GPU limit not reached", row.tolist() == [3, 0, 2, 4])
     # whole call: the fair-share candidate scores exactly 1; a changed row is penalised; violations
     J, N, Gm, Gs = 3, 3, 8, 3
     jp = np.zeros((14, J))
