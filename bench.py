@@ -29,12 +29,15 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 # scaled by 2.0) + WRITE_SIZE (686 833 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
 # size in the same runs (profiles/pairs_kernel_large.md).  Valid for the kernel those counters were taken on.
 SWEEP_HBM_BYTES = {"large": 2077094 * 1024 * 2.0 + 686833 * 1024 * 1.0}
+# fp64 operations the same kernel executes per launch on "large", from the instruction counters of the same
+# profile: 64 lanes x (ADD_F64 + MUL_F64 + 2 x FMA_F64 wave-instructions)
+SWEEP_EXECUTED_FLOPS = {"large": 64 * (1.288e8 + 2.554e7 + 2 * 4.0316e8)}
 GA_SEED = 0x2008_1226_5EED_0001
 def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
     return (1 << 32) // J
 
 
-def cpu_baseline(wl, cfg, target_seconds=15.0):
+def cpu_baseline(wl, cfg, target_seconds=30.0):
     """The CPU checker, as it stands, on a bounded sample of the same workload (fitness + search step)."""
     import numpy as np
     import oracle as O
@@ -183,27 +186,43 @@ def main():
         # full sweep per (candidate, job), and in memoised mode (identical matrices and fitness).
         mcfg = W.CONFIGS["mid"]
         mwl = W.make(mcfg)
-        for label, flags in (("ga_loop_mid", 0), ("ga_loop_mid_memoised", px.PX_FLAG_MEMOISE)):
+        for label, flags, mut in (("ga_loop_mid", 0, mut_threshold(mcfg.J)),
+                                  ("ga_loop_mid_memoised", px.PX_FLAG_MEMOISE, mut_threshold(mcfg.J)),
+                                  ("ga_loop_mid_mutation_1_in_8", 0, 1 << 29)):
             mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid,
                                    mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta,
                                    flags=flags, device=dev)
             ma = torch.from_numpy(mwl.population).to(dev)
             for g in range(5):
                 mcall.run(ma, stream=stream, outputs="fitness")
-                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream,
-                              flags=px.PX_GA_IN_PLACE)
+                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, flags=px.PX_GA_IN_PLACE)
             torch.cuda.synchronize()
             tg0 = time.perf_counter()
             for g in range(5, 105):
                 mcall.run(ma, stream=stream, outputs="fitness", keep_job_tables=True)
-                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut_threshold(mcfg.J), stream=stream,
-                              flags=px.PX_GA_IN_PLACE)
+                mcall.ga_step(ma, ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, flags=px.PX_GA_IN_PLACE)
             torch.cuda.synchronize()
             tg1 = time.perf_counter()
             extra[label + "_generations_per_s"] = 100.0 / (tg1 - tg0)
             if not flags:
                 extra[label + "_evals_per_s"] = 100.0 * mcfg.evals_per_call / (tg1 - tg0)
             extra[label + "_best_fitness"] = float(mcall.fitness.max().item())
+
+        # one fitness call on the mid configuration in fp64 and in fp32 arithmetic (launch overhead included)
+        ma = torch.from_numpy(mwl.population).to(dev)
+        for label, precision in (("mid_fitness_call_fp64_ms", 0), ("mid_fitness_call_fp32_ms", 1)):
+            mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid,
+                                   mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta,
+                                   precision=precision, device=dev)
+            for _ in range(3):
+                mcall.run(ma, stream=stream, outputs="fitness")
+            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            f0.record(stream)
+            for _ in range(20):
+                mcall.run(ma, stream=stream, outputs="fitness")
+            f1.record(stream)
+            torch.cuda.synchronize()
+            extra[label] = f0.elapsed_time(f1) / 20
 
     out = {
         "metric": "(m,s) goodput evals/sec + GA generations/sec; % of FP64 VALU peak",
@@ -219,7 +238,9 @@ def main():
         "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": SWEEP_HBM_BYTES.get(cfg.name),
                      "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL,
-                     "avg_launch_ms": sweep_avg_ms},
+                     "avg_launch_ms": sweep_avg_ms,
+                     "executed_flop_frac": (SWEEP_EXECUTED_FLOPS[cfg.name] / (sweep_avg_ms * 1e-3) / 1e12 /
+                                            FP64_VECTOR_PEAK_TFLOPS) if cfg.name in SWEEP_EXECUTED_FLOPS else None},
         "extra": extra,
     }
     if not args.no_cpu_baseline:
