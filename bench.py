@@ -224,6 +224,23 @@ def main():
             torch.cuda.synchronize()
             extra[label] = f0.elapsed_time(f1) / 20
 
+    # the step before the path: theta_sys of all jobs of the workload fitted to synthetic records (Sec. 4.1)
+    records = W.observations(cfg, max_obs=48)
+    i32 = lambda x: torch.as_tensor(np.ascontiguousarray(x, dtype=np.int32)).to(dev)
+    rec_dev = [i32(records[k]) for k in ("count", "K", "nodes", "m", "s")] + [torch.as_tensor(records["T"]).to(dev)]
+    th_out = torch.empty((7, cfg.J), dtype=torch.float64, device=dev)
+    err_out = torch.empty(cfg.J, dtype=torch.float64, device=dev)
+    px.pollux_fit_theta(*rec_dev, th_out, err_out, max_iter=300, n_starts=3, stream=stream)
+    q0, q1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    q0.record(stream)
+    for _ in range(3):
+        px.pollux_fit_theta(*rec_dev, th_out, err_out, max_iter=300, n_starts=3, stream=stream)
+    q1.record(stream)
+    torch.cuda.synchronize()
+    extra["theta_fit_ms"] = q0.elapsed_time(q1) / 3
+    extra["theta_fit_jobs"] = cfg.J
+    extra["theta_fit_median_rmsle"] = float(err_out.median().item())
+
     out = {
         "metric": "(m,s) goodput evals/sec + GA generations/sec; % of FP64 VALU peak",
         "value": evals_per_step * args.steps / elapsed,
@@ -245,6 +262,13 @@ def main():
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(wl, cfg)
+        import oracle.theta as TH
+        tq = time.perf_counter()
+        sample = range(0, cfg.J, max(1, cfg.J // 25))
+        for j in sample:
+            n = records["count"][j]
+            TH.fit(*(records[k][j, :n] for k in ("K", "nodes", "m", "s", "T")), n_starts=3)
+        out["cpu_baseline"]["theta_fit_seconds_per_job"] = (time.perf_counter() - tq) / len(sample)
     print(json.dumps(out))
 
 

@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define POLLUX_VERSION 101
+#define POLLUX_VERSION 102
 
 typedef struct {
     int32_t P;         /* candidates in the population                          */
@@ -212,6 +212,47 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; Gm, Gs, precis
                    int32_t *children,                    /* [P,J,N] out, must not overlap parents; with
                                                             PX_GA_IN_PLACE it must equal parents */
                    void *hip_stream);
+
+/*
+ * Online fitting of theta_sys (Sec. 4.1, "Online model fitting"): for each job the seven
+ * throughput parameters (Eq. 12) that minimise the root mean squared logarithmic error
+ * between Eq. 11 and the iteration times the job has recorded, subject to every alpha and
+ * beta >= 0 and 1 <= gamma <= 10.  A record is (K, nodes, m, s, T_iter): GPUs and nodes of the
+ * allocation it was measured on (what Eq. 9 sees of it), per-GPU batch size, accumulation
+ * steps, seconds per iteration; record o of job j is element [j * max_obs + o] of each obs_*
+ * array, o < obs_count[j] <= max_obs.  K >= 1, nodes >= 1, m >= 1, s >= 0, T_iter > 0 are the
+ * caller's responsibility.
+ * "Prior-driven exploration" (same section): the node pair alpha_sync^node, beta_sync^node is
+ * held at 0 while the job has no record on more than one node, both beta_sync while it has
+ * none with more than two GPUs, and all four sync parameters while it has none with more
+ * than one GPU.
+ * The minimiser is a box-constrained damped Gauss-Newton iteration, at most max_iter steps
+ * (accepted or rejected) per starting point, one wavefront per job.  It starts from
+ * theta_init[.,j] when theta_init is given, else from T_min = min_o T_o/(s_o+1) (first record on
+ * ties): alpha_grad = T_min/2, beta_grad = T_min/(2 m at that record), alpha_sync = T_min/10,
+ * beta_sync = T_min/100, gamma = 2.  The error has several local minima; with n_starts > 1 (at
+ * most 5) the iteration is repeated from that start with the four sync parameters scaled by 3,
+ * 0.3, 0.3, 3 and gamma set to 1.2, 5, 1.2, 5, and the best end point is kept (the earliest on ties).
+ * theta[i*J + j] is parameter i of job j in the order PX_ALPHA_G .. PX_GAMMA, i.e. the first
+ * seven rows of job_params; rmsle[j] is the error reached; iterations[j] the steps taken over
+ * all starting points.
+ * A job without records gets theta = (0,0,0,0,0,0,1) and rmsle 0.
+ * Returns PX_E_INVALID_ARG for null pointers (theta_init and iterations may be NULL), J < 1,
+ * max_obs < 1, max_iter < 0 or n_starts outside 1..5.  No workspace; nothing is allocated.
+ */
+int pollux_fit_theta(int32_t J, int32_t max_obs,
+                     const int32_t *obs_count,           /* [J] */
+                     const int32_t *obs_K,               /* [J,max_obs] */
+                     const int32_t *obs_nodes,           /* [J,max_obs] */
+                     const int32_t *obs_m,               /* [J,max_obs] */
+                     const int32_t *obs_s,               /* [J,max_obs] */
+                     const double *obs_T,                /* [J,max_obs] seconds */
+                     const double *theta_init,           /* [7,J] or NULL */
+                     int32_t max_iter, int32_t n_starts,
+                     double *theta,                      /* [7,J] out */
+                     double *rmsle,                      /* [J] out */
+                     int32_t *iterations,                /* [J] out, may be NULL */
+                     void *hip_stream);
 
 /* Copies the status word of the last pollux_fitness call that used `workspace`
  * to *host_out.  Synchronises `hip_stream`. */

@@ -20,7 +20,7 @@ PX_GA_IN_PLACE = 1
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
-           "pollux_last_status", "pollux_set_sweep_events")
+           "pollux_fit_theta", "pollux_last_status", "pollux_set_sweep_events")
 
 
 class PolluxError(RuntimeError):
@@ -59,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.pollux_fitness.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz] + [vp] * 6 + [vp]
         L.pollux_ga_step.restype = i
         L.pollux_ga_step.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp, sz, vp, vp]
+        L.pollux_fit_theta.restype = i
+        L.pollux_fit_theta.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7 + [ctypes.c_int32, ctypes.c_int32] + [vp] * 4
         L.pollux_last_status.restype = i
         L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
         L.pollux_set_sweep_events.restype = i
@@ -114,6 +116,36 @@ def pollux_ga_step(dims: Dims, parents, fitness, node_capacity, ga: GaParams, wo
         workspace.numel() * workspace.element_size(), _ptr(children), _stream_handle(stream))
     if rc != PX_OK:
         raise PolluxError(rc, "pollux_ga_step")
+
+
+def pollux_fit_theta(obs_count, obs_K, obs_nodes, obs_m, obs_s, obs_T, theta, rmsle, iterations=None, theta_init=None,
+                     max_iter=200, n_starts=3, stream=None) -> None:
+    """pollux_fit_theta of the C ABI on torch device tensors (records [J,max_obs], outputs theta [7,J], rmsle [J])."""
+    J, max_obs = obs_K.shape
+    rc = lib().pollux_fit_theta(J, max_obs, _ptr(obs_count), _ptr(obs_K), _ptr(obs_nodes), _ptr(obs_m), _ptr(obs_s),
+                                _ptr(obs_T), _ptr(theta_init), max_iter, n_starts, _ptr(theta), _ptr(rmsle), _ptr(iterations),
+                                _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_fit_theta")
+
+
+def fit_theta(records: dict, theta_init=None, max_iter=200, n_starts=3, device="cuda", stream=None) -> dict:
+    """Marshal host record arrays (count [J]; K, nodes, m, s int32 [J,max_obs]; T float64 [J,max_obs]) to the
+    device, call pollux_fit_theta and return theta [7,J], rmsle [J], iterations [J] as numpy arrays."""
+    import numpy as np
+    import torch
+    dev = torch.device(device)
+    i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+    count, K, nodes, m, s = (i32(records[k]) for k in ("count", "K", "nodes", "m", "s"))
+    T = torch.as_tensor(np.ascontiguousarray(records["T"], dtype=np.float64)).to(dev)
+    J = K.shape[0]
+    theta = torch.empty((7, J), dtype=torch.float64, device=dev)
+    rmsle = torch.empty(J, dtype=torch.float64, device=dev)
+    iters = torch.empty(J, dtype=torch.int32, device=dev)
+    init = None if theta_init is None else torch.as_tensor(np.ascontiguousarray(theta_init, dtype=np.float64)).to(dev)
+    pollux_fit_theta(count, K, nodes, m, s, T, theta, rmsle, iters, init, max_iter, n_starts, stream)
+    torch.cuda.synchronize()
+    return dict(theta=theta.cpu().numpy(), rmsle=rmsle.cpu().numpy(), iterations=iters.cpu().numpy())
 
 
 def pollux_last_status(workspace, stream=None) -> int:

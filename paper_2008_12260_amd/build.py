@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpollux_hip.so")
-SOURCES = ["pollux_api.hip", "pollux_fitness.hip", "pollux_ga.hip"]
+SOURCES = ["pollux_api.hip", "pollux_fitness.hip", "pollux_ga.hip", "pollux_theta.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -121,6 +121,20 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
                               (hipStream_t)hip_stream);
 }
 
+int pollux_fit_theta(int32_t J, int32_t max_obs, const int32_t *obs_count, const int32_t *obs_K,
+                     const int32_t *obs_nodes, const int32_t *obs_m, const int32_t *obs_s, const double *obs_T,
+                     const double *theta_init, int32_t max_iter, int32_t n_starts, double *theta, double *rmsle,
+                     int32_t *iterations, void *hip_stream)
+{
+    if (J < 1 || max_obs < 1 || max_iter < 0 || n_starts < 1 || n_starts > 5) return PX_E_INVALID_ARG;
+    if ((long long)J * max_obs > 0x7FFFFFFFll) return PX_E_INVALID_ARG;
+    if (!obs_count || !obs_K || !obs_nodes || !obs_m || !obs_s || !obs_T || !theta || !rmsle) return PX_E_INVALID_ARG;
+    const int rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_fit_theta(J, max_obs, max_iter, n_starts, obs_count, obs_K, obs_nodes, obs_m, obs_s, obs_T, theta_init,
+                                theta, rmsle, iterations, (hipStream_t)hip_stream);
+}
+
 int pollux_set_sweep_events(void *hip_event_start, void *hip_event_stop)
 {
     if ((hip_event_start == nullptr) != (hip_event_stop == nullptr)) return PX_E_INVALID_ARG;

@@ -78,4 +78,8 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
                    const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
 
+int launch_fit_theta(int J, int max_obs, int max_iter, int n_starts, const int32_t *count, const int32_t *K, const int32_t *nodes,
+                     const int32_t *m, const int32_t *s, const double *T, const double *init, double *theta,
+                     double *rmsle, int32_t *iterations, hipStream_t stream);
+
 }  // namespace px

@@ -210,6 +210,54 @@ def sampled(wl: Workload) -> Workload:
     return dataclasses.replace(wl, m_grid=total_batch_grid(wl.param("M0"), wl.param("M_max"), wl.cfg.Gm))
 
 
+def observations(cfg: Config | str, max_obs: int = 48, seed: int | None = None) -> dict:
+    """Recorded (K, nodes, m, s, T_iter) tuples per job, as a job's agent would have collected them.
+
+    The times come from a measurement process of this module's own, not from the throughput model that is
+    fitted to them: a pass costs c0 + c1 m seconds, an all-reduce a latency that grows with log2(K) and is
+    dearer across nodes, the two overlap imperfectly (the longer plus 30 % of the shorter), and every
+    measurement carries 3 % log-normal noise.  Jobs differ in how far they have explored: one GPU only (10 %),
+    at most two GPUs (10 %), one node (30 %), several nodes (50 %).  Returns count [J] and K, nodes, m, s
+    int32 [J,max_obs], T float64 [J,max_obs] (unused slots hold K = nodes = m = 1, s = 0, T = 1)."""
+    if isinstance(cfg, str):
+        cfg = CONFIGS[cfg]
+    rng = np.random.Generator(np.random.PCG64((cfg.seed if seed is None else seed) + 0x0B5E))
+    J, cap = cfg.J, cfg.cap
+    _, m_max = draw_job_params(cfg, np.random.Generator(np.random.PCG64(cfg.seed)))
+    grid = m_grid(m_max, 16)
+    count = rng.integers(6, max_obs + 1, J).astype(np.int32)
+    level = rng.choice(4, J, p=[0.1, 0.1, 0.3, 0.5])
+    k_max = np.array([1, 2, cap, 4 * cap])[level]
+    c0 = rng.uniform(0.01, 0.2, J)
+    c1 = np.exp(rng.uniform(np.log(1e-5), np.log(1e-3), J))
+    lat_local = rng.uniform(0.005, 0.05, J)
+    lat_node = rng.uniform(0.02, 0.2, J)
+    K = np.ones((J, max_obs), np.int32)
+    nodes = np.ones((J, max_obs), np.int32)
+    m = np.ones((J, max_obs), np.int32)
+    s = np.zeros((J, max_obs), np.int32)
+    T = np.ones((J, max_obs), np.float64)
+    for j in range(J):
+        n = int(count[j])
+        k = rng.integers(1, k_max[j] + 1, n)
+        packed = -(-k // cap)
+        spread = np.minimum(k, rng.integers(1, 5, n))
+        nd = np.where(rng.uniform(size=n) < 0.7, packed, np.maximum(packed, spread))
+        coin = rng.uniform(size=n) < 0.5
+        if level[j] == 0 or level[j] == 2:
+            nd = np.ones(n, dtype=k.dtype)                       # one GPU, or one node (k <= cap)
+        elif level[j] == 1:
+            nd = np.where((k == 2) & coin, 2, 1)                 # two GPUs on one node or on two
+        mm = grid[j, rng.integers(0, grid.shape[1], n)]
+        ss = rng.integers(0, 4, n)
+        compute = c0[j] + c1[j] * mm
+        comm = np.where(k == 1, 0.0, np.where(nd == 1, lat_local[j], lat_node[j]) * (1.0 + 0.15 * np.log2(k)))
+        t = ss * compute + np.maximum(compute, comm) + 0.3 * np.minimum(compute, comm)
+        t = t * np.exp(0.03 * rng.standard_normal(n))
+        K[j, :n], nodes[j, :n], m[j, :n], s[j, :n], T[j, :n] = k, nd, mm, ss, t
+    return dict(count=count, K=K, nodes=nodes, m=m, s=s, T=T)
+
+
 def custom(name: str, **kw) -> Config:
     """A one-off configuration (tests use this for ragged and degenerate shapes)."""
     kw.setdefault("index", 100)
