@@ -24,6 +24,9 @@ Readings
     alpha_grad = T_min / 2, beta_grad = T_min / (2 m at that record), alpha_sync = T_min / 10,
     beta_sync = T_min / 100, gamma = 2.  Sync parameters must start above 0: at T_sync = 0 and gamma > 1 the
     derivative of Eq. 10 with respect to T_sync vanishes and a descent method never leaves 0.
+  * Local minima.  The error is not convex; which minimum a local method ends in depends on the method.  The
+    checks against the GPU library therefore pin the objective, the constraints and stationarity exactly and
+    compare the attained minimum statistically ("parity partial" for the choice among local minima).
   * Scale.  The unknowns differ by four orders of magnitude (beta_grad ~ 1e-4 s/example, gamma ~ 2), so the
     minimiser works on theta / start (gamma unscaled); the minimum is the same.
 """

@@ -202,3 +202,24 @@ def test_job_gpu_limits_on_long_unaligned_rows():
     call.ga_step(parents, children, SEED, 1, 2, 1 << 31, fitness=torch.as_tensor(fit).cuda(), job_gpu_cap=torch.as_tensor(limits).cuda())
     want = O.ga_step(pop, fit, wl.node_capacity, SEED, 1, 2, 1 << 31, job_gpu_cap=limits)
     assert np.array_equal(children.cpu().numpy(), want)
+
+
+def test_large_config_one_generation_in_place_bit_exact():
+    """The search step as bench.py runs it (in place, 2048 children formed) on the full population."""
+    import torch
+    import paper_2008_12260_amd as px
+    cfg = W.CONFIGS["large"]
+    wl = W.make(cfg, with_population=False)
+    pop = W.candidates(cfg, 0, cfg.P)
+    rng = np.random.default_rng(18)
+    fit = rng.uniform(0.2, 1.0, cfg.P)
+    fit[::20] = -3.0
+    call = gpu_call(wl)
+    dev = torch.from_numpy(pop).cuda()
+    call.ga_step(dev, dev, SEED, 7, cfg.P // 2, (1 << 32) // cfg.J, fitness=torch.as_tensor(fit).cuda(),
+                 flags=px.PX_GA_IN_PLACE)
+    got = dev.cpu().numpy()
+    del dev
+    want = O.ga_step(pop, fit, wl.node_capacity, SEED, 7, cfg.P // 2, (1 << 32) // cfg.J, flags=O.GA_IN_PLACE)
+    for lo in range(0, cfg.P, 256):
+        assert np.array_equal(got[lo:lo + 256], want[lo:lo + 256]), f"candidates {lo}..{lo + 255}"
