@@ -78,7 +78,7 @@ struct FitnessArgs {
     double p, delta;
     // workspace
     int32_t *status;
-    double *rs, *sv, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
     unsigned long long *fmask;    // [J,kTableK,ni,gs_pad] feasibility lane masks (see last_kernel)
     int ni, gs_pad;               // ceil(Gm / 64); Gs rounded up to a multiple of 32
     int32_t *running, *meta;
@@ -135,16 +135,13 @@ __device__ __forceinline__ SyncParams load_sync(const Job &q)
 // M0 <= K m (s+1) <= M_max holds exactly when ceil(M0/m) <= K (s+1) <= floor(M_max/m),
 // i.e. for s between trunc(ql5 / K) and trunc(qh5 / K) - 1; the halves keep the
 // quotients at least 1/(2K) away from an integer, so a rounded 1/K cannot move them
-// across one.  Also rs[s] = 1/(s+1), sv[s] = s, rk[K] = 1/K, and the status word is cleared.
+// across one.  Also rs[s] = 1/(s+1), rk[K] = 1/K, and the status word is cleared.
 __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0) *a.status = 0;
     const int rs_len = ((a.Gs + 31) / 32) * 32;
-    if (t < rs_len) {
-        a.rs[t] = 1.0 / (double)(t + 1);
-        a.sv[t] = (double)t;
-    }
+    if (t < rs_len) a.rs[t] = 1.0 / (double)(t + 1);
     if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
     if (t < a.J * a.Gm) {
         const int j = t / a.Gm;
@@ -266,44 +263,8 @@ struct JobTables {
     const double *__restrict__ tg, *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
     const double *__restrict__ lt;    // rows of this job in the last-pass table
     const unsigned long long *__restrict__ fmask;   // feasibility masks of this job, [kTableK, ni, gs_pad]
-    const double *__restrict__ sv;    // sv[s] = s
     int ni, gs_pad;
 };
-
-__device__ __forceinline__ double vmin(double a, double b)
-{
-    double r;
-    asm("v_min_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
-__device__ __forceinline__ double vmax(double a, double b)
-{
-    double r;
-    asm("v_max_f64 %0, %1, %2" : "=v"(r) : "v"(a), "v"(b));
-    return r;
-}
-
-// A value that is the same in every lane, moved to scalar registers.
-__device__ __forceinline__ double uniform(double v)
-{
-    return __hiloint2double(__builtin_amdgcn_readfirstlane(__double2hiint(v)),
-                            __builtin_amdgcn_readfirstlane(__double2loint(v)));
-}
-
-__device__ __forceinline__ unsigned long long uniform(unsigned long long v)
-{
-    return ((unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(v >> 32)) << 32) |
-           (unsigned long long)(unsigned)__builtin_amdgcn_readfirstlane((int)(v & 0xFFFFFFFFull));
-}
-
-template <int STEP = 0>
-__device__ __forceinline__ double wave_vmax(double v)
-{
-    v = vmax(v, exchange<STEP>(v));
-    if constexpr (STEP < 5) return wave_vmax<STEP + 1>(v);
-    return v;
-}
 
 // Wave-wide argmax of non-negative goodput values g (0 = the lane has no point): positive
 // doubles order like their bit patterns, so the maximum is found as two unsigned 32-bit
@@ -533,7 +494,7 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 {
     const size_t o = (size_t)j * a.Gm;
     return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
-                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.fmask + (size_t)j * kTableK * a.ni * a.gs_pad, a.sv, a.ni, a.gs_pad};
+                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.fmask + (size_t)j * kTableK * a.ni * a.gs_pad, a.ni, a.gs_pad};
 }
 
 // ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
@@ -1016,7 +977,6 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.p = p; a.delta = delta;
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
-    a.sv = (double *)(ws + L.sv);
     a.rk = (double *)(ws + L.rk);
     a.tg = (double *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);

@@ -17,7 +17,6 @@ constexpr int kTableK = 64;
 struct WorkspaceLayout {
     size_t status;    // int32 status word
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
-    size_t sv;        // double [as rs]   s as a double
     size_t rk;        // double [256]     1/K
     size_t tg;        // double [J,Gm]    T_grad(m_i)
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
@@ -46,7 +45,6 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
-    L.sv = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
     L.rk = o;      o = up(o + 8 * 256);
     L.tg = o;      o = up(o + 8 * J * Gm);
     L.lntg = o;    o = up(o + 8 * J * Gm);
