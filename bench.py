@@ -241,6 +241,21 @@ def main():
     extra["theta_fit_jobs"] = cfg.J
     extra["theta_fit_median_rmsle"] = float(err_out.median().item())
 
+    if not args.no_ga_loop:
+        # the scheduling loop on the mid configuration: per interval 20 generations from the current allocation,
+        # the best matrix applied, one simulator tick (the paper reports about 1 s per 60 s interval on one vCPU)
+        from paper_2008_12260_amd import closed_loop
+        lwl = W.make("mid", with_population=False, current="fair")
+        lcfg = lwl.cfg
+        largs = (lwl.job_params, lwl.m_grid, lwl.fair_share, lwl.node_capacity, np.full(lcfg.J, 1e7),
+                 W.noise_scale_schedule(lwl.param("phi")), lwl.current_alloc)
+        lkw = dict(P=lcfg.P, Gs=lcfg.Gs, p=lcfg.p, delta=lcfg.delta, generations=20, seed=GA_SEED)
+        closed_loop.run(*largs, intervals=1, **lkw)
+        tl0 = time.perf_counter()
+        lstate = closed_loop.run(*largs, intervals=5, **lkw)
+        extra["closed_loop_mid_ms_per_interval"] = (time.perf_counter() - tl0) * 1e3 / 5
+        extra["closed_loop_mid_best_fitness"] = lstate.history[-1]["best_fitness"]
+
     out = {
         "metric": "(m,s) goodput evals/sec + GA generations/sec; % of FP64 VALU peak",
         "value": evals_per_step * args.steps / elapsed,

@@ -30,7 +30,7 @@
 extern "C" {
 #endif
 
-#define POLLUX_VERSION 102
+#define POLLUX_VERSION 103
 
 typedef struct {
     int32_t P;         /* candidates in the population                          */
@@ -253,6 +253,57 @@ int pollux_fit_theta(int32_t J, int32_t max_obs,
                      double *rmsle,                      /* [J] out */
                      int32_t *iterations,                /* [J] out, may be NULL */
                      void *hip_stream);
+
+/*
+ * Goodput-based auto-scaling (Sec. 5.3.3, "Cloud auto-scaling"), in two calls.
+ *
+ * pollux_goodput_per_gpu: per_gpu[j*(max_nodes+1) + 0] = max over (m, s) of GOODPUT of job j on one GPU, the
+ * "predicted ideal goodput assuming perfect scalability" per GPU; per_gpu[j*(max_nodes+1) + n], n = 1..max_nodes,
+ * = max over (m, s) of GOODPUT on n full nodes (K = n * gpus_per_node GPUs on n nodes) divided by K.  The
+ * maximum is the one of Eq. 13 over the same grid as pollux_fitness (dims->Gm, dims->Gs, m_grid); dims->P and
+ * dims->N only size the workspace (pollux_workspace_size(dims)) and may be 1; precision 0 and flags 0 only.
+ *
+ * pollux_autoscale: job j, now on nodes_now[j] nodes, scales up when per_gpu[j][nodes_now[j]] > U * per_gpu[j][0];
+ * nodes are then added one at a time while the next count still has per_gpu >= L * per_gpu[j][0] and does not
+ * exceed max_nodes.  Otherwise (or with nodes_now[j] outside 1..max_nodes) nodes_new[j] = nodes_now[j].  The
+ * paper uses U = 2/3, L = 1/2.
+ */
+int pollux_goodput_per_gpu(const pollux_dims *dims,      /* host */
+                           const double *job_params,     /* [PX_NPARAM,J] */
+                           const int32_t *m_grid,        /* [J,Gm] */
+                           int32_t gpus_per_node, int32_t max_nodes,
+                           void *workspace, size_t workspace_bytes,
+                           double *per_gpu,              /* [J,max_nodes+1] out */
+                           void *hip_stream);
+int pollux_autoscale(int32_t J, int32_t max_nodes,
+                     const double *per_gpu,              /* [J,max_nodes+1] */
+                     const int32_t *nodes_now,           /* [J] */
+                     double U, double L,
+                     int32_t *nodes_new,                 /* [J] out */
+                     void *hip_stream);
+
+/*
+ * One interval of a discrete-time simulation of the jobs (Sec. 5.3, "Simulator construction", "Simulator
+ * fidelity"; the paper replays measured profiles, this call replays the goodput model itself).  Job j holds
+ * K[j] GPUs on nodes[j] nodes.  Its goodput[j] is the maximum of Eq. 13 there (the batch size and
+ * accumulation steps its agent would choose), 0 if K[j] = 0 or the job has finished; its progress[j]
+ * (in/out, examples at the efficiency of the initial batch size) advances by
+ * goodput[j] * (dt - restart_delay if changed[j] != 0), never backwards; finished[j] = progress[j] >= target[j].
+ * dims as for pollux_goodput_per_gpu.
+ */
+int pollux_sim_tick(const pollux_dims *dims,             /* host */
+                    const double *job_params,            /* [PX_NPARAM,J] */
+                    const int32_t *m_grid,               /* [J,Gm] */
+                    const int32_t *K,                    /* [J] */
+                    const int32_t *nodes,                /* [J] */
+                    const int32_t *changed,              /* [J] allocation changed in this interval */
+                    const double *target,                /* [J] */
+                    double dt, double restart_delay,     /* seconds; the paper injects 30 s per re-allocation */
+                    void *workspace, size_t workspace_bytes,
+                    double *progress,                    /* [J] in/out */
+                    double *goodput,                     /* [J] out */
+                    int32_t *finished,                   /* [J] out */
+                    void *hip_stream);
 
 /* Copies the status word of the last pollux_fitness call that used `workspace`
  * to *host_out.  Synchronises `hip_stream`. */

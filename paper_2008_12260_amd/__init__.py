@@ -13,6 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpollux_hip.so")
 
 NPARAM = 14
+PARAM_PHI = 7            # row of job_params that holds the gradient noise scale (PX_PHI)
 PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
 PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
 PX_FLAG_SAMPLE_M = 16
@@ -20,7 +21,8 @@ PX_GA_IN_PLACE = 1
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
-           "pollux_fit_theta", "pollux_last_status", "pollux_set_sweep_events")
+           "pollux_fit_theta", "pollux_goodput_per_gpu", "pollux_autoscale", "pollux_sim_tick", "pollux_last_status",
+           "pollux_set_sweep_events")
 
 
 class PolluxError(RuntimeError):
@@ -61,6 +63,12 @@ def lib() -> ctypes.CDLL:
         L.pollux_ga_step.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp, sz, vp, vp]
         L.pollux_fit_theta.restype = i
         L.pollux_fit_theta.argtypes = [ctypes.c_int32, ctypes.c_int32] + [vp] * 7 + [ctypes.c_int32, ctypes.c_int32] + [vp] * 4
+        L.pollux_goodput_per_gpu.restype = i
+        L.pollux_goodput_per_gpu.argtypes = [ctypes.POINTER(Dims), vp, vp, ctypes.c_int32, ctypes.c_int32, vp, sz, vp, vp]
+        L.pollux_autoscale.restype = i
+        L.pollux_autoscale.argtypes = [ctypes.c_int32, ctypes.c_int32, vp, vp, d, d, vp, vp]
+        L.pollux_sim_tick.restype = i
+        L.pollux_sim_tick.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz, vp, vp, vp, vp]
         L.pollux_last_status.restype = i
         L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
         L.pollux_set_sweep_events.restype = i
@@ -146,6 +154,31 @@ def fit_theta(records: dict, theta_init=None, max_iter=200, n_starts=3, device="
     pollux_fit_theta(count, K, nodes, m, s, T, theta, rmsle, iters, init, max_iter, n_starts, stream)
     torch.cuda.synchronize()
     return dict(theta=theta.cpu().numpy(), rmsle=rmsle.cpu().numpy(), iterations=iters.cpu().numpy())
+
+
+def pollux_goodput_per_gpu(dims: Dims, job_params, m_grid, gpus_per_node, max_nodes, workspace, per_gpu, stream=None) -> None:
+    rc = lib().pollux_goodput_per_gpu(ctypes.byref(dims), _ptr(job_params), _ptr(m_grid), gpus_per_node, max_nodes,
+                                      _ptr(workspace), workspace.numel() * workspace.element_size(), _ptr(per_gpu),
+                                      _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_goodput_per_gpu")
+
+
+def pollux_autoscale(per_gpu, nodes_now, U, L, nodes_new, stream=None) -> None:
+    J, cols = per_gpu.shape
+    rc = lib().pollux_autoscale(J, cols - 1, _ptr(per_gpu), _ptr(nodes_now), U, L, _ptr(nodes_new), _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_autoscale")
+
+
+def pollux_sim_tick(dims: Dims, job_params, m_grid, K, nodes, changed, target, dt, restart_delay, workspace, progress,
+                    goodput, finished, stream=None) -> None:
+    rc = lib().pollux_sim_tick(ctypes.byref(dims), _ptr(job_params), _ptr(m_grid), _ptr(K), _ptr(nodes), _ptr(changed),
+                               _ptr(target), dt, restart_delay, _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _ptr(progress), _ptr(goodput),
+                               _ptr(finished), _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_sim_tick")
 
 
 def pollux_last_status(workspace, stream=None) -> int:

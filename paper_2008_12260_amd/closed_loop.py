@@ -1,0 +1,80 @@
+"""A scheduling loop on synthetic jobs, built from the library's calls only (Pollux, arXiv 2008.12260,
+Sec. 4: every scheduling interval PolluxSched searches for a better allocation matrix, applies the best one,
+and the jobs run on it until the next interval; Sec. 5.3: discrete-time simulation with a restart delay).
+
+Per interval:
+  1. the jobs' gradient noise scale phi_t is refreshed from their progress (the caller's `phi_of` function);
+  2. the population search runs `generations` steps of pollux_fitness + pollux_ga_step (in place) from a
+     population seeded with the current allocation, and the best candidate of the last evaluation is taken;
+  3. jobs whose row changed are marked re-allocated;
+  4. pollux_sim_tick advances every job on its new allocation.
+
+This module marshals arguments and moves a few small arrays between host and device; every step of the
+method runs in the library's kernels.  It fails if the library is missing, like the rest of the package.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass, field
+
+import numpy as np
+
+from . import (PX_FLAG_MEMOISE, PX_GA_IN_PLACE, Dims, FitnessCall, PARAM_PHI, pollux_sim_tick)
+
+
+@dataclass
+class LoopState:
+    alloc: np.ndarray                 # int32 [J,N] current allocation
+    progress: np.ndarray              # float64 [J]
+    finished: np.ndarray              # bool [J]
+    interval: int = 0
+    history: list = field(default_factory=list)
+
+
+def run(job_params, m_grid, fair_share, node_capacity, target, phi_of, alloc0, *, P=256, Gs=16, p=-1.0, delta=30.0,
+        interval_s=60.0, restart_delay=30.0, generations=20, intervals=10, seed=1, memoise=True, on_interval=None):
+    """Run `intervals` scheduling intervals; returns the final LoopState.
+
+    phi_of(progress / target) -> phi_t per job (numpy, float64 [J]); on_interval(state, record) is called after
+    every interval with a dict holding what was decided and measured (for tests and reports)."""
+    import torch
+    job_params = np.array(job_params, dtype=np.float64, copy=True)
+    J, Gm = m_grid.shape
+    N = len(node_capacity)
+    dev = torch.device("cuda")
+    state = LoopState(alloc=np.array(alloc0, dtype=np.int32, copy=True), progress=np.zeros(J), finished=np.zeros(J, bool))
+    d_target = torch.as_tensor(np.asarray(target, np.float64)).to(dev)
+    d_progress = torch.zeros(J, dtype=torch.float64, device=dev)
+    d_goodput = torch.empty(J, dtype=torch.float64, device=dev)
+    d_finished = torch.empty(J, dtype=torch.int32, device=dev)
+    mut = max(1, (1 << 32) // J)
+    for it in range(intervals):
+        job_params[PARAM_PHI] = phi_of(np.minimum(state.progress / np.asarray(target, np.float64), 1.0))
+        call = FitnessCall(P, J, N, Gm, Gs, job_params, m_grid, fair_share, state.alloc, node_capacity, p=p, delta=delta,
+                           flags=PX_FLAG_MEMOISE if memoise else 0, device=dev)
+        pop = torch.as_tensor(state.alloc).to(dev).unsqueeze(0).repeat(P, 1, 1).contiguous()
+        for g in range(generations):
+            call.run(pop, outputs="fitness", keep_job_tables=g > 0)
+            call.ga_step(pop, pop, seed, it * generations + g, max(1, P // 2), mut, flags=PX_GA_IN_PLACE)
+        call.run(pop, outputs="fitness", keep_job_tables=True)
+        best = int(torch.argmax(call.fitness).item())
+        best_fitness = float(call.fitness[best].item())
+        new_alloc = pop[best].cpu().numpy()
+        changed = (new_alloc != state.alloc).any(axis=1) & (state.alloc.sum(axis=1) > 0)
+        K = new_alloc.sum(axis=1).astype(np.int32)
+        nodes = (new_alloc > 0).sum(axis=1).astype(np.int32)
+        i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+        pollux_sim_tick(Dims(P, J, N, Gm, Gs, 0, 0), call.job_params, call.m_grid, i32(K), i32(nodes), i32(changed), d_target, interval_s,
+                        restart_delay, call.workspace, d_progress, d_goodput, d_finished)
+        record = dict(interval=it, phi=job_params[PARAM_PHI].copy(), previous_alloc=state.alloc, alloc=new_alloc,
+                      best_fitness=best_fitness, changed=changed, progress_before=state.progress.copy(),
+                      goodput=d_goodput.cpu().numpy(), status=call.status())
+        state.alloc = new_alloc
+        state.progress = d_progress.cpu().numpy()
+        state.finished = d_finished.cpu().numpy().astype(bool)
+        state.interval = it + 1
+        record["progress"] = state.progress.copy()
+        state.history.append(dict(interval=it, best_fitness=best_fitness, gpus=int(K.sum()), changed=int(changed.sum()),
+                                  finished=int(state.finished.sum())))
+        if on_interval is not None:
+            on_interval(state, record)
+    return state

@@ -121,6 +121,59 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
                               (hipStream_t)hip_stream);
 }
 
+namespace {
+
+// dims of the calls that use the job-level tables only: the grid sweep in fp64, no flags
+bool query_dims_ok(const pollux_dims *d)
+{
+    return dims_ok(d, true) && d->precision == 0 && d->flags == 0;
+}
+
+}  // namespace
+
+int pollux_goodput_per_gpu(const pollux_dims *dims, const double *job_params, const int32_t *m_grid,
+                           int32_t gpus_per_node, int32_t max_nodes, void *workspace, size_t workspace_bytes,
+                           double *per_gpu, void *hip_stream)
+{
+    if (!query_dims_ok(dims) || !job_params || !m_grid || !per_gpu) return PX_E_INVALID_ARG;
+    if (gpus_per_node < 1 || max_nodes < 1) return PX_E_INVALID_ARG;
+    if ((long long)gpus_per_node * max_nodes > 0x7FFFFFFFll || (long long)dims->J * (max_nodes + 1ll) > 0x7FFFFFFFll)
+        return PX_E_INVALID_ARG;
+    int rc = check_workspace(dims, workspace, workspace_bytes);
+    if (rc != PX_OK) return rc;
+    rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_goodput_per_gpu(dims, job_params, m_grid, gpus_per_node, max_nodes, workspace, per_gpu,
+                                      (hipStream_t)hip_stream);
+}
+
+int pollux_autoscale(int32_t J, int32_t max_nodes, const double *per_gpu, const int32_t *nodes_now, double U, double L,
+                     int32_t *nodes_new, void *hip_stream)
+{
+    if (J < 1 || max_nodes < 1 || !per_gpu || !nodes_now || !nodes_new) return PX_E_INVALID_ARG;
+    if (!isfinite(U) || !isfinite(L)) return PX_E_INVALID_ARG;
+    const int rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_autoscale(J, max_nodes, per_gpu, nodes_now, U, L, nodes_new, (hipStream_t)hip_stream);
+}
+
+int pollux_sim_tick(const pollux_dims *dims, const double *job_params, const int32_t *m_grid, const int32_t *K,
+                    const int32_t *nodes, const int32_t *changed, const double *target, double dt, double restart_delay,
+                    void *workspace, size_t workspace_bytes, double *progress, double *goodput, int32_t *finished,
+                    void *hip_stream)
+{
+    if (!query_dims_ok(dims) || !job_params || !m_grid || !K || !nodes || !changed || !target || !progress || !goodput ||
+        !finished)
+        return PX_E_INVALID_ARG;
+    if (!isfinite(dt) || !isfinite(restart_delay) || dt < 0.0 || restart_delay < 0.0) return PX_E_INVALID_ARG;
+    int rc = check_workspace(dims, workspace, workspace_bytes);
+    if (rc != PX_OK) return rc;
+    rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_sim_tick(dims, job_params, m_grid, K, nodes, changed, target, dt, restart_delay, workspace,
+                               progress, goodput, finished, (hipStream_t)hip_stream);
+}
+
 int pollux_fit_theta(int32_t J, int32_t max_obs, const int32_t *obs_count, const int32_t *obs_K,
                      const int32_t *obs_nodes, const int32_t *obs_m, const int32_t *obs_s, const double *obs_T,
                      const double *theta_init, int32_t max_iter, int32_t n_starts, double *theta, double *rmsle,

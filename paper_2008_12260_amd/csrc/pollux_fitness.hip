@@ -877,6 +877,72 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     }
 }
 
+// ---- the argmax alone, for the consumers outside the search ----------------------------
+// One wavefront per query (job, K, nodes): the same sweep and pricing as a (candidate, job) pair.
+//   per_gpu mode   query (j, n), n = 0..max_nodes: column 0 is the job on one GPU, column n >= 1
+//                  the job on n full nodes of gpus_per_node GPUs; the goodput is divided by the
+//                  GPUs held (auto-scaling rule of Sec. 5.3.3)
+//   tick mode      query j: the job at its current (K, nodes); its progress advances by
+//                  goodput x (dt - restart delay if its allocation was changed) (Sec. 5.3)
+struct QueryArgs {
+    int mode;                       // 0 per_gpu, 1 tick
+    int gpus_per_node, max_nodes;
+    double *per_gpu;                // [J, max_nodes + 1]
+    const int32_t *K, *nodes, *changed;
+    const double *target;
+    double dt, restart_delay;
+    double *progress, *goodput;
+    int32_t *finished;
+};
+
+template <int CH>
+__global__ void __launch_bounds__(256) queries_kernel(FitnessArgs a, QueryArgs q)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const long long id = (long long)blockIdx.x * kWavesPerBlock + wave;
+    const int per_job = q.mode == 0 ? q.max_nodes + 1 : 1;
+    if (id >= (long long)a.J * per_job) return;
+    const int j = (int)(id / per_job), n = (int)(id % per_job);
+    int K, nodes;
+    if (q.mode == 0) {
+        K = n == 0 ? 1 : n * q.gpus_per_node;
+        nodes = n == 0 ? 1 : n;
+    } else {
+        K = q.K[j];
+        nodes = q.nodes[j];
+        if (!(q.progress[j] < q.target[j])) K = 0;              // a finished job is left as it is
+    }
+    Best best = {0.0, -1, -1};
+    if (K > 0) best = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+    if (lane_id() != 0) return;
+    if (q.mode == 0) {
+        q.per_gpu[id] = best.goodput / (double)K;
+    } else {
+        const double before = q.progress[j];
+        const double run = q.dt - (q.changed[j] ? q.restart_delay : 0.0);
+        const double after = (K > 0 && run > 0.0) ? before + best.goodput * run : before;
+        q.goodput[j] = best.goodput;
+        q.progress[j] = after;
+        q.finished[j] = after >= q.target[j];
+    }
+}
+
+// Sec. 5.3.3: a job scales up when its goodput per GPU exceeds U of the ideal (one GPU, column 0), to the
+// node count reached by adding nodes while the next count still predicts at least L of the ideal per GPU.
+__global__ void __launch_bounds__(256) autoscale_kernel(int J, int max_nodes, const double *__restrict__ per_gpu,
+                                                       const int32_t *__restrict__ nodes_now, double U, double L,
+                                                       int32_t *__restrict__ nodes_new)
+{
+    const int j = blockIdx.x * blockDim.x + threadIdx.x;
+    if (j >= J) return;
+    const double *__restrict__ row = per_gpu + (size_t)j * (max_nodes + 1);
+    int n = nodes_now[j];
+    if (n >= 1 && n <= max_nodes && row[n] > U * row[0]) {
+        while (n < max_nodes && row[n + 1] >= L * row[0]) ++n;
+    }
+    nodes_new[j] = n;
+}
+
 // ---- per candidate -------------------------------------------------------------
 
 constexpr int kCandThreads = 256;
@@ -962,6 +1028,80 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
 // ---- host side -----------------------------------------------------------------
 
 namespace px {
+
+// The job-level part of the arguments: dimensions, inputs that describe the jobs, workspace sections.
+static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params, const int32_t *m_grid, void *workspace)
+{
+    const WorkspaceLayout L = workspace_layout(*d);
+    char *ws = (char *)workspace;
+    FitnessArgs a = {};
+    a.P = d->P; a.J = d->J; a.N = d->N; a.Gm = d->Gm; a.Gs = d->Gs; a.flags = d->flags;
+    a.m_grid = m_grid; a.job_params = job_params;
+    a.status = (int32_t *)(ws + L.status);
+    a.rs = (double *)(ws + L.rs);
+    a.rk = (double *)(ws + L.rk);
+    a.tg = (double *)(ws + L.tg);
+    a.lntg = (double *)(ws + L.lntg);
+    a.pu = (double *)(ws + L.pu);
+    a.qh5 = (double *)(ws + L.qh5);
+    a.ql5 = (double *)(ws + L.ql5);
+    a.lt = (double *)(ws + L.lt);
+    a.fmask = (unsigned long long *)(ws + L.fmask);
+    a.ni = (d->Gm + 63) / 64;
+    a.gs_pad = ((d->Gs + 31) / 32) * 32;
+    return a;
+}
+
+// tables_kernel and last_kernel: everything the sweep of a (job, K, nodes) needs
+static void launch_job_tables(const pollux_dims *d, const FitnessArgs &a, hipStream_t stream)
+{
+    long long table_items = (long long)d->J * d->Gm;
+    if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
+    if (table_items < kRecipTable) table_items = kRecipTable;
+    hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
+    const long long lt_rows = (long long)d->J * 2 * kTableK;
+    hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+}
+
+static int launch_queries(const pollux_dims *d, const double *job_params, const int32_t *m_grid, void *workspace,
+                          const QueryArgs &q, hipStream_t stream)
+{
+    const FitnessArgs a = job_level_args(d, job_params, m_grid, workspace);
+    launch_job_tables(d, a, stream);
+    const long long queries = (long long)d->J * (q.mode == 0 ? q.max_nodes + 1 : 1);
+    const dim3 grid((unsigned)((queries + kWavesPerBlock - 1) / kWavesPerBlock));
+    const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
+    if (ch == 8) hipLaunchKernelGGL((queries_kernel<8>), grid, dim3(256), 0, stream, a, q);
+    else if (ch == 16) hipLaunchKernelGGL((queries_kernel<16>), grid, dim3(256), 0, stream, a, q);
+    else hipLaunchKernelGGL((queries_kernel<32>), grid, dim3(256), 0, stream, a, q);
+    return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
+}
+
+int launch_goodput_per_gpu(const pollux_dims *d, const double *job_params, const int32_t *m_grid, int gpus_per_node,
+                           int max_nodes, void *workspace, double *per_gpu, hipStream_t stream)
+{
+    QueryArgs q = {};
+    q.mode = 0; q.gpus_per_node = gpus_per_node; q.max_nodes = max_nodes; q.per_gpu = per_gpu;
+    return launch_queries(d, job_params, m_grid, workspace, q, stream);
+}
+
+int launch_autoscale(int J, int max_nodes, const double *per_gpu, const int32_t *nodes_now, double U, double L,
+                     int32_t *nodes_new, hipStream_t stream)
+{
+    hipLaunchKernelGGL(autoscale_kernel, dim3((unsigned)((J + 255) / 256)), dim3(256), 0, stream, J, max_nodes, per_gpu,
+                       nodes_now, U, L, nodes_new);
+    return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
+}
+
+int launch_sim_tick(const pollux_dims *d, const double *job_params, const int32_t *m_grid, const int32_t *K,
+                    const int32_t *nodes, const int32_t *changed, const double *target, double dt, double restart_delay,
+                    void *workspace, double *progress, double *goodput, int32_t *finished, hipStream_t stream)
+{
+    QueryArgs q = {};
+    q.mode = 1; q.K = K; q.nodes = nodes; q.changed = changed; q.target = target; q.dt = dt;
+    q.restart_delay = restart_delay; q.progress = progress; q.goodput = goodput; q.finished = finished;
+    return launch_queries(d, job_params, m_grid, workspace, q, stream);
+}
 
 int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,

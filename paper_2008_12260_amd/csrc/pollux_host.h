@@ -76,6 +76,16 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
                    const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
 
+int launch_goodput_per_gpu(const pollux_dims *d, const double *job_params, const int32_t *m_grid, int gpus_per_node,
+                           int max_nodes, void *workspace, double *per_gpu, hipStream_t stream);
+
+int launch_autoscale(int J, int max_nodes, const double *per_gpu, const int32_t *nodes_now, double U, double L,
+                     int32_t *nodes_new, hipStream_t stream);
+
+int launch_sim_tick(const pollux_dims *d, const double *job_params, const int32_t *m_grid, const int32_t *K,
+                    const int32_t *nodes, const int32_t *changed, const double *target, double dt, double restart_delay,
+                    void *workspace, double *progress, double *goodput, int32_t *finished, hipStream_t stream);
+
 int launch_fit_theta(int J, int max_obs, int max_iter, int n_starts, const int32_t *count, const int32_t *K, const int32_t *nodes,
                      const int32_t *m, const int32_t *s, const double *T, const double *init, double *theta,
                      double *rmsle, int32_t *iterations, hipStream_t stream);

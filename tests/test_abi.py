@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = px.lib()
     for n in names:
         assert getattr(L, n) is not None
-    assert px.version() == 102
+    assert px.version() == 103
     assert px.strerror(0) == "success" and "workspace" in px.strerror(px.PX_E_WORKSPACE)
     assert px.strerror(-99) == "unknown error code"
 

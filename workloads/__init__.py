@@ -258,6 +258,14 @@ def observations(cfg: Config | str, max_obs: int = 48, seed: int | None = None) 
     return dict(count=count, K=K, nodes=nodes, m=m, s=s, T=T)
 
 
+def noise_scale_schedule(phi_start: np.ndarray, growth: float = 100.0):
+    """The simulated environment's gradient noise scale: it grows geometrically with training progress, from
+    phi_start at the beginning to growth * phi_start at the target (the paper observes growth over training,
+    Sec. 3.1; the shape here is synthetic).  Returns phi_of(fraction done) for the closed loop."""
+    phi_start = np.asarray(phi_start, np.float64).copy()
+    return lambda done: phi_start * growth ** np.clip(done, 0.0, 1.0)
+
+
 def custom(name: str, **kw) -> Config:
     """A one-off configuration (tests use this for ragged and degenerate shapes)."""
     kw.setdefault("index", 100)
