@@ -48,6 +48,7 @@ struct GaArgs {
     const double *fitness;
     int32_t *children, *order;
     uint32_t key0, key1, generation, elite_k, mut_threshold;
+    int max_entries;   // capacity of the per-node entry lists in LDS
     int in_place;      // children == parents: only children c >= elite_k are formed, child c goes to slot order[c]
 };
 
@@ -99,7 +100,14 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 // fallback; __syncthreads() orders those accesses (one CU, one L1).
 
 constexpr int kGaThreads = 512;     // eight wavefronts keep enough row loads in flight to approach copy bandwidth
-constexpr int kGaMaxEntries = 3072;
+// Capacity of the per-node entry lists: one and a half entries per job (allocations hold a little more than one
+// node per job), in steps of 256, between 512 and 3072.  Fewer entries mean less LDS per workgroup and more
+// workgroups per CU, i.e. more rows in flight; a matrix with more positive entries takes the column path.
+inline int ga_max_entries(int J)
+{
+    long long e = (((long long)J * 3 / 2 + 255) / 256) * 256;
+    return (int)(e < 512 ? 512 : (e > 3072 ? 3072 : e));
+}
 
 struct GaShared {
     unsigned long long *colsum;
@@ -107,7 +115,7 @@ struct GaShared {
     int32_t *ent_j, *ent_v, *ent_next;
 };
 
-__device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N)
+__device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N, int max_entries)
 {
     GaShared sh;
     sh.colsum = (unsigned long long *)base;                         // 8-byte aligned first
@@ -118,12 +126,12 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.decx = sh.dec + J;
     sh.head = sh.decx + J;
     sh.ent_j = sh.head + N;
-    sh.ent_v = sh.ent_j + kGaMaxEntries;
-    sh.ent_next = sh.ent_v + kGaMaxEntries;
+    sh.ent_v = sh.ent_j + max_entries;
+    sh.ent_next = sh.ent_v + max_entries;
     return sh;
 }
 
-inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)kGaMaxEntries; }
+inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J); }
 
 // Number of positive entries of a row; every lane returns the same value.
 __device__ __forceinline__ int count_occupied(const int32_t *__restrict__ row, int N, int lane)
@@ -186,7 +194,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         return;
     }
 
-    const GaShared sh = carve_shared(ga_lds, a.J, a.N);
+    const GaShared sh = carve_shared(ga_lds, a.J, a.N, a.max_entries);
     for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1; }
     if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; }
 
@@ -218,7 +226,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
         if (v > 0) {
             const int e = atomicAdd(&n_ent, 1);
-            if (e < kGaMaxEntries) {
+            if (e < a.max_entries) {
                 sh.ent_j[e] = j;
                 sh.ent_v[e] = v;
                 sh.ent_next[e] = atomicExch(&sh.head[n], e);
@@ -333,7 +341,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     }
     __syncthreads();
 
-    if (n_ent <= kGaMaxEntries) {
+    if (n_ent <= a.max_entries) {
         // ---- step B on the node lists ----
         for (int n = tid; n < a.N; n += kGaThreads) {
             long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
@@ -466,6 +474,7 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.key1 = (uint32_t)(ga->seed >> 32);
     a.generation = ga->generation; a.elite_k = ga->elite_k; a.mut_threshold = ga->mut_threshold;
     a.in_place = (ga->flags & PX_GA_IN_PLACE) ? 1 : 0;
+    a.max_entries = ga_max_entries(d->J);
 
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);

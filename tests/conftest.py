@@ -13,7 +13,7 @@ def pytest_configure(config):
 
 
 def pytest_collection_modifyitems(config, items):
-    """Skip GPU tests cleanly where no device is visible (they are selected with -m gpu on the GPU machine)."""
+    """Skip GPU tests cleanly where no device is visible (they are selected with -m gpu where a device is present)."""
     try:
         import torch
         have_gpu = torch.cuda.is_available()
