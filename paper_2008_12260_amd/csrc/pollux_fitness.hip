@@ -244,9 +244,16 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
         const int i = g * kWave + lane;
         int s_lo = 1, s_hi = 0;
         if (i < a.Gm) feasible_range(a.ql5[o + i], a.qh5[o + i], rK, a.Gs, s_lo, s_hi);
-        for (int s = 0; s < a.gs_pad; ++s) {
-            const unsigned long long m = __ballot(s_lo <= s && s <= s_hi);
-            if (lane == (s & 63)) out[(size_t)g * a.gs_pad + s] = m;
+        for (int s0 = 0; s0 < a.gs_pad; s0 += kWave) {
+            // lane l collects the mask of s0 + l; one coalesced store per 64 accumulation counts
+            unsigned long long mine = 0ull;
+            const int span = a.gs_pad - s0 < kWave ? a.gs_pad - s0 : kWave;
+            for (int l = 0; l < span; ++l) {
+                const int s = s0 + l;
+                const unsigned long long m = __ballot(s_lo <= s && s <= s_hi);
+                if (lane == l) mine = m;
+            }
+            if (lane < span) out[(size_t)g * a.gs_pad + s0 + lane] = mine;
         }
     }
 }
