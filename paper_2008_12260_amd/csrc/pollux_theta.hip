@@ -5,8 +5,8 @@
 // beta >= 0 and 1 <= gamma <= 10, and with the parameters the exploration priors hold
 // at zero.
 //
-// One wavefront per job.  The lanes share the job's records; everything about the seven
-// unknowns is the same in every lane.  The error is a sum of squares of
+// One workgroup per job, one wavefront per starting point.  The lanes of a wavefront share the
+// job's records; everything about the seven unknowns is the same in every lane.  The error is a sum of squares of
 //     r_o = ln T_iter(theta; K_o, nodes_o, m_o, s_o) - ln T_o,
 // so the minimiser is a damped Gauss-Newton (Levenberg-Marquardt) iteration on the box:
 // per iteration the lanes form r_o and its seven partial derivatives, the wave reduces
@@ -190,14 +190,20 @@ __device__ __forceinline__ bool damped_step(const Normal &q, double lambda, unsi
     return ok;
 }
 
-__global__ void __launch_bounds__(64) fit_theta_kernel(FitArgs f)
+constexpr int kMaxStarts = 5;
+
+__global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
 {
+    __shared__ double end_sse[kMaxStarts];
+    __shared__ double end_z[kMaxStarts][kTheta];
+    __shared__ int end_it[kMaxStarts];
     const int j = blockIdx.x;
     const int lane = lane_id();
+    const int k = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));      // this wavefront's starting point
     const int n = f.count[j] < f.max_obs ? f.count[j] : f.max_obs;
     if (n <= 0) {
-        if (lane < kTheta) f.theta[(size_t)lane * f.J + j] = lane == PX_GAMMA ? 1.0 : 0.0;
-        if (lane == 0) {
+        if (k == 0 && lane < kTheta) f.theta[(size_t)lane * f.J + j] = lane == PX_GAMMA ? 1.0 : 0.0;
+        if (k == 0 && lane == 0) {
             f.rmsle[j] = 0.0;
             if (f.iterations) f.iterations[j] = 0;
         }
@@ -250,12 +256,9 @@ __global__ void __launch_bounds__(64) fit_theta_kernel(FitArgs f)
     }
 
     // The error has several local minima (and a flat spot at T_sync = 0 when gamma > 1), so the iteration is
-    // run from a few starting points and the best end point is kept (the first one on ties): the start itself,
-    // then the sync parameters scaled by 3 or 0.3 with gamma = 1.2 or 5.
-    double best_z[kTheta];
-    double best_sse = __builtin_inf();
-    int total_it = 0;
-    for (int k = 0; k < f.n_starts; ++k) {
+    // run from a few starting points, one per wavefront, and the best end point is kept (the first one on
+    // ties): the start itself, then the sync parameters scaled by 3 or 0.3 with gamma = 1.2 or 5.
+    {
         const double sync_factor = (k == 0) ? 1.0 : ((k == 1 || k == 4) ? 3.0 : 0.3);
         const double gamma0 = (k == 0) ? start[PX_GAMMA] : ((k & 1) ? 1.2 : 5.0);
         double z[kTheta];
@@ -321,21 +324,29 @@ __global__ void __launch_bounds__(64) fit_theta_kernel(FitArgs f)
                 if (lambda > 1e15 || moved < 1e-15) break;
             }
         }
-        total_it += it;
-        if (cur.sse < best_sse || k == 0) {
-            best_sse = cur.sse;
+        if (lane == 0) {
+            end_sse[k] = cur.sse;
+            end_it[k] = it;
 #pragma unroll
-            for (int i = 0; i < kTheta; ++i) best_z[i] = z[i];
+            for (int i = 0; i < kTheta; ++i) end_z[k][i] = z[i];
         }
     }
+    __syncthreads();
+    if (k != 0) return;
 
+    int best_k = 0, total_it = 0;
+    for (int c = 0; c < f.n_starts; ++c) {
+        total_it += end_it[c];
+        if (end_sse[c] < end_sse[best_k]) best_k = c;
+    }
+    const double best_sse = end_sse[best_k];
     if (lane < kTheta) {
-        double v = 0.0;
+        double sc = 1.0;
 #pragma unroll
         for (int i = 0; i < kTheta; ++i) {
-            if (lane == i) v = best_z[i] * scale[i];
+            if (lane == i) sc = scale[i];
         }
-        f.theta[(size_t)lane * f.J + j] = v;
+        f.theta[(size_t)lane * f.J + j] = end_z[best_k][lane] * sc;
     }
     if (lane == 0) {
         f.rmsle[j] = sqrt(best_sse / (double)n);
@@ -351,7 +362,7 @@ int launch_fit_theta(int J, int max_obs, int max_iter, int n_starts, const int32
     f.J = J; f.max_obs = max_obs; f.max_iter = max_iter; f.n_starts = n_starts;
     f.count = count; f.K = K; f.nodes = nodes; f.m = m; f.s = s; f.T = T; f.init = init;
     f.theta = theta; f.rmsle = rmsle; f.iterations = iterations;
-    hipLaunchKernelGGL(fit_theta_kernel, dim3((unsigned)J), dim3(64), 0, stream, f);
+    hipLaunchKernelGGL(fit_theta_kernel, dim3((unsigned)J), dim3(64 * (unsigned)n_starts), 0, stream, f);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 
