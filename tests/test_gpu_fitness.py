@@ -347,3 +347,22 @@ def test_population_that_is_not_16_byte_aligned():
     assert view.data_ptr() % 16 == 4
     call.run(view)
     assert compare(wl, call.results(), run_oracle(wl)) == 0
+
+
+def test_many_random_shapes_and_parameter_draws():
+    """Forty seeded configurations with shapes and seeds of their own (grid sizes around the wavefront and chunk
+    boundaries, duplicate-heavy grids, few and many GPUs per node).  The election of (m*, s*) must agree with
+    the oracle everywhere; a disagreement is tolerated only as a tie below fp64 resolution, which compare()
+    verifies against the oracle in extended precision and counts."""
+    rng = np.random.default_rng(2024)
+    ties = 0
+    for trial in range(40):
+        shape = dict(P=int(rng.integers(1, 12)), J=int(rng.integers(1, 40)), N=int(rng.choice([1, 2, 3, 4, 8, 16, 63, 64, 65, 256])),
+                     cap=int(rng.choice([1, 2, 4, 8, 16])), Gm=int(rng.choice([1, 2, 7, 31, 63, 64, 65, 127, 128, 129, 200])),
+                     Gs=int(rng.choice([1, 2, 3, 7, 8, 9, 15, 16, 17, 31, 32, 33, 64, 65])), index=200 + trial)
+        wl = W.make(W.custom(f"random{trial}", **shape))
+        p = float(rng.choice([-2.0, -1.0, 0.0, 1.0]))
+        ref = run_oracle(wl, p=p)
+        for flags in (0, 4):
+            ties += compare(wl, run_gpu(wl, p=p, flags=flags), ref)
+    assert ties == 0
