@@ -548,7 +548,8 @@ __device__ __forceinline__ Best sweep_sampled(const Job &q, const int32_t *__res
 
 // ---- fp32 variant of the sweep --------------------------------------------------
 // The same model with every parameter rounded to fp32 and all arithmetic of Eq. 4-11 in
-// fp32, written the plain way (two divisions per grid point, powf for Eq. 10).  The
+// fp32 (powf for Eq. 10).  Each lane elects its best s with the rearranged form of the fp64
+// sweep, evaluated in fp32, and prices the elected point with Eq. 4 in the plain form.  The
 // feasibility interval M0 <= K m (s+1) <= M_max stays the exact integer test of the fp64
 // path.  Ties go to the lowest flat index.
 
@@ -599,12 +600,23 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
         const int s_lo = (int)(tb.ql5[i] * rK);
         int s_hi = (int)(tb.qh5[i] * rK) - 1;
         s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
+        // the lane's best s by the same rearrangement as the fp64 sweep, in fp32: argmax GOODPUT = argmin h,
+        // h = (last + u tg) + s tg + (last - tg) u / (s + 1), u = phi / (K m); ties to the smaller s
         const float Km = Kf * mf;
+        const float u = q.phi / Km;
+        const float A0 = fmaf(u, tg, last), B0 = (last - tg) * u;
+        float hbest = __builtin_inff();
+        int sb = -1;
         for (int sI = s_lo; sI <= s_hi; ++sI) {
-            const float M = Km * (float)(sI + 1);
-            const float t_iter = (float)sI * tg + last;                      // Eq. 11
+            const float h = fmaf(B0, __builtin_amdgcn_rcpf((float)(sI + 1)), fmaf((float)sI, tg, A0));
+            if (h < hbest) { hbest = h; sb = sI; }
+        }
+        if (sb >= 0) {
+            // Eq. 4 at the elected point, plain form
+            const float M = Km * (float)(sb + 1);
+            const float t_iter = (float)sb * tg + last;                      // Eq. 11
             const float g = (M / t_iter) * (q.a / (q.phi + M));              // Eq. 7 x Eq. 6
-            if (g > gbest) { gbest = g; flat = i * Gs + sI; m_best = m; s_best = sI; }
+            if (g > gbest) { gbest = g; flat = i * Gs + sb; m_best = m; s_best = sb; }
         }
     }
     return wave_argmax((double)gbest, flat, m_best, s_best);
