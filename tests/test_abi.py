@@ -75,3 +75,35 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     bad = list(gargs); bad[4] = null
     assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
     assert L.pollux_last_status(null, null, None) == px.PX_E_INVALID_ARG
+
+
+def test_the_newer_entry_points_reject_bad_arguments_without_a_device():
+    L = px.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    ok_fit = [4, 8] + [fake] * 6 + [null, 100, 3, fake, fake, null, null]
+    for pos, value in ((0, 0), (1, 0), (9, -1), (10, 0), (10, 6), (2, null), (7, null), (11, null), (12, null)):
+        bad = list(ok_fit)
+        bad[pos] = value
+        assert L.pollux_fit_theta(*bad) == px.PX_E_INVALID_ARG, pos
+    d = px.Dims(1, 8, 1, 32, 8, 0, 0)
+    ws = px.workspace_size(d)
+    assert L.pollux_goodput_per_gpu(ctypes.byref(d), fake, fake, 0, 4, fake, ws, fake, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_goodput_per_gpu(ctypes.byref(d), fake, fake, 4, 0, fake, ws, fake, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_goodput_per_gpu(ctypes.byref(d), fake, fake, 4, 4, fake, ws, null, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_goodput_per_gpu(ctypes.byref(d), fake, fake, 4, 4, fake, ws - 1, fake, null) == px.PX_E_WORKSPACE
+    flagged = px.Dims(1, 8, 1, 32, 8, 0, px.PX_FLAG_MEMOISE)
+    assert L.pollux_goodput_per_gpu(ctypes.byref(flagged), fake, fake, 4, 4, fake, ws, fake, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_autoscale(0, 4, fake, fake, 0.6, 0.5, fake, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_autoscale(8, 4, fake, fake, float("inf"), 0.5, fake, null) == px.PX_E_INVALID_ARG
+    assert L.pollux_autoscale(8, 4, null, fake, 0.6, 0.5, fake, null) == px.PX_E_INVALID_ARG
+    tick = [ctypes.byref(d)] + [fake] * 6 + [60.0, 30.0, fake, ws, fake, fake, fake, null]
+    for pos, value in ((7, -1.0), (8, float("nan")), (3, null), (11, null), (13, null)):
+        bad = list(tick)
+        bad[pos] = value
+        assert L.pollux_sim_tick(*bad) == px.PX_E_INVALID_ARG, pos
+    sampled = px.Dims(16, 8, 4, 32, 8, 1, px.PX_FLAG_SAMPLE_M)        # the sampling argmax exists in fp64 only
+    with pytest.raises(px.PolluxError):
+        px.workspace_size(sampled)
+    ga = px.GaParams(1, 0, 8, 0, 2)                                    # unknown search flag
+    dd = px.Dims(16, 8, 4, 32, 8, 0, 0)
+    assert L.pollux_ga_step(ctypes.byref(dd), fake, fake, fake, ctypes.byref(ga), fake, 1 << 30, ctypes.c_void_p(0x90000000), null) == px.PX_E_INVALID_ARG
