@@ -969,6 +969,8 @@ constexpr int kCandThreads = 256;
 __device__ __forceinline__ double pmean_term(double s, double w, double p)
 {
     if (p == 0.0) return w * log(s);      // log(0) = -inf
+    if (p == 1.0) return w * s;
+    if (p == -1.0) return w * (1.0 / s);  // 1/0 = +inf, as pow(0, -1)
     return w * pow(s, p);                 // pow(0, p<0) = +inf
 }
 
@@ -978,7 +980,13 @@ __device__ __forceinline__ float pmean_term(float s, float w, float p)
     return w * powf(s, p);
 }
 
-__device__ __forceinline__ double pmean_finish(double mean, double p) { return p == 0.0 ? exp(mean) : pow(mean, 1.0 / p); }
+__device__ __forceinline__ double pmean_finish(double mean, double p)
+{
+    if (p == 0.0) return exp(mean);
+    if (p == 1.0) return mean;
+    if (p == -1.0) return 1.0 / mean;
+    return pow(mean, 1.0 / p);
+}
 __device__ __forceinline__ float pmean_finish(float mean, float p) { return p == 0.0f ? expf(mean) : powf(mean, 1.0f / p); }
 
 // REAL = double, or float for the fp32 variant (SPEEDUP, the penalty and the mean are then formed in fp32).
