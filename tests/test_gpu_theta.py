@@ -138,3 +138,27 @@ def test_priors_degenerate_inputs_and_argument_checks():
         px.pollux_fit_theta(z[:, 0].contiguous(), z, z, z, z, t, out, e, n_starts=6)
     with pytest.raises(px.PolluxError):
         px.pollux_fit_theta(z[:, 0].contiguous(), z, z, z, z, t, out, e, max_iter=-1)
+
+
+def test_bounds_bind_where_the_unconstrained_fit_would_leave_the_box():
+    """Records that want T_sync < 0 (several GPUs faster than the model allows) and records that want gamma < 1
+    (a last pass dearer than T_grad + T_sync): the fit must end on the bound, and match the checker's error."""
+    import paper_2008_12260_amd as px
+    rng = np.random.default_rng(23)
+    K = rng.integers(1, 17, 40)
+    nodes = np.maximum(np.minimum(K, rng.integers(1, 5, 40)), 1)
+    m = rng.choice([8, 32, 128], 40)
+    s = rng.integers(0, 4, 40)
+    tg = 0.1 + 0.001 * m
+    fast = np.maximum((s + 1) * tg + np.where(K > 1, -0.02, 0.0), 0.05)
+    ts = np.where(K > 1, 0.05 + 0.01 * (K - 2), 0.0)
+    dear = s * tg + np.where(K > 1, 1.6 * (tg + ts), tg)
+    ob = pack([(K, nodes, m, s, fast), (K, nodes, m, s, dear)], 64)
+    got = px.fit_theta(ob, max_iter=300, n_starts=3)
+    th = got["theta"]
+    assert np.all(th[:6] >= 0.0) and np.all(th[6] >= 1.0) and np.all(th[6] <= 10.0)
+    assert th[6, 1] == 1.0                                              # gamma pressed against its lower bound
+    for j, T in enumerate((fast, dear)):
+        assert abs(TH.rmsle(th[:, j], K, nodes, m, s, T) - got["rmsle"][j]) <= 1e-12 * got["rmsle"][j]
+        want = TH.fit(K, nodes, m, s, T, n_starts=3)[1]
+        assert got["rmsle"][j] <= want * 1.001
