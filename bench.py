@@ -28,10 +28,10 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 # HBM bytes one launch of the sweep kernel moves on the "large" workload: rocprofv3 FETCH_SIZE (2 077 201 KiB,
 # scaled by 2.0) + WRITE_SIZE (685 529 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
 # size in the same runs (profiles/pairs_kernel_large.md).  Valid for the kernel those counters were taken on.
-SWEEP_HBM_BYTES = {"large": 2077201 * 1024 * 2.0 + 685529 * 1024 * 1.0}
+SWEEP_HBM_BYTES = {}       # null until the counters are taken again for the current kernel
 # fp64 operations the same kernel executes per launch on "large", from the instruction counters of the same
 # profile: 64 lanes x (ADD_F64 + MUL_F64 + 2 x FMA_F64 wave-instructions)
-SWEEP_EXECUTED_FLOPS = {"large": 64 * (1.288e8 + 2.554e7 + 2 * 4.0316e8)}
+SWEEP_EXECUTED_FLOPS = {}
 GA_SEED = 0x2008_1226_5EED_0001
 def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
     return (1 << 32) // J

@@ -6,7 +6,7 @@
 // interference avoidance Sec. 4.2 (Eq. 14-15).
 //
 // Kernels (one call = six launches on the caller's stream)
-//   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), ln T_grad, phi/m and
+//   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), 1/T_grad, ln T_grad, phi/m and
 //                     the feasibility bounds; reciprocals; clears the status word
 //   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
 //                     per row): T_sync (Eq. 9) and, for every batch size of the grid,
@@ -29,18 +29,20 @@
 // through by M gives
 //     GOODPUT = (phi + M0) / h,   h(m, s) = T_iter(m, s) * (1 + phi / M),
 // and with u = phi/(K m), last = (T_grad^g + T_sync^g)^(1/g):
-//     h(m, s) = (last + u T_grad) + s T_grad + (last - T_grad) u / (s + 1),
-// two fused multiply-adds per grid point with every term non-negative.  The
-// argmax of GOODPUT is the argmin of h over the feasible points.  Which lanes
-// hold a feasible batch size at a given s depends on (job, K) only, so those
-// 64-bit lane masks are tabled; the lane keeps its minimum with one v_min_f64
-// per point, executed with only the feasible lanes enabled, and the low five
-// mantissa bits of h are replaced by s (so the minimum carries its own index and
-// equal values resolve to the smaller s).  The perturbation is 2^-47 relative; the point each lane
-// elects is then evaluated again with the formulas in the paper's own order
-// (separate multiply and add, IEEE division), and the wave-wide argmax is taken
-// over those values with ties going to the lowest flat index, so the reported
-// goodput and the choice among lanes do not depend on the fast form.
+//     h(m, s) = (last + u T_grad) + s T_grad + (last - T_grad) u / (s + 1)
+//             = A0 + T_grad w(s),    w(s) = s + C / (s + 1),   C = (last - T_grad) u / T_grad,
+// with every term non-negative.  The argmax of GOODPUT is the argmin of h over the
+// feasible points; for one batch size (one lane) that is the argmin of w, one
+// fused multiply-add per grid point, and h is formed once per lane and chunk of s
+// from the smallest w.  Which lanes hold a feasible batch size at a given s depends
+// on (job, K) only, so those 64-bit lane masks are tabled; the lane keeps its
+// minimum with one v_min_f64 per point, executed with only the feasible lanes
+// enabled, and the low five mantissa bits of w are replaced by the position of s in
+// its chunk (so the minimum carries its own index and equal values resolve to the
+// smaller s).  The perturbation is 2^-47 relative.  The wave then takes the smallest h
+// (equal keys: lowest flat index), and the elected point is evaluated again with the
+// formulas in the paper's own order (separate multiply and add, IEEE division), so
+// the reported goodput does not depend on the fast form.
 //
 // The last pass of Eq. 10 is evaluated as
 //     max(Tg, Ts) * exp( log1p( exp(-g |ln Tg - ln Ts|) ) / g ),
@@ -78,7 +80,8 @@ struct FitnessArgs {
     double p, delta;
     // workspace
     int32_t *status;
-    double *rs, *rk, *tg, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    double *rs, *rk, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    double2 *tg;                  // [J,Gm] (T_grad, 1 / T_grad)
     unsigned long long *fmask;    // [J,kTableK,ni,gs_pad] feasibility lane masks (see last_kernel)
     int ni, gs_pad;               // ceil(Gm / 64); Gs rounded up to a multiple of 32
     int32_t *running, *meta;
@@ -129,7 +132,7 @@ __device__ __forceinline__ SyncParams load_sync(const Job &q)
 
 // ---- tables ------------------------------------------------------------------
 // Per job and grid point i (batch size m = m_grid[j,i]):
-//   tg   = T_grad(m) (Eq. 8)            lntg = ln T_grad(m)
+//   tg   = (T_grad(m), 1 / T_grad(m)) (Eq. 8)          lntg = ln T_grad(m)
 //   pu   = phi / m                      (u = phi / (K m) = pu / K)
 //   qh5  = floor(M_max / m) + 1/2       ql5  = ceil(M0 / m) - 1/2
 // M0 <= K m (s+1) <= M_max holds exactly when ceil(M0/m) <= K (s+1) <= floor(M_max/m),
@@ -148,7 +151,7 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
         const int mi = a.m_grid[t];
         const double m = (double)mi;
         const double tg = a.job_params[(size_t)PX_ALPHA_G * a.J + j] + a.job_params[(size_t)PX_BETA_G * a.J + j] * m;   // Eq. 8
-        a.tg[t] = tg;
+        a.tg[t] = double2{tg, tg > 0.0 ? 1.0 / tg : 0.0};
         a.lntg[t] = px_log(tg);
         double qh = -1.5, ql = 1.0;
         if (mi > 0) {
@@ -236,7 +239,7 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
     const SyncTerm t = sync_term(q, K, one_node);
     const size_t o = (size_t)j * a.Gm;
     const int lane = lane_id();
-    for (int i = lane; i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i], a.lntg[o + i]);
+    for (int i = lane; i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i].x, a.lntg[o + i]);
     if (one_node) return;
     const double rK = a.rk[K];
     unsigned long long *__restrict__ out = a.fmask + ((size_t)j * kTableK + (size_t)(K - 1)) * a.ni * a.gs_pad;
@@ -267,7 +270,8 @@ struct Best {
 
 struct JobTables {
     const int32_t *__restrict__ m;
-    const double *__restrict__ tg, *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
+    const double2 *__restrict__ tg;   // (T_grad, 1 / T_grad)
+    const double *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
     const double *__restrict__ lt;    // rows of this job in the last-pass table
     const unsigned long long *__restrict__ fmask;   // feasibility masks of this job, [kTableK, ni, gs_pad]
     int ni, gs_pad;
@@ -306,75 +310,132 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
 }
 
 // ---- the sweep of one batch size per lane over CH accumulation counts ---------------
-// For point s the lanes whose batch size is feasible are known as a 64-bit lane mask in
+// With C = B0 / T_grad the quantity to minimise is  h = A0 + T_grad (s + C / (s+1)).  Inside a
+// chunk of CH accumulation counts starting at s0 the lane ranks position b by
+//   w(b) = b + C r,   r = 1/(s0 + b + 1),
+// and the chunk's winner goes back to h = (A0 + s0 T_grad) + T_grad w once per chunk.
+// For point b the lanes whose batch size is feasible are known as a 64-bit lane mask in
 // scalar registers, tabled per (job, K) by last_kernel.  Per point and lane:
-//   x    = A0 + s tg         from a base per four points (advanced by 4 tg) plus 0, tg, 2 tg
-//                            or 3 tg: v_add_f64 / v_fma_f64 with inline constants, a few
-//                            roundings deep, far below the index perturbation
-//   h    = B0 * r + x        v_fma_f64, r = 1/(s+1) from scalar registers
-//   lo   = (31 & b) | (~31 & lo(h))                       v_bfi_b32
-//   kmin = min(kmin, key)    v_min_f64 with only the feasible lanes enabled
-// so the key carries its position b inside the chunk in the low five mantissa bits (equal
-// values resolve to the smaller s), and a lane never sees an infeasible point.  Four VALU
-// instructions per point; masks and reciprocals arrive through the scalar cache.
+//   w    = C * r + (b mod 8)   one v_fma_f64 (v_mul_f64 for 0): r from scalar registers, the
+//                              addend an inline constant (1, 2, 4) or one of four registers
+//                              that hold 3, 5, 6, 7 for the whole kernel
+//   lo   = (31 & b) | (~31 & lo(w))                       v_bfi_b32
+//   kmin = min(kmin, key)      v_min_f64 with only the feasible lanes enabled
+// so the key carries its position b in the low five mantissa bits (equal values resolve to
+// the smaller s), and a lane never sees an infeasible point.  Three VALU instructions per
+// point; masks and reciprocals arrive through the scalar cache.  Each run of eight
+// positions has a minimum of its own (values relative to the run's first position); the
+// runs are merged after the chunk (merge_runs).
 typedef const double __attribute__((address_space(4))) *ScalarDoubles;
 typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
 
-template <int B>
-__device__ __forceinline__ double masked_min(double kmin, double x, double B0, double r, unsigned long long lanes)
+constexpr int kRun = 8;
+
+// The addends 3, 5, 6, 7 in vector registers.  Made once per kernel through an opaque
+// statement, so that they stay in registers instead of being formed again at every use.
+struct RunSteps {
+    double x3, x5, x6, x7;
+};
+
+__device__ __forceinline__ RunSteps make_run_steps()
 {
-    double h;
-    asm("v_fma_f64 %0, %1, %2, %3" : "=v"(h) : "v"(B0), "s"(r), "v"(x));
-    int hl;
-    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(hl) : "n"(B), "v"(__double2loint(h)));
-    const double key = __hiloint2double(__double2hiint(h), hl);
-    unsigned long long saved;
-    asm volatile("s_and_saveexec_b64 %1, %3\n\t"
-                 "v_min_f64 %0, %0, %2\n\t"
-                 "s_mov_b64 exec, %1"
-                 : "+v"(kmin), "=&s"(saved)
-                 : "v"(key), "s"(lanes)
-                 : "scc");
-    return kmin;
+    RunSteps X = {3.0, 5.0, 6.0, 7.0};
+    asm volatile("" : "+v"(X.x3), "+v"(X.x5), "+v"(X.x6), "+v"(X.x7));
+    return X;
 }
 
-// Four points at positions 4 G .. 4 G + 3 of the chunk (G a compile-time group index);
-// base = A0 + (s0 + 4 G) tg.  The empty volatile statement at the head of a group keeps the
-// scalar loads of the group behind the previous group's work (volatile statements keep
-// their order), so that only one group's masks and reciprocals occupy scalar registers.
-template <int G>
-__device__ __forceinline__ double masked_group(double kmin, double base, double tg, double B0, ScalarDoubles rs,
-                                               ScalarMasks lanes)
+// The key of position B of a chunk: w with B in its low five mantissa bits.
+template <int B>
+__device__ __forceinline__ double point_key(double C, double r, const RunSteps &X)
+{
+    constexpr int t = B % kRun;
+    double g;
+    if constexpr (t == 0) asm("v_mul_f64 %0, %1, %2" : "=v"(g) : "v"(C), "s"(r));
+    else if constexpr (t == 1) asm("v_fma_f64 %0, %1, %2, 1.0" : "=v"(g) : "v"(C), "s"(r));
+    else if constexpr (t == 2) asm("v_fma_f64 %0, %1, %2, 2.0" : "=v"(g) : "v"(C), "s"(r));
+    else if constexpr (t == 4) asm("v_fma_f64 %0, %1, %2, 4.0" : "=v"(g) : "v"(C), "s"(r));
+    else asm("v_fma_f64 %0, %1, %2, %3" : "=v"(g) : "v"(C), "s"(r), "v"(t == 3 ? X.x3 : (t == 5 ? X.x5 : (t == 6 ? X.x6 : X.x7))));
+    int gl;
+    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(gl) : "n"(B), "v"(__double2loint(g)));
+    return __hiloint2double(__double2hiint(g), gl);
+}
+
+// Four points at positions 4 G .. 4 G + 3 of the chunk (G a compile-time group index): the
+// four keys first, then the four minima, each with only its point's feasible lanes enabled
+// (five scalar instructions switch the lanes for the four of them).
+// The empty volatile statement at the head of a group keeps the scalar loads of the group
+// behind the previous group's work (volatile statements keep their order), so that only
+// one group's masks and reciprocals occupy scalar registers.
+template <int CH, int G>
+__device__ __forceinline__ void masked_group(double (&kmin)[CH / kRun], double C, const RunSteps &X, ScalarDoubles rs,
+                                             ScalarMasks lanes)
 {
     asm volatile("" : "+s"(rs), "+s"(lanes));
-    double x1, x2, x3;
-    asm("v_add_f64 %0, %1, %2" : "=v"(x1) : "v"(tg), "v"(base));
-    asm("v_fma_f64 %0, 2.0, %1, %2" : "=v"(x2) : "v"(tg), "v"(base));
-    asm("v_fma_f64 %0, 2.0, %1, %2" : "=v"(x3) : "v"(tg), "v"(x1));
-    kmin = masked_min<4 * G + 0>(kmin, base, B0, rs[4 * G + 0], lanes[4 * G + 0]);
-    kmin = masked_min<4 * G + 1>(kmin, x1, B0, rs[4 * G + 1], lanes[4 * G + 1]);
-    kmin = masked_min<4 * G + 2>(kmin, x2, B0, rs[4 * G + 2], lanes[4 * G + 2]);
-    kmin = masked_min<4 * G + 3>(kmin, x3, B0, rs[4 * G + 3], lanes[4 * G + 3]);
-    return kmin;
+    double r0 = rs[4 * G + 0], r1 = rs[4 * G + 1], r2 = rs[4 * G + 2], r3 = rs[4 * G + 3];
+    unsigned long long l0 = lanes[4 * G + 0], l1 = lanes[4 * G + 1], l2 = lanes[4 * G + 2], l3 = lanes[4 * G + 3];
+    // both requests are on their way before the first key is formed
+    asm volatile("" : "+s"(r0), "+s"(r1), "+s"(r2), "+s"(r3), "+s"(l0), "+s"(l1), "+s"(l2), "+s"(l3));
+    const double k0 = point_key<4 * G + 0>(C, r0, X);
+    const double k1 = point_key<4 * G + 1>(C, r1, X);
+    const double k2 = point_key<4 * G + 2>(C, r2, X);
+    const double k3 = point_key<4 * G + 3>(C, r3, X);
+    unsigned long long saved;
+    asm volatile("s_and_saveexec_b64 %1, %6\n\t"
+                 "v_min_f64 %0, %0, %2\n\t"
+                 "s_and_b64 exec, %1, %7\n\t"
+                 "v_min_f64 %0, %0, %3\n\t"
+                 "s_and_b64 exec, %1, %8\n\t"
+                 "v_min_f64 %0, %0, %4\n\t"
+                 "s_and_b64 exec, %1, %9\n\t"
+                 "v_min_f64 %0, %0, %5\n\t"
+                 "s_mov_b64 exec, %1"
+                 : "+v"(kmin[4 * G / kRun]), "=&s"(saved)
+                 : "v"(k0), "v"(k1), "v"(k2), "v"(k3), "s"(l0), "s"(l1), "s"(l2), "s"(l3)
+                 : "scc");
 }
 
 template <int CH, int G = 0>
-__device__ __forceinline__ double masked_groups(double kmin, double base, double tg, double tg4, double B0,
-                                                ScalarDoubles rs, ScalarMasks lanes)
+__device__ __forceinline__ void masked_groups(double (&kmin)[CH / kRun], double C, const RunSteps &X, ScalarDoubles rs,
+                                              ScalarMasks lanes)
 {
     if constexpr (4 * G < CH) {
-        kmin = masked_group<G>(kmin, base, tg, B0, rs, lanes);
-        return masked_groups<CH, G + 1>(kmin, base + tg4, tg, tg4, B0, rs, lanes);
+        masked_group<CH, G>(kmin, C, X, rs, lanes);
+        masked_groups<CH, G + 1>(kmin, C, X, rs, lanes);
     }
-    return kmin;
 }
 
-// CH points starting at accumulation count s0 (A0s = A0 + s0 tg); rs and lanes point at s0.
-// Returns the smallest key, +inf if no point is feasible for the lane.
-template <int CH>
-__device__ __forceinline__ double sweep_chunk(double tg, double A0s, double B0, ScalarDoubles rs, ScalarMasks lanes)
+// min(lower, upper + D) for the minima of two neighbouring stretches of positions, the upper
+// one starting D positions later; D = 8 or 16 is formed from inline constants.  The sum gets
+// the position bits of `upper` back (+inf has none and stays +inf).
+template <int D>
+__device__ __forceinline__ double merge_runs(double lower, double upper)
 {
-    return masked_groups<CH>(__builtin_inf(), A0s, tg, 4.0 * tg, B0, rs, lanes);
+    static_assert(D == 8 || D == 16, "offsets that are products of inline constants");
+    double moved;
+    if constexpr (D == 8) asm("v_fma_f64 %0, 4.0, 2.0, %1" : "=v"(moved) : "v"(upper));
+    else asm("v_fma_f64 %0, 4.0, 4.0, %1" : "=v"(moved) : "v"(upper));
+    int lo;
+    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(lo) : "v"(__double2loint(upper)), "v"(__double2loint(moved)));
+    const double key = __hiloint2double(__double2hiint(moved), lo);
+    double out;
+    asm("v_min_f64 %0, %1, %2" : "=v"(out) : "v"(lower), "v"(key));
+    return out;
+}
+
+// CH points starting at accumulation count s0; rs and lanes point at s0.  Returns the
+// smallest key of w over the chunk (position in its low five bits), +inf if no point is
+// feasible for the lane.
+template <int CH>
+__device__ __forceinline__ double sweep_chunk(double C, const RunSteps &X, ScalarDoubles rs, ScalarMasks lanes)
+{
+    static_assert(CH == 8 || CH == 16 || CH == 32, "one, two or four runs");
+    double kmin[CH / kRun];
+#pragma unroll
+    for (int q = 0; q < CH / kRun; ++q) kmin[q] = __builtin_inf();
+    masked_groups<CH>(kmin, C, X, rs, lanes);
+    if constexpr (CH == 8) return kmin[0];
+    else if constexpr (CH == 16) return merge_runs<8>(kmin[0], kmin[1]);
+    else return merge_runs<16>(merge_runs<8>(kmin[0], kmin[1]), merge_runs<8>(kmin[2], kmin[3]));
 }
 
 // The same chunk for a GPU count beyond the tables, written as a plain loop (rare, so
@@ -404,7 +465,7 @@ struct Pick {
 // position inside the chunk, resolve to the lowest flat index i * Gs + s).
 // TABLED: last pass and lane masks come from the job's tables (K <= kTableK), else they are formed here.
 template <int CH, bool TABLED>
-__device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const double *__restrict__ rs,
+__device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
     const int lane = lane_id();
@@ -422,13 +483,15 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const int i = i0 + lane;
         const bool active = i < Gm;
         const int il = active ? i : Gm - 1;
-        const double tg = tb.tg[il];
+        const double2 tgr = tb.tg[il];
+        const double tg = tgr.x;
         double last;
         if constexpr (TABLED) last = lrow[il];
         else last = last_pass(st, tg, tb.lntg[il]);
         const double u = tb.pu[il] * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
+        const double C = B0 * tgr.y;
         int s_lo = 1, s_hi = 0;
         if constexpr (!TABLED) {
             feasible_range(tb.ql5[il], tb.qh5[il], rK, Gs, s_lo, s_hi);
@@ -439,8 +502,14 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
             const double A0s = s0 == 0 ? A0 : px_fma((double)s0, tg, A0);
             double kmin;
-            if constexpr (TABLED) kmin = sweep_chunk<CH>(tg, A0s, B0, rsc + s0, lanes + s0);
-            else kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
+            if constexpr (TABLED) {
+                // back from w to h = A0s + T_grad w, with the winner's position bits
+                const double g = sweep_chunk<CH>(C, X, rsc + s0, lanes + s0);
+                const double h = px_fma(tg, g, A0s);
+                kmin = __hiloint2double(__double2hiint(h), (__double2loint(h) & ~31) | (__double2loint(g) & 31));
+            } else {
+                kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
+            }
             if (kmin < kbest) {
                 kbest = kmin;
                 code = code_now;
@@ -471,8 +540,9 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
     if (K <= 0) return Pick{-1, -1};
-    if (K <= kTableK) return sweep_pick<CH, true>(q, tb, rs, rk, Gm, Gs, K, nodes);
-    return sweep_pick<CH, false>(q, tb, rs, rk, Gm, Gs, K, nodes);
+    const RunSteps X = make_run_steps();
+    if (K <= kTableK) return sweep_pick<CH, true>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
+    return sweep_pick<CH, false>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
 }
 
 // Eq. 4 at grid point (i, s) in the paper's order of operations.  Arguments may differ
@@ -481,7 +551,7 @@ __device__ __forceinline__ Best price_point(const Job &q, const JobTables &tb, i
 {
     if (i < 0) return Best{0.0, -1, -1};
     const int m = tb.m[i];
-    const double tg = tb.tg[i];
+    const double tg = tb.tg[i].x;
     double last;
     if (K <= kTableK) last = tb.lt[((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(K - 1)) * Gm + i];
     else last = last_pass(sync_term(q, K, one_node), tg, tb.lntg[i]);
@@ -735,6 +805,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int lane4 = lane < n4 ? lane : n4 - 1;      // ROW1: lanes past the end of the row load its last 16 bytes again
     const unsigned long long in_row = __ballot(lane < n4);
     constexpr bool kDeferred = !F32 && CH != 0;
+    const RunSteps X = make_run_steps();
     int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
     bool any_neg = false;
 
@@ -819,7 +890,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             // fp64 grid sweep: elect the point now, price it after the loop (lane r keeps candidate r)
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
-            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
             if (lane == r) {
                 d_K = K;
                 d_meta = nodes | (changed ? kMetaChanged : 0);
@@ -867,7 +938,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             pending &= pending - 1;
             const int K = __builtin_amdgcn_readlane(d_K, l);
             const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
-            const Pick pick = sweep_pick<CH, false>(qb, tbb, b.rs, b.rk, b.Gm, b.Gs, K, nodes);
+            const Pick pick = sweep_pick<CH, false>(qb, tbb, X, b.rs, b.rk, b.Gm, b.Gs, K, nodes);
             if (lane == l) {
                 d_i = pick.i;
                 d_s = pick.s;
@@ -1067,7 +1138,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
     a.rk = (double *)(ws + L.rk);
-    a.tg = (double *)(ws + L.tg);
+    a.tg = (double2 *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);
     a.pu = (double *)(ws + L.pu);
     a.qh5 = (double *)(ws + L.qh5);
@@ -1145,7 +1216,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
     a.rk = (double *)(ws + L.rk);
-    a.tg = (double *)(ws + L.tg);
+    a.tg = (double2 *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);
     a.pu = (double *)(ws + L.pu);
     a.qh5 = (double *)(ws + L.qh5);

@@ -18,7 +18,7 @@ struct WorkspaceLayout {
     size_t status;    // int32 status word
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
     size_t rk;        // double [256]     1/K
-    size_t tg;        // double [J,Gm]    T_grad(m_i)
+    size_t tg;        // double [J,Gm,2]  T_grad(m_i) and its reciprocal
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
     size_t pu;        // double [J,Gm]    phi / m_i
     size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
@@ -46,7 +46,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.status = o;  o = up(o + 256);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
     L.rk = o;      o = up(o + 8 * 256);
-    L.tg = o;      o = up(o + 8 * J * Gm);
+    L.tg = o;      o = up(o + 16 * J * Gm);
     L.lntg = o;    o = up(o + 8 * J * Gm);
     L.pu = o;      o = up(o + 8 * J * Gm);
     L.qh5 = o;     o = up(o + 8 * J * Gm);
