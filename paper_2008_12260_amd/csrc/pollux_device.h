@@ -58,49 +58,43 @@ __device__ __forceinline__ long long wave_sum(long long v)
     return v;
 }
 
-// 32-bit reductions: the four DPP steps are folded into the arithmetic
-// instruction itself (one VALU instruction per step).
-#define PX_DPP_STEPS(OP, v)                                                                              \
+// 32-bit reductions: every step is folded into the arithmetic instruction itself (one VALU
+// instruction per step).  Four steps inside each row of 16 lanes leave the row's result in all of
+// its lanes; row_bcast:15 then combines rows 0 and 1 into row 1 and rows 2 and 3 into row 3, and
+// row_bcast:31 combines those into row 3, so lane 63 holds the result of the wavefront, which is
+// read back as a scalar (the same value for every lane).
+#define PX_DPP_REDUCE(OP, v)                                                                             \
     asm("s_nop 1\n\t"                                                                                     \
         OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                     \
         OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                     \
         OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                         \
-        OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"                                             \
+        OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                              \
+        OP " %0, %0, %0 row_bcast:15 row_mask:0xa bank_mask:0xf\n\ts_nop 1\n\t"                            \
+        OP " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"                                           \
         : "+v"(v))
 
 __device__ __forceinline__ int wave_sum(int v)
 {
-    PX_DPP_STEPS("v_add_u32_dpp", v);
-    v += exchange<4>(v);
-    v += exchange<5>(v);
-    return v;
+    PX_DPP_REDUCE("v_add_u32_dpp", v);
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ __forceinline__ int wave_min(int v)
 {
-    PX_DPP_STEPS("v_min_i32_dpp", v);
-    int o = exchange<4>(v);
-    v = o < v ? o : v;
-    o = exchange<5>(v);
-    return o < v ? o : v;
+    PX_DPP_REDUCE("v_min_i32_dpp", v);
+    return __builtin_amdgcn_readlane(v, 63);
 }
 
 __device__ __forceinline__ unsigned wave_min(unsigned v)
 {
-    PX_DPP_STEPS("v_min_u32_dpp", v);
-    unsigned o = (unsigned)exchange<4>((int)v);
-    v = o < v ? o : v;
-    o = (unsigned)exchange<5>((int)v);
-    return o < v ? o : v;
+    PX_DPP_REDUCE("v_min_u32_dpp", v);
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 __device__ __forceinline__ unsigned wave_max(unsigned v)
 {
-    PX_DPP_STEPS("v_max_u32_dpp", v);
-    unsigned o = (unsigned)exchange<4>((int)v);
-    v = o > v ? o : v;
-    o = (unsigned)exchange<5>((int)v);
-    return o > v ? o : v;
+    PX_DPP_REDUCE("v_max_u32_dpp", v);
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
 }
 
 }  // namespace px

@@ -483,12 +483,14 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const int i = i0 + lane;
         const bool active = i < Gm;
         const int il = active ? i : Gm - 1;
-        const double2 tgr = tb.tg[il];
+        // a uniform base plus a 32-bit byte offset per lane: the address needs no 64-bit vector arithmetic
+        const unsigned at = (unsigned)il * 8u;
+        const double2 tgr = *(const double2 *)((const char *)tb.tg + 2u * at);
         const double tg = tgr.x;
         double last;
-        if constexpr (TABLED) last = lrow[il];
+        if constexpr (TABLED) last = *(const double *)((const char *)lrow + at);
         else last = last_pass(st, tg, tb.lntg[il]);
-        const double u = tb.pu[il] * rK;
+        const double u = *(const double *)((const char *)tb.pu + at) * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
         const double C = B0 * tgr.y;
