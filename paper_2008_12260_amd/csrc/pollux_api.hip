@@ -43,6 +43,8 @@ bool dims_ok(const pollux_dims *d, bool need_grid)
     if (need_grid && (long long)d->Gm * d->Gs > 0x7FFFFFFFll) return false;
     if (need_grid && (d->Gm > (1 << 20) || d->Gs > (1 << 14))) return false;   // chunk ids are packed into one word
     if (need_grid && (long long)d->J * d->Gm > 0x7FFFFFFFll) return false;
+    // offsets inside one job's tables (last pass [2,64,Gm], lane masks [64,Gm/64,Gs up to 32]) are kept in 32 bits
+    if (need_grid && ((long long)d->Gm + 63) * (((long long)d->Gs + 31) / 32 * 32) > (1ll << 28)) return false;
     return true;
 }
 

@@ -471,7 +471,8 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     const int lane = lane_id();
     const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
-    const double *__restrict__ lrow = tb.lt + ((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(TABLED ? K - 1 : 0)) * Gm;
+    // offsets inside one job's tables fit 32 bits (checked on the host)
+    const double *__restrict__ lrow = tb.lt + (unsigned)((one_node ? kTableK : 0) + (TABLED ? K - 1 : 0)) * (unsigned)Gm;
     SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
@@ -499,7 +500,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             feasible_range(tb.ql5[il], tb.qh5[il], rK, Gs, s_lo, s_hi);
             if (!active) s_hi = -1;
         }
-        const ScalarMasks lanes = (ScalarMasks)(tb.fmask + ((size_t)(TABLED ? K - 1 : 0) * tb.ni + (size_t)(i0 >> 6)) * tb.gs_pad);
+        const ScalarMasks lanes = (ScalarMasks)(tb.fmask + ((unsigned)(TABLED ? K - 1 : 0) * (unsigned)tb.ni + (unsigned)(i0 >> 6)) * (unsigned)tb.gs_pad);
         int code_now = i0 << 10;
         for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
             const double A0s = s0 == 0 ? A0 : px_fma((double)s0, tg, A0);
@@ -555,7 +556,7 @@ __device__ __forceinline__ Best price_point(const Job &q, const JobTables &tb, i
     const int m = tb.m[i];
     const double tg = tb.tg[i].x;
     double last;
-    if (K <= kTableK) last = tb.lt[((size_t)(one_node ? 1 : 0) * kTableK + (size_t)(K - 1)) * Gm + i];
+    if (K <= kTableK) last = tb.lt[(unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm + (unsigned)i];
     else last = last_pass(sync_term(q, K, one_node), tg, tb.lntg[i]);
     return Best{goodput_point(q, (double)K * (double)m, tg, last, s), m, s};
 }
@@ -817,9 +818,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int32_t *__restrict__ row = a.population + ((size_t)c0 * a.J + j) * a.N - row_step;
     unsigned long long *__restrict__ cp = a.colpack + (size_t)c0 * a.N - (size_t)kWavesPerBlock * a.N;
 
-    for (int r = 0; r < a.cand_per_wave; ++r) {
-        const int c = c0 + kWavesPerBlock * r;
-        if (c >= a.P) break;
+    // The row stage of candidate c0 + 4 r: row reduce and constraint counters.
+    auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out) {
         row += row_step;
         cp += (size_t)kWavesPerBlock * a.N;
         // row reduce: K = sum, nodes = #positive, changed = differs from the current row
@@ -864,7 +864,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 neg |= __ballot(v < 0) != 0;
             }
         }
-        const int K = __builtin_amdgcn_readfirstlane(wave_sum(ksum));
+        const int K = wave_sum(ksum);
 
         // constraint check, part one: the row's non-zero entries (a job sits on few nodes) go to the
         // candidate's per-node counters; a multi-node job also counts once on each of its nodes.
@@ -887,20 +887,45 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 }
             }
         }
+        K_out = K; nodes_out = nodes; changed_out = changed; neg_out = neg;
+    };
 
-        if constexpr (kDeferred) {
-            // fp64 grid sweep: elect the point now, price it after the loop (lane r keeps candidate r)
+    if constexpr (kDeferred) {
+        // fp64 grid sweep, in two passes over the wavefront's candidates so that neither pass keeps the
+        // other's addresses in scalar registers: first the row stage of every candidate (lane r keeps K and
+        // nodes | changed of candidate r), then the sweeps, which elect a point per candidate; the points are
+        // priced after the loop.
+        int rows = 0;
+        for (int r = 0; r < a.cand_per_wave; ++r) {
+            if (c0 + kWavesPerBlock * r >= a.P) break;
+            int K, nodes;
+            bool changed, neg;
+            row_stage(K, nodes, changed, neg);
+            if (lane == r) {
+                d_K = K;
+                d_meta = nodes | (changed ? kMetaChanged : 0);
+            }
+            any_neg |= neg;
+            rows = r + 1;
+        }
+        for (int r = 0; r < rows; ++r) {
+            const int K = __builtin_amdgcn_readlane(d_K, r);
+            const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
             else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
             if (lane == r) {
-                d_K = K;
-                d_meta = nodes | (changed ? kMetaChanged : 0);
                 d_i = pick.i;
                 d_s = pick.s;
             }
-            any_neg |= neg;
-        } else {
+        }
+    } else {
+        for (int r = 0; r < a.cand_per_wave; ++r) {
+            const int c = c0 + kWavesPerBlock * r;
+            if (c >= a.P) break;
+            int K, nodes;
+            bool changed, neg;
+            row_stage(K, nodes, changed, neg);
             Best best;
             if (MEMO && K >= 1 && K <= kTableK) {
                 const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
