@@ -316,31 +316,36 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
 // and the chunk's winner goes back to h = (A0 + s0 T_grad) + T_grad w once per chunk.
 // For point b the lanes whose batch size is feasible are known as a 64-bit lane mask in
 // scalar registers, tabled per (job, K) by last_kernel.  Per point and lane:
-//   w    = C * r + (b mod 8)   one v_fma_f64 (v_mul_f64 for 0): r from scalar registers, the
-//                              addend an inline constant (1, 2, 4) or one of four registers
-//                              that hold 3, 5, 6, 7 for the whole kernel
+//   w    = C * r + (b mod 16)  one v_fma_f64 (v_mul_f64 for 0): r from scalar registers, the
+//                              addend an inline constant (1, 2, 4) or one of twelve register
+//                              pairs that hold 3, 5, 6, .. 15 for the whole kernel
 //   lo   = (31 & b) | (~31 & lo(w))                       v_bfi_b32
 //   kmin = min(kmin, key)      v_min_f64 with only the feasible lanes enabled
 // so the key carries its position b in the low five mantissa bits (equal values resolve to
 // the smaller s), and a lane never sees an infeasible point.  Three VALU instructions per
-// point; masks and reciprocals arrive through the scalar cache.  Each run of eight
+// point; masks and reciprocals arrive through the scalar cache.  Each run of sixteen
 // positions has a minimum of its own (values relative to the run's first position); the
 // runs are merged after the chunk (merge_runs).
 typedef const double __attribute__((address_space(4))) *ScalarDoubles;
 typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
 
-constexpr int kRun = 8;
+constexpr int kRun = 16;
+constexpr int runs_of(int CH) { return CH > kRun ? CH / kRun : 1; }
 
-// The addends 3, 5, 6, 7 in vector registers.  Made once per kernel through an opaque
-// statement, so that they stay in registers instead of being formed again at every use.
+// The addends that are not inline constants (3, 5 .. 15) in vector registers.  Made once
+// per kernel through an opaque statement, so that they stay in registers instead of being formed
+// again at every use.
 struct RunSteps {
-    double x3, x5, x6, x7;
+    double x[kRun];
 };
 
 __device__ __forceinline__ RunSteps make_run_steps()
 {
-    RunSteps X = {3.0, 5.0, 6.0, 7.0};
-    asm volatile("" : "+v"(X.x3), "+v"(X.x5), "+v"(X.x6), "+v"(X.x7));
+    RunSteps X;
+#pragma unroll
+    for (int t = 0; t < kRun; ++t) X.x[t] = (double)t;
+    asm volatile("" : "+v"(X.x[3]), "+v"(X.x[5]), "+v"(X.x[6]), "+v"(X.x[7]), "+v"(X.x[8]), "+v"(X.x[9]), "+v"(X.x[10]),
+                      "+v"(X.x[11]), "+v"(X.x[12]), "+v"(X.x[13]), "+v"(X.x[14]), "+v"(X.x[15]));
     return X;
 }
 
@@ -354,7 +359,7 @@ __device__ __forceinline__ double point_key(double C, double r, const RunSteps &
     else if constexpr (t == 1) asm("v_fma_f64 %0, %1, %2, 1.0" : "=v"(g) : "v"(C), "s"(r));
     else if constexpr (t == 2) asm("v_fma_f64 %0, %1, %2, 2.0" : "=v"(g) : "v"(C), "s"(r));
     else if constexpr (t == 4) asm("v_fma_f64 %0, %1, %2, 4.0" : "=v"(g) : "v"(C), "s"(r));
-    else asm("v_fma_f64 %0, %1, %2, %3" : "=v"(g) : "v"(C), "s"(r), "v"(t == 3 ? X.x3 : (t == 5 ? X.x5 : (t == 6 ? X.x6 : X.x7))));
+    else asm("v_fma_f64 %0, %1, %2, %3" : "=v"(g) : "v"(C), "s"(r), "v"(X.x[t]));
     int gl;
     asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(gl) : "n"(B), "v"(__double2loint(g)));
     return __hiloint2double(__double2hiint(g), gl);
@@ -367,7 +372,7 @@ __device__ __forceinline__ double point_key(double C, double r, const RunSteps &
 // behind the previous group's work (volatile statements keep their order), so that only
 // one group's masks and reciprocals occupy scalar registers.
 template <int CH, int G>
-__device__ __forceinline__ void masked_group(double (&kmin)[CH / kRun], double C, const RunSteps &X, ScalarDoubles rs,
+__device__ __forceinline__ void masked_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles rs,
                                              ScalarMasks lanes)
 {
     asm volatile("" : "+s"(rs), "+s"(lanes));
@@ -395,7 +400,7 @@ __device__ __forceinline__ void masked_group(double (&kmin)[CH / kRun], double C
 }
 
 template <int CH, int G = 0>
-__device__ __forceinline__ void masked_groups(double (&kmin)[CH / kRun], double C, const RunSteps &X, ScalarDoubles rs,
+__device__ __forceinline__ void masked_groups(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles rs,
                                               ScalarMasks lanes)
 {
     if constexpr (4 * G < CH) {
@@ -405,15 +410,14 @@ __device__ __forceinline__ void masked_groups(double (&kmin)[CH / kRun], double 
 }
 
 // min(lower, upper + D) for the minima of two neighbouring stretches of positions, the upper
-// one starting D positions later; D = 8 or 16 is formed from inline constants.  The sum gets
+// one starting D positions later; D is formed from inline constants.  The sum gets
 // the position bits of `upper` back (+inf has none and stays +inf).
 template <int D>
 __device__ __forceinline__ double merge_runs(double lower, double upper)
 {
-    static_assert(D == 8 || D == 16, "offsets that are products of inline constants");
+    static_assert(D == 16, "an offset that is a product of inline constants");
     double moved;
-    if constexpr (D == 8) asm("v_fma_f64 %0, 4.0, 2.0, %1" : "=v"(moved) : "v"(upper));
-    else asm("v_fma_f64 %0, 4.0, 4.0, %1" : "=v"(moved) : "v"(upper));
+    asm("v_fma_f64 %0, 4.0, 4.0, %1" : "=v"(moved) : "v"(upper));
     int lo;
     asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(lo) : "v"(__double2loint(upper)), "v"(__double2loint(moved)));
     const double key = __hiloint2double(__double2hiint(moved), lo);
@@ -428,14 +432,13 @@ __device__ __forceinline__ double merge_runs(double lower, double upper)
 template <int CH>
 __device__ __forceinline__ double sweep_chunk(double C, const RunSteps &X, ScalarDoubles rs, ScalarMasks lanes)
 {
-    static_assert(CH == 8 || CH == 16 || CH == 32, "one, two or four runs");
-    double kmin[CH / kRun];
+    static_assert(CH == 8 || CH == 16 || CH == 32, "one or two runs");
+    double kmin[runs_of(CH)];
 #pragma unroll
-    for (int q = 0; q < CH / kRun; ++q) kmin[q] = __builtin_inf();
+    for (int q = 0; q < runs_of(CH); ++q) kmin[q] = __builtin_inf();
     masked_groups<CH>(kmin, C, X, rs, lanes);
-    if constexpr (CH == 8) return kmin[0];
-    else if constexpr (CH == 16) return merge_runs<8>(kmin[0], kmin[1]);
-    else return merge_runs<16>(merge_runs<8>(kmin[0], kmin[1]), merge_runs<8>(kmin[2], kmin[3]));
+    if constexpr (runs_of(CH) == 1) return kmin[0];
+    else return merge_runs<kRun>(kmin[0], kmin[1]);
 }
 
 // The same chunk for a GPU count beyond the tables, written as a plain loop (rare, so
@@ -520,22 +523,32 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         }
     }
 
-    // positive doubles order like their bit patterns: two unsigned 32-bit wave minima
+    // positive doubles order like their bit patterns: unsigned 32-bit wave minima, high words first;
+    // the low words only among several lanes that share the smallest high word
     const unsigned hi = (unsigned)__double2hiint(kbest), lo = (unsigned)__double2loint(kbest);
     const unsigned hmin = wave_min(hi);
     if (hmin >= 0x7FF00000u) return Pick{-1, -1};              // every lane still holds +inf
-    const unsigned lmin = wave_min(hi == hmin ? lo : 0xFFFFFFFFu);
-    const bool top = hi == hmin && lo == lmin;
-    const int ibest = (code >> 10) + lane;
-    const int sbest = (code & 1023) * CH + (int)(lo & 31u);
-    unsigned long long winners = __ballot(top);
-    if (__popcll(winners) > 1) {
-        const int flat = ibest * Gs + sbest;
-        const int first = wave_min(top ? flat : 0x7FFFFFFF);
-        winners = __ballot(top && flat == first);
+    unsigned long long winners = __builtin_amdgcn_ballot_w64(hi == hmin);
+    if (winners & (winners - 1)) {
+        const unsigned lmin = wave_min(hi == hmin ? lo : 0xFFFFFFFFu);
+        winners &= __builtin_amdgcn_ballot_w64(lo == lmin);
+        if (winners & (winners - 1)) {
+            // equal keys (duplicated batch sizes): the lowest flat index i * Gs + s.  Winners of one
+            // chunk differ in the lane only, so the lowest lane has it; else a third minimum.
+            const int code0 = __builtin_amdgcn_readlane(code, __ffsll(winners) - 1);
+            const unsigned long long same = __builtin_amdgcn_ballot_w64(code == code0);
+            if ((winners & ~same) != 0) {
+                const bool top = ((winners >> lane) & 1ull) != 0;
+                const int flat = ((code >> 10) + lane) * Gs + (code & 1023) * CH + (int)(lo & 31u);
+                const int first = wave_min(top ? flat : 0x7FFFFFFF);
+                winners &= __builtin_amdgcn_ballot_w64(flat == first);
+            }
+        }
     }
-    const int wl = __builtin_amdgcn_readfirstlane(__ffsll(winners) - 1);
-    return Pick{__builtin_amdgcn_readlane(ibest, wl), __builtin_amdgcn_readlane(sbest, wl)};
+    const int wl = __ffsll(winners) - 1;
+    const int wcode = __builtin_amdgcn_readlane(code, wl);
+    const int wlo = __builtin_amdgcn_readlane((int)lo, wl);
+    return Pick{(wcode >> 10) + wl, (wcode & 1023) * CH + (wlo & 31)};
 }
 
 template <int CH>
