@@ -372,8 +372,8 @@ __device__ __forceinline__ double point_key(double C, double r, const RunSteps &
 // behind the previous group's work (volatile statements keep their order), so that only
 // one group's masks and reciprocals occupy scalar registers.
 template <int CH, int G>
-__device__ __forceinline__ void masked_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles rs,
-                                             ScalarMasks lanes)
+__device__ __forceinline__ void masked_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles &rs,
+                                             ScalarMasks &lanes)
 {
     asm volatile("" : "+s"(rs), "+s"(lanes));
     double r0 = rs[4 * G + 0], r1 = rs[4 * G + 1], r2 = rs[4 * G + 2], r3 = rs[4 * G + 3];
@@ -400,8 +400,8 @@ __device__ __forceinline__ void masked_group(double (&kmin)[runs_of(CH)], double
 }
 
 template <int CH, int G = 0>
-__device__ __forceinline__ void masked_groups(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles rs,
-                                              ScalarMasks lanes)
+__device__ __forceinline__ void masked_groups(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles &rs,
+                                              ScalarMasks &lanes)
 {
     if constexpr (4 * G < CH) {
         masked_group<CH, G>(kmin, C, X, rs, lanes);
