@@ -512,7 +512,9 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                 // back from w to h = A0s + T_grad w, with the winner's position bits
                 const double g = sweep_chunk<CH>(C, X, rsc + s0, lanes + s0);
                 const double h = px_fma(tg, g, A0s);
-                kmin = __hiloint2double(__double2hiint(h), (__double2loint(h) & ~31) | (__double2loint(g) & 31));
+                int hl;
+                asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(hl) : "v"(__double2loint(g)), "v"(__double2loint(h)));
+                kmin = __hiloint2double(__double2hiint(h), hl);
             } else {
                 kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
             }
