@@ -240,6 +240,9 @@ __global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
     if (max_k <= 1) prior |= (1u << PX_ALPHA_SL) | (1u << PX_BETA_SL) | (1u << PX_ALPHA_SN) | (1u << PX_BETA_SN);
     if (max_nodes <= 1) prior |= (1u << PX_ALPHA_SN) | (1u << PX_BETA_SN);
     if (max_k <= 2) prior |= (1u << PX_BETA_SL) | (1u << PX_BETA_SN);
+    // Held in a vector register on purpose: everything derived from it (the active set, the iterate) then lives in
+    // vector registers, which this kernel has to spare, instead of in scalar registers, which it would spill.
+    asm("" : "+v"(prior));
 
     double start[kTheta] = {t_min * 0.5, t_min / (2.0 * m_at), t_min / 10.0, t_min / 100.0, t_min / 10.0, t_min / 100.0, 2.0};
     if (f.init) {
