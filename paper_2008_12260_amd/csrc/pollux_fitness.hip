@@ -834,7 +834,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     unsigned long long *__restrict__ cp = a.colpack + (size_t)c0 * a.N - (size_t)kWavesPerBlock * a.N;
 
     // The row stage of candidate c0 + 4 r: row reduce and constraint counters.
-    auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out) {
+    // ROW1 callers that have the row in registers already pass it as `have`; otherwise it is read here.
+    auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out, const int4 *have = nullptr) {
         row += row_step;
         cp += (size_t)kWavesPerBlock * a.N;
         // row reduce: K = sum, nodes = #positive, changed = differs from the current row
@@ -842,7 +843,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         bool changed = false, neg = false;
         int4 v0 = {0, 0, 0, 0};       // the lane's first four entries (the whole row when N <= 256)
         if constexpr (ROW1) {
-            const int4 v = ((const int4 *)row)[lane4];
+            const int4 v = have ? *have : ((const int4 *)row)[lane4];
             v0 = v;
             const int part = (v.x + v.y) + (v.z + v.w);
             ksum = lane < n4 ? part : 0;
@@ -910,18 +911,43 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         // other's addresses in scalar registers: first the row stage of every candidate (lane r keeps K and
         // nodes | changed of candidate r), then the sweeps, which elect a point per candidate; the points are
         // priced after the loop.
-        int rows = 0;
-        for (int r = 0; r < a.cand_per_wave; ++r) {
-            if (c0 + kWavesPerBlock * r >= a.P) break;
-            int K, nodes;
-            bool changed, neg;
-            row_stage(K, nodes, changed, neg);
-            if (lane == r) {
-                d_K = K;
-                d_meta = nodes | (changed ? kMetaChanged : 0);
+        int rows = a.cand_per_wave;
+        if (c0 + kWavesPerBlock * (rows - 1) >= a.P) rows = c0 < a.P ? (a.P - c0 + kWavesPerBlock - 1) / kWavesPerBlock : 0;
+        if constexpr (ROW1) {
+            // four rows are requested together: their latencies overlap
+            constexpr int kAhead = 4;
+            for (int r0 = 0; r0 < rows; r0 += kAhead) {
+                int4 v[kAhead];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
+                    v[u] = ((const int4 *)(row + (size_t)(ru - r0 + 1) * row_step))[lane4];
+                }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    if (r0 + u < rows) {
+                        int K, nodes;
+                        bool changed, neg;
+                        row_stage(K, nodes, changed, neg, &v[u]);
+                        if (lane == r0 + u) {
+                            d_K = K;
+                            d_meta = nodes | (changed ? kMetaChanged : 0);
+                        }
+                        any_neg |= neg;
+                    }
+                }
             }
-            any_neg |= neg;
-            rows = r + 1;
+        } else {
+            for (int r = 0; r < rows; ++r) {
+                int K, nodes;
+                bool changed, neg;
+                row_stage(K, nodes, changed, neg);
+                if (lane == r) {
+                    d_K = K;
+                    d_meta = nodes | (changed ? kMetaChanged : 0);
+                }
+                any_neg |= neg;
+            }
         }
         for (int r = 0; r < rows; ++r) {
             const int K = __builtin_amdgcn_readlane(d_K, r);
