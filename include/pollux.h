@@ -36,8 +36,9 @@ typedef struct {
     int32_t P;         /* candidates in the population                          */
     int32_t J;         /* jobs (running and pending), rows of an allocation matrix */
     int32_t N;         /* nodes, columns of an allocation matrix                */
-    int32_t Gm;        /* points of the per-GPU batch-size grid of each job     */
-    int32_t Gs;        /* gradient-accumulation steps considered: s = 0..Gs-1   */
+    int32_t Gm;        /* points of the per-GPU batch-size grid of each job, at most 2^20 */
+    int32_t Gs;        /* gradient-accumulation steps considered: s = 0..Gs-1, at most 2^14;
+                          (Gm + 63) x (Gs rounded up to a multiple of 32) at most 2^28   */
     int32_t precision; /* 0 = fp64 arithmetic, 1 = fp32 arithmetic              */
     int32_t flags;     /* PX_FLAG_* */
 } pollux_dims;

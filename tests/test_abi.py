@@ -61,6 +61,8 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
     d0 = px.Dims(16, 8, 4, 0, 8, 0, 0)
     assert L.pollux_fitness(ctypes.byref(d0), *args) == px.PX_E_INVALID_ARG
+    d_big = px.Dims(16, 8, 4, 1 << 20, 1 << 13, 0, 0)       # a job's lane-mask table would pass 2^31 bytes
+    assert L.pollux_fitness(ctypes.byref(d_big), *args) == px.PX_E_INVALID_ARG
 
     ga = px.GaParams(1, 0, 8, 0, 0)
     gargs = [fake, fake, fake, ctypes.byref(ga), fake, 1 << 30, ctypes.c_void_p(0x100000), null]
