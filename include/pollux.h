@@ -95,7 +95,9 @@ enum {
 /* bits of the status word */
 enum {
     PX_ST_BAD_PARAM = 1,    /* a job parameter outside the domain documented at PX_* above,
-                               or alpha_grad = beta_grad = 0 */
+                               or alpha_grad = beta_grad = 0; what is reported for such a job
+                               (and the fitness of every candidate, which averages over it) is
+                               then unspecified, the other jobs' results are unaffected */
     PX_ST_ZERO_FAIR = 2,    /* a job's fair-share goodput is 0: its SPEEDUP is set to 0 */
     PX_ST_BAD_RESTART = 4,  /* T_j - R_j * delta <= 0 for some job (penalty enabled) */
     PX_ST_NEG_ALLOC = 8     /* a negative entry in population or current_alloc */

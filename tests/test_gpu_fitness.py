@@ -111,6 +111,24 @@ def test_status_bits():
     assert run_gpu(wl, population=pop)["status"] == 8
 
 
+def test_a_job_without_gradient_time_is_flagged_and_leaves_the_other_jobs_alone():
+    """alpha_grad = beta_grad = 0 (T_grad = 0, outside the model's domain): status bit on both sides, the
+    call completes, and every other job's elected point and goodput still match the oracle."""
+    wl = W.make("physical")
+    ix = W.PARAM_INDEX
+    jp = wl.job_params.copy()
+    bad = 5
+    jp[ix["alpha_grad"], bad] = 0.0
+    jp[ix["beta_grad"], bad] = 0.0
+    g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
+    assert g["status"] & 1 and r["status"] & 1
+    others = np.arange(wl.cfg.J) != bad
+    for k in ("best_m", "best_s"):
+        assert np.array_equal(g[k][:, others], r[k][:, others])
+    for k in ("best_goodput", "speedup"):
+        assert np.allclose(g[k][:, others], r[k][:, others], rtol=1e-12, atol=0.0)
+
+
 def test_starved_jobs_and_duplicate_batch_sizes():
     wl = W.make("tiny")
     pop = wl.population.copy()
