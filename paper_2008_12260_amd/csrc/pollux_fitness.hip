@@ -1218,22 +1218,23 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     return a;
 }
 
-// tables_kernel and last_kernel: everything the sweep of a (job, K, nodes) needs
-static void launch_job_tables(const pollux_dims *d, const FitnessArgs &a, hipStream_t stream)
+// tables_kernel and, for the fp64 grid sweep, last_kernel: everything the sweep of a (job, K, nodes) needs
+static void launch_job_tables(const pollux_dims *d, const FitnessArgs &a, bool last_pass_tables, hipStream_t stream)
 {
     long long table_items = (long long)d->J * d->Gm;
-    if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
+    if (table_items < a.gs_pad) table_items = a.gs_pad;
     if (table_items < kRecipTable) table_items = kRecipTable;
     hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
     const long long lt_rows = (long long)d->J * 2 * kTableK;
-    hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+    if (last_pass_tables)
+        hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
 }
 
 static int launch_queries(const pollux_dims *d, const double *job_params, const int32_t *m_grid, void *workspace,
                           const QueryArgs &q, hipStream_t stream)
 {
     const FitnessArgs a = job_level_args(d, job_params, m_grid, workspace);
-    launch_job_tables(d, a, stream);
+    launch_job_tables(d, a, true, stream);
     const long long queries = (long long)d->J * (q.mode == 0 ? q.max_nodes + 1 : 1);
     const dim3 grid((unsigned)((queries + kWavesPerBlock - 1) / kWavesPerBlock));
     const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
@@ -1276,23 +1277,10 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
 {
     const WorkspaceLayout L = workspace_layout(*d);
     char *ws = (char *)workspace;
-    FitnessArgs a;
-    a.P = d->P; a.J = d->J; a.N = d->N; a.Gm = d->Gm; a.Gs = d->Gs; a.flags = d->flags;
-    a.population = population; a.m_grid = m_grid; a.fair_share = fair_share; a.current_alloc = current_alloc;
-    a.node_capacity = node_capacity; a.job_params = job_params;
+    FitnessArgs a = job_level_args(d, job_params, m_grid, workspace);
+    a.population = population; a.fair_share = fair_share; a.current_alloc = current_alloc;
+    a.node_capacity = node_capacity;
     a.p = p; a.delta = delta;
-    a.status = (int32_t *)(ws + L.status);
-    a.rs = (double *)(ws + L.rs);
-    a.rk = (double *)(ws + L.rk);
-    a.tg = (double2 *)(ws + L.tg);
-    a.lntg = (double *)(ws + L.lntg);
-    a.pu = (double *)(ws + L.pu);
-    a.qh5 = (double *)(ws + L.qh5);
-    a.ql5 = (double *)(ws + L.ql5);
-    a.lt = (double *)(ws + L.lt);
-    a.fmask = (unsigned long long *)(ws + L.fmask);
-    a.ni = (d->Gm + 63) / 64;
-    a.gs_pad = ((d->Gs + 31) / 32) * 32;
     a.denom = (double *)(ws + L.denom);
     a.factor = (double *)(ws + L.factor);
     a.running = (int32_t *)(ws + L.running);
@@ -1324,12 +1312,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
     if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         // everything that depends on the jobs only (not on the population)
-        long long table_items = (long long)d->J * d->Gm;
-        if (table_items < ((d->Gs + 31) / 32) * 32) table_items = ((d->Gs + 31) / 32) * 32;
-        if (table_items < kRecipTable) table_items = kRecipTable;
-        hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
-        if (!f32 && !sampled)
-            hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+        launch_job_tables(d, a, !f32 && !sampled, stream);
         const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
         if (sampled) hipLaunchKernelGGL((jobs_kernel<0, false>), job_grid, dim3(256), 0, stream, a);
         else if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
