@@ -82,8 +82,8 @@ struct FitnessArgs {
     int32_t *status;
     double *rs, *rk, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
     double2 *tg;                  // [J,Gm] (T_grad, 1 / T_grad)
-    unsigned long long *fmask;    // [J,kTableK,ni,gs_pad] feasibility lane masks (see last_kernel)
-    int ni, gs_pad;               // ceil(Gm / 64); Gs rounded up to a multiple of 32
+    int32_t *srange;              // [J,kTableK,Gm] feasible accumulation counts per (job, K, grid point) (see last_kernel)
+    int gs_pad;                   // Gs rounded up to a multiple of 32: length of rs
     int32_t *running, *meta;
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
@@ -225,8 +225,8 @@ __device__ __forceinline__ void feasible_range(double ql5, double qh5, double rK
 
 // One wavefront per row (job, placement class, K): lt[row][i] for every grid point i.
 // Row index ((j * 2 + one_node) * kTableK + (K - 1)).  The rows of the "several nodes"
-// class also write the feasibility masks of (job, K), which do not depend on the class:
-// fmask[j][K-1][g][s] has bit l set when grid point 64 g + l is feasible at s.
+// class also write the feasible accumulation counts of (job, K, i), which do not depend on
+// the class: srange[j][K-1][i] = first | last << 16, first > last when there is none.
 __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -242,22 +242,12 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
     for (int i = lane; i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i].x, a.lntg[o + i]);
     if (one_node) return;
     const double rK = a.rk[K];
-    unsigned long long *__restrict__ out = a.fmask + ((size_t)j * kTableK + (size_t)(K - 1)) * a.ni * a.gs_pad;
-    for (int g = 0; g < a.ni; ++g) {
-        const int i = g * kWave + lane;
-        int s_lo = 1, s_hi = 0;
-        if (i < a.Gm) feasible_range(a.ql5[o + i], a.qh5[o + i], rK, a.Gs, s_lo, s_hi);
-        for (int s0 = 0; s0 < a.gs_pad; s0 += kWave) {
-            // lane l collects the mask of s0 + l; one coalesced store per 64 accumulation counts
-            unsigned long long mine = 0ull;
-            const int span = a.gs_pad - s0 < kWave ? a.gs_pad - s0 : kWave;
-            for (int l = 0; l < span; ++l) {
-                const int s = s0 + l;
-                const unsigned long long m = __ballot(s_lo <= s && s <= s_hi);
-                if (lane == l) mine = m;
-            }
-            if (lane < span) out[(size_t)g * a.gs_pad + s0 + lane] = mine;
-        }
+    int32_t *__restrict__ out = a.srange + ((size_t)j * kTableK + (size_t)(K - 1)) * a.Gm;
+    for (int i = lane; i < a.Gm; i += kWave) {
+        int s_lo, s_hi;
+        feasible_range(a.ql5[o + i], a.qh5[o + i], rK, a.Gs, s_lo, s_hi);
+        if (s_lo > s_hi || s_hi < 0) { s_lo = 1; s_hi = 0; }
+        out[i] = s_lo | (s_hi << 16);
     }
 }
 
@@ -273,8 +263,7 @@ struct JobTables {
     const double2 *__restrict__ tg;   // (T_grad, 1 / T_grad)
     const double *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
     const double *__restrict__ lt;    // rows of this job in the last-pass table
-    const unsigned long long *__restrict__ fmask;   // feasibility masks of this job, [kTableK, ni, gs_pad]
-    int ni, gs_pad;
+    const int32_t *__restrict__ srange;   // feasible accumulation counts of this job, [kTableK, Gm]
 };
 
 // Wave-wide argmax of non-negative goodput values g (0 = the lane has no point): positive
@@ -310,24 +299,21 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
 }
 
 // ---- the sweep of one batch size per lane over CH accumulation counts ---------------
-// With C = B0 / T_grad the quantity to minimise is  h = A0 + T_grad (s + C / (s+1)).  Inside a
-// chunk of CH accumulation counts starting at s0 the lane ranks position b by
-//   w(b) = b + C r,   r = 1/(s0 + b + 1),
-// and the chunk's winner goes back to h = (A0 + s0 T_grad) + T_grad w once per chunk.
-// For point b the lanes whose batch size is feasible are known as a 64-bit lane mask in
-// scalar registers, tabled per (job, K) by last_kernel.  Per point and lane:
-//   w    = C * r + (b mod 16)  one v_fma_f64 (v_mul_f64 for 0): r from scalar registers, the
-//                              addend an inline constant (1, 2, 4) or one of twelve register
-//                              pairs that hold 3, 5, 6, .. 15 for the whole kernel
+// With C = B0 / T_grad the quantity to minimise is  h = A0 + T_grad w(s),  w(s) = s + C / (s+1),
+// for the lane's batch size.  The lane scans w over all accumulation counts, feasible or not;
+// C >= 0 makes w convex in s, and the feasible counts of a batch size form an interval (tabled
+// per (job, K, i) by last_kernel), so the smallest feasible w sits at the scan's argmin clamped
+// to that interval (sweep_pick).  Inside a chunk of CH counts starting at s0, per point and lane:
+//   w    = C * r + (b mod 16)  one v_fma_f64 (v_mul_f64 for 0): r = 1/(s0 + b + 1) from scalar
+//                              registers, the addend an inline constant (1, 2, 4) or one of
+//                              twelve register pairs that hold 3, 5, 6, .. 15 for the whole kernel
 //   lo   = (31 & b) | (~31 & lo(w))                       v_bfi_b32
-//   kmin = min(kmin, key)      v_min_f64 with only the feasible lanes enabled
+//   kmin = min(kmin, key)                                 v_min_f64
 // so the key carries its position b in the low five mantissa bits (equal values resolve to
-// the smaller s), and a lane never sees an infeasible point.  Three VALU instructions per
-// point; masks and reciprocals arrive through the scalar cache.  Each run of sixteen
-// positions has a minimum of its own (values relative to the run's first position); the
-// runs are merged after the chunk (merge_runs).
+// the smaller s).  Three VALU instructions per point; the reciprocals arrive through the
+// scalar cache.  Each run of sixteen positions has a minimum of its own (values relative to
+// the run's first position); the runs are merged after the chunk (merge_runs).
 typedef const double __attribute__((address_space(4))) *ScalarDoubles;
-typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
 
 constexpr int kRun = 16;
 constexpr int runs_of(int CH) { return CH > kRun ? CH / kRun : 1; }
@@ -366,52 +352,61 @@ __device__ __forceinline__ double point_key(double C, double r, const RunSteps &
 }
 
 // Four points at positions 4 G .. 4 G + 3 of the chunk (G a compile-time group index): the
-// four keys first, then the four minima, each with only its point's feasible lanes enabled
-// (five scalar instructions switch the lanes for the four of them).
-// The empty volatile statement at the head of a group keeps the scalar loads of the group
-// behind the previous group's work (volatile statements keep their order), so that only
-// one group's masks and reciprocals occupy scalar registers.
-template <int CH, int G>
-__device__ __forceinline__ void masked_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles &rs,
-                                             ScalarMasks &lanes)
+// four keys, then the four minima.  The volatile statements keep their order, so the
+// reciprocals of a group are requested after the previous group's work and only one group's
+// operands occupy scalar registers.
+struct GroupRecips {
+    double r0, r1, r2, r3;
+};
+
+template <int G>
+__device__ __forceinline__ GroupRecips load_group(ScalarDoubles &rs)
 {
-    asm volatile("" : "+s"(rs), "+s"(lanes));
-    double r0 = rs[4 * G + 0], r1 = rs[4 * G + 1], r2 = rs[4 * G + 2], r3 = rs[4 * G + 3];
-    unsigned long long l0 = lanes[4 * G + 0], l1 = lanes[4 * G + 1], l2 = lanes[4 * G + 2], l3 = lanes[4 * G + 3];
-    // both requests are on their way before the first key is formed
-    asm volatile("" : "+s"(r0), "+s"(r1), "+s"(r2), "+s"(r3), "+s"(l0), "+s"(l1), "+s"(l2), "+s"(l3));
-    const double k0 = point_key<4 * G + 0>(C, r0, X);
-    const double k1 = point_key<4 * G + 1>(C, r1, X);
-    const double k2 = point_key<4 * G + 2>(C, r2, X);
-    const double k3 = point_key<4 * G + 3>(C, r3, X);
-    unsigned long long saved;
-    asm volatile("s_and_saveexec_b64 %1, %6\n\t"
-                 "v_min_f64 %0, %0, %2\n\t"
-                 "s_and_b64 exec, %1, %7\n\t"
-                 "v_min_f64 %0, %0, %3\n\t"
-                 "s_and_b64 exec, %1, %8\n\t"
-                 "v_min_f64 %0, %0, %4\n\t"
-                 "s_and_b64 exec, %1, %9\n\t"
-                 "v_min_f64 %0, %0, %5\n\t"
-                 "s_mov_b64 exec, %1"
-                 : "+v"(kmin[4 * G / kRun]), "=&s"(saved)
-                 : "v"(k0), "v"(k1), "v"(k2), "v"(k3), "s"(l0), "s"(l1), "s"(l2), "s"(l3)
-                 : "scc");
+    asm volatile("" : "+s"(rs));
+    return GroupRecips{rs[4 * G + 0], rs[4 * G + 1], rs[4 * G + 2], rs[4 * G + 3]};
 }
 
+template <int CH, int G>
+__device__ __forceinline__ void scan_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, const GroupRecips &o)
+{
+    const double k0 = point_key<4 * G + 0>(C, o.r0, X);
+    const double k1 = point_key<4 * G + 1>(C, o.r1, X);
+    const double k2 = point_key<4 * G + 2>(C, o.r2, X);
+    const double k3 = point_key<4 * G + 3>(C, o.r3, X);
+    if constexpr ((4 * G) % kRun == 0) {
+        // the first group of a run starts its minimum
+        asm volatile("v_min_f64 %0, %1, %2\n\t"
+                     "v_min_f64 %0, %0, %3\n\t"
+                     "v_min_f64 %0, %0, %4"
+                     : "=&v"(kmin[4 * G / kRun])
+                     : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+    } else {
+        asm volatile("v_min_f64 %0, %0, %1\n\t"
+                     "v_min_f64 %0, %0, %2\n\t"
+                     "v_min_f64 %0, %0, %3\n\t"
+                     "v_min_f64 %0, %0, %4"
+                     : "+v"(kmin[4 * G / kRun])
+                     : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+    }
+}
+
+// The reciprocals of a group are requested one group ahead of their use.
 template <int CH, int G = 0>
-__device__ __forceinline__ void masked_groups(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles &rs,
-                                              ScalarMasks &lanes)
+__device__ __forceinline__ void scan_groups(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, ScalarDoubles &rs,
+                                            GroupRecips cur)
 {
     if constexpr (4 * G < CH) {
-        masked_group<CH, G>(kmin, C, X, rs, lanes);
-        masked_groups<CH, G + 1>(kmin, C, X, rs, lanes);
+        asm volatile("" : "+s"(cur.r0), "+s"(cur.r1), "+s"(cur.r2), "+s"(cur.r3));
+        GroupRecips next = cur;
+        if constexpr (4 * (G + 1) < CH) next = load_group<G + 1>(rs);
+        scan_group<CH, G>(kmin, C, X, cur);
+        scan_groups<CH, G + 1>(kmin, C, X, rs, next);
     }
 }
 
 // min(lower, upper + D) for the minima of two neighbouring stretches of positions, the upper
 // one starting D positions later; D is formed from inline constants.  The sum gets
-// the position bits of `upper` back (+inf has none and stays +inf).
+// the position bits of `upper` back.
 template <int D>
 __device__ __forceinline__ double merge_runs(double lower, double upper)
 {
@@ -426,17 +421,14 @@ __device__ __forceinline__ double merge_runs(double lower, double upper)
     return out;
 }
 
-// CH points starting at accumulation count s0; rs and lanes point at s0.  Returns the
-// smallest key of w over the chunk (position in its low five bits), +inf if no point is
-// feasible for the lane.
+// CH points starting at accumulation count s0; rs points at s0.  Returns the smallest key of
+// w over the chunk (values relative to s0, position in the low five bits).
 template <int CH>
-__device__ __forceinline__ double sweep_chunk(double C, const RunSteps &X, ScalarDoubles rs, ScalarMasks lanes)
+__device__ __forceinline__ double scan_chunk(double C, const RunSteps &X, ScalarDoubles rs)
 {
     static_assert(CH == 8 || CH == 16 || CH == 32, "one or two runs");
     double kmin[runs_of(CH)];
-#pragma unroll
-    for (int q = 0; q < runs_of(CH); ++q) kmin[q] = __builtin_inf();
-    masked_groups<CH>(kmin, C, X, rs, lanes);
+    scan_groups<CH>(kmin, C, X, rs, load_group<0>(rs));
     if constexpr (runs_of(CH) == 1) return kmin[0];
     else return merge_runs<kRun>(kmin[0], kmin[1]);
 }
@@ -464,9 +456,9 @@ struct Pick {
 };
 
 // All 64 lanes call this with the same (job, K >= 1, nodes).  Every lane returns the same result:
-// the point with the smallest key over the whole grid (equal keys, i.e. equal h and equal
-// position inside the chunk, resolve to the lowest flat index i * Gs + s).
-// TABLED: last pass and lane masks come from the job's tables (K <= kTableK), else they are formed here.
+// the feasible point with the smallest h over the whole grid (equal values resolve to the
+// lowest flat index i * Gs + s).
+// TABLED: last pass and feasible ranges come from the job's tables (K <= kTableK), else they are formed here.
 template <int CH, bool TABLED>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
@@ -474,13 +466,14 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     const int lane = lane_id();
     const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
-    // offsets inside one job's tables fit 32 bits (checked on the host)
+    // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
     const double *__restrict__ lrow = tb.lt + (unsigned)((one_node ? kTableK : 0) + (TABLED ? K - 1 : 0)) * (unsigned)Gm;
+    const int32_t *__restrict__ srow = tb.srange + (unsigned)(TABLED ? K - 1 : 0) * (unsigned)Gm;
     SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
-    double kbest = __builtin_inf();   // smallest key seen by this lane
-    int code = 0;                     // (first grid index of the m chunk) << 10 | (s chunk) of kbest
+    double kbest = __builtin_inf();   // smallest h seen by this lane
+    int sbest = 0, ibase = 0;         // its accumulation count, and the first grid index of its group of 64
     const ScalarDoubles rsc = (ScalarDoubles)rs;
 
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
@@ -497,31 +490,48 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const double u = *(const double *)((const char *)tb.pu + at) * rK;
         const double A0 = px_fma(u, tg, last);
         const double B0 = (last - tg) * u;
-        const double C = B0 * tgr.y;
-        int s_lo = 1, s_hi = 0;
-        if constexpr (!TABLED) {
+        double key = __builtin_inf();    // h of this batch size at its best feasible count s_c
+        int s_c = 0;
+        bool feasible;
+        if constexpr (TABLED) {
+            const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
+            const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
+            feasible = active && s_lo <= s_hi;
+            // the argmin of w over all counts: position bits of the smallest key, chunk by chunk
+            const double C = B0 * tgr.y;
+            double wmin = scan_chunk<CH>(C, X, rsc);
+            int s_star = __double2loint(wmin) & 31;
+            for (int s0 = CH; s0 < Gs; s0 += CH) {
+                const double w = scan_chunk<CH>(C, X, rsc + s0);
+                const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
+                if (moved < wmin) {
+                    wmin = moved;
+                    s_star = s0 + (__double2loint(w) & 31);
+                }
+            }
+            // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
+            s_c = s_star < s_hi ? s_star : s_hi;
+            s_c = s_c > s_lo ? s_c : s_lo;
+            const double w_c = px_fma(C, *(const double *)((const char *)rs + 8u * (unsigned)s_c), (double)s_c);
+            key = px_fma(tg, w_c, A0);
+        } else {
+            int s_lo = 1, s_hi = 0;
             feasible_range(tb.ql5[il], tb.qh5[il], rK, Gs, s_lo, s_hi);
             if (!active) s_hi = -1;
+            for (int s0 = 0; s0 < Gs; s0 += CH) {
+                const double A0s = s0 == 0 ? A0 : px_fma((double)s0, tg, A0);
+                const double kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
+                if (kmin < key) {
+                    key = kmin;
+                    s_c = s0 + (__double2loint(kmin) & 31);
+                }
+            }
+            feasible = key < __builtin_inf();
         }
-        const ScalarMasks lanes = (ScalarMasks)(tb.fmask + ((unsigned)(TABLED ? K - 1 : 0) * (unsigned)tb.ni + (unsigned)(i0 >> 6)) * (unsigned)tb.gs_pad);
-        int code_now = i0 << 10;
-        for (int s0 = 0; s0 < Gs; s0 += CH, ++code_now) {
-            const double A0s = s0 == 0 ? A0 : px_fma((double)s0, tg, A0);
-            double kmin;
-            if constexpr (TABLED) {
-                // back from w to h = A0s + T_grad w, with the winner's position bits
-                const double g = sweep_chunk<CH>(C, X, rsc + s0, lanes + s0);
-                const double h = px_fma(tg, g, A0s);
-                int hl;
-                asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(hl) : "v"(__double2loint(g)), "v"(__double2loint(h)));
-                kmin = __hiloint2double(__double2hiint(h), hl);
-            } else {
-                kmin = sweep_chunk_plain<CH>(tg, A0s, B0, rs + s0, s_lo - s0, s_hi - s0);
-            }
-            if (kmin < kbest) {
-                kbest = kmin;
-                code = code_now;
-            }
+        if (feasible && key < kbest) {
+            kbest = key;
+            sbest = s_c;
+            ibase = i0;
         }
     }
 
@@ -535,22 +545,21 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const unsigned lmin = wave_min(hi == hmin ? lo : 0xFFFFFFFFu);
         winners &= __builtin_amdgcn_ballot_w64(lo == lmin);
         if (winners & (winners - 1)) {
-            // equal keys (duplicated batch sizes): the lowest flat index i * Gs + s.  Winners of one
-            // chunk differ in the lane only, so the lowest lane has it; else a third minimum.
-            const int code0 = __builtin_amdgcn_readlane(code, __ffsll(winners) - 1);
-            const unsigned long long same = __builtin_amdgcn_ballot_w64(code == code0);
+            // equal values (duplicated batch sizes): the lowest flat index i * Gs + s.  Winners with one
+            // group of 64 and one count differ in the lane only, so the lowest lane has it; else a third minimum.
+            const int first_lane = __ffsll(winners) - 1;
+            const int ibase0 = __builtin_amdgcn_readlane(ibase, first_lane), sbest0 = __builtin_amdgcn_readlane(sbest, first_lane);
+            const unsigned long long same = __builtin_amdgcn_ballot_w64(ibase == ibase0 && sbest == sbest0);
             if ((winners & ~same) != 0) {
                 const bool top = ((winners >> lane) & 1ull) != 0;
-                const int flat = ((code >> 10) + lane) * Gs + (code & 1023) * CH + (int)(lo & 31u);
+                const int flat = (ibase + lane) * Gs + sbest;
                 const int first = wave_min(top ? flat : 0x7FFFFFFF);
                 winners &= __builtin_amdgcn_ballot_w64(flat == first);
             }
         }
     }
     const int wl = __ffsll(winners) - 1;
-    const int wcode = __builtin_amdgcn_readlane(code, wl);
-    const int wlo = __builtin_amdgcn_readlane((int)lo, wl);
-    return Pick{(wcode >> 10) + wl, (wcode & 1023) * CH + (wlo & 31)};
+    return Pick{__builtin_amdgcn_readlane(ibase, wl) + wl, __builtin_amdgcn_readlane(sbest, wl)};
 }
 
 template <int CH>
@@ -589,7 +598,7 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 {
     const size_t o = (size_t)j * a.Gm;
     return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
-                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.fmask + (size_t)j * kTableK * a.ni * a.gs_pad, a.ni, a.gs_pad};
+                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.srange + (size_t)j * kTableK * a.Gm};
 }
 
 // ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
@@ -1212,8 +1221,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     a.qh5 = (double *)(ws + L.qh5);
     a.ql5 = (double *)(ws + L.ql5);
     a.lt = (double *)(ws + L.lt);
-    a.fmask = (unsigned long long *)(ws + L.fmask);
-    a.ni = (d->Gm + 63) / 64;
+    a.srange = (int32_t *)(ws + L.srange);
     a.gs_pad = ((d->Gs + 31) / 32) * 32;
     return a;
 }

@@ -24,8 +24,8 @@ struct WorkspaceLayout {
     size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
     size_t ql5;       // double [J,Gm]    ceil(M0 / m_i) - 1/2
     size_t lt;        // double [J,2,kTableK,Gm]  last pass of Eq. 10 by (job, one node?, K)
-    size_t fmask;     // uint64 [J,kTableK,ceil(Gm/64),Gs up to a multiple of 32]  lanes whose batch size is
-                      //                  feasible at accumulation count s, by (job, K, group of 64 grid points)
+    size_t srange;    // int32  [J,kTableK,Gm]  feasible accumulation counts of grid point i with K GPUs:
+                      //                  first | last << 16 (first > last: none)
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
     size_t running;   // int32  [J]       job holds GPUs in current_alloc
@@ -52,7 +52,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.qh5 = o;     o = up(o + 8 * J * Gm);
     L.ql5 = o;     o = up(o + 8 * J * Gm);
     L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
-    L.fmask = o;   o = up(o + 8 * J * kTableK * ((Gm + 63) / 64) * (((Gs + 31) / 32) * 32));
+    L.srange = o;  o = up(o + 4 * J * kTableK * Gm);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
     L.running = o; o = up(o + 4 * J);
