@@ -13,7 +13,7 @@
 //                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
 //                     term depends on the allocation only through K and on whether
 //                     the job sits on one node, so it is shared by the population;
-//                     also the feasibility lane masks per (job, K, s)
+//                     also the feasible accumulation counts per (job, K, batch size)
 //   jobs_kernel       per job (one wavefront): parameter checks, restart factor,
 //                     fair-share goodput (denominator of Eq. 15)
 //   pairs_kernel      per (candidate, job) (one wavefront): row reduce, sweep of the
@@ -32,17 +32,17 @@
 //     h(m, s) = (last + u T_grad) + s T_grad + (last - T_grad) u / (s + 1)
 //             = A0 + T_grad w(s),    w(s) = s + C / (s + 1),   C = (last - T_grad) u / T_grad,
 // with every term non-negative.  The argmax of GOODPUT is the argmin of h over the
-// feasible points; for one batch size (one lane) that is the argmin of w, one
-// fused multiply-add per grid point, and h is formed once per lane and chunk of s
-// from the smallest w.  Which lanes hold a feasible batch size at a given s depends
-// on (job, K) only, so those 64-bit lane masks are tabled; the lane keeps its
-// minimum with one v_min_f64 per point, executed with only the feasible lanes
-// enabled, and the low five mantissa bits of w are replaced by the position of s in
-// its chunk (so the minimum carries its own index and equal values resolve to the
-// smaller s).  The perturbation is 2^-47 relative.  The wave then takes the smallest h
-// (equal keys: lowest flat index), and the elected point is evaluated again with the
-// formulas in the paper's own order (separate multiply and add, IEEE division), so
-// the reported goodput does not depend on the fast form.
+// feasible points.  For one batch size (one lane) that is the argmin of w over its
+// feasible s, which form an interval s_lo..s_hi that depends on (job, K, m) only and is
+// tabled.  The lane scans w over ALL s, one fused multiply-add per grid point, keeping
+// the minimum with one v_min_f64 per point after the low five mantissa bits of w have been
+// replaced by the position of s in its chunk (so the minimum carries its own index and equal
+// values resolve to the smaller s; the perturbation is 2^-47 relative).  w is convex in s
+// (C >= 0), so the feasible optimum sits at the scan's argmin clamped to s_lo..s_hi; h is
+// formed there once per lane and group of 64 batch sizes.  The wave then takes the
+// smallest h (equal values: lowest flat index), and the elected point is evaluated
+// again with the formulas in the paper's own order (separate multiply and add, IEEE
+// division), so the reported goodput does not depend on the fast form.
 //
 // The last pass of Eq. 10 is evaluated as
 //     max(Tg, Ts) * exp( log1p( exp(-g |ln Tg - ln Ts|) ) / g ),
