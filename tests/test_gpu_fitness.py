@@ -95,6 +95,29 @@ def test_tight_batch_limits_and_nothing_feasible():
     assert compare(wl, g, r, job_params=jp) == 0
 
 
+def test_feasible_windows_that_cut_off_the_unconstrained_optimum_on_either_side():
+    """Accumulation counts far beyond one chunk (Gs = 100).  Jobs with a heavy synchronisation cost want many
+    accumulation steps but a small M_max allows few; jobs with almost none want s = 0 but a large M0 forbids
+    small s: the elected point then sits on the boundary of the feasible window, in whichever chunk that is."""
+    cfg = W.custom("windows", P=24, J=30, N=8, cap=8, Gm=70, Gs=100)
+    wl = W.make(cfg)
+    ix = W.PARAM_INDEX
+    jp = wl.job_params.copy()
+    jp[ix["alpha_sync_local"], 0::3] = 5.0          # s* large ...
+    jp[ix["alpha_sync_node"], 0::3] = 8.0
+    jp[ix["M_max"], 0::3] = 4.0 * jp[ix["M0"], 0::3]    # ... but only a few counts are allowed
+    jp[ix["alpha_sync_local"], 1::3] = 1e-6         # s* = 0 ...
+    jp[ix["beta_sync_local"], 1::3] = 0.0
+    jp[ix["alpha_sync_node"], 1::3] = 1e-6
+    jp[ix["beta_sync_node"], 1::3] = 0.0
+    jp[ix["M0"], 1::3] = 6000.0                     # ... but small batches need many counts
+    jp[ix["M_max"], 1::3] = 60000.0
+    g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
+    assert compare(wl, g, r, job_params=jp) == 0
+    s = r["best_s"]
+    assert (s[:, 1::3] >= 8).any() and (s[:, 0::3] >= 1).any() and (s >= 32).any()     # the cases are really there
+
+
 def test_status_bits():
     wl = W.make("tiny")
     ix = W.PARAM_INDEX
