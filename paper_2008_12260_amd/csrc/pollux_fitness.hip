@@ -1304,7 +1304,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
     const long long pairs = (long long)d->P * d->J;
     // candidates per wavefront: enough wavefronts to fill the chip several times over, at most 16 per wavefront
-    long long per_wave = pairs / 40000;
+    long long per_wave = pairs / 25000;
     per_wave = per_wave < 1 ? 1 : (per_wave > 16 ? 16 : per_wave);
     a.cand_per_wave = (int)per_wave;
     a.cand_groups = (int)((d->P + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
