@@ -89,10 +89,12 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 //         its entries to colsum and to the node lists.
 // Step B  one thread per node over capacity: visit the jobs present in cyclic order
 //         from the drawn start and take GPUs away until the node fits.
-// Step C  one thread walks the nodes in ascending order: among the multi-node jobs
-//         present it keeps the largest holder (lowest job on ties) and zeroes the
-//         others there.  Sequential by definition: a job that loses a node may stop
-//         being multi-node, which later nodes must see.
+// Step C  the nodes are taken in ascending order: among the multi-node jobs present the
+//         largest holder stays (lowest job on ties) and the others are zeroed there.
+//         Sequential by definition: a job that loses a node may stop being multi-node,
+//         which later nodes must see.  One thread per node first lists the node's
+//         multi-node entries (up to four) in LDS; one wavefront then visits only the nodes
+//         that list two or more, four lanes looking at a node's entries together.
 // When a matrix has more positive entries than the lists hold (dense matrices) steps
 // B and C run the same rules on columns read from memory instead.
 //
@@ -109,10 +111,13 @@ inline int ga_max_entries(int J)
     return (int)(e < 512 ? 512 : (e > 3072 ? 3072 : e));
 }
 
+constexpr int kNodeSlots = 4;       // multi-node entries listed per node for step C (more: that node's list is walked)
+
 struct GaShared {
     unsigned long long *colsum;
     int32_t *nodes_of, *colcnt, *dist, *dec, *decx, *head;
     int32_t *ent_j, *ent_v, *ent_next;
+    uint16_t *slot;                 // [N, kNodeSlots] entry indices; shares the memory of dec / decx, which step A is done with
 };
 
 __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N, int max_entries)
@@ -128,10 +133,15 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.ent_j = sh.head + N;
     sh.ent_v = sh.ent_j + max_entries;
     sh.ent_next = sh.ent_v + max_entries;
+    // 2 * kNodeSlots bytes per node: inside dec / decx (8 bytes per job) when J >= N, else behind the entry arrays
+    sh.slot = J >= N ? (uint16_t *)sh.dec : (uint16_t *)(sh.ent_next + max_entries);
     return sh;
 }
 
-inline size_t ga_shared_bytes(int J, int N) { return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J); }
+inline size_t ga_shared_bytes(int J, int N)
+{
+    return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J) + (J >= N ? 0 : 2 * kNodeSlots * (size_t)N);
+}
 
 // Number of positive entries of a row; every lane returns the same value.
 __device__ __forceinline__ int count_occupied(const int32_t *__restrict__ row, int N, int lane)
@@ -370,34 +380,69 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         }
         __syncthreads();
         // ---- step C on the node lists ----
-        // which nodes hold two or more multi-node jobs now (later removals can only lower the count)
+        // which multi-node jobs each node holds now (later removals can only take some away)
         for (int n = tid; n < a.N; n += kGaThreads) {
             int cnt = 0;
-            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e])
-                cnt += (sh.ent_v[e] > 0 && sh.nodes_of[sh.ent_j[e]] >= 2);
+            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                if (sh.ent_v[e] > 0 && sh.nodes_of[sh.ent_j[e]] >= 2) {
+                    if (cnt < kNodeSlots) sh.slot[n * kNodeSlots + cnt] = (uint16_t)e;
+                    cnt++;
+                }
+            }
             sh.colcnt[n] = cnt;
         }
         __syncthreads();
-        if (tid != 0) return;
-        for (int n = 0; n < a.N; ++n) {
-            if (sh.colcnt[n] <= 1) continue;
-            int cnt = 0;
-            unsigned long long best = 0ull;
-            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
-                const int j = sh.ent_j[e];
-                if (sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
-                    cnt++;
-                    const unsigned long long key = holder_key(sh.ent_v[e], j);
-                    best = key > best ? key : best;
-                }
-            }
-            if (cnt <= 1) continue;
-            const int keeper = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
-            for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
-                const int j = sh.ent_j[e];
-                if (j != keeper && sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
-                    child[(size_t)j * a.N + n] = 0;
-                    sh.nodes_of[j] -= 1;
+        if (wave != 0) return;
+        for (int n0 = 0; n0 < a.N; n0 += kWave) {
+            unsigned long long conflicts = __ballot(n0 + lane < a.N && sh.colcnt[n0 + lane < a.N ? n0 + lane : 0] > 1);
+            while (conflicts) {
+                const int n = n0 + __ffsll(conflicts) - 1;
+                conflicts &= conflicts - 1;
+                const int listed = __builtin_amdgcn_readfirstlane(sh.colcnt[n]);
+                if (listed <= kNodeSlots) {
+                    // lane k < listed looks at the k-th listed entry
+                    int j = 0;
+                    int32_t v = 0;
+                    bool multi = false;
+                    if (lane < listed) {
+                        const int e = sh.slot[n * kNodeSlots + lane];
+                        j = sh.ent_j[e];
+                        v = sh.ent_v[e];
+                        multi = sh.nodes_of[j] >= 2;
+                    }
+                    if (__popcll(__ballot(multi)) > 1) {
+                        long long key = multi ? (long long)holder_key(v, j) : 0ll;      // below 2^63: v is positive
+                        long long other = exchange<0>(key);
+                        key = other > key ? other : key;
+                        other = exchange<1>(key);
+                        key = other > key ? other : key;                                  // the four lanes agree
+                        const int keeper = (int)(0xFFFFFFFFu - (uint32_t)((unsigned long long)key & 0xFFFFFFFFull));
+                        if (multi && j != keeper) {
+                            child[(size_t)j * a.N + n] = 0;
+                            sh.nodes_of[j] -= 1;
+                        }
+                    }
+                } else if (lane == 0) {
+                    int cnt = 0;
+                    unsigned long long best = 0ull;
+                    for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                        const int j = sh.ent_j[e];
+                        if (sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
+                            cnt++;
+                            const unsigned long long key = holder_key(sh.ent_v[e], j);
+                            best = key > best ? key : best;
+                        }
+                    }
+                    if (cnt > 1) {
+                        const int keeper = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+                        for (int e = sh.head[n]; e >= 0; e = sh.ent_next[e]) {
+                            const int j = sh.ent_j[e];
+                            if (j != keeper && sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
+                                child[(size_t)j * a.N + n] = 0;
+                                sh.nodes_of[j] -= 1;
+                            }
+                        }
+                    }
                 }
             }
         }
