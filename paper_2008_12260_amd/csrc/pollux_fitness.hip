@@ -832,8 +832,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int lane4 = lane < n4 ? lane : n4 - 1;      // ROW1: lanes past the end of the row load its last 16 bytes again
     const unsigned long long in_row = __ballot(lane < n4);
     constexpr bool kDeferred = !F32 && CH != 0;
-    const RunSteps X = make_run_steps();
     int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
+    RunSteps X = {};
     bool any_neg = false;
 
     // candidate c = c0 + kWavesPerBlock * r; its row of job j and its counters are reached by stepping pointers
@@ -923,8 +923,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         int rows = a.cand_per_wave;
         if (c0 + kWavesPerBlock * (rows - 1) >= a.P) rows = c0 < a.P ? (a.P - c0 + kWavesPerBlock - 1) / kWavesPerBlock : 0;
         if constexpr (ROW1) {
-            // four rows are requested together: their latencies overlap
-            constexpr int kAhead = 4;
+            // eight rows are requested together: their latencies overlap
+            constexpr int kAhead = 8;
             for (int r0 = 0; r0 < rows; r0 += kAhead) {
                 int4 v[kAhead];
 #pragma unroll
@@ -958,6 +958,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 any_neg |= neg;
             }
         }
+        X = make_run_steps();      // after the row pass, whose rows in flight use the registers these occupy
         for (int r = 0; r < rows; ++r) {
             const int K = __builtin_amdgcn_readlane(d_K, r);
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
