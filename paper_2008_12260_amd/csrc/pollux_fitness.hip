@@ -94,6 +94,7 @@ struct FitnessArgs {
 };
 
 constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
+constexpr int kNearRecips = 256;          // pairs kernel: reciprocals kept in LDS when Gs (rounded up to 32) is at most this
 constexpr int kPending = -2;             // pairs kernel: grid index of a row whose sweep is still to be done
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
@@ -461,8 +462,10 @@ struct Pick {
 // TABLED: last pass and feasible ranges come from the job's tables (K <= kTableK), else they are formed here.
 template <int CH, bool TABLED>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
-                                           const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
+                                           const double *__restrict__ rk, int Gm, int Gs, int K, int nodes,
+                                           const double *r_near = nullptr)
 {
+    // r_near: a copy of rs that is quicker to read per lane (LDS), or null
     const int lane = lane_id();
     const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
@@ -512,7 +515,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
-            const double w_c = px_fma(C, *(const double *)((const char *)rs + 8u * (unsigned)s_c), (double)s_c);
+            const double w_c = px_fma(C, *(const double *)((const char *)(r_near ? r_near : rs) + 8u * (unsigned)s_c), (double)s_c);
             key = px_fma(tg, w_c, A0);
         } else {
             int s_lo = 1, s_hi = 0;
@@ -820,6 +823,16 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     if (j >= a.J) return;
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
+    // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
+    __shared__ double r_lds[kNearRecips];
+    const double *r_near = nullptr;
+    if constexpr (!F32 && CH != 0 && !MEMO) {
+        if (a.gs_pad <= kNearRecips) {
+            for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) r_lds[t] = a.rs[t];
+            __syncthreads();
+            r_near = r_lds;
+        }
+    }
     const Job q = load_job(a.job_params, a.J, j);
     JobF32 qf = {};
     if constexpr (F32) qf = load_job_f32(a.job_params, a.J, j);
@@ -964,7 +977,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
-            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, r_near);
             if (lane == r) {
                 d_i = pick.i;
                 d_s = pick.s;
