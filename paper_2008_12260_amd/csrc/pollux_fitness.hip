@@ -467,7 +467,10 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
 {
     // r_near: a copy of rs that is quicker to read per lane (LDS), or null
     const int lane = lane_id();
-    const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
+    K = __builtin_amdgcn_readfirstlane(K);        // the same in every lane (see above): kept in scalar registers
+    nodes = __builtin_amdgcn_readfirstlane(nodes);
+    // 1/K arrives through the scalar cache
+    const double rK = K < kRecipTable ? ((ScalarDoubles)rk)[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
     // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
     const double *__restrict__ lrow = tb.lt + (unsigned)((one_node ? kTableK : 0) + (TABLED ? K - 1 : 0)) * (unsigned)Gm;
@@ -569,6 +572,8 @@ template <int CH>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
 {
+    K = __builtin_amdgcn_readfirstlane(K);             // the same in every lane: scalar from here on
+    nodes = __builtin_amdgcn_readfirstlane(nodes);
     if (K <= 0) return Pick{-1, -1};
     const RunSteps X = make_run_steps();
     if (K <= kTableK) return sweep_pick<CH, true>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
@@ -1093,6 +1098,8 @@ __global__ void __launch_bounds__(256) queries_kernel(FitnessArgs a, QueryArgs q
         nodes = q.nodes[j];
         if (!(q.progress[j] < q.target[j])) K = 0;              // a finished job is left as it is
     }
+    K = __builtin_amdgcn_readfirstlane(K);             // one query per wavefront: the same in every lane
+    nodes = __builtin_amdgcn_readfirstlane(nodes);
     Best best = {0.0, -1, -1};
     if (K > 0) best = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
     if (lane_id() != 0) return;
