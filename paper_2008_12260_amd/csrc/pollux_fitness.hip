@@ -479,7 +479,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
     double kbest = __builtin_inf();   // smallest h seen by this lane
-    int sbest = 0, ibase = 0;         // its accumulation count, and the first grid index of its group of 64
+    int where = 0;                    // its accumulation count | (index of its group of 64 batch sizes) << 16
     const ScalarDoubles rsc = (ScalarDoubles)rs;
 
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
@@ -536,8 +536,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         }
         if (feasible && key < kbest) {
             kbest = key;
-            sbest = s_c;
-            ibase = i0;
+            where = s_c | ((i0 / kWave) << 16);
         }
     }
 
@@ -554,18 +553,19 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             // equal values (duplicated batch sizes): the lowest flat index i * Gs + s.  Winners with one
             // group of 64 and one count differ in the lane only, so the lowest lane has it; else a third minimum.
             const int first_lane = __ffsll(winners) - 1;
-            const int ibase0 = __builtin_amdgcn_readlane(ibase, first_lane), sbest0 = __builtin_amdgcn_readlane(sbest, first_lane);
-            const unsigned long long same = __builtin_amdgcn_ballot_w64(ibase == ibase0 && sbest == sbest0);
+            const int where0 = __builtin_amdgcn_readlane(where, first_lane);
+            const unsigned long long same = __builtin_amdgcn_ballot_w64(where == where0);
             if ((winners & ~same) != 0) {
                 const bool top = ((winners >> lane) & 1ull) != 0;
-                const int flat = (ibase + lane) * Gs + sbest;
+                const int flat = ((where >> 16) * kWave + lane) * Gs + (where & 0xFFFF);
                 const int first = wave_min(top ? flat : 0x7FFFFFFF);
                 winners &= __builtin_amdgcn_ballot_w64(flat == first);
             }
         }
     }
     const int wl = __ffsll(winners) - 1;
-    return Pick{__builtin_amdgcn_readlane(ibase, wl) + wl, __builtin_amdgcn_readlane(sbest, wl)};
+    const int wwhere = __builtin_amdgcn_readlane(where, wl);
+    return Pick{(wwhere >> 16) * kWave + wl, wwhere & 0xFFFF};
 }
 
 template <int CH>
