@@ -482,7 +482,8 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     int where = 0;                    // its accumulation count | (index of its group of 64 batch sizes) << 16
     const ScalarDoubles rsc = (ScalarDoubles)rs;
 
-    for (int i0 = 0; i0 < Gm; i0 += kWave) {
+    // the counter of this loop is advanced on the scalar unit (it would otherwise be copied to a vector register)
+    for (int i0 = 0; i0 < Gm;) {
         const int i = i0 + lane;
         const bool active = i < Gm;
         const int il = active ? i : Gm - 1;
@@ -538,6 +539,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             kbest = key;
             where = s_c | ((i0 / kWave) << 16);
         }
+        asm volatile("s_add_i32 %0, %0, 64" : "+s"(i0) : : "scc");
     }
 
     // positive doubles order like their bit patterns: unsigned 32-bit wave minima, high words first;
