@@ -460,7 +460,8 @@ struct Pick {
 // the feasible point with the smallest h over the whole grid (equal values resolve to the
 // lowest flat index i * Gs + s).
 // TABLED: last pass and feasible ranges come from the job's tables (K <= kTableK), else they are formed here.
-template <int CH, bool TABLED>
+// WHOLE: the caller has checked that Gm is a multiple of 64, so no lane runs past the grid of batch sizes.
+template <int CH, bool TABLED, bool WHOLE = false>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes,
                                            const double *r_near = nullptr)
@@ -485,7 +486,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     // the counter of this loop is advanced on the scalar unit (it would otherwise be copied to a vector register)
     for (int i0 = 0; i0 < Gm;) {
         const int i = i0 + lane;
-        const bool active = i < Gm;
+        const bool active = WHOLE || i < Gm;
         const int il = active ? i : Gm - 1;
         // a uniform base plus a 32-bit byte offset per lane: the address needs no 64-bit vector arithmetic
         const unsigned at = (unsigned)il * 8u;
@@ -821,7 +822,8 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 
 // ROW1: the host has checked that a row is at most 256 entries, a multiple of four, and that
 // population and current_alloc are 16-byte aligned, so one 16-byte load per lane covers a row.
-template <int CH, bool F32, bool MEMO, bool ROW1>
+// WHOLE: the host has checked that Gm is a multiple of 64 (tabled sweeps then skip the test for the end of the grid).
+template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -984,7 +986,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
-            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, r_near);
+            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, r_near);
             if (lane == r) {
                 d_i = pick.i;
                 d_s = pick.s;
@@ -1361,12 +1363,14 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
+    const bool whole = d->Gm % kWave == 0;
 #define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1) \
     hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1>), dim3(pair_blocks), dim3(256), 0, stream, a)
 #define PX_LAUNCH_PAIRS_FP64(CH)                                   \
     do {                                                           \
         if (memo && row1) PX_LAUNCH_PAIRS(CH, false, true, true);  \
         else if (memo) PX_LAUNCH_PAIRS(CH, false, true, false);    \
+        else if (row1 && whole) hipLaunchKernelGGL((pairs_kernel<CH, false, false, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
         else if (row1) PX_LAUNCH_PAIRS(CH, false, false, true);    \
         else PX_LAUNCH_PAIRS(CH, false, false, false);             \
     } while (0)
