@@ -9,7 +9,7 @@
 //   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), 1/T_grad, ln T_grad, phi/m and
 //                     the feasibility bounds; reciprocals; clears the status word
 //   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
-//                     per row): T_sync (Eq. 9) and, for every batch size of the grid,
+//                     per eight rows): T_sync (Eq. 9) and, for every batch size of the grid,
 //                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
 //                     term depends on the allocation only through K and on whether
 //                     the job sits on one node, so it is shared by the population;
@@ -224,31 +224,56 @@ __device__ __forceinline__ void feasible_range(double ql5, double qh5, double rK
     s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
 }
 
-// One wavefront per row (job, placement class, K): lt[row][i] for every grid point i.
-// Row index ((j * 2 + one_node) * kTableK + (K - 1)).  The rows of the "several nodes"
+// lt[row][i] for every grid point i, row index ((j * 2 + one_node) * kTableK + (K - 1)).
+// One wavefront fills kLastRows rows of one (job, placement class): their inputs are read once and lane r
+// prepares T_sync and its logarithm for the r-th of them.  The rows of the "several nodes"
 // class also write the feasible accumulation counts of (job, K, i), which do not depend on
 // the class: srange[j][K-1][i] = first | last << 16, first > last when there is none.
+constexpr int kLastRows = 8;
+static_assert(kTableK % kLastRows == 0, "the rows of a wavefront belong to one job and class");
+
+__device__ __forceinline__ double wave_read(double v, int src)
+{
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), src), __builtin_amdgcn_readlane(__double2loint(v), src));
+}
+
 __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const long long row = (long long)blockIdx.x * kWavesPerBlock + wave;
-    if (row >= (long long)a.J * 2 * kTableK) return;
-    const int K = (int)(row % kTableK) + 1;
-    const bool one_node = ((row / kTableK) & 1) != 0;
-    const int j = (int)(row / (2 * kTableK));
+    const long long row0 = ((long long)blockIdx.x * kWavesPerBlock + wave) * kLastRows;
+    if (row0 >= (long long)a.J * 2 * kTableK) return;
+    const int K0 = (int)(row0 % kTableK) + 1;
+    const bool one_node = ((row0 / kTableK) & 1) != 0;
+    const int j = (int)(row0 / (2 * kTableK));
     const Job q = load_job(a.job_params, a.J, j);
-    const SyncTerm t = sync_term(q, K, one_node);
-    const size_t o = (size_t)j * a.Gm;
     const int lane = lane_id();
-    for (int i = lane; i < a.Gm; i += kWave) a.lt[(size_t)row * a.Gm + i] = last_pass(t, a.tg[o + i].x, a.lntg[o + i]);
-    if (one_node) return;
-    const double rK = a.rk[K];
-    int32_t *__restrict__ out = a.srange + ((size_t)j * kTableK + (size_t)(K - 1)) * a.Gm;
+    const SyncTerm mine = sync_term(q, K0 + (lane < kLastRows ? lane : 0), one_node);
+    SyncTerm t[kLastRows];
+#pragma unroll
+    for (int r = 0; r < kLastRows; ++r) {
+        t[r].ts = wave_read(mine.ts, r);
+        t[r].lnts = wave_read(mine.lnts, r);
+        t[r].gamma = mine.gamma;
+        t[r].inv_gamma = mine.inv_gamma;
+        t[r].mode = __builtin_amdgcn_readlane(mine.mode, r);
+    }
+    const size_t o = (size_t)j * a.Gm;
     for (int i = lane; i < a.Gm; i += kWave) {
-        int s_lo, s_hi;
-        feasible_range(a.ql5[o + i], a.qh5[o + i], rK, a.Gs, s_lo, s_hi);
-        if (s_lo > s_hi || s_hi < 0) { s_lo = 1; s_hi = 0; }
-        out[i] = s_lo | (s_hi << 16);
+        const double tg = a.tg[o + i].x, lntg = a.lntg[o + i];
+#pragma unroll
+        for (int r = 0; r < kLastRows; ++r) a.lt[(size_t)(row0 + r) * a.Gm + i] = last_pass(t[r], tg, lntg);
+    }
+    if (one_node) return;
+    int32_t *__restrict__ out = a.srange + ((size_t)j * kTableK + (size_t)(K0 - 1)) * a.Gm;
+    for (int i = lane; i < a.Gm; i += kWave) {
+        const double ql5 = a.ql5[o + i], qh5 = a.qh5[o + i];
+#pragma unroll
+        for (int r = 0; r < kLastRows; ++r) {
+            int s_lo, s_hi;
+            feasible_range(ql5, qh5, a.rk[K0 + r], a.Gs, s_lo, s_hi);
+            if (s_lo > s_hi || s_hi < 0) { s_lo = 1; s_hi = 0; }
+            out[(size_t)r * a.Gm + i] = s_lo | (s_hi << 16);
+        }
     }
 }
 
@@ -1260,7 +1285,7 @@ static void launch_job_tables(const pollux_dims *d, const FitnessArgs &a, bool l
     hipLaunchKernelGGL(tables_kernel, dim3((unsigned)((table_items + 255) / 256)), dim3(256), 0, stream, a);
     const long long lt_rows = (long long)d->J * 2 * kTableK;
     if (last_pass_tables)
-        hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
+        hipLaunchKernelGGL(last_kernel, dim3((unsigned)((lt_rows / kLastRows + kWavesPerBlock - 1) / kWavesPerBlock)), dim3(256), 0, stream, a);
 }
 
 static int launch_queries(const pollux_dims *d, const double *job_params, const int32_t *m_grid, void *workspace,
