@@ -63,13 +63,26 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
     const int lane = lane_id();
     double f = a.fitness[c];
     if (!(f == f)) f = -__builtin_inf();
-    int before = 0;
-    for (int o0 = 0; o0 < a.P; o0 += kWave) {
-        const int o = o0 + lane;
-        double g = o < a.P ? a.fitness[o] : -__builtin_inf();
-        if (!(g == g)) g = -__builtin_inf();
-        before += __popcll(__ballot(o < a.P && ((g > f) || (g == f && o < c))));
+    // every lane counts among the candidates o = lane, lane + 64, ...; eight loads are requested together
+    // (past the end the last candidate is read again and not counted)
+    constexpr int kBatch = 8;
+    int mine = 0;
+    for (int o0 = 0; o0 < a.P; o0 += kBatch * kWave) {
+        double g[kBatch];
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int o = o0 + u * kWave + lane;
+            g[u] = a.fitness[o < a.P ? o : a.P - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < kBatch; ++u) {
+            const int o = o0 + u * kWave + lane;
+            const double gu = (g[u] == g[u]) ? g[u] : -__builtin_inf();
+            const bool first = (gu > f) | ((gu == f) & (o < c));
+            mine += (int)((o < a.P) & first);
+        }
     }
+    const int before = wave_sum(mine);
     if (lane == 0) a.order[before] = c;
 }
 
