@@ -34,10 +34,13 @@
 // with every term non-negative.  The argmax of GOODPUT is the argmin of h over the
 // feasible points.  For one batch size (one lane) that is the argmin of w over its
 // feasible s, which form an interval s_lo..s_hi that depends on (job, K, m) only and is
-// tabled.  The lane scans w over ALL s, one fused multiply-add per grid point, keeping
-// the minimum with one v_min_f64 per point after the low five mantissa bits of w have been
-// replaced by the position of s in its chunk (so the minimum carries its own index and equal
-// values resolve to the smaller s; the perturbation is 2^-47 relative).  w is convex in s
+// tabled.  The lane scans w over ALL s, one fused multiply-add per grid point; the four values
+// of a group of four consecutive s are reduced with three v_min_f64, and the running minimum takes
+// that result after its low five mantissa bits have been replaced by the index of the group (so
+// the minimum carries the group it came from and equal values resolve to the earlier group; the
+// perturbation is 2^-47 relative).  The s inside the winning group is found once per lane
+// afterwards, from the group's four values formed again with their position in the low bits
+// (equal values: the smaller s).  w is convex in s
 // (C >= 0), so the feasible optimum sits at the scan's argmin clamped to s_lo..s_hi; h is
 // formed there once per lane and group of 64 batch sizes.  The wave then takes the
 // smallest h (equal values: lowest flat index), and the elected point is evaluated
@@ -329,17 +332,22 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
 // for the lane's batch size.  The lane scans w over all accumulation counts, feasible or not;
 // C >= 0 makes w convex in s, and the feasible counts of a batch size form an interval (tabled
 // per (job, K, i) by last_kernel), so the smallest feasible w sits at the scan's argmin clamped
-// to that interval (sweep_pick).  Inside a chunk of CH counts starting at s0, per point and lane:
-//   w    = C * r + (b mod 16)  one v_fma_f64 (v_mul_f64 for 0): r = 1/(s0 + b + 1) from scalar
+// to that interval (sweep_pick).  Inside a chunk of CH counts starting at s0, per group of four
+// positions b = 4 G .. 4 G + 3 and lane:
+//   w_b  = C * r + (b mod 16)  one v_fma_f64 each (v_mul_f64 for 0): r = 1/(s0 + b + 1) from scalar
 //                              registers, the addend an inline constant (1, 2, 4) or one of
 //                              twelve register pairs that hold 3, 5, 6, .. 15 for the whole kernel
-//   lo   = (31 & b) | (~31 & lo(w))                       v_bfi_b32
+//   g    = min of the four                                three v_min_f64
+//   lo   = (31 & G) | (~31 & lo(g))                       v_bfi_b32
 //   kmin = min(kmin, key)                                 v_min_f64
-// so the key carries its position b in the low five mantissa bits (equal values resolve to
-// the smaller s).  Three VALU instructions per point; the reciprocals arrive through the
+// so the key carries its group G in the low five mantissa bits (equal values resolve to
+// the earlier group): nine VALU instructions per four points; the reciprocals arrive through the
 // scalar cache.  Each run of sixteen positions has a minimum of its own (values relative to
-// the run's first position); the runs are merged after the chunk (merge_runs).
+// the run's first position); the runs are merged after the chunk (merge_runs).  The position
+// inside the winning group is found afterwards, once per lane (sweep_pick).
 typedef const double __attribute__((address_space(4))) *ScalarDoubles;
+typedef const double __attribute__((address_space(3))) *LdsDoubles;
+typedef double Double2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRun = 16;
 constexpr int runs_of(int CH) { return CH > kRun ? CH / kRun : 1; }
@@ -361,9 +369,9 @@ __device__ __forceinline__ RunSteps make_run_steps()
     return X;
 }
 
-// The key of position B of a chunk: w with B in its low five mantissa bits.
+// w at position B of a chunk, relative to the first position of its run.
 template <int B>
-__device__ __forceinline__ double point_key(double C, double r, const RunSteps &X)
+__device__ __forceinline__ double point_w(double C, double r, const RunSteps &X)
 {
     constexpr int t = B % kRun;
     double g;
@@ -372,13 +380,20 @@ __device__ __forceinline__ double point_key(double C, double r, const RunSteps &
     else if constexpr (t == 2) asm("v_fma_f64 %0, %1, %2, 2.0" : "=v"(g) : "v"(C), "s"(r));
     else if constexpr (t == 4) asm("v_fma_f64 %0, %1, %2, 4.0" : "=v"(g) : "v"(C), "s"(r));
     else asm("v_fma_f64 %0, %1, %2, %3" : "=v"(g) : "v"(C), "s"(r), "v"(X.x[t]));
-    int gl;
-    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(gl) : "n"(B), "v"(__double2loint(g)));
-    return __hiloint2double(__double2hiint(g), gl);
+    return g;
+}
+
+// v with TAG in its low five mantissa bits.
+template <int TAG>
+__device__ __forceinline__ double tagged(double v)
+{
+    int lo;
+    asm("v_bfi_b32 %0, 31, %1, %2" : "=v"(lo) : "n"(TAG), "v"(__double2loint(v)));
+    return __hiloint2double(__double2hiint(v), lo);
 }
 
 // Four points at positions 4 G .. 4 G + 3 of the chunk (G a compile-time group index): the
-// four keys, then the four minima.  The volatile statements keep their order, so the
+// four values, their minimum, its key.  The volatile statements keep their order, so the
 // reciprocals of a group are requested after the previous group's work and only one group's
 // operands occupy scalar registers.
 struct GroupRecips {
@@ -395,25 +410,19 @@ __device__ __forceinline__ GroupRecips load_group(ScalarDoubles &rs)
 template <int CH, int G>
 __device__ __forceinline__ void scan_group(double (&kmin)[runs_of(CH)], double C, const RunSteps &X, const GroupRecips &o)
 {
-    const double k0 = point_key<4 * G + 0>(C, o.r0, X);
-    const double k1 = point_key<4 * G + 1>(C, o.r1, X);
-    const double k2 = point_key<4 * G + 2>(C, o.r2, X);
-    const double k3 = point_key<4 * G + 3>(C, o.r3, X);
-    if constexpr ((4 * G) % kRun == 0) {
-        // the first group of a run starts its minimum
-        asm volatile("v_min_f64 %0, %1, %2\n\t"
-                     "v_min_f64 %0, %0, %3\n\t"
-                     "v_min_f64 %0, %0, %4"
-                     : "=&v"(kmin[4 * G / kRun])
-                     : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
-    } else {
-        asm volatile("v_min_f64 %0, %0, %1\n\t"
-                     "v_min_f64 %0, %0, %2\n\t"
-                     "v_min_f64 %0, %0, %3\n\t"
-                     "v_min_f64 %0, %0, %4"
-                     : "+v"(kmin[4 * G / kRun])
-                     : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
-    }
+    const double w0 = point_w<4 * G + 0>(C, o.r0, X);
+    const double w1 = point_w<4 * G + 1>(C, o.r1, X);
+    const double w2 = point_w<4 * G + 2>(C, o.r2, X);
+    const double w3 = point_w<4 * G + 3>(C, o.r3, X);
+    double g, g2;
+    asm volatile("v_min_f64 %0, %2, %3\n\t"
+                 "v_min_f64 %1, %4, %5\n\t"
+                 "v_min_f64 %0, %0, %1"
+                 : "=&v"(g), "=&v"(g2)
+                 : "v"(w0), "v"(w1), "v"(w2), "v"(w3));
+    const double key = tagged<G>(g);
+    if constexpr ((4 * G) % kRun == 0) kmin[4 * G / kRun] = key;      // the first group of a run starts its minimum
+    else asm volatile("v_min_f64 %0, %0, %1" : "+v"(kmin[4 * G / kRun]) : "v"(key));
 }
 
 // The reciprocals of a group are requested one group ahead of their use.
@@ -432,7 +441,7 @@ __device__ __forceinline__ void scan_groups(double (&kmin)[runs_of(CH)], double 
 
 // min(lower, upper + D) for the minima of two neighbouring stretches of positions, the upper
 // one starting D positions later; D is formed from inline constants.  The sum gets
-// the position bits of `upper` back.
+// the group bits of `upper` back.
 template <int D>
 __device__ __forceinline__ double merge_runs(double lower, double upper)
 {
@@ -448,7 +457,7 @@ __device__ __forceinline__ double merge_runs(double lower, double upper)
 }
 
 // CH points starting at accumulation count s0; rs points at s0.  Returns the smallest key of
-// w over the chunk (values relative to s0, position in the low five bits).
+// w over the chunk (values relative to s0, group of four positions in the low five bits).
 template <int CH>
 __device__ __forceinline__ double scan_chunk(double C, const RunSteps &X, ScalarDoubles rs)
 {
@@ -489,9 +498,9 @@ struct Pick {
 template <int CH, bool TABLED, bool WHOLE = false>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes,
-                                           const double *r_near = nullptr)
+                                           LdsDoubles near = nullptr, bool has_near = false)
 {
-    // r_near: a copy of rs that is quicker to read per lane (LDS), or null
+    // near: a copy of rs in LDS (quicker to read per lane) when has_near
     const int lane = lane_id();
     K = __builtin_amdgcn_readfirstlane(K);        // the same in every lane (see above): kept in scalar registers
     nodes = __builtin_amdgcn_readfirstlane(nodes);
@@ -530,22 +539,42 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active && s_lo <= s_hi;
-            // the argmin of w over all counts: position bits of the smallest key, chunk by chunk
+            // the group of four counts that holds the argmin of w over all counts: group bits of the smallest key, chunk by chunk
             const double C = B0 * tgr.y;
             double wmin = scan_chunk<CH>(C, X, rsc);
-            int s_star = __double2loint(wmin) & 31;
+            int g_star = __double2loint(wmin) & 31;
             for (int s0 = CH; s0 < Gs; s0 += CH) {
                 const double w = scan_chunk<CH>(C, X, rsc + s0);
                 const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
                 if (moved < wmin) {
                     wmin = moved;
-                    s_star = s0 + (__double2loint(w) & 31);
+                    g_star = s0 / 4 + (__double2loint(w) & 31);
                 }
             }
+            // inside that group: its four values once more (relative to the group's first count), each with
+            // its position in the low bits
+            Double2 r01, r23;
+            if (has_near) {
+                r01 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star);
+                r23 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star + 2);
+            } else {
+                r01 = *(const Double2 *)(rs + 4 * g_star);
+                r23 = *(const Double2 *)(rs + 4 * g_star + 2);
+            }
+            const double k0 = tagged<0>(C * r01.x), k1 = tagged<1>(px_fma(C, r01.y, 1.0));
+            const double k2 = tagged<2>(px_fma(C, r23.x, 2.0)), k3 = tagged<3>(px_fma(C, r23.y, X.x[3]));
+            double kk;
+            asm("v_min_f64 %0, %1, %2\n\t"
+                "v_min_f64 %0, %0, %3\n\t"
+                "v_min_f64 %0, %0, %4"
+                : "=&v"(kk)
+                : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+            const int s_star = 4 * g_star + (__double2loint(kk) & 3);
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
-            const double w_c = px_fma(C, *(const double *)((const char *)(r_near ? r_near : rs) + 8u * (unsigned)s_c), (double)s_c);
+            const double r_c = has_near ? near[s_c] : *(const double *)((const char *)rs + 8u * (unsigned)s_c);
+            const double w_c = px_fma(C, r_c, (double)s_c);
             key = px_fma(tg, w_c, A0);
         } else {
             int s_lo = 1, s_hi = 0;
@@ -859,12 +888,12 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int lane = lane_id();
     // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
     __shared__ double r_lds[kNearRecips];
-    const double *r_near = nullptr;
+    bool has_near = false;
     if constexpr (!F32 && CH != 0 && !MEMO) {
         if (a.gs_pad <= kNearRecips) {
             for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) r_lds[t] = a.rs[t];
             __syncthreads();
-            r_near = r_lds;
+            has_near = true;
         }
     }
     const Job q = load_job(a.job_params, a.J, j);
@@ -1011,7 +1040,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
-            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, r_near);
+            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near);
             if (lane == r) {
                 d_i = pick.i;
                 d_s = pick.s;
