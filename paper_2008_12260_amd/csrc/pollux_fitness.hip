@@ -351,6 +351,9 @@ typedef double Double2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRun = 16;
 constexpr int runs_of(int CH) { return CH > kRun ? CH / kRun : 1; }
+// Chunks of 32 tag per group of four positions; the shorter ones tag every position (twelve instructions per
+// four points, and nothing left to find afterwards: quicker for few counts per batch size).
+constexpr bool grouped_tags(int CH) { return CH >= 32; }
 
 // The addends that are not inline constants (3, 5 .. 15) in vector registers.  Made once
 // per kernel through an opaque statement, so that they stay in registers instead of being formed
@@ -414,15 +417,33 @@ __device__ __forceinline__ void scan_group(double (&kmin)[runs_of(CH)], double C
     const double w1 = point_w<4 * G + 1>(C, o.r1, X);
     const double w2 = point_w<4 * G + 2>(C, o.r2, X);
     const double w3 = point_w<4 * G + 3>(C, o.r3, X);
-    double g, g2;
-    asm volatile("v_min_f64 %0, %2, %3\n\t"
-                 "v_min_f64 %1, %4, %5\n\t"
-                 "v_min_f64 %0, %0, %1"
-                 : "=&v"(g), "=&v"(g2)
-                 : "v"(w0), "v"(w1), "v"(w2), "v"(w3));
-    const double key = tagged<G>(g);
-    if constexpr ((4 * G) % kRun == 0) kmin[4 * G / kRun] = key;      // the first group of a run starts its minimum
-    else asm volatile("v_min_f64 %0, %0, %1" : "+v"(kmin[4 * G / kRun]) : "v"(key));
+    if constexpr (grouped_tags(CH)) {
+        double g, g2;
+        asm volatile("v_min_f64 %0, %2, %3\n\t"
+                     "v_min_f64 %1, %4, %5\n\t"
+                     "v_min_f64 %0, %0, %1"
+                     : "=&v"(g), "=&v"(g2)
+                     : "v"(w0), "v"(w1), "v"(w2), "v"(w3));
+        const double key = tagged<G>(g);
+        if constexpr ((4 * G) % kRun == 0) kmin[4 * G / kRun] = key;      // the first group of a run starts its minimum
+        else asm volatile("v_min_f64 %0, %0, %1" : "+v"(kmin[4 * G / kRun]) : "v"(key));
+    } else {
+        const double k0 = tagged<4 * G + 0>(w0), k1 = tagged<4 * G + 1>(w1), k2 = tagged<4 * G + 2>(w2), k3 = tagged<4 * G + 3>(w3);
+        if constexpr ((4 * G) % kRun == 0) {
+            asm volatile("v_min_f64 %0, %1, %2\n\t"
+                         "v_min_f64 %0, %0, %3\n\t"
+                         "v_min_f64 %0, %0, %4"
+                         : "=&v"(kmin[4 * G / kRun])
+                         : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+        } else {
+            asm volatile("v_min_f64 %0, %0, %1\n\t"
+                         "v_min_f64 %0, %0, %2\n\t"
+                         "v_min_f64 %0, %0, %3\n\t"
+                         "v_min_f64 %0, %0, %4"
+                         : "+v"(kmin[4 * G / kRun])
+                         : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+        }
+    }
 }
 
 // The reciprocals of a group are requested one group ahead of their use.
@@ -539,37 +560,41 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active && s_lo <= s_hi;
-            // the group of four counts that holds the argmin of w over all counts: group bits of the smallest key, chunk by chunk
+            // the argmin of w over all counts (its group of four, where keys carry groups): low bits of the smallest key, chunk by chunk
             const double C = B0 * tgr.y;
             double wmin = scan_chunk<CH>(C, X, rsc);
+            constexpr int kPerTag = grouped_tags(CH) ? 4 : 1;
             int g_star = __double2loint(wmin) & 31;
             for (int s0 = CH; s0 < Gs; s0 += CH) {
                 const double w = scan_chunk<CH>(C, X, rsc + s0);
                 const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
                 if (moved < wmin) {
                     wmin = moved;
-                    g_star = s0 / 4 + (__double2loint(w) & 31);
+                    g_star = s0 / kPerTag + (__double2loint(w) & 31);
                 }
             }
-            // inside that group: its four values once more (relative to the group's first count), each with
-            // its position in the low bits
-            Double2 r01, r23;
-            if (has_near) {
-                r01 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star);
-                r23 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star + 2);
-            } else {
-                r01 = *(const Double2 *)(rs + 4 * g_star);
-                r23 = *(const Double2 *)(rs + 4 * g_star + 2);
+            int s_star = g_star;
+            if constexpr (grouped_tags(CH)) {
+                // inside that group: its four values once more (relative to the group's first count), each with
+                // its position in the low bits
+                Double2 r01, r23;
+                if (has_near) {
+                    r01 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star);
+                    r23 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star + 2);
+                } else {
+                    r01 = *(const Double2 *)(rs + 4 * g_star);
+                    r23 = *(const Double2 *)(rs + 4 * g_star + 2);
+                }
+                const double k0 = tagged<0>(C * r01.x), k1 = tagged<1>(px_fma(C, r01.y, 1.0));
+                const double k2 = tagged<2>(px_fma(C, r23.x, 2.0)), k3 = tagged<3>(px_fma(C, r23.y, X.x[3]));
+                double kk;
+                asm("v_min_f64 %0, %1, %2\n\t"
+                    "v_min_f64 %0, %0, %3\n\t"
+                    "v_min_f64 %0, %0, %4"
+                    : "=&v"(kk)
+                    : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
+                s_star = 4 * g_star + (__double2loint(kk) & 3);
             }
-            const double k0 = tagged<0>(C * r01.x), k1 = tagged<1>(px_fma(C, r01.y, 1.0));
-            const double k2 = tagged<2>(px_fma(C, r23.x, 2.0)), k3 = tagged<3>(px_fma(C, r23.y, X.x[3]));
-            double kk;
-            asm("v_min_f64 %0, %1, %2\n\t"
-                "v_min_f64 %0, %0, %3\n\t"
-                "v_min_f64 %0, %0, %4"
-                : "=&v"(kk)
-                : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
-            const int s_star = 4 * g_star + (__double2loint(kk) & 3);
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;

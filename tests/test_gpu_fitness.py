@@ -118,6 +118,24 @@ def test_feasible_windows_that_cut_off_the_unconstrained_optimum_on_either_side(
     assert (s[:, 1::3] >= 8).any() and (s[:, 0::3] >= 1).any() and (s >= 32).any()     # the cases are really there
 
 
+def test_more_accumulation_counts_than_the_reciprocal_table_kept_on_chip():
+    """Gs = 300: the table of 1/(s+1) no longer fits the on-chip copy, so the count inside the winning group of
+    four and the reciprocal at the clamped count come from memory.  Heavy synchronisation costs push the
+    elected count far up; M_max is wide enough to allow it."""
+    cfg = W.custom("long_s", P=6, J=9, N=8, cap=8, Gm=20, Gs=300)
+    wl = W.make(cfg)
+    ix = W.PARAM_INDEX
+    jp = wl.job_params.copy()
+    jp[ix["alpha_sync_local"], 0::2] = 10.0
+    jp[ix["alpha_sync_node"], 0::2] = 15.0
+    jp[ix["phi"], 0::2] = 1e6
+    jp[ix["M_max"], :] = 1e7
+    g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
+    assert compare(wl, g, r, job_params=jp) == 0
+    s = r["best_s"]
+    assert ((s >= 256) & (s < 299)).any() and ((s >= 100) & (s < 256)).any() and (s < 32).any()     # inside the range, not only at its end
+
+
 def test_status_bits():
     wl = W.make("tiny")
     ix = W.PARAM_INDEX
