@@ -73,6 +73,22 @@ __device__ __forceinline__ long long wave_sum(long long v)
         OP " %0, %0, %0 row_bcast:31 row_mask:0xc bank_mask:0xf"                                           \
         : "+v"(v))
 
+// The same four steps alone: every lane receives the result of its own row of 16 lanes.
+#define PX_DPP_ROW_REDUCE(OP, v)                                                                         \
+    asm("s_nop 1\n\t"                                                                                     \
+        OP " %0, %0, %0 quad_perm:[1,0,3,2] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                     \
+        OP " %0, %0, %0 quad_perm:[2,3,0,1] row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                     \
+        OP " %0, %0, %0 row_half_mirror row_mask:0xf bank_mask:0xf\n\ts_nop 1\n\t"                         \
+        OP " %0, %0, %0 row_mirror row_mask:0xf bank_mask:0xf"                                             \
+        : "+v"(v))
+
+// Sum over the lane's row of 16 lanes, returned in every lane of that row.
+__device__ __forceinline__ int row16_sum(int v)
+{
+    PX_DPP_ROW_REDUCE("v_add_u32_dpp", v);
+    return v;
+}
+
 __device__ __forceinline__ int wave_sum(int v)
 {
     PX_DPP_REDUCE("v_add_u32_dpp", v);

@@ -902,7 +902,9 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // ROW1: the host has checked that a row is at most 256 entries, a multiple of four, and that
 // population and current_alloc are 16-byte aligned, so one 16-byte load per lane covers a row.
 // WHOLE: the host has checked that Gm is a multiple of 64 (tabled sweeps then skip the test for the end of the grid).
-template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false>
+// ROW4: ROW1 and a row is at most 64 entries, so one load of the wavefront covers the rows of four candidates
+// (16 lanes each); cand_per_wave is at most 16.
+template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -1023,7 +1025,64 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         // priced after the loop.
         int rows = a.cand_per_wave;
         if (c0 + kWavesPerBlock * (rows - 1) >= a.P) rows = c0 < a.P ? (a.P - c0 + kWavesPerBlock - 1) / kWavesPerBlock : 0;
-        if constexpr (ROW1) {
+        if constexpr (ROW4) {
+            // Lanes 16 g .. 16 g + 15 hold the row of candidate 4 b + g of the wavefront in batch b; all
+            // batches are requested together.  Sums over a row are sums over 16 lanes (four DPP steps).
+            static_assert(ROW1, "rows of 16-byte groups");
+            const int g = lane >> 4, l16 = lane & 15;
+            const bool in_row16 = l16 < n4;
+            const int4 *__restrict__ row1 = (const int4 *)(row + row_step) + (in_row16 ? l16 : n4 - 1);
+            unsigned long long *__restrict__ cp1 = cp + (size_t)kWavesPerBlock * a.N + 4 * l16;
+            const int4 curg = ((const int4 *)cur)[in_row16 ? l16 : n4 - 1];
+            constexpr int kBatches = 4;
+            int4 v[kBatches];
+            int kb[kBatches] = {0, 0, 0, 0}, mb[kBatches] = {0, 0, 0, 0};
+#pragma unroll
+            for (int b = 0; b < kBatches; ++b) {
+                if (4 * b < rows) {
+                    const int r = 4 * b + g < rows ? 4 * b + g : rows - 1;             // the tail reads the last row again
+                    v[b] = *(const int4 *)((const int32_t *)row1 + (size_t)r * row_step);
+                }
+            }
+#pragma unroll
+            for (int b = 0; b < kBatches; ++b) {
+                if (4 * b < rows) {
+                    const int r = 4 * b + g;
+                    const bool live = in_row16 && r < rows;
+                    const int4 w = v[b];
+                    const int part = (w.x + w.y) + (w.z + w.w);
+                    const int positive = (w.x > 0 ? 1 : 0) + (w.y > 0 ? 1 : 0) + (w.z > 0 ? 1 : 0) + (w.w > 0 ? 1 : 0);
+                    const int differs = ((w.x != curg.x) | (w.y != curg.y) | (w.z != curg.z) | (w.w != curg.w)) ? 1 : 0;
+                    const int negative = ((w.x | w.y | w.z | w.w) < 0) ? 1 : 0;
+                    // one word carries three small counts: positive entries (at most 64), lanes that differ, lanes with a negative entry
+                    const int counts = row16_sum(live ? positive | (differs << 12) | (negative << 20) : 0);
+                    const int K = row16_sum(live ? part : 0);
+                    const int nodes = counts & 0xFFF;
+                    kb[b] = K;
+                    mb[b] = nodes | (((counts >> 12) & 0xFF) != 0 ? kMetaChanged : 0);
+                    any_neg |= __ballot(live && (counts >> 20) != 0) != 0ull;
+                    if (a.need_constraints && live) {
+                        // every non-zero entry goes to the candidate's per-node counters (a negative one as it is)
+                        const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
+                        unsigned long long *__restrict__ to = cp1 + (size_t)r * kWavesPerBlock * a.N;
+                        if (w.x != 0) atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
+                        if (w.y != 0) atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
+                        if (w.z != 0) atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
+                        if (w.w != 0) atomicAdd(&to[3], (unsigned long long)(long long)w.w + (w.w > 0 ? one_job : 0ull));
+                    }
+                }
+            }
+            // lane r takes over what candidate r needs: from lane 16 (r mod 4) of batch r / 4
+#pragma unroll
+            for (int b = 0; b < kBatches; ++b) {
+                const int from = ((lane & 3) * 16) << 2;
+                const int K = __builtin_amdgcn_ds_bpermute(from, kb[b]), meta = __builtin_amdgcn_ds_bpermute(from, mb[b]);
+                if ((lane >> 2) == b) {
+                    d_K = K;
+                    d_meta = meta;
+                }
+            }
+        } else if constexpr (ROW1) {
             // eight rows are requested together: their latencies overlap
             constexpr int kAhead = 8;
             for (int r0 = 0; r0 < rows; r0 += kAhead) {
@@ -1443,12 +1502,15 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool whole = d->Gm % kWave == 0;
+    const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
 #define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1) \
     hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1>), dim3(pair_blocks), dim3(256), 0, stream, a)
 #define PX_LAUNCH_PAIRS_FP64(CH)                                   \
     do {                                                           \
-        if (memo && row1) PX_LAUNCH_PAIRS(CH, false, true, true);  \
+        if (memo && row4) hipLaunchKernelGGL((pairs_kernel<CH, false, true, true, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+        else if (memo && row1) PX_LAUNCH_PAIRS(CH, false, true, true);  \
         else if (memo) PX_LAUNCH_PAIRS(CH, false, true, false);    \
+        else if (row4 && whole) hipLaunchKernelGGL((pairs_kernel<CH, false, false, true, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
         else if (row1 && whole) hipLaunchKernelGGL((pairs_kernel<CH, false, false, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
         else if (row1) PX_LAUNCH_PAIRS(CH, false, false, true);    \
         else PX_LAUNCH_PAIRS(CH, false, false, false);             \

@@ -152,6 +152,27 @@ def test_status_bits():
     assert run_gpu(wl, population=pop)["status"] == 8
 
 
+@pytest.mark.parametrize("flags", [0, 4])
+@pytest.mark.parametrize("shape", [dict(P=37, J=11, N=64, cap=8, Gm=64, Gs=16), dict(P=21, J=9, N=16, cap=4, Gm=64, Gs=8),
+                                   dict(P=522, J=200, N=64, cap=8, Gm=64, Gs=16)])       # the last: several candidates per wavefront
+def test_negative_entries_in_rows_of_at_most_64_nodes(shape, flags):
+    """Rows of at most 64 nodes are read four to a wavefront load.  A negative entry (invalid input) is
+    flagged, and K, the node count, the penalty and the per-node totals still follow the plain definitions
+    (the entry counts as it is), as in the oracle; plain and memoised (flags = 4)."""
+    cfg = W.custom("neg64", **shape)
+    wl = W.make(cfg)
+    pop = wl.population.copy()
+    rng = np.random.default_rng(5)
+    for cand in (0, 3, 4, 5, 6, cfg.P - 1):
+        for j in rng.choice(cfg.J, size=3, replace=False):
+            n = int(rng.integers(cfg.N))
+            pop[cand, j, n] = -int(rng.integers(1, 3))
+            pop[cand, j, (n + 5) % cfg.N] += 3          # most of these rows keep K >= 1
+    g, r = run_gpu(wl, population=pop, flags=flags), run_oracle(wl, population=pop)
+    assert g["status"] & 8 and r["status"] & 8
+    assert compare(wl, g, r, population=pop) == 0
+
+
 def test_a_job_without_gradient_time_is_flagged_and_leaves_the_other_jobs_alone():
     """alpha_grad = beta_grad = 0 (T_grad = 0, outside the model's domain): status bit on both sides, the
     call completes, and every other job's elected point and goodput still match the oracle."""
