@@ -190,6 +190,8 @@ __device__ __forceinline__ unsigned long long holder_key(int32_t v, int j)
     return ((unsigned long long)(uint32_t)v << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)j);
 }
 
+// FOUR: the host has checked that rows are 16-byte groups of at most 64 nodes and no per-job GPU limit is given.
+template <bool FOUR>
 __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
 {
     extern __shared__ __align__(16) unsigned char ga_lds[];
@@ -257,8 +259,36 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         }
     };
 
+    // Rows of at most 64 nodes that are copied unchanged (no move drawn, no GPU limit to apply): four rows per
+    // load of the wavefront, 16 lanes each.  The loop after this one then takes only the rows with a move.
+    if constexpr (FOUR) {
+        const int n4 = a.N >> 2;
+        const int g = lane >> 4, l16 = lane & 15;
+        for (int j0 = 4 * wave; j0 < a.J; j0 += 4 * waves) {
+            const int j = j0 + g;
+            const int d = j < a.J ? sh.dec[j] : 2;
+            const bool plain = (d >> 1) == 0;
+            int4 v = {0, 0, 0, 0};
+            if (plain && l16 < n4) {
+                v = ((const int4 *)(((d & 1) ? pb : pa) + (size_t)j * a.N))[l16];
+                ((int4 *)(child + (size_t)j * a.N))[l16] = v;
+                const int n = 4 * l16;
+                if (v.x != 0) record(j, n, v.x);
+                if (v.y != 0) record(j, n + 1, v.y);
+                if (v.z != 0) record(j, n + 2, v.z);
+                if (v.w != 0) record(j, n + 3, v.w);
+            }
+            const int nodes = row16_sum((v.x > 0 ? 1 : 0) + (v.y > 0 ? 1 : 0) + (v.z > 0 ? 1 : 0) + (v.w > 0 ? 1 : 0));
+            if (plain && l16 == 0) {
+                sh.nodes_of[j] = nodes;
+                if (nodes >= 2) sh.dist[atomicAdd(&n_dist, 1)] = j;
+            }
+        }
+    }
+
     for (int j = wave; j < a.J; j += waves) {
         const int d = __builtin_amdgcn_readfirstlane(sh.dec[j]);
+        if (FOUR && (d >> 1) == 0) continue;
         const int32_t *__restrict__ src = ((d & 1) ? pb : pa) + (size_t)j * a.N;
         int32_t *__restrict__ dst = child + (size_t)j * a.N;
         const int move = ((d >> 1) & 3) - 1;
@@ -536,13 +566,16 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
 
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);
+    const bool four = (d->N & 3) == 0 && d->N <= kWave && !a.job_gpu_cap && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
+    const void *kernel = four ? (const void *)generation_kernel<true> : (const void *)generation_kernel<false>;
     if (lds > 48 * 1024) {
-        if (hipFuncSetAttribute((const void *)generation_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
-            hipSuccess)
-            return PX_E_HIP;
+        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return PX_E_HIP;
     }
     const unsigned children_formed = a.in_place ? (unsigned)d->P - ga->elite_k : (unsigned)d->P;
-    if (children_formed > 0) hipLaunchKernelGGL(generation_kernel, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
+    if (children_formed > 0) {
+        if (four) hipLaunchKernelGGL(generation_kernel<true>, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
+        else hipLaunchKernelGGL(generation_kernel<false>, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
+    }
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 
