@@ -26,9 +26,9 @@ if ROOT not in sys.path:
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 (FMA) x 2.4 GHz
 FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 divisions, each counted as one
 # HBM bytes one launch of the sweep kernel moves on the "large" workload: rocprofv3 FETCH_SIZE (2 068 970 KiB,
-# scaled by 2.0) + WRITE_SIZE (698 128 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
+# scaled by 2.0) + WRITE_SIZE (698 395 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
 # size in the same runs (profiles/pairs_kernel_large.md).  Valid for the kernel those counters were taken on.
-SWEEP_HBM_BYTES = {"large": 2068970 * 1024 * 2.0 + 698128 * 1024 * 1.0}
+SWEEP_HBM_BYTES = {"large": 2068970 * 1024 * 2.0 + 698395 * 1024 * 1.0}
 # fp64 operations the same kernel executes per launch on "large", from the instruction counters of the same
 # profile: 64 lanes x (ADD_F64 + MUL_F64 + 2 x FMA_F64 wave-instructions)
 SWEEP_EXECUTED_FLOPS = {"large": 64 * (8.7697e6 + 4.9547e7 + 2 * 2.99136e8)}
