@@ -67,6 +67,7 @@
 namespace px {
 
 constexpr int kWavesPerBlock = 4;
+constexpr int kMaxCandPerWave = 16;   // pairs kernel: candidates one wavefront walks at most (lane r keeps what candidate r needs)
 constexpr int kRecipTable = 256;      // 1/K is tabled for K below this
 
 // Result of the sweep for one (job, placement class, K); filled and used only in memoised mode.
@@ -1034,9 +1035,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             const int4 *__restrict__ row1 = (const int4 *)(row + row_step) + (in_row16 ? l16 : n4 - 1);
             unsigned long long *__restrict__ cp1 = cp + (size_t)kWavesPerBlock * a.N + 4 * l16;
             const int4 curg = ((const int4 *)cur)[in_row16 ? l16 : n4 - 1];
-            constexpr int kBatches = 4;
+            constexpr int kBatches = kMaxCandPerWave / 4;
             int4 v[kBatches];
-            int kb[kBatches] = {0, 0, 0, 0}, mb[kBatches] = {0, 0, 0, 0};
+            int kb[kBatches] = {}, mb[kBatches] = {};
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
                 if (4 * b < rows) {
@@ -1466,9 +1467,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     // unrolled s-chunk: the smallest of 8, 16, 32 that covers Gs (32 with several chunks beyond that)
     const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
     const long long pairs = (long long)d->P * d->J;
-    // candidates per wavefront: enough wavefronts to fill the chip several times over, at most 16 per wavefront
+    // candidates per wavefront: enough wavefronts to fill the chip several times over
     long long per_wave = pairs / 25000;
-    per_wave = per_wave < 1 ? 1 : (per_wave > 16 ? 16 : per_wave);
+    per_wave = per_wave < 1 ? 1 : (per_wave > kMaxCandPerWave ? kMaxCandPerWave : per_wave);
     a.cand_per_wave = (int)per_wave;
     a.cand_groups = (int)((d->P + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
     const unsigned pair_blocks = (unsigned)(8 * ((d->J + 7) / 8) * a.cand_groups);
