@@ -1206,6 +1206,98 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     }
 }
 
+// ---- memoised mode, candidate by candidate ------------------------------------------------
+// With the sweeps looked up (PX_FLAG_MEMOISE) a pair costs its row reduce only, so the pass is bound by
+// reading the population.  This kernel walks it in memory order: a workgroup takes 64 consecutive jobs of one
+// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, four rows of the candidate and of
+// the current allocation requested together; lane r then finishes the pair of the wavefront's r-th job, so the
+// results of a wavefront are consecutive in memory too.  Launched when rows are 16-byte groups of 65 to 256
+// entries (shorter rows: pairs_kernel with four rows per load).  A row with more GPUs than the memo table
+// covers is swept here by the whole wavefront (rare).
+template <int CH>
+__global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
+{
+    constexpr int kJobsPerWave = 16, kAhead = 4;
+    const int tiles = (a.J + kWavesPerBlock * kJobsPerWave - 1) / (kWavesPerBlock * kJobsPerWave);
+    const int c = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int j0 = (tile * kWavesPerBlock + wave) * kJobsPerWave;
+    if (c >= a.P || j0 >= a.J) return;
+    const int rows = a.J - j0 < kJobsPerWave ? a.J - j0 : kJobsPerWave;
+    const int n4 = a.N >> 2;
+    const int lane4 = lane < n4 ? lane : n4 - 1;          // lanes past the end of a row load its last 16 bytes again
+    const unsigned long long in_row = __ballot(lane < n4);
+    const int4 *__restrict__ rowp = (const int4 *)(a.population + ((size_t)c * a.J + j0) * a.N) + lane4;
+    const int4 *__restrict__ curp = (const int4 *)(a.current_alloc + (size_t)j0 * a.N) + lane4;
+    unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
+    int d_K = 0, d_meta = 0;                              // lane r: K and nodes | changed of job j0 + r
+    bool any_neg = false;
+
+    for (int r0 = 0; r0 < rows; r0 += kAhead) {
+        int4 v[kAhead], cv[kAhead];
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int ru = r0 + u < rows ? r0 + u : rows - 1;                 // the tail reads the last row again
+            v[u] = rowp[(size_t)ru * n4];
+            cv[u] = curp[(size_t)ru * n4];
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            if (r0 + u < rows) {
+                const int4 w = v[u], was = cv[u];
+                const int part = (w.x + w.y) + (w.z + w.w);
+                const int K = wave_sum(lane < n4 ? part : 0);
+                const int nodes = __popcll(__ballot(w.x > 0) & in_row) + __popcll(__ballot(w.y > 0) & in_row) +
+                                  __popcll(__ballot(w.z > 0) & in_row) + __popcll(__ballot(w.w > 0) & in_row);
+                const bool changed = ((__ballot(w.x != was.x) | __ballot(w.y != was.y) | __ballot(w.z != was.z) | __ballot(w.w != was.w)) & in_row) != 0;
+                any_neg |= (__ballot((w.x | w.y | w.z | w.w) < 0) & in_row) != 0;
+                if (a.need_constraints && lane < n4) {
+                    // every non-zero entry goes to the candidate's per-node counters (a negative one as it is)
+                    const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
+                    unsigned long long *__restrict__ to = cp + 4 * lane;
+                    if (w.x != 0) atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
+                    if (w.y != 0) atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
+                    if (w.z != 0) atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
+                    if (w.w != 0) atomicAdd(&to[3], (unsigned long long)(long long)w.w + (w.w > 0 ? one_job : 0ull));
+                }
+                if (lane == r0 + u) {
+                    d_K = K;
+                    d_meta = nodes | (changed ? kMetaChanged : 0);
+                }
+            }
+        }
+    }
+
+    // rows beyond the memo table: swept and priced here
+    Best beyond = {0.0, -1, -1};
+    unsigned long long pending = __ballot(lane < rows && d_K > kTableK);
+    while (pending) {
+        const int l = __ffsll(pending) - 1;
+        pending &= pending - 1;
+        const int K = __builtin_amdgcn_readlane(d_K, l);
+        const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
+        const Best b = sweep<CH>(load_job(a.job_params, a.J, j0 + l), job_tables(a, j0 + l), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        if (lane == l) beyond = b;
+    }
+    if (lane < rows) {
+        const int j = j0 + lane;
+        const size_t pair = (size_t)c * a.J + j;
+        const int nodes = d_meta & ~kMetaChanged;
+        Best best = beyond;
+        if (d_K >= 1 && d_K <= kTableK) {
+            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
+            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+        }
+        a.G[pair] = best.goodput;
+        a.meta[pair] = d_meta;
+        a.best_m[pair] = best.m;
+        a.best_s[pair] = best.s;
+        if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+    }
+    if (any_neg && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
+}
+
 // ---- the argmax alone, for the consumers outside the search ----------------------------
 // One wavefront per query (job, K, nodes): the same sweep and pricing as a (candidate, job) pair.
 //   per_gpu mode   query (j, n), n = 0..max_nodes: column 0 is the job on one GPU, column n >= 1
@@ -1516,7 +1608,14 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         else if (row1) PX_LAUNCH_PAIRS(CH, false, false, true);    \
         else PX_LAUNCH_PAIRS(CH, false, false, false);             \
     } while (0)
-    if (sampled) {
+    if (memo && !sampled && !f32 && row1 && !row4) {
+        // memoised pass over rows of 65 to 256 entries: in memory order
+        const unsigned tiles = (unsigned)((d->J + kWavesPerBlock * 16 - 1) / (kWavesPerBlock * 16));
+        const dim3 memo_pairs_grid((unsigned)d->P * tiles);
+        if (ch == 8) hipLaunchKernelGGL(memo_pairs_kernel<8>, memo_pairs_grid, dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL(memo_pairs_kernel<16>, memo_pairs_grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL(memo_pairs_kernel<32>, memo_pairs_grid, dim3(256), 0, stream, a);
+    } else if (sampled) {
         if (memo) PX_LAUNCH_PAIRS(0, false, true, false);
         else PX_LAUNCH_PAIRS(0, false, false, false);
     } else if (f32) {

@@ -304,6 +304,28 @@ def test_memoised_mode_gives_the_same_results(name):
         assert np.array_equal(g[k], plain[k], equal_nan=True), k
 
 
+@pytest.mark.parametrize("shape", [dict(P=7, J=70, N=128, cap=2, Gm=20, Gs=6),          # a second, partly filled tile of jobs
+                                   dict(P=5, J=21, N=68, cap=40, Gm=33, Gs=5),          # K beyond the memo table
+                                   dict(P=3, J=130, N=256, cap=8, Gm=64, Gs=32)])
+def test_memoised_mode_on_rows_of_65_to_256_nodes(shape):
+    """These rows take the memoised pass that walks the population candidate by candidate; negative entries in a
+    few rows as well (flagged, counted as they are)."""
+    cfg = W.custom("memo_rows", **shape)
+    wl = W.make(cfg)
+    g = run_gpu(wl, flags=4)
+    assert compare(wl, g, run_oracle(wl)) == 0
+    plain = run_gpu(wl)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations"):
+        assert np.array_equal(g[k], plain[k], equal_nan=True), k
+    pop = wl.population.copy()
+    pop[0, 1, 3] = -1
+    pop[cfg.P - 1, cfg.J - 1, cfg.N - 1] = -2
+    pop[cfg.P - 1, cfg.J - 1, 0] += 4
+    g, r = run_gpu(wl, population=pop, flags=4), run_oracle(wl, population=pop)
+    assert g["status"] & 8 and r["status"] & 8
+    assert compare(wl, g, r, population=pop) == 0
+
+
 def test_memoised_mode_with_rows_beyond_the_table_and_in_fp32():
     cfg = W.custom("bigK", P=6, J=40, N=9, cap=40, Gm=33, Gs=5)      # K up to 160: beyond the 64-entry table
     wl = W.make(cfg)
