@@ -21,6 +21,8 @@
 //                     per-candidate, per-node counters with integer atomics
 //   candidates_kernel per candidate (one workgroup): SPEEDUP, penalty, constraint
 //                     check from those counters and the generalized mean
+// With PX_FLAG_MEMOISE, memo_kernel sweeps once per (job, placement class, K <= 64) and the population pass
+// (pairs_kernel, or memo_pairs_kernel for rows of 65 to 256 nodes) looks the result up.
 // With PX_FLAG_SAMPLE_M the sweep is replaced by sweep_sampled (Sec. 4.3), the kernels
 // instantiated with CH = 0, and last_kernel is not launched.
 //
