@@ -52,7 +52,8 @@ enum {
     PX_FLAG_KEEP_JOB_TABLES = 8,      /* reuse what the previous pollux_fitness call on this workspace derived from
                                          the jobs alone (tables, fair-share goodput, restart factors, memoised
                                          sweeps): the caller guarantees that dims, job_params, m_grid, fair_share,
-                                         current_alloc, delta and the other flags are unchanged since that call,
+                                         current_alloc, delta and the other flags are unchanged since that call
+                                         and that nothing but this library has written to the workspace,
                                          as in the generations of one scheduling interval.  The status word is
                                          then not cleared and keeps accumulating. */
     PX_FLAG_SAMPLE_M = 16             /* the argmax of Eq. 13 by the sampling procedure of Sec. 4.3 instead of the

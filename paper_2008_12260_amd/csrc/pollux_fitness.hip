@@ -1426,9 +1426,11 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     // constraint check, part two: per node, multi-node jobs beyond the first and GPUs beyond capacity
     long long v = 0;
     if (a.need_constraints) {
-        const unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
+        // the counters are left at zero for the next call on this workspace (see launch_fitness)
+        unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
         for (int n = t; n < a.N; n += kCandThreads) {
             const long long x = (long long)cp[n];
+            cp[n] = 0ull;
             const long long asked = (x << 24) >> 24;              // low 40 bits, sign-extended
             const long long distributed = (x - asked) >> 40;
             if (distributed > 1) v += distributed - 1;
@@ -1572,7 +1574,10 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool f32 = d->precision == 1;
     const bool memo = (d->flags & PX_FLAG_MEMOISE) != 0;
     const bool sampled = (d->flags & PX_FLAG_SAMPLE_M) != 0;       // fp64 only (checked by the caller)
-    if (a.need_constraints) {
+    // The per-node counters start every call at zero.  A call that uses them leaves them at zero again
+    // (candidates_kernel clears what it reads), so a call that keeps the job tables, whose caller guarantees an
+    // untouched workspace and unchanged dimensions, does not clear them once more.
+    if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         long long zb = ((long long)d->P * d->N + 255) / 256;
         hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
     }

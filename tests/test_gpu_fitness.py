@@ -349,7 +349,10 @@ def test_keep_job_tables_reuses_the_job_level_work():
                               wl.node_capacity, p=c.p, delta=c.delta, flags=flags)
         first = torch.as_tensor(wl.population).cuda()
         other = torch.as_tensor(np.ascontiguousarray(wl.population[::-1])).cuda()
+        crowded = torch.as_tensor(np.ascontiguousarray(wl.population * 3)).cuda()      # over capacity on many nodes
         call.run(first)
+        call.run(crowded, keep_job_tables=True)       # leaves no trace in the per-node counters of the next call
+        assert call.results()["violations"].max() > 0
         call.run(other, keep_job_tables=True)
         kept = call.results()
         call.run(other)
