@@ -471,3 +471,26 @@ def test_many_random_shapes_and_parameter_draws():
         for flags in (0, 4):
             ties += compare(wl, run_gpu(wl, p=p, flags=flags), ref)
     assert ties == 0
+
+
+def test_random_mid_sized_shapes_with_several_candidates_per_wavefront():
+    """Sixteen seeded configurations large enough that a wavefront walks several candidates (ragged counts of
+    candidates, rows of 4 to 256 nodes, grids around the wavefront and chunk sizes), a third of them with a few
+    negative entries; plain and memoised, bit-exact elections."""
+    rng = np.random.default_rng(11)
+    ties = 0
+    for trial in range(16):
+        shape = dict(P=int(rng.integers(150, 1400)), J=int(rng.integers(40, 220)),
+                     N=int(rng.choice([4, 8, 16, 32, 60, 64, 68, 128, 256])), cap=int(rng.choice([2, 4, 8])),
+                     Gm=int(rng.choice([31, 63, 64, 65, 128])), Gs=int(rng.choice([7, 8, 16, 17, 32, 33])), index=900 + trial)
+        wl = W.make(W.custom(f"several{trial}", **shape))
+        p = float(rng.choice([-1.0, 0.0, 1.0]))
+        pop = wl.population
+        if trial % 3 == 0:
+            pop = pop.copy()
+            for _ in range(20):
+                pop[rng.integers(shape["P"]), rng.integers(shape["J"]), rng.integers(shape["N"])] -= 2
+        ref = run_oracle(wl, population=pop, p=p)
+        for flags in (0, 4):
+            ties += compare(wl, run_gpu(wl, population=pop, p=p, flags=flags), ref, population=pop)
+    assert ties == 0
