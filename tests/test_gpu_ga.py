@@ -38,6 +38,8 @@ def test_single_step_matches_oracle(name, mut):
     dict(P=7, J=5, N=3, cap=1, Gm=2, Gs=1),
     dict(P=6, J=300, N=70, cap=2, Gm=2, Gs=1),
     dict(P=5, J=9, N=300, cap=3, Gm=2, Gs=1),
+    dict(P=6, J=150, N=48, cap=2, Gm=2, Gs=1),       # short rows: the unchanged ones are copied four to a wavefront load
+    dict(P=9, J=33, N=64, cap=1, Gm=2, Gs=1),
 ])
 def test_ragged_shapes_and_heavy_repair(shape):
     import torch
