@@ -1211,7 +1211,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
 // ---- memoised mode, candidate by candidate ------------------------------------------------
 // With the sweeps looked up (PX_FLAG_MEMOISE) a pair costs its row reduce only, so the pass is bound by
 // reading the population.  This kernel walks it in memory order: a workgroup takes 64 consecutive jobs of one
-// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, four rows of the candidate and of
+// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, eight rows of the candidate and of
 // the current allocation requested together; lane r then finishes the pair of the wavefront's r-th job, so the
 // results of a wavefront are consecutive in memory too.  Launched when rows are 16-byte groups of 65 to 256
 // entries (shorter rows: pairs_kernel with four rows per load).  A row with more GPUs than the memo table
@@ -1219,7 +1219,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
 template <int CH>
 __global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
 {
-    constexpr int kJobsPerWave = 16, kAhead = 4;
+    constexpr int kJobsPerWave = 16, kAhead = 8;
     const int tiles = (a.J + kWavesPerBlock * kJobsPerWave - 1) / (kWavesPerBlock * kJobsPerWave);
     const int c = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
