@@ -1211,7 +1211,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
 // ---- memoised mode, candidate by candidate ------------------------------------------------
 // With the sweeps looked up (PX_FLAG_MEMOISE) a pair costs its row reduce only, so the pass is bound by
 // reading the population.  This kernel walks it in memory order: a workgroup takes 64 consecutive jobs of one
-// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, eight rows of the candidate and of
+// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, four rows of the candidate and of
 // the current allocation requested together; lane r then finishes the pair of the wavefront's r-th job, so the
 // results of a wavefront are consecutive in memory too.  Launched when rows are 16-byte groups of 65 to 256
 // entries (shorter rows: pairs_kernel with four rows per load).  A row with more GPUs than the memo table
@@ -1219,7 +1219,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
 template <int CH>
 __global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
 {
-    constexpr int kJobsPerWave = 16, kAhead = 8;
+    constexpr int kJobsPerWave = 16, kAhead = 4;
     const int tiles = (a.J + kWavesPerBlock * kJobsPerWave - 1) / (kWavesPerBlock * kJobsPerWave);
     const int c = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
@@ -1236,14 +1236,17 @@ __global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
     int d_K = 0, d_meta = 0;                              // lane r: K and nodes | changed of job j0 + r
     bool any_neg = false;
 
-    for (int r0 = 0; r0 < rows; r0 += kAhead) {
-        int4 v[kAhead], cv[kAhead];
+    // Two buffers of kAhead rows: the next batch is requested before the current one is worked on, so that
+    // requests are in flight all the time.
+    auto request = [&](int r0, int4 (&v)[kAhead], int4 (&cv)[kAhead]) {
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             const int ru = r0 + u < rows ? r0 + u : rows - 1;                 // the tail reads the last row again
             v[u] = rowp[(size_t)ru * n4];
             cv[u] = curp[(size_t)ru * n4];
         }
+    };
+    auto work = [&](int r0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
             if (r0 + u < rows) {
@@ -1269,7 +1272,17 @@ __global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
                 }
             }
         }
-    }
+    };
+    static_assert(kJobsPerWave == 4 * kAhead, "four batches, unrolled below");
+    int4 v0[kAhead], c0v[kAhead], v1[kAhead], c1v[kAhead];
+    request(0, v0, c0v);
+    if (kAhead < rows) request(kAhead, v1, c1v);
+    work(0, v0, c0v);
+    if (2 * kAhead < rows) request(2 * kAhead, v0, c0v);
+    if (kAhead < rows) work(kAhead, v1, c1v);
+    if (3 * kAhead < rows) request(3 * kAhead, v1, c1v);
+    if (2 * kAhead < rows) work(2 * kAhead, v0, c0v);
+    if (3 * kAhead < rows) work(3 * kAhead, v1, c1v);
 
     // rows beyond the memo table: swept and priced here
     Best beyond = {0.0, -1, -1};
