@@ -773,7 +773,10 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
     const double rK = K < kRecipTable ? rk[K] : 1.0 / (double)K;
     float ts = 0.0f;                                                          // Eq. 9
     if (K > 1) ts = (nodes == 1) ? q.alpha_sl + q.beta_sl * (float)(K - 2) : q.alpha_sn + q.beta_sn * (float)(K - 2);
-    const float tsg = (ts != 0.0f && q.gamma != 1.0f) ? powf(ts, q.gamma) : 0.0f;
+    // Eq. 10 for K within the tables: the fp64 table of last_kernel, rounded to fp32 (two powf per batch size otherwise)
+    const bool tabled = K <= kTableK;
+    const double *__restrict__ lrow = tb.lt + (unsigned)((nodes == 1 ? kTableK : 0) + (tabled ? K - 1 : 0)) * (unsigned)Gm;
+    const float tsg = (!tabled && ts != 0.0f && q.gamma != 1.0f) ? powf(ts, q.gamma) : 0.0f;
 
     float gbest = -1.0f;
     int flat = 0x7FFFFFFF, m_best = -1, s_best = -1;
@@ -786,6 +789,7 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
         float last;                                                           // Eq. 10
         if (ts == 0.0f) last = tg;
         else if (q.gamma == 1.0f) last = tg + ts;
+        else if (tabled) last = (float)lrow[i];
         else last = powf(powf(tg, q.gamma) + tsg, q.inv_gamma);
         const int s_lo = (int)(tb.ql5[i] * rK);
         int s_hi = (int)(tb.qh5[i] * rK) - 1;
@@ -1596,7 +1600,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
     if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         // everything that depends on the jobs only (not on the population)
-        launch_job_tables(d, a, !f32 && !sampled, stream);
+        launch_job_tables(d, a, !sampled, stream);
         const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
         if (sampled) hipLaunchKernelGGL((jobs_kernel<0, false>), job_grid, dim3(256), 0, stream, a);
         else if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
