@@ -1503,7 +1503,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     return a;
 }
 
-// tables_kernel and, for the fp64 grid sweep, last_kernel: everything the sweep of a (job, K, nodes) needs
+// tables_kernel and, for the grid sweeps (not the sampling argmax), last_kernel: everything the sweep of a (job, K, nodes) needs
 static void launch_job_tables(const pollux_dims *d, const FitnessArgs &a, bool last_pass_tables, hipStream_t stream)
 {
     long long table_items = (long long)d->J * d->Gm;
