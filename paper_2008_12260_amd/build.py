@@ -27,7 +27,21 @@ def build(verbose: bool = False, save_temps: str | None = None) -> str:
         cmd += ["-save-temps=cwd"]
     if verbose:
         print(" ".join(cmd), flush=True)
-    subprocess.run(cmd, check=True, cwd=save_temps or HERE)
+    run = subprocess.run(cmd, cwd=save_temps or HERE, stderr=subprocess.PIPE, text=True)
+    # The host pass of every source does not know the device feature named above and says so; that one line is
+    # dropped (and counted) so that any other diagnostic stands out.
+    known = "'-packed-fp32-ops' is not a recognized feature for this target (ignoring feature)"
+    lines = run.stderr.splitlines()
+    other = [ln for ln in lines if ln.strip() != known]
+    if other:
+        print("\n".join(other), file=sys.stderr, flush=True)
+    if verbose and len(other) != len(lines):
+        print(f"({len(lines) - len(other)} host-pass notices about -packed-fp32-ops dropped)", flush=True)
+    if run.returncode != 0:
+        raise subprocess.CalledProcessError(run.returncode, cmd)
+    if verbose:
+        version = subprocess.run([hipcc, "--version"], capture_output=True, text=True).stdout.splitlines()
+        print("compiler:", "; ".join(v for v in version[:2]), flush=True)
     return LIB
 
 

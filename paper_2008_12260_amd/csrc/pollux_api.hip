@@ -5,6 +5,8 @@
 #include <math.h>
 #include <string.h>
 
+#include <atomic>
+
 #include "../../include/pollux.h"
 #include "pollux_host.h"
 
@@ -15,19 +17,24 @@ hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;
 namespace {
 
 constexpr int kMaxDevices = 64;
-int g_arch_ok[kMaxDevices];   // 0 unknown, 1 gfx950, -1 something else
+// Per device: 0 unknown, 1 gfx950, -1 something else.  A cache of a property that never changes: two threads
+// that find it unknown both query the device and store the same value.
+std::atomic<int> g_arch_ok[kMaxDevices];
 
-int check_device()
+int check_device(int *device = nullptr)
 {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return PX_E_HIP;
     if (dev < 0 || dev >= kMaxDevices) return PX_E_HIP;
-    if (g_arch_ok[dev] == 0) {
+    if (device) *device = dev;
+    int ok = g_arch_ok[dev].load(std::memory_order_relaxed);
+    if (ok == 0) {
         hipDeviceProp_t prop;
         if (hipGetDeviceProperties(&prop, dev) != hipSuccess) return PX_E_HIP;
-        g_arch_ok[dev] = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+        ok = strncmp(prop.gcnArchName, "gfx950", 6) == 0 ? 1 : -1;
+        g_arch_ok[dev].store(ok, std::memory_order_relaxed);
     }
-    return g_arch_ok[dev] == 1 ? PX_OK : PX_E_UNSUPPORTED_ARCH;
+    return ok == 1 ? PX_OK : PX_E_UNSUPPORTED_ARCH;
 }
 
 bool dims_ok(const pollux_dims *d, bool need_grid)

@@ -13,11 +13,23 @@ namespace px {
 // The last pass of Eq. 10 is tabled for GPU counts K = 1..kTableK; larger K are computed in place.
 constexpr int kTableK = 64;
 
-// Byte offsets of the sections of the caller's workspace (each 256-byte aligned).
+// Byte offsets of the sections of the caller's workspace (each 256-byte aligned).  The sections whose size
+// depends on P, J and N only come first, so that their offsets are the same for every grid: the search step
+// (which ignores Gm and Gs) and a fitness call that keeps the job tables may then share one workspace
+// whatever grid dimensions the former is given.
 struct WorkspaceLayout {
     size_t status;    // int32 status word
-    size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
+    size_t order;     // int32  [P]       candidates by rank (search step)
     size_t rk;        // double [256]     1/K
+    size_t denom;     // double [J]       fair-share goodput
+    size_t factor;    // double [J]       re-allocation factor
+    size_t running;   // int32  [J]       job holds GPUs in current_alloc
+    size_t G;         // double [P,J]     best goodput of the pair
+    size_t meta;      // int32  [P,J]     nodes occupied by the row | changed flag
+    size_t memo;      // 16 bytes [J,2,kTableK]  best point per (job, one node?, K) in memoised mode
+    size_t colpack;   // uint64 [P,N]     per node of each candidate: GPUs asked + multi-node jobs << 40
+    // from here on the offsets depend on the grid
+    size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
     size_t tg;        // double [J,Gm,2]  T_grad(m_i) and its reciprocal
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
     size_t pu;        // double [J,Gm]    phi / m_i
@@ -26,14 +38,6 @@ struct WorkspaceLayout {
     size_t lt;        // double [J,2,kTableK,Gm]  last pass of Eq. 10 by (job, one node?, K)
     size_t srange;    // int32  [J,kTableK,Gm]  feasible accumulation counts of grid point i with K GPUs:
                       //                  first | last << 16 (first > last: none)
-    size_t denom;     // double [J]       fair-share goodput
-    size_t factor;    // double [J]       re-allocation factor
-    size_t running;   // int32  [J]       job holds GPUs in current_alloc
-    size_t G;         // double [P,J]     best goodput of the pair
-    size_t meta;      // int32  [P,J]     nodes occupied by the row | changed flag
-    size_t memo;      // 16 bytes [J,2,kTableK]  best point per (job, one node?, K) in memoised mode
-    size_t colpack;   // uint64 [P,N]     per node of each candidate: GPUs asked + multi-node jobs << 40
-    size_t order;     // int32  [P]       candidates by rank (search step)
     size_t total;
 };
 
@@ -44,15 +48,8 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     size_t o = 0;
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
-    L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
+    L.order = o;   o = up(o + 4 * P);
     L.rk = o;      o = up(o + 8 * 256);
-    L.tg = o;      o = up(o + 16 * J * Gm);
-    L.lntg = o;    o = up(o + 8 * J * Gm);
-    L.pu = o;      o = up(o + 8 * J * Gm);
-    L.qh5 = o;     o = up(o + 8 * J * Gm);
-    L.ql5 = o;     o = up(o + 8 * J * Gm);
-    L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
-    L.srange = o;  o = up(o + 4 * J * kTableK * Gm);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
     L.running = o; o = up(o + 4 * J);
@@ -60,7 +57,14 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.meta = o;    o = up(o + 4 * P * J);
     L.memo = o;    o = up(o + 16 * J * 2 * kTableK);
     L.colpack = o; o = up(o + 8 * P * (size_t)d.N);
-    L.order = o;   o = up(o + 4 * P);
+    L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
+    L.tg = o;      o = up(o + 16 * J * Gm);
+    L.lntg = o;    o = up(o + 8 * J * Gm);
+    L.pu = o;      o = up(o + 8 * J * Gm);
+    L.qh5 = o;     o = up(o + 8 * J * Gm);
+    L.ql5 = o;     o = up(o + 8 * J * Gm);
+    L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
+    L.srange = o;  o = up(o + 4 * J * kTableK * Gm);
     L.total = o;
     return L;
 }
