@@ -14,6 +14,7 @@
  *   - No call allocates or frees device memory; scratch space is the
  *     caller-provided `workspace` (size from pollux_workspace_size, 256-byte
  *     aligned).  Two calls that overlap in time must use different workspaces.
+ *     pollux_fitness_static uses an array inside the library instead.
  *   - Return value: PX_OK (0) or a negative PX_E_* code.  Arguments that can be
  *     checked on the host are checked before anything is launched.  Conditions
  *     that depend on device data are OR-ed into a status word inside the
@@ -30,7 +31,7 @@
 extern "C" {
 #endif
 
-#define POLLUX_VERSION 103
+#define POLLUX_VERSION 104
 
 typedef struct {
     int32_t P;         /* candidates in the population                          */
@@ -160,6 +161,51 @@ int pollux_fitness(const pollux_dims *dims,              /* host */
                    double *speedup,                      /* [P,J] out, may be NULL: SPEEDUP_j after the penalty */
                    int32_t *violations,                  /* [P] out, may be NULL: V */
                    void *hip_stream);
+
+/*
+ * pollux_fitness for callers that cannot allocate device memory or hand over a workspace: code
+ * running under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * same computation with the same kernels and the same results as pollux_fitness; the scratch
+ * memory is an array of POLLUX_STATIC_SCRATCH_BYTES that is part of the library's code object
+ * (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing.  Its first use on a device looks the array's address up (one
+ * HIP runtime query, which may load the code object on that device); later calls only enqueue
+ * kernels.
+ *
+ * Limit: pollux_workspace_size(dims) must not exceed POLLUX_STATIC_SCRATCH_BYTES, otherwise
+ * PX_E_WORKSPACE is returned before anything is launched (32 MiB holds, for example, 1000
+ * candidates x 200 jobs x 64 nodes with a 64 x 16 grid).
+ *
+ * Every call on a GPU uses that GPU's one array: two calls that overlap in time on one GPU
+ * (different streams or threads) race and give undefined results; calls on one stream, or
+ * otherwise ordered, are fine.  The array keeps what the last call left, so
+ * PX_FLAG_KEEP_JOB_TABLES works as with a workspace of the caller's: the previous call through
+ * this entry point on this GPU must then have had the same dims, job_params, m_grid, fair_share,
+ * current_alloc, delta and other flags.  Without that flag the call itself clears what must
+ * start at zero.
+ *
+ * status: device pointer to one int32, or NULL.  When given, the status word (PX_ST_* bits) of
+ * this call is copied there on the stream after the last kernel; the host is not synchronised
+ * (pollux_last_status does not apply: there is no workspace to name).
+ * All other arguments, results and error codes as for pollux_fitness.
+ */
+#define POLLUX_STATIC_SCRATCH_BYTES (32u << 20)
+int pollux_fitness_static(const pollux_dims *dims,       /* host */
+                          const int32_t *population,     /* [P,J,N] */
+                          const double *job_params,      /* [PX_NPARAM,J] */
+                          const int32_t *m_grid,         /* [J,Gm] */
+                          const int32_t *fair_share,     /* [J,2] */
+                          const int32_t *current_alloc,  /* [J,N] */
+                          const int32_t *node_capacity,  /* [N] */
+                          double p, double delta,
+                          double *fitness,               /* [P] out */
+                          int32_t *best_m,               /* [P,J] out */
+                          int32_t *best_s,               /* [P,J] out */
+                          double *best_goodput,          /* [P,J] out, may be NULL */
+                          double *speedup,               /* [P,J] out, may be NULL */
+                          int32_t *violations,           /* [P] out, may be NULL */
+                          int32_t *status,               /* [1] out, may be NULL */
+                          void *hip_stream);
 
 typedef struct {
     uint64_t seed;           /* Philox key (low word, high word) */

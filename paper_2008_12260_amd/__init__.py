@@ -20,7 +20,8 @@ PX_FLAG_SAMPLE_M = 16
 PX_GA_IN_PLACE = 1
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
-EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_ga_step",
+EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_fitness_static",
+           "pollux_ga_step",
            "pollux_fit_theta", "pollux_goodput_per_gpu", "pollux_autoscale", "pollux_sim_tick", "pollux_last_status",
            "pollux_set_sweep_events")
 
@@ -59,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.pollux_workspace_size.argtypes = [ctypes.POINTER(Dims), ctypes.POINTER(sz)]
         L.pollux_fitness.restype = i
         L.pollux_fitness.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz] + [vp] * 6 + [vp]
+        L.pollux_fitness_static.restype = i
+        L.pollux_fitness_static.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d] + [vp] * 7 + [vp]
         L.pollux_ga_step.restype = i
         L.pollux_ga_step.argtypes = [ctypes.POINTER(Dims), vp, vp, vp, ctypes.POINTER(GaParams), vp, sz, vp, vp]
         L.pollux_fit_theta.restype = i
@@ -115,6 +118,21 @@ def pollux_fitness(dims: Dims, population, job_params, m_grid, fair_share, curre
         _stream_handle(stream))
     if rc != PX_OK:
         raise PolluxError(rc, "pollux_fitness")
+
+
+STATIC_SCRATCH_BYTES = 32 << 20
+
+
+def pollux_fitness_static(dims: Dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity,
+                          p: float, delta: float, fitness, best_m, best_s, best_goodput=None, speedup=None,
+                          violations=None, status=None, stream=None) -> None:
+    """pollux_fitness_static of the C ABI: no workspace argument, the library's own scratch array is used."""
+    rc = lib().pollux_fitness_static(
+        ctypes.byref(dims), _ptr(population), _ptr(job_params), _ptr(m_grid), _ptr(fair_share), _ptr(current_alloc),
+        _ptr(node_capacity), float(p), float(delta), _ptr(fitness), _ptr(best_m), _ptr(best_s), _ptr(best_goodput),
+        _ptr(speedup), _ptr(violations), _ptr(status), _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_fitness_static")
 
 
 def pollux_ga_step(dims: Dims, parents, fitness, node_capacity, ga: GaParams, workspace, children, stream=None) -> None:

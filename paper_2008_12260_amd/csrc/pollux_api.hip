@@ -6,6 +6,7 @@
 #include <string.h>
 
 #include <atomic>
+#include <mutex>
 
 #include "../../include/pollux.h"
 #include "pollux_host.h"
@@ -13,6 +14,13 @@
 namespace px {
 hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;
 }
+
+// ---- scratch memory owned by the library (pollux_fitness_static) -------------------------------------------
+// One array per GPU, part of the code object: every device the library runs on holds its own copy, at its own
+// address, from the moment the code object is loaded there until the process ends.  In host code the name
+// `scratch` only stands for the symbol; the address kernels can use is looked up once per device, with that
+// device current, and kept.
+static __device__ __align__(256) unsigned char scratch[POLLUX_STATIC_SCRATCH_BYTES];
 
 namespace {
 
@@ -35,6 +43,22 @@ int check_device(int *device = nullptr)
         g_arch_ok[dev].store(ok, std::memory_order_relaxed);
     }
     return ok == 1 ? PX_OK : PX_E_UNSUPPORTED_ARCH;
+}
+
+void *g_scratch_ptr[kMaxDevices];     // device address of `scratch` on each device, null until looked up
+std::mutex g_scratch_lock;
+
+int static_scratch(int dev, void **out)
+{
+    std::lock_guard<std::mutex> hold(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PX_E_HIP;
+        if (((uintptr_t)ptr & 255u) != 0) return PX_E_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PX_OK;
 }
 
 bool dims_ok(const pollux_dims *d, bool need_grid)
@@ -104,6 +128,31 @@ int pollux_fitness(const pollux_dims *dims, const int32_t *population, const dou
     return px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
                               workspace, fitness, best_m, best_s, best_goodput, speedup, violations,
                               (hipStream_t)hip_stream);
+}
+
+int pollux_fitness_static(const pollux_dims *dims, const int32_t *population, const double *job_params,
+                          const int32_t *m_grid, const int32_t *fair_share, const int32_t *current_alloc,
+                          const int32_t *node_capacity, double p, double delta, double *fitness, int32_t *best_m,
+                          int32_t *best_s, double *best_goodput, double *speedup, int32_t *violations,
+                          int32_t *status, void *hip_stream)
+{
+    if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
+    if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !fitness ||
+        !best_m || !best_s)
+        return PX_E_INVALID_ARG;
+    if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
+    // the problem must fit the library's array: checked on the host, before any device is touched
+    if (px::workspace_layout(*dims).total > (size_t)POLLUX_STATIC_SCRATCH_BYTES) return PX_E_WORKSPACE;
+    int dev = 0;
+    int rc = check_device(&dev);
+    if (rc != PX_OK) return rc;
+    void *ws = nullptr;
+    rc = static_scratch(dev, &ws);
+    if (rc != PX_OK) return rc;
+    rc = px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
+                            ws, fitness, best_m, best_s, best_goodput, speedup, violations, (hipStream_t)hip_stream);
+    if (rc != PX_OK) return rc;
+    return status ? px::launch_copy_status(ws, status, (hipStream_t)hip_stream) : PX_OK;
 }
 
 int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double *fitness,

@@ -1555,6 +1555,19 @@ int launch_sim_tick(const pollux_dims *d, const double *job_params, const int32_
     return launch_queries(d, job_params, m_grid, workspace, q, stream);
 }
 
+__global__ void copy_status_kernel(const int32_t *__restrict__ from, int32_t *__restrict__ to)
+{
+    if (threadIdx.x == 0) *to = *from;
+}
+
+int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t stream)
+{
+    pollux_dims d = {1, 1, 1, 1, 1, 0, 0};
+    const int32_t *word = (const int32_t *)((const char *)workspace + workspace_layout(d).status);
+    hipLaunchKernelGGL(copy_status_kernel, dim3(1), dim3(64), 0, stream, word, status_out);
+    return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
+}
+
 int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,

@@ -77,6 +77,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
                    double *best_goodput, double *speedup, int32_t *violations, hipStream_t stream);
 
+// Copies the status word of `workspace` to *status_out (device memory) on the stream.
+int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t stream);
+
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
                    const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
 

@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = px.lib()
     for n in names:
         assert getattr(L, n) is not None
-    assert px.version() == 103
+    assert px.version() == 104
     assert px.strerror(0) == "success" and "workspace" in px.strerror(px.PX_E_WORKSPACE)
     assert px.strerror(-99) == "unknown error code"
 
@@ -77,6 +77,28 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     bad = list(gargs); bad[4] = null
     assert L.pollux_ga_step(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
     assert L.pollux_last_status(null, null, None) == px.PX_E_INVALID_ARG
+
+
+def test_the_entry_point_with_library_owned_scratch_checks_its_limit_on_the_host():
+    """pollux_fitness_static: same argument checks as pollux_fitness, and a problem whose scratch need exceeds the
+    library's array is refused before any device is touched."""
+    L = px.lib()
+    fake, null = ctypes.c_void_p(0x1000), ctypes.c_void_p(0)
+    ok = [fake] * 6 + [-1.0, 30.0] + [fake] * 7 + [null]
+    big = px.Dims(4096, 1000, 256, 128, 32, 0, 0)
+    assert px.workspace_size(big) > px.STATIC_SCRATCH_BYTES
+    assert L.pollux_fitness_static(ctypes.byref(big), *ok) == px.PX_E_WORKSPACE
+    fits = px.Dims(1000, 200, 64, 64, 16, 0, 0)
+    assert px.workspace_size(fits) <= px.STATIC_SCRATCH_BYTES
+    bad = list(ok); bad[0] = null
+    assert L.pollux_fitness_static(ctypes.byref(fits), *bad) == px.PX_E_INVALID_ARG
+    bad = list(ok); bad[6] = float("inf")
+    assert L.pollux_fitness_static(ctypes.byref(fits), *bad) == px.PX_E_INVALID_ARG
+    bad = list(ok); bad[7] = -1.0
+    assert L.pollux_fitness_static(ctypes.byref(fits), *bad) == px.PX_E_INVALID_ARG
+    assert L.pollux_fitness_static(None, *ok) == px.PX_E_INVALID_ARG
+    text = open(os.path.join(ROOT, "include", "pollux.h")).read()
+    assert f"#define POLLUX_STATIC_SCRATCH_BYTES ({px.STATIC_SCRATCH_BYTES >> 20}u << 20)" in text
 
 
 def test_the_newer_entry_points_reject_bad_arguments_without_a_device():
