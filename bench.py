@@ -116,15 +116,13 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
-        px.pollux_set_sweep_events(*ev[k])
         fit_ev[k][0].record(stream)
-        call.run(a, stream=stream, outputs="fitness")      # full call every step: job-level kernels included
+        call.run(a, stream=stream, outputs="fitness", sweep_events=ev[k])      # full call every step: job-level kernels included
         fit_ev[k][1].record(stream)
         call.ga_step(a, a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, flags=px.PX_GA_IN_PLACE)
         gen += 1
     torch.cuda.synchronize()
     t1 = time.perf_counter()
-    px.pollux_set_sweep_events(None, None)
 
     # the same search step out of place (survivors copied into a second buffer), for comparison
     b = torch.empty_like(a)

@@ -20,6 +20,9 @@
  *     that depend on device data are OR-ed into a status word inside the
  *     workspace (PX_ST_* bits), read back with pollux_last_status.
  *   - Matrices are row-major with the last index contiguous.
+ *   - The library keeps no state between calls that changes what a call computes or
+ *     enqueues; calls from several threads or on several streams are independent as
+ *     long as their workspaces differ (pollux_fitness_static: see there).
  */
 #ifndef POLLUX_H
 #define POLLUX_H
@@ -88,7 +91,8 @@ enum {
 enum {
     PX_OK = 0,
     PX_E_INVALID_ARG = -1,       /* null pointer, non-positive size, non-finite p or delta, delta < 0,
-                                    unknown precision, elite_k outside 1..P, aliasing children/parents */
+                                    unknown precision, elite_k outside 1..P, aliasing children/parents,
+                                    a shape beyond a documented limit */
     PX_E_WORKSPACE = -2,         /* workspace null, misaligned or smaller than pollux_workspace_size */
     PX_E_UNSUPPORTED_ARCH = -3,  /* the current device is not gfx950 */
     PX_E_HIP = -4                /* a HIP runtime call failed (launch, attribute query, copy) */
@@ -158,9 +162,25 @@ int pollux_fitness(const pollux_dims *dims,              /* host */
                    int32_t *best_m,                      /* [P,J] out: m* (the batch size, not its index), -1 if none */
                    int32_t *best_s,                      /* [P,J] out: s*, -1 if none */
                    double *best_goodput,                 /* [P,J] out, may be NULL */
-                   double *speedup,                      /* [P,J] out, may be NULL: SPEEDUP_j after the penalty */
+                   double *speedup,                      /* [P,J] out, may be NULL: SPEEDUP_j (Eq. 15) after the penalty */
                    int32_t *violations,                  /* [P] out, may be NULL: V */
                    void *hip_stream);
+
+/*
+ * pollux_fitness with two HIP events (hipEvent_t cast to void*, created by the caller, both
+ * required) recorded on the call's stream immediately before and immediately after the
+ * grid-sweep kernel, the kernel that evaluates Eq. 4 over the (m, s) grid for every
+ * (candidate, job) pair, so that a caller can time that kernel alone.  Everything else as
+ * pollux_fitness.
+ */
+int pollux_fitness_timed(const pollux_dims *dims, const int32_t *population, const double *job_params,
+                         const int32_t *m_grid, const int32_t *fair_share, const int32_t *current_alloc,
+                         const int32_t *node_capacity, double p, double delta,
+                         void *workspace, size_t workspace_bytes,
+                         double *fitness, int32_t *best_m, int32_t *best_s, double *best_goodput, double *speedup,
+                         int32_t *violations,
+                         void *sweep_start_event, void *sweep_stop_event,   /* host handles */
+                         void *hip_stream);
 
 /*
  * pollux_fitness for callers that cannot allocate device memory or hand over a workspace: code
@@ -252,8 +272,16 @@ enum {
  *                   present keep the one with most GPUs there (lowest j on ties), zero
  *                   the others there (their node counts drop, which later nodes see).
  * All arithmetic is integer; the result is a pure function of the arguments.
+ *
+ * dims: P, J, N and nothing else are read (Gm, Gs, precision and flags may hold anything, zero included);
+ * the part of the workspace this call uses does not move with the grid, so it may share the workspace of
+ * the pollux_fitness calls of a search, PX_FLAG_KEEP_JOB_TABLES included.  workspace_bytes must be at
+ * least pollux_workspace_size of these dims with Gm and Gs taken as 1 when they are not positive.
+ * Limit: the per-job and per-node bookkeeping of a child lives in the 160 KB of on-chip memory of a
+ * compute unit: 16 N + 16 J + 12 E (+ 8 N if J < N) bytes, E = 1.5 J rounded up to a multiple of 256 and
+ * kept within 512..3072, must not exceed 159 KB; beyond that PX_E_INVALID_ARG (e.g. J = 1000 jobs allow up to N = 5349 nodes).
  */
-int pollux_ga_step(const pollux_dims *dims,              /* host; Gm, Gs, precision ignored */
+int pollux_ga_step(const pollux_dims *dims,              /* host; only P, J, N are read */
                    const int32_t *parents,               /* [P,J,N] */
                    const double *fitness,                /* [P] */
                    const int32_t *node_capacity,         /* [N] */
@@ -355,19 +383,29 @@ int pollux_sim_tick(const pollux_dims *dims,             /* host */
                     int32_t *finished,                   /* [J] out */
                     void *hip_stream);
 
-/* Copies the status word of the last pollux_fitness call that used `workspace`
- * to *host_out.  Synchronises `hip_stream`. */
-int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out /* host */);
-
 /*
- * Profiling aid.  While a pair of HIP events (hipEvent_t cast to void*) is
- * registered, every pollux_fitness call records `start` immediately before and
- * `stop` immediately after its grid-sweep kernel (the kernel that evaluates
- * Eq. 4 over the (m, s) grid for every (candidate, job) pair), on the call's
- * stream, so that a caller can time that kernel alone.  The registration is
- * process-wide and not thread-safe; pass two NULLs to clear it.  Host call.
+ * The end of a scheduling interval (Sec. 4.3: the allocation matrix of highest fitness is applied): picks the
+ * best candidate, the first in the order of pollux_ga_step's ranking (fitness descending, index ascending, NaN
+ * last), writes its index to best[0] and its matrix over current_alloc, and reports per job what the jobs'
+ * agents and pollux_sim_tick need: K[j] = GPUs, nodes[j] = nodes with at least one GPU, changed[j] = 1 when the
+ * job's row differs from its previous row in current_alloc and that previous row held at least one GPU (the
+ * jobs that pay the re-allocation delay, Sec. 4.2).  dims: P, J, N are read.  No workspace.
  */
-int pollux_set_sweep_events(void *hip_event_start, void *hip_event_stop);
+int pollux_apply_best(const pollux_dims *dims,           /* host */
+                      const int32_t *population,         /* [P,J,N] */
+                      const double *fitness,             /* [P] */
+                      int32_t *current_alloc,            /* [J,N] in/out */
+                      int32_t *best,                     /* [1] out */
+                      int32_t *K,                        /* [J] out */
+                      int32_t *nodes,                    /* [J] out */
+                      int32_t *changed,                  /* [J] out */
+                      void *hip_stream);
+
+/* Copies the status word of the last pollux_fitness (or pollux_fitness_timed) call that used `workspace`
+ * to *host_out.  Synchronises `hip_stream`.  pollux_goodput_per_gpu and pollux_sim_tick neither clear nor
+ * set the word; they do rewrite the job tables of the workspace, so a pollux_fitness call with
+ * PX_FLAG_KEEP_JOB_TABLES may follow them only if they were given the same job_params, m_grid and grid. */
+int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out /* host */);
 
 /* Text for a PX_* return code (static storage, never NULL). */
 const char *pollux_strerror(int code);

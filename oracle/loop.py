@@ -18,6 +18,9 @@ Readings
     by a job whose allocation was changed in this interval; a job with no GPUs does not advance; a job is
     finished when its progress reaches its target.  The goodput is the maximum of Eq. 13 at the job's current
     (K, nodes), i.e. with the batch size and accumulation steps its agent would choose.
+  * Applying the search's outcome (Sec. 4.3: the allocation matrix with the highest fitness is applied).  The
+    best candidate is the first in the search's ranking (fitness descending, lowest index among equals, NaN
+    last); a job is re-allocated when its row changes and it held GPUs before (Sec. 4.2).
 """
 from __future__ import annotations
 
@@ -70,3 +73,19 @@ def sim_tick(job_params, m_grid, Gs, K, nodes, changed, progress, target, dt, re
             if run > 0.0:
                 new[j] = progress[j] + goodput[j] * run
     return goodput, new, new >= np.asarray(target, np.float64)
+
+
+def apply_best(population, fitness, current_alloc):
+    """The end of a scheduling interval: (index of the best candidate, its matrix, K [J], nodes [J], changed [J])."""
+    f = np.asarray(fitness, np.float64)
+    best, best_f = -1, -np.inf
+    for c in range(len(f)):
+        v = f[c] if f[c] == f[c] else -np.inf
+        if best < 0 or v > best_f:
+            best, best_f = c, v
+    new = np.array(population[best], dtype=np.int32, copy=True)
+    cur = np.asarray(current_alloc)
+    K = new.sum(axis=1).astype(np.int32)
+    nodes = (new > 0).sum(axis=1).astype(np.int32)
+    changed = (new != cur).any(axis=1) & (cur.sum(axis=1) > 0)
+    return best, new, K, nodes, changed

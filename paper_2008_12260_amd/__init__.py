@@ -23,7 +23,7 @@ PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_fitness_static",
            "pollux_ga_step",
            "pollux_fit_theta", "pollux_goodput_per_gpu", "pollux_autoscale", "pollux_sim_tick", "pollux_last_status",
-           "pollux_set_sweep_events")
+           "pollux_fitness_timed", "pollux_apply_best")
 
 
 class PolluxError(RuntimeError):
@@ -74,8 +74,10 @@ def lib() -> ctypes.CDLL:
         L.pollux_sim_tick.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz, vp, vp, vp, vp]
         L.pollux_last_status.restype = i
         L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
-        L.pollux_set_sweep_events.restype = i
-        L.pollux_set_sweep_events.argtypes = [vp, vp]
+        L.pollux_fitness_timed.restype = i
+        L.pollux_fitness_timed.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz] + [vp] * 6 + [vp, vp, vp]
+        L.pollux_apply_best.restype = i
+        L.pollux_apply_best.argtypes = [ctypes.POINTER(Dims)] + [vp] * 7 + [vp]
         _lib = L
     return _lib
 
@@ -109,13 +111,17 @@ def _stream_handle(stream):
 
 def pollux_fitness(dims: Dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity,
                    p: float, delta: float, workspace, fitness, best_m, best_s, best_goodput=None, speedup=None,
-                   violations=None, stream=None) -> None:
-    """pollux_fitness of the C ABI on torch device tensors (already allocated, contiguous)."""
-    rc = lib().pollux_fitness(
-        ctypes.byref(dims), _ptr(population), _ptr(job_params), _ptr(m_grid), _ptr(fair_share), _ptr(current_alloc),
-        _ptr(node_capacity), float(p), float(delta), _ptr(workspace), workspace.numel() * workspace.element_size(),
-        _ptr(fitness), _ptr(best_m), _ptr(best_s), _ptr(best_goodput), _ptr(speedup), _ptr(violations),
-        _stream_handle(stream))
+                   violations=None, stream=None, sweep_events=None) -> None:
+    """pollux_fitness of the C ABI on torch device tensors (already allocated, contiguous); with
+    sweep_events = (start, stop), two torch.cuda.Event objects, pollux_fitness_timed."""
+    args = [ctypes.byref(dims), _ptr(population), _ptr(job_params), _ptr(m_grid), _ptr(fair_share), _ptr(current_alloc),
+            _ptr(node_capacity), float(p), float(delta), _ptr(workspace), workspace.numel() * workspace.element_size(),
+            _ptr(fitness), _ptr(best_m), _ptr(best_s), _ptr(best_goodput), _ptr(speedup), _ptr(violations)]
+    if sweep_events is None:
+        rc = lib().pollux_fitness(*args, _stream_handle(stream))
+    else:
+        rc = lib().pollux_fitness_timed(*args, ctypes.c_void_p(sweep_events[0].cuda_event),
+                                        ctypes.c_void_p(sweep_events[1].cuda_event), _stream_handle(stream))
     if rc != PX_OK:
         raise PolluxError(rc, "pollux_fitness")
 
@@ -207,12 +213,12 @@ def pollux_last_status(workspace, stream=None) -> int:
     return out.value
 
 
-def pollux_set_sweep_events(start=None, stop=None) -> None:
-    """Register (or clear) torch.cuda.Event objects recorded around the grid-sweep kernel."""
-    h = lambda e: None if e is None else ctypes.c_void_p(e.cuda_event)
-    rc = lib().pollux_set_sweep_events(h(start), h(stop))
+def pollux_apply_best(dims: Dims, population, fitness, current_alloc, best, K, nodes, changed, stream=None) -> None:
+    """pollux_apply_best of the C ABI on torch device tensors (current_alloc is overwritten)."""
+    rc = lib().pollux_apply_best(ctypes.byref(dims), _ptr(population), _ptr(fitness), _ptr(current_alloc), _ptr(best),
+                                 _ptr(K), _ptr(nodes), _ptr(changed), _stream_handle(stream))
     if rc != PX_OK:
-        raise PolluxError(rc, "pollux_set_sweep_events")
+        raise PolluxError(rc, "pollux_apply_best")
 
 
 class FitnessCall:
@@ -245,7 +251,7 @@ class FitnessCall:
         self.speedup = torch.empty((P, J), dtype=torch.float64, device=dev)
         self.violations = torch.empty(P, dtype=torch.int32, device=dev)
 
-    def run(self, population, stream=None, outputs="all", keep_job_tables=False):
+    def run(self, population, stream=None, outputs="all", keep_job_tables=False, sweep_events=None):
         full = outputs == "all"
         dims = self.dims
         if keep_job_tables:
@@ -253,7 +259,7 @@ class FitnessCall:
         pollux_fitness(dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
                        self.node_capacity, self.p, self.delta, self.workspace, self.fitness, self.best_m, self.best_s,
                        self.best_goodput if full else None, self.speedup if full else None, self.violations,
-                       stream)
+                       stream, sweep_events)
 
     def status(self, stream=None) -> int:
         return pollux_last_status(self.workspace, stream)

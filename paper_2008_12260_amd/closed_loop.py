@@ -5,12 +5,14 @@ and the jobs run on it until the next interval; Sec. 5.3: discrete-time simulati
 Per interval:
   1. the jobs' gradient noise scale phi_t is refreshed from their progress (the caller's `phi_of` function);
   2. the population search runs `generations` steps of pollux_fitness + pollux_ga_step (in place) from a
-     population seeded with the current allocation, and the best candidate of the last evaluation is taken;
-  3. jobs whose row changed are marked re-allocated;
+     population seeded with the current allocation;
+  3. pollux_apply_best takes the best candidate of the last evaluation, makes it the current allocation and
+     marks the jobs whose row changed as re-allocated;
   4. pollux_sim_tick advances every job on its new allocation.
 
-This module marshals arguments and moves a few small arrays between host and device; every step of the
-method runs in the library's kernels.  It fails if the library is missing, like the rest of the package.
+This module marshals arguments and copies results to the host for the caller's records; every step of the
+method (the search, the choice of the best matrix, K / nodes / changed of its rows, the tick) runs in the
+library's kernels.  It fails if the library is missing, like the rest of the package.
 """
 from __future__ import annotations
 
@@ -18,7 +20,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-from . import (PX_FLAG_MEMOISE, PX_GA_IN_PLACE, Dims, FitnessCall, PARAM_PHI, pollux_sim_tick)
+from . import (PX_FLAG_MEMOISE, PX_GA_IN_PLACE, Dims, FitnessCall, PARAM_PHI, pollux_apply_best, pollux_sim_tick)
 
 
 @dataclass
@@ -46,28 +48,30 @@ def run(job_params, m_grid, fair_share, node_capacity, target, phi_of, alloc0, *
     d_progress = torch.zeros(J, dtype=torch.float64, device=dev)
     d_goodput = torch.empty(J, dtype=torch.float64, device=dev)
     d_finished = torch.empty(J, dtype=torch.int32, device=dev)
+    d_best = torch.empty(1, dtype=torch.int32, device=dev)
+    d_K, d_nodes, d_changed = (torch.empty(J, dtype=torch.int32, device=dev) for _ in range(3))
     mut = max(1, (1 << 32) // J)
     for it in range(intervals):
         job_params[PARAM_PHI] = phi_of(np.minimum(state.progress / np.asarray(target, np.float64), 1.0))
         call = FitnessCall(P, J, N, Gm, Gs, job_params, m_grid, fair_share, state.alloc, node_capacity, p=p, delta=delta,
                            flags=PX_FLAG_MEMOISE if memoise else 0, device=dev)
-        pop = torch.as_tensor(state.alloc).to(dev).unsqueeze(0).repeat(P, 1, 1).contiguous()
+        pop = call.current_alloc.unsqueeze(0).repeat(P, 1, 1).contiguous()
         for g in range(generations):
             call.run(pop, outputs="fitness", keep_job_tables=g > 0)
             call.ga_step(pop, pop, seed, it * generations + g, max(1, P // 2), mut, flags=PX_GA_IN_PLACE)
         call.run(pop, outputs="fitness", keep_job_tables=True)
-        best = int(torch.argmax(call.fitness).item())
+        status = call.status()          # of the search's fitness calls, accumulated over the generations
+        pollux_apply_best(call.dims, pop, call.fitness, call.current_alloc, d_best, d_K, d_nodes, d_changed)
+        pollux_sim_tick(Dims(P, J, N, Gm, Gs, 0, 0), call.job_params, call.m_grid, d_K, d_nodes, d_changed, d_target,
+                        interval_s, restart_delay, call.workspace, d_progress, d_goodput, d_finished)
+        best = int(d_best.item())
         best_fitness = float(call.fitness[best].item())
-        new_alloc = pop[best].cpu().numpy()
-        changed = (new_alloc != state.alloc).any(axis=1) & (state.alloc.sum(axis=1) > 0)
-        K = new_alloc.sum(axis=1).astype(np.int32)
-        nodes = (new_alloc > 0).sum(axis=1).astype(np.int32)
-        i32 = lambda a: torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
-        pollux_sim_tick(Dims(P, J, N, Gm, Gs, 0, 0), call.job_params, call.m_grid, i32(K), i32(nodes), i32(changed), d_target, interval_s,
-                        restart_delay, call.workspace, d_progress, d_goodput, d_finished)
+        new_alloc = call.current_alloc.cpu().numpy()
+        changed = d_changed.cpu().numpy().astype(bool)
+        K = d_K.cpu().numpy()
         record = dict(interval=it, phi=job_params[PARAM_PHI].copy(), previous_alloc=state.alloc, alloc=new_alloc,
                       best_fitness=best_fitness, changed=changed, progress_before=state.progress.copy(),
-                      goodput=d_goodput.cpu().numpy(), status=call.status())
+                      goodput=d_goodput.cpu().numpy(), status=status, best=best)
         state.alloc = new_alloc
         state.progress = d_progress.cpu().numpy()
         state.finished = d_finished.cpu().numpy().astype(bool)

@@ -11,10 +11,6 @@
 #include "../../include/pollux.h"
 #include "pollux_host.h"
 
-namespace px {
-hipEvent_t g_sweep_start = nullptr, g_sweep_stop = nullptr;
-}
-
 // ---- scratch memory owned by the library (pollux_fitness_static) -------------------------------------------
 // One array per GPU, part of the code object: every device the library runs on holds its own copy, at its own
 // address, from the moment the code object is loaded there until the process ends.  In host code the name
@@ -111,10 +107,13 @@ int pollux_workspace_size(const pollux_dims *dims, size_t *bytes)
     return PX_OK;
 }
 
-int pollux_fitness(const pollux_dims *dims, const int32_t *population, const double *job_params, const int32_t *m_grid,
-                   const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
-                   double delta, void *workspace, size_t workspace_bytes, double *fitness, int32_t *best_m,
-                   int32_t *best_s, double *best_goodput, double *speedup, int32_t *violations, void *hip_stream)
+namespace {
+
+int fitness_call(const pollux_dims *dims, const int32_t *population, const double *job_params, const int32_t *m_grid,
+                 const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
+                 double delta, void *workspace, size_t workspace_bytes, double *fitness, int32_t *best_m,
+                 int32_t *best_s, double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
+                 hipEvent_t sweep_stop, void *hip_stream)
 {
     if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
     if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !fitness ||
@@ -126,8 +125,32 @@ int pollux_fitness(const pollux_dims *dims, const int32_t *population, const dou
     rc = check_device();
     if (rc != PX_OK) return rc;
     return px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
-                              workspace, fitness, best_m, best_s, best_goodput, speedup, violations,
-                              (hipStream_t)hip_stream);
+                              workspace, fitness, best_m, best_s, best_goodput, speedup, violations, sweep_start,
+                              sweep_stop, (hipStream_t)hip_stream);
+}
+
+}  // namespace
+
+int pollux_fitness(const pollux_dims *dims, const int32_t *population, const double *job_params, const int32_t *m_grid,
+                   const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
+                   double delta, void *workspace, size_t workspace_bytes, double *fitness, int32_t *best_m,
+                   int32_t *best_s, double *best_goodput, double *speedup, int32_t *violations, void *hip_stream)
+{
+    return fitness_call(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
+                        workspace, workspace_bytes, fitness, best_m, best_s, best_goodput, speedup, violations, nullptr,
+                        nullptr, hip_stream);
+}
+
+int pollux_fitness_timed(const pollux_dims *dims, const int32_t *population, const double *job_params,
+                         const int32_t *m_grid, const int32_t *fair_share, const int32_t *current_alloc,
+                         const int32_t *node_capacity, double p, double delta, void *workspace, size_t workspace_bytes,
+                         double *fitness, int32_t *best_m, int32_t *best_s, double *best_goodput, double *speedup,
+                         int32_t *violations, void *sweep_start_event, void *sweep_stop_event, void *hip_stream)
+{
+    if (!sweep_start_event || !sweep_stop_event) return PX_E_INVALID_ARG;
+    return fitness_call(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
+                        workspace, workspace_bytes, fitness, best_m, best_s, best_goodput, speedup, violations,
+                        (hipEvent_t)sweep_start_event, (hipEvent_t)sweep_stop_event, hip_stream);
 }
 
 int pollux_fitness_static(const pollux_dims *dims, const int32_t *population, const double *job_params,
@@ -150,7 +173,8 @@ int pollux_fitness_static(const pollux_dims *dims, const int32_t *population, co
     rc = static_scratch(dev, &ws);
     if (rc != PX_OK) return rc;
     rc = px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
-                            ws, fitness, best_m, best_s, best_goodput, speedup, violations, (hipStream_t)hip_stream);
+                            ws, fitness, best_m, best_s, best_goodput, speedup, violations, nullptr, nullptr,
+                            (hipStream_t)hip_stream);
     if (rc != PX_OK) return rc;
     return status ? px::launch_copy_status(ws, status, (hipStream_t)hip_stream) : PX_OK;
 }
@@ -162,7 +186,7 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (!dims_ok(dims, false)) return PX_E_INVALID_ARG;
     if (!parents || !fitness || !node_capacity || !params || !children) return PX_E_INVALID_ARG;
     if (params->elite_k < 1u || params->elite_k > (uint32_t)dims->P) return PX_E_INVALID_ARG;
-    if (16 * (size_t)dims->J + 16 * (size_t)dims->N > 120 * 1024) return PX_E_INVALID_ARG;   // per-job and per-node bookkeeping lives in LDS
+    if (!px::ga_shapes_fit(dims->J, dims->N)) return PX_E_INVALID_ARG;   // per-job and per-node bookkeeping lives in LDS
     const size_t bytes = sizeof(int32_t) * (size_t)dims->P * dims->J * dims->N;
     const char *a = (const char *)parents, *b = (const char *)children;
     if (params->flags & ~(uint32_t)PX_GA_IN_PLACE) return PX_E_INVALID_ARG;
@@ -177,6 +201,16 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (rc != PX_OK) return rc;
     return px::launch_ga_step(dims, parents, fitness, node_capacity, params, workspace, children,
                               (hipStream_t)hip_stream);
+}
+
+int pollux_apply_best(const pollux_dims *dims, const int32_t *population, const double *fitness, int32_t *current_alloc,
+                      int32_t *best, int32_t *K, int32_t *nodes, int32_t *changed, void *hip_stream)
+{
+    if (!dims_ok(dims, false)) return PX_E_INVALID_ARG;
+    if (!population || !fitness || !current_alloc || !best || !K || !nodes || !changed) return PX_E_INVALID_ARG;
+    const int rc = check_device();
+    if (rc != PX_OK) return rc;
+    return px::launch_apply_best(dims, population, fitness, current_alloc, best, K, nodes, changed, (hipStream_t)hip_stream);
 }
 
 namespace {
@@ -244,14 +278,6 @@ int pollux_fit_theta(int32_t J, int32_t max_obs, const int32_t *obs_count, const
     if (rc != PX_OK) return rc;
     return px::launch_fit_theta(J, max_obs, max_iter, n_starts, obs_count, obs_K, obs_nodes, obs_m, obs_s, obs_T, theta_init,
                                 theta, rmsle, iterations, (hipStream_t)hip_stream);
-}
-
-int pollux_set_sweep_events(void *hip_event_start, void *hip_event_stop)
-{
-    if ((hip_event_start == nullptr) != (hip_event_stop == nullptr)) return PX_E_INVALID_ARG;
-    px::g_sweep_start = (hipEvent_t)hip_event_start;
-    px::g_sweep_stop = (hipEvent_t)hip_event_stop;
-    return PX_OK;
 }
 
 int pollux_last_status(const void *workspace, void *hip_stream, int32_t *host_out)

@@ -94,6 +94,7 @@ struct FitnessArgs {
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
     int need_constraints;
+    int clear_status;             // tables_kernel starts a new status word (fitness calls; the query calls leave it alone)
     // outputs
     double *fitness, *best_goodput, *speedup;
     int32_t *best_m, *best_s, *violations;
@@ -145,11 +146,11 @@ __device__ __forceinline__ SyncParams load_sync(const Job &q)
 // M0 <= K m (s+1) <= M_max holds exactly when ceil(M0/m) <= K (s+1) <= floor(M_max/m),
 // i.e. for s between trunc(ql5 / K) and trunc(qh5 / K) - 1; the halves keep the
 // quotients at least 1/(2K) away from an integer, so a rounded 1/K cannot move them
-// across one.  Also rs[s] = 1/(s+1), rk[K] = 1/K, and the status word is cleared.
+// across one.  Also rs[s] = 1/(s+1), rk[K] = 1/K, and a fitness call clears the status word here.
 __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
-    if (t == 0) *a.status = 0;
+    if (t == 0 && a.clear_status) *a.status = 0;
     const int rs_len = ((a.Gs + 31) / 32) * 32;
     if (t < rs_len) a.rs[t] = 1.0 / (double)(t + 1);
     if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
@@ -598,6 +599,21 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                     : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
                 s_star = 4 * g_star + (__double2loint(kk) & 3);
             }
+            // The keys of the scan carry index bits, so two neighbouring counts whose values agree to 2^-47 may
+            // have been taken in the wrong order (convexity rules out any other near-tie).  The order of
+            // neighbours is known exactly: w(s+1) < w(s) precisely when C > (s+1)(s+2), both sides exact in fp64.
+            {
+                double t_lo, t_hi;                 // s (s+1) and (s+1)(s+2) at s = s_star; -1 for s = 0, so that it never moves below 0
+                if (has_near) {
+                    const Double2 t = *(const Double2 __attribute__((address_space(3))) *)(near + kNearRecips + 2 * s_star);
+                    t_lo = t.x; t_hi = t.y;
+                } else {
+                    const double sd = (double)s_star;
+                    t_lo = s_star > 0 ? px_fma(sd, sd, sd) : -1.0;
+                    t_hi = px_fma(sd, sd, px_fma(3.0, sd, 2.0));
+                }
+                s_star = C <= t_lo ? s_star - 1 : (C > t_hi ? s_star + 1 : s_star);
+            }
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
@@ -617,6 +633,15 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                 }
             }
             feasible = key < __builtin_inf();
+            if (feasible) {
+                // the same exact order of neighbours as in the tabled path, inside the feasible counts; the key
+                // is then formed again without index bits
+                const double C = B0 * tgr.y, sd = (double)s_c;
+                const double t_lo = px_fma(sd, sd, sd), t_hi = px_fma(sd, sd, px_fma(3.0, sd, 2.0));
+                if (s_c > s_lo && C <= t_lo) s_c -= 1;
+                else if (s_c < s_hi && C > t_hi) s_c += 1;
+                key = px_fma(B0, rs[s_c], px_fma((double)s_c, tg, A0));
+            }
         }
         if (feasible && key < kbest) {
             kbest = key;
@@ -921,11 +946,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
-    __shared__ double r_lds[kNearRecips];
+    // behind them, per count s, the pair s (s+1), (s+1)(s+2) that decides the order of neighbouring counts (sweep_pick)
+    __shared__ __align__(16) double r_lds[3 * kNearRecips];
     bool has_near = false;
     if constexpr (!F32 && CH != 0 && !MEMO) {
         if (a.gs_pad <= kNearRecips) {
-            for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) r_lds[t] = a.rs[t];
+            for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) {
+                r_lds[t] = a.rs[t];
+                const double sd = (double)t;
+                r_lds[kNearRecips + 2 * t] = t > 0 ? sd * (sd + 1.0) : -1.0;
+                r_lds[kNearRecips + 2 * t + 1] = (sd + 1.0) * (sd + 2.0);
+            }
             __syncthreads();
             has_near = true;
         }
@@ -1571,7 +1602,8 @@ int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t s
 int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
-                   double *best_goodput, double *speedup, int32_t *violations, hipStream_t stream)
+                   double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
+                   hipEvent_t sweep_stop, hipStream_t stream)
 {
     const WorkspaceLayout L = workspace_layout(*d);
     char *ws = (char *)workspace;
@@ -1579,6 +1611,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.population = population; a.fair_share = fair_share; a.current_alloc = current_alloc;
     a.node_capacity = node_capacity;
     a.p = p; a.delta = delta;
+    a.clear_status = 1;
     a.denom = (double *)(ws + L.denom);
     a.factor = (double *)(ws + L.factor);
     a.running = (int32_t *)(ws + L.running);
@@ -1629,7 +1662,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
             else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
         }
     }
-    if (g_sweep_start) (void)hipEventRecord(g_sweep_start, stream);
+    if (sweep_start) (void)hipEventRecord(sweep_start, stream);
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool whole = d->Gm % kWave == 0;
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
@@ -1667,7 +1700,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
 #undef PX_LAUNCH_PAIRS_FP64
 #undef PX_LAUNCH_PAIRS
-    if (g_sweep_stop) (void)hipEventRecord(g_sweep_stop, stream);
+    if (sweep_stop) (void)hipEventRecord(sweep_stop, stream);
     if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;

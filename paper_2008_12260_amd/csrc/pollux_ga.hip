@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <mutex>
+
 #include "../../include/pollux.h"
 #include "pollux_device.h"
 #include "pollux_host.h"
@@ -155,6 +157,12 @@ inline size_t ga_shared_bytes(int J, int N)
 {
     return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J) + (J >= N ? 0 : 2 * kNodeSlots * (size_t)N);
 }
+
+// What a workgroup may use: the 160 KB of a compute unit less the kernel's few static variables, rounded down.
+constexpr size_t kGaMaxShared = 159 * 1024;
+constexpr int kGaDevices = 64;
+
+bool ga_shapes_fit(int J, int N) { return ga_shared_bytes(J, N) <= kGaMaxShared; }
 
 // Number of positive entries of a row; every lane returns the same value.
 __device__ __forceinline__ int count_occupied(const int32_t *__restrict__ row, int N, int lane)
@@ -548,6 +556,81 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     }
 }
 
+// ---- applying the outcome of a search --------------------------------------------------
+// The matrix PolluxSched applies at the end of a scheduling interval is the candidate of highest fitness
+// (Sec. 4.3), i.e. the first in the order of rank_kernel: fitness descending, index ascending, NaN last.
+__global__ void __launch_bounds__(256) best_kernel(int P, const double *__restrict__ fitness, int32_t *__restrict__ best)
+{
+    __shared__ double red_f[256];
+    __shared__ int red_c[256];
+    const int t = threadIdx.x;
+    double f = -__builtin_inf();
+    int c = 0x7FFFFFFF;
+    for (int o = t; o < P; o += 256) {
+        double g = fitness[o];
+        if (!(g == g)) g = -__builtin_inf();
+        if (c == 0x7FFFFFFF || g > f) { f = g; c = o; }        // ascending o: an equal value keeps the lower index
+    }
+    red_f[t] = f;
+    red_c[t] = c;
+    __syncthreads();
+    for (int half = 128; half > 0; half >>= 1) {
+        if (t < half) {
+            const double g = red_f[t + half];
+            const int o = red_c[t + half];
+            if (o != 0x7FFFFFFF && (red_c[t] == 0x7FFFFFFF || g > red_f[t] || (g == red_f[t] && o < red_c[t]))) {
+                red_f[t] = g;
+                red_c[t] = o;
+            }
+        }
+        __syncthreads();
+    }
+    if (t == 0) *best = red_c[0];
+}
+
+// One wavefront per job: the job's row of the best candidate becomes its current row; K, nodes and the
+// re-allocation flag (row differs from the previous current row, which held at least one GPU) are reported.
+__global__ void __launch_bounds__(256) apply_kernel(int J, int N, const int32_t *__restrict__ population,
+                                                    const int32_t *__restrict__ best, int32_t *__restrict__ current,
+                                                    int32_t *__restrict__ K_out, int32_t *__restrict__ nodes_out,
+                                                    int32_t *__restrict__ changed_out)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int j = blockIdx.x * 4 + wave;
+    if (j >= J) return;
+    const int lane = lane_id();
+    const int32_t *__restrict__ row = population + ((size_t)*best * J + j) * N;
+    int32_t *__restrict__ cur = current + (size_t)j * N;
+    long long k = 0, held = 0;
+    int nodes = 0;
+    bool differs = false;
+    for (int n0 = 0; n0 < N; n0 += kWave) {
+        const int n = n0 + lane;
+        const int32_t v = n < N ? row[n] : 0, was = n < N ? cur[n] : 0;
+        k += v;
+        held += was;
+        nodes += __popcll(__ballot(v > 0));
+        differs |= __ballot(v != was) != 0;
+        if (n < N) cur[n] = v;
+    }
+    k = wave_sum(k);
+    held = wave_sum(held);
+    if (lane == 0) {
+        K_out[j] = (int32_t)k;
+        nodes_out[j] = nodes;
+        changed_out[j] = (differs && held > 0) ? 1 : 0;
+    }
+}
+
+int launch_apply_best(const pollux_dims *d, const int32_t *population, const double *fitness, int32_t *current_alloc,
+                      int32_t *best, int32_t *K, int32_t *nodes, int32_t *changed, hipStream_t stream)
+{
+    hipLaunchKernelGGL(best_kernel, dim3(1), dim3(256), 0, stream, d->P, fitness, best);
+    hipLaunchKernelGGL(apply_kernel, dim3((unsigned)((d->J + 3) / 4)), dim3(256), 0, stream, d->J, d->N, population, best,
+                       current_alloc, K, nodes, changed);
+    return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
+}
+
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
                    const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream)
 {
@@ -567,9 +650,19 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);
     const bool four = (d->N & 3) == 0 && d->N <= kWave && !a.job_gpu_cap && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
-    const void *kernel = four ? (const void *)generation_kernel<true> : (const void *)generation_kernel<false>;
     if (lds > 48 * 1024) {
-        if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return PX_E_HIP;
+        // Beyond 48 KB a kernel must be allowed its dynamic LDS explicitly.  The allowance is raised per kernel
+        // instance and device, and only when a call needs more than any earlier one did.
+        static std::mutex lock;
+        static size_t allowed[2][kGaDevices];
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kGaDevices) return PX_E_HIP;
+        std::lock_guard<std::mutex> hold(lock);
+        if (allowed[four ? 1 : 0][dev] < lds) {
+            const void *kernel = four ? (const void *)generation_kernel<true> : (const void *)generation_kernel<false>;
+            if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return PX_E_HIP;
+            allowed[four ? 1 : 0][dev] = lds;
+        }
     }
     const unsigned children_formed = a.in_place ? (unsigned)d->P - ga->elite_k : (unsigned)d->P;
     if (children_formed > 0) {

@@ -69,19 +69,23 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     return L;
 }
 
-// Events recorded around the grid-sweep kernel (profiling aid), or null.
-extern hipEvent_t g_sweep_start, g_sweep_stop;
-
 int launch_fitness(const pollux_dims *d, const int32_t *population, const double *job_params, const int32_t *m_grid,
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
-                   double *best_goodput, double *speedup, int32_t *violations, hipStream_t stream);
+                   double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
+                   hipEvent_t sweep_stop, hipStream_t stream);   // the two events, if given, bracket the grid-sweep kernel
 
 // Copies the status word of `workspace` to *status_out (device memory) on the stream.
 int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t stream);
 
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
                    const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
+
+// True when the search step's per-job and per-node bookkeeping for J jobs and N nodes fits the LDS of a workgroup.
+bool ga_shapes_fit(int J, int N);
+
+int launch_apply_best(const pollux_dims *d, const int32_t *population, const double *fitness, int32_t *current_alloc,
+                      int32_t *best, int32_t *K, int32_t *nodes, int32_t *changed, hipStream_t stream);
 
 int launch_goodput_per_gpu(const pollux_dims *d, const double *job_params, const int32_t *m_grid, int gpus_per_node,
                            int max_nodes, void *workspace, double *per_gpu, hipStream_t stream);

@@ -131,3 +131,13 @@ def test_the_newer_entry_points_reject_bad_arguments_without_a_device():
     ga = px.GaParams(1, 0, 8, 0, 2)                                    # unknown search flag
     dd = px.Dims(16, 8, 4, 32, 8, 0, 0)
     assert L.pollux_ga_step(ctypes.byref(dd), fake, fake, fake, ctypes.byref(ga), fake, 1 << 30, ctypes.c_void_p(0x90000000), null) == px.PX_E_INVALID_ARG
+
+
+def test_shapes_whose_bookkeeping_does_not_fit_on_chip_are_rejected():
+    fake, null = ctypes.c_void_p(0x100000), ctypes.c_void_p(0)
+    ga = px.GaParams(1, 0, 1, 0, 0, None)
+    for J, N, ok in ((1000, 5000, True), (1000, 5400, False), (8, 6000, True), (8, 6600, False), (7000, 256, True), (8000, 256, False)):
+        d = px.Dims(2, J, N, 1, 1, 0, 0)
+        rc = px.lib().pollux_ga_step(ctypes.byref(d), fake, fake, fake, ctypes.byref(ga), null, 0, ctypes.c_void_p(0x7f0000000000), null)
+        # a shape that fits gets as far as the workspace check; one that does not is refused before it
+        assert rc == (px.PX_E_WORKSPACE if ok else px.PX_E_INVALID_ARG), (J, N, rc)

@@ -225,3 +225,67 @@ def test_large_config_one_generation_in_place_bit_exact():
     want = O.ga_step(pop, fit, wl.node_capacity, SEED, 7, cfg.P // 2, (1 << 32) // cfg.J, flags=O.GA_IN_PLACE)
     for lo in range(0, cfg.P, 256):
         assert np.array_equal(got[lo:lo + 256], want[lo:lo + 256]), f"candidates {lo}..{lo + 255}"
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_search_loop_in_the_benchmark_shape_matches_oracle_every_generation(flags):
+    """The loop as bench.py runs it on the 64 x 8 cluster: step in place, job tables kept after the first
+    generation, the library's own fitness driving its own step, plain and memoised (flags = 4); the checker
+    runs its own independent loop.  Matrices, elected points and violation counts are compared at every one of
+    100 generations."""
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("mid")
+    c = wl.cfg
+    call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                          wl.node_capacity, p=c.p, delta=c.delta, flags=flags)
+    host = wl.population.copy()
+    dev = torch.as_tensor(host).cuda()
+    mut = (1 << 32) // c.J
+    first_best = None
+    for gen in range(100):
+        call.run(dev, outputs="fitness", keep_job_tables=gen > 0)
+        ref = run_oracle(wl, population=host)
+        if gen % 10 == 0 or gen == 99:
+            got = call.results()
+            assert got["status"] == ref["status"] == 0
+            assert np.array_equal(got["best_m"], ref["best_m"]) and np.array_equal(got["best_s"], ref["best_s"]), gen
+            assert np.array_equal(got["violations"], ref["violations"]), gen
+            err = np.abs(got["fitness"] - ref["fitness"]) / np.where(ref["fitness"] == 0, 1.0, np.abs(ref["fitness"]))
+            assert err.max() <= 1e-12, gen
+        first_best = ref["fitness"].max() if first_best is None else first_best
+        call.ga_step(dev, dev, SEED, gen, c.P // 2, mut, flags=px.PX_GA_IN_PLACE)
+        host = O.ga_step(host, ref["fitness"], wl.node_capacity, SEED, gen, c.P // 2, mut, flags=O.GA_IN_PLACE)
+        got = dev.cpu().numpy()
+        assert np.array_equal(got, host), f"generation {gen}: {np.argwhere((got != host).any(axis=(1, 2))).ravel()[:8]}"
+    assert run_oracle(wl, population=host)["fitness"].max() >= first_best
+
+
+def test_step_with_zero_grid_dims_between_fitness_calls_that_keep_their_tables():
+    """pollux_ga_step reads P, J, N only: called through the C ABI with Gm = Gs = 0 on the workspace of a search
+    whose fitness calls keep their job tables, it must leave those tables alone."""
+    import ctypes
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("physical")
+    c = wl.cfg
+    call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                          wl.node_capacity, p=c.p, delta=c.delta)
+    dev = torch.as_tensor(wl.population).cuda()
+    call.run(dev)
+    first = call.results()
+    bare = px.Dims(c.P, c.J, c.N, 0, 0, 0, 0)
+    ga = px.GaParams(SEED, 0, c.P // 2, (1 << 32) // c.J, px.PX_GA_IN_PLACE, None)
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    ptr = lambda t: ctypes.c_void_p(t.data_ptr())
+    rc = px.lib().pollux_ga_step(ctypes.byref(bare), ptr(dev), ptr(call.fitness), ptr(call.node_capacity), ctypes.byref(ga),
+                                 ptr(call.workspace), call.workspace.numel(), ptr(dev), stream)
+    assert rc == px.PX_OK
+    want = O.ga_step(wl.population, first["fitness"], wl.node_capacity, SEED, 0, c.P // 2, (1 << 32) // c.J, flags=O.GA_IN_PLACE)
+    assert np.array_equal(dev.cpu().numpy(), want)
+    call.run(dev, keep_job_tables=True)
+    kept = call.results()
+    ref = run_oracle(wl, population=want)
+    assert np.array_equal(kept["best_m"], ref["best_m"]) and np.array_equal(kept["best_s"], ref["best_s"])
+    assert np.allclose(kept["fitness"], ref["fitness"], rtol=1e-12, atol=0.0)
+    assert np.allclose(kept["best_goodput"], ref["best_goodput"], rtol=1e-12, atol=0.0)

@@ -117,6 +117,49 @@ def test_argument_checks():
         px.pollux_autoscale(out, z, float("nan"), 0.5, z.clone())
 
 
+@pytest.mark.parametrize("name", ["tiny", "physical", "mid"])
+def test_apply_best_matches_the_checker(name):
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make(name)
+    c = wl.cfg
+    rng = np.random.default_rng(41)
+    dev = lambda a: torch.as_tensor(np.ascontiguousarray(a)).cuda()
+    pop = dev(wl.population)
+    for case in range(4):
+        fit = rng.choice([0.3, 0.8, 0.8, -2.0, np.nan], c.P) if case < 2 else rng.uniform(size=c.P)
+        if case == 3:
+            fit[:] = np.nan
+        cur = wl.current_alloc.copy()
+        cur[::3] = 0                                            # pending jobs: nothing to restart
+        d_cur = dev(cur)
+        best = torch.empty(1, dtype=torch.int32, device="cuda")
+        K, nodes, changed = (torch.empty(c.J, dtype=torch.int32, device="cuda") for _ in range(3))
+        px.pollux_apply_best(px.Dims(c.P, c.J, c.N, 0, 0, 0, 0), pop, dev(fit), d_cur, best, K, nodes, changed)
+        w_best, w_new, w_K, w_nodes, w_changed = LP.apply_best(wl.population, fit, cur)
+        assert int(best.item()) == w_best
+        assert np.array_equal(d_cur.cpu().numpy(), w_new)
+        assert np.array_equal(K.cpu().numpy(), w_K) and np.array_equal(nodes.cpu().numpy(), w_nodes)
+        assert np.array_equal(changed.cpu().numpy().astype(bool), w_changed)
+
+
+def test_closed_loop_reports_the_status_of_its_search():
+    """A job whose re-allocation factor is not positive (T_j - R_j delta <= 0) raises a status bit in every fitness
+    call of the search; the simulator tick that follows on the same workspace must not wipe it."""
+    import paper_2008_12260_amd as px
+    from paper_2008_12260_amd import closed_loop
+    wl = W.make("tiny", current="fair")
+    c = wl.cfg
+    jp = wl.job_params.copy()
+    jp[W.PARAM_INDEX["age_T"], 1] = 10.0
+    jp[W.PARAM_INDEX["restarts_R"], 1] = 3.0
+    seen = []
+    closed_loop.run(jp, wl.m_grid, wl.fair_share, wl.node_capacity, np.full(c.J, 1e9), W.noise_scale_schedule(wl.param("phi")),
+                    wl.current_alloc, P=32, Gs=c.Gs, generations=3, intervals=2, seed=5,
+                    on_interval=lambda state, rec: seen.append(rec["status"]))
+    assert seen == [px.PX_ST_BAD_RESTART] * 2
+
+
 def test_closed_loop_is_checked_interval_by_interval():
     """The scheduling loop of paper_2008_12260_amd.closed_loop on the testbed-shaped workload: every interval's
     decision and tick are recomputed by the CPU checker from the inputs the loop used."""
@@ -137,7 +180,7 @@ def test_closed_loop_is_checked_interval_by_interval():
         assert abs(ref["fitness"][0] - rec["best_fitness"]) <= 1e-12 * abs(ref["fitness"][0])
         assert ref["fitness"][0] >= ref["fitness"][1] * (1 - 1e-12)                   # never worse than staying put
         changed = (rec["alloc"] != rec["previous_alloc"]).any(1) & (rec["previous_alloc"].sum(1) > 0)
-        assert np.array_equal(changed, rec["changed"])
+        assert np.array_equal(changed, rec["changed"])              # what pollux_apply_best reported
         g, new, fin = LP.sim_tick(jp, wl.m_grid, c.Gs, rec["alloc"].sum(1), (rec["alloc"] > 0).sum(1), changed,
                                   rec["progress_before"], target, 60.0, 30.0)
         assert rel_err(rec["goodput"], g).max() <= RTOL and rel_err(rec["progress"], new).max() <= RTOL

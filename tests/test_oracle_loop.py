@@ -71,3 +71,25 @@ def test_simulator_tick_bookkeeping():
     target2 = np.full(J, 100.0 + 0.5 * g[0] * 60.0)
     _, _, fin2 = LP.sim_tick(wl.job_params, wl.m_grid, c.Gs, K, nodes, changed, progress, target2, 60.0, 30.0)
     assert fin2[0]
+
+
+def test_apply_best_on_a_case_worked_out_by_hand():
+    """Three candidates for two jobs on three nodes; fitness ties go to the lower index, NaN ranks last (the
+    order of the search step's ranking, checked against it)."""
+    pop = np.array([[[1, 0, 0], [0, 2, 0]],
+                    [[0, 1, 1], [0, 2, 0]],
+                    [[2, 0, 0], [0, 0, 0]]], np.int32)
+    cur = np.array([[1, 0, 0], [0, 0, 0]], np.int32)             # job 1 is pending: nothing to restart
+    best, new, K, nodes, changed = LP.apply_best(pop, [0.5, 0.9, 0.9], cur)
+    assert best == 1 and np.array_equal(new, pop[1])
+    assert K.tolist() == [2, 2] and nodes.tolist() == [2, 1] and changed.tolist() == [True, False]
+    best, new, K, nodes, changed = LP.apply_best(pop, [np.nan, -3.0, np.nan], cur)
+    assert best == 1
+    best, new, K, nodes, changed = LP.apply_best(pop, [0.7, 0.1, 0.2], cur)
+    assert best == 0 and changed.tolist() == [False, False] and K.tolist() == [1, 2]
+    best, *_ = LP.apply_best(pop, [np.nan, np.nan, np.nan], cur)
+    assert best == 0
+    rng = np.random.default_rng(3)
+    for _ in range(50):
+        f = rng.choice([0.25, 0.5, np.nan, -2.0, 1.0], 9)
+        assert LP.apply_best(np.zeros((9, 1, 1), np.int32), f, np.zeros((1, 1), np.int32))[0] == O.rank(f)[0]
