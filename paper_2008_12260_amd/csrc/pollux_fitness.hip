@@ -87,6 +87,7 @@ struct FitnessArgs {
     // workspace
     int32_t *status;
     double *rs, *rk, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
+    float *rsf;                   // 1/(s+1) in fp32, as long as rs
     double2 *tg;                  // [J,Gm] (T_grad, 1 / T_grad)
     int32_t *srange;              // [J,kTableK,Gm] feasible accumulation counts per (job, K, grid point) (see last_kernel)
     int gs_pad;                   // Gs rounded up to a multiple of 32: length of rs
@@ -152,7 +153,10 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0 && a.clear_status) *a.status = 0;
     const int rs_len = ((a.Gs + 31) / 32) * 32;
-    if (t < rs_len) a.rs[t] = 1.0 / (double)(t + 1);
+    if (t < rs_len) {
+        a.rs[t] = 1.0 / (double)(t + 1);
+        a.rsf[t] = 1.0f / (float)(t + 1);
+    }
     if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
     if (t < a.J * a.Gm) {
         const int j = t / a.Gm;
@@ -841,6 +845,175 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
     return wave_argmax((double)gbest, flat, m_best, s_best);
 }
 
+// ---- fp32 variant: the same scan-and-clamp sweep as the fp64 one ------------------------------
+// For GPU counts within the tables.  Lane l owns batch sizes i = l, l + 64, ...; for each it scans
+// w(s) = s + C / (s + 1) over all accumulation counts in chunks of 16, one v_fma_f32 per grid point
+// (1/(s+1) from scalar registers, s from sixteen vector registers that hold 0 .. 15 for the whole
+// kernel), one v_bfi_b32 that puts the position in the chunk into the low four mantissa bits, and one
+// v_min3_f32 per two points: five instructions per two grid points.  The argmin over all counts is then
+// put right between neighbours (the same exact test as in fp64: w(s+1) < w(s) exactly when
+// C > (s+1)(s+2)), clamped to the feasible counts of (job, K, i) from the table, and h is formed there.
+// The wave takes the smallest h (equal values: lowest flat index).  The elected point is priced with
+// Eq. 4 in the plain form, in fp32 (price_point_f32).  T_grad, u and C are formed in fp32 from the
+// parameters rounded to fp32; the last pass of Eq. 10 is the fp64 table rounded to fp32.
+typedef const float __attribute__((address_space(4))) *ScalarFloats;
+typedef const float __attribute__((address_space(3))) *LdsFloats;
+
+struct RunStepsF32 {
+    float x[16];
+};
+
+__device__ __forceinline__ RunStepsF32 make_run_steps_f32()
+{
+    RunStepsF32 X;
+#pragma unroll
+    for (int t = 0; t < 16; ++t) X.x[t] = (float)t;
+    asm volatile("" : "+v"(X.x[0]), "+v"(X.x[1]), "+v"(X.x[2]), "+v"(X.x[3]), "+v"(X.x[4]), "+v"(X.x[5]), "+v"(X.x[6]), "+v"(X.x[7]));
+    asm volatile("" : "+v"(X.x[8]), "+v"(X.x[9]), "+v"(X.x[10]), "+v"(X.x[11]), "+v"(X.x[12]), "+v"(X.x[13]), "+v"(X.x[14]), "+v"(X.x[15]));
+    return X;
+}
+
+// Two grid points at positions B, B + 1 of a chunk: their values of w relative to the chunk's first count,
+// tagged with their positions, folded into the running minimum.
+template <int B>
+__device__ __forceinline__ void scan_two_f32(float &kmin, float C, float r0, float r1, const RunStepsF32 &X)
+{
+    float w0, w1;
+    int k0, k1;
+    asm("v_fma_f32 %0, %1, %2, %3" : "=v"(w0) : "v"(C), "s"(r0), "v"(X.x[B]));
+    asm("v_fma_f32 %0, %1, %2, %3" : "=v"(w1) : "v"(C), "s"(r1), "v"(X.x[B + 1]));
+    asm("v_bfi_b32 %0, 15, %1, %2" : "=v"(k0) : "n"(B), "v"(__float_as_int(w0)));
+    asm("v_bfi_b32 %0, 15, %1, %2" : "=v"(k1) : "n"(B + 1), "v"(__float_as_int(w1)));
+    if constexpr (B == 0) asm("v_min_f32 %0, %1, %2" : "=v"(kmin) : "v"(__int_as_float(k0)), "v"(__int_as_float(k1)));
+    else asm("v_min3_f32 %0, %0, %1, %2" : "+v"(kmin) : "v"(__int_as_float(k0)), "v"(__int_as_float(k1)));
+}
+
+template <int CH, int B = 0>
+__device__ __forceinline__ void scan_chunk_f32(float &kmin, float C, ScalarFloats r, const RunStepsF32 &X)
+{
+    if constexpr (B < CH) {
+        scan_two_f32<B>(kmin, C, r[B], r[B + 1], X);
+        scan_chunk_f32<CH, B + 2>(kmin, C, r, X);
+    }
+}
+
+// All 64 lanes call this with the same (job, 1 <= K <= kTableK, nodes); every lane returns the same result.
+// rsf: 1/(s+1) in fp32, padded to a multiple of 32 counts; near: a copy of it in LDS when has_near.
+template <int CH, bool WHOLE>
+__device__ __forceinline__ Pick sweep_pick_f32(const JobF32 &q, const JobTables &tb, const RunStepsF32 &X,
+                                               const float *__restrict__ rsf, int Gm, int Gs, int K, int nodes,
+                                               LdsFloats near = nullptr, bool has_near = false)
+{
+    static_assert(CH == 8 || CH == 16, "positions of a chunk fit four tag bits");
+    const int lane = lane_id();
+    K = __builtin_amdgcn_readfirstlane(K);
+    nodes = __builtin_amdgcn_readfirstlane(nodes);
+    const bool one_node = nodes == 1;
+    const float Kf = (float)K;
+    float ts = 0.0f;                                                          // Eq. 9
+    if (K > 1) ts = one_node ? q.alpha_sl + q.beta_sl * (float)(K - 2) : q.alpha_sn + q.beta_sn * (float)(K - 2);
+    const int mode = ts == 0.0f ? 0 : (q.gamma == 1.0f ? 1 : 2);
+    const double *__restrict__ lrow = tb.lt + (unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm;
+    const int32_t *__restrict__ srow = tb.srange + (unsigned)(K - 1) * (unsigned)Gm;
+    const ScalarFloats rsc = (ScalarFloats)rsf;
+
+    float kbest = __builtin_inff();   // smallest h seen by this lane
+    int where = 0;                    // its accumulation count | (index of its group of 64 batch sizes) << 16
+    for (int i0 = 0; i0 < Gm; i0 += kWave) {
+        const int i = i0 + lane;
+        const bool active = WHOLE || i < Gm;
+        const int il = active ? i : Gm - 1;
+        const float mf = (float)tb.m[il];
+        const float tg = q.alpha_g + q.beta_g * mf;                           // Eq. 8
+        float last;                                                           // Eq. 10
+        if (mode == 0) last = tg;
+        else if (mode == 1) last = tg + ts;
+        else last = (float)lrow[il];
+        const float u = q.phi * __builtin_amdgcn_rcpf(Kf * mf);
+        const float A0 = fmaf(u, tg, last);
+        const float C = (last - tg) * u * __builtin_amdgcn_rcpf(tg);
+        const int bounds = srow[il];
+        const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
+        const bool feasible = active && s_lo <= s_hi;
+        // argmin of w over all counts: chunk by chunk, values relative to the chunk's first count
+        float wmin;
+        scan_chunk_f32<CH>(wmin, C, rsc, X);
+        int s_star = __float_as_int(wmin) & 15;
+        for (int s0 = CH; s0 < Gs; s0 += CH) {
+            float w;
+            scan_chunk_f32<CH>(w, C, rsc + s0, X);
+            const float moved = w + (float)s0;                               // strictly smaller only: ties keep the smaller s
+            if (moved < wmin) {
+                wmin = moved;
+                s_star = s0 + (__float_as_int(w) & 15);
+            }
+        }
+        // neighbours in their exact order (the tags may have swapped two that agree to 2^-19)
+        {
+            const float sd = (float)s_star;
+            const float t_lo = s_star > 0 ? fmaf(sd, sd, sd) : -1.0f, t_hi = fmaf(sd, sd, fmaf(3.0f, sd, 2.0f));
+            s_star = C <= t_lo ? s_star - 1 : (C > t_hi ? s_star + 1 : s_star);
+        }
+        int s_c = s_star < s_hi ? s_star : s_hi;
+        s_c = s_c > s_lo ? s_c : s_lo;
+        const float r_c = has_near ? near[s_c] : rsf[s_c];
+        const float key = fmaf(tg, fmaf(C, r_c, (float)s_c), A0);
+        if (feasible && key < kbest) {
+            kbest = key;
+            where = s_c | ((i0 / kWave) << 16);
+        }
+    }
+    // positive floats order like their bit patterns
+    const unsigned bits = (unsigned)__float_as_int(kbest);
+    const unsigned bmin = wave_min(bits);
+    if (bmin >= 0x7F800000u) return Pick{-1, -1};               // every lane still holds +inf (or a NaN)
+    unsigned long long winners = __builtin_amdgcn_ballot_w64(bits == bmin);
+    if (winners & (winners - 1)) {
+        // equal values: the lowest flat index i * Gs + s
+        const bool top = ((winners >> lane) & 1ull) != 0;
+        const int flat = ((where >> 16) * kWave + lane) * Gs + (where & 0xFFFF);
+        const int first = wave_min(top ? flat : 0x7FFFFFFF);
+        winners &= __builtin_amdgcn_ballot_w64(flat == first);
+    }
+    const int wl = __ffsll(winners) - 1;
+    const int wwhere = __builtin_amdgcn_readlane(where, wl);
+    return Pick{(wwhere >> 16) * kWave + wl, wwhere & 0xFFFF};
+}
+
+// Eq. 4 at grid point (i, s) in the plain form, in fp32, for a GPU count within the tables.  Arguments may
+// differ from lane to lane.
+__device__ __forceinline__ Best price_point_f32(const JobF32 &q, const JobTables &tb, int Gm, int K, bool one_node, int i, int s)
+{
+    if (i < 0) return Best{0.0, -1, -1};
+    const int m = tb.m[i];
+    const float mf = (float)m;
+    const float tg = q.alpha_g + q.beta_g * mf;                               // Eq. 8
+    float ts = 0.0f;                                                          // Eq. 9
+    if (K > 1) ts = one_node ? q.alpha_sl + q.beta_sl * (float)(K - 2) : q.alpha_sn + q.beta_sn * (float)(K - 2);
+    float last;                                                               // Eq. 10
+    if (ts == 0.0f) last = tg;
+    else if (q.gamma == 1.0f) last = tg + ts;
+    else last = (float)tb.lt[(unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm + (unsigned)i];
+    const float M = (float)K * mf * (float)(s + 1);
+    const float t_iter = (float)s * tg + last;                                // Eq. 11
+    const float g = (M / t_iter) * (q.a / (q.phi + M));                       // Eq. 7 x Eq. 6
+    return Best{(double)g, m, s};
+}
+
+// The fp32 sweep of one (job, K, nodes) whatever K: scan and price within the tables, the plain loop beyond.
+// Every lane returns the same result.
+template <int CH>
+__device__ __forceinline__ Best sweep_any_f32(const JobF32 &q, const JobTables &tb, const float *__restrict__ rsf,
+                                              const double *__restrict__ rk, int Gm, int Gs, int K, int nodes)
+{
+    K = __builtin_amdgcn_readfirstlane(K);
+    nodes = __builtin_amdgcn_readfirstlane(nodes);
+    if (K <= 0) return Best{0.0, -1, -1};
+    if (K > kTableK) return sweep_f32(q, tb, rk, Gm, Gs, K, nodes);
+    const Pick pick = sweep_pick_f32<CH, false>(q, tb, make_run_steps_f32(), rsf, Gm, Gs, K, nodes);
+    return price_point_f32(q, tb, Gm, K, nodes == 1, pick.i, pick.s);
+}
+
 // ---- per job -----------------------------------------------------------------
 
 template <int CH, bool F32>
@@ -886,8 +1059,8 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     if constexpr (CH == 0)
         fair = sweep_sampled(q, a.m_grid + (size_t)j * a.Gm, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
     else if constexpr (F32)
-        fair = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, a.fair_share[2 * j],
-                         a.fair_share[2 * j + 1]);
+        fair = sweep_any_f32<CH>(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rsf, a.rk, a.Gm, a.Gs,
+                                 a.fair_share[2 * j], a.fair_share[2 * j + 1]);
     else
         fair = sweep<CH>(q, job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, a.fair_share[2 * j], a.fair_share[2 * j + 1]);
     if (!(fair.goodput > 0.0)) st |= PX_ST_ZERO_FAIR;
@@ -916,7 +1089,7 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
     const int j = (int)(row / (2 * kTableK));
     Best best;
     if constexpr (CH == 0) best = sweep_sampled(load_job(a.job_params, a.J, j), a.m_grid + (size_t)j * a.Gm, a.Gm, a.Gs, K, nodes);
-    else if constexpr (F32) best = sweep_f32(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rk, a.Gm, a.Gs, K, nodes);
+    else if constexpr (F32) best = sweep_any_f32<CH>(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rsf, a.rk, a.Gm, a.Gs, K, nodes);
     else best = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
     if (lane_id() == 0) {
         MemoEntry e;
@@ -949,13 +1122,17 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     // behind them, per count s, the pair s (s+1), (s+1)(s+2) that decides the order of neighbouring counts (sweep_pick)
     __shared__ __align__(16) double r_lds[3 * kNearRecips];
     bool has_near = false;
-    if constexpr (!F32 && CH != 0 && !MEMO) {
+    if constexpr (CH != 0 && !MEMO) {
         if (a.gs_pad <= kNearRecips) {
             for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) {
-                r_lds[t] = a.rs[t];
-                const double sd = (double)t;
-                r_lds[kNearRecips + 2 * t] = t > 0 ? sd * (sd + 1.0) : -1.0;
-                r_lds[kNearRecips + 2 * t + 1] = (sd + 1.0) * (sd + 2.0);
+                if constexpr (F32) {
+                    ((float *)r_lds)[t] = a.rsf[t];
+                } else {
+                    r_lds[t] = a.rs[t];
+                    const double sd = (double)t;
+                    r_lds[kNearRecips + 2 * t] = t > 0 ? sd * (sd + 1.0) : -1.0;
+                    r_lds[kNearRecips + 2 * t + 1] = (sd + 1.0) * (sd + 2.0);
+                }
             }
             __syncthreads();
             has_near = true;
@@ -972,9 +1149,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     if (vec4) cur0 = ((const int4 *)cur)[lane < n4 ? lane : n4 - 1];
     const int lane4 = lane < n4 ? lane : n4 - 1;      // ROW1: lanes past the end of the row load its last 16 bytes again
     const unsigned long long in_row = __ballot(lane < n4);
-    constexpr bool kDeferred = !F32 && CH != 0;
+    constexpr bool kDeferred = CH != 0;               // the grid sweeps of both precisions (not the sampling argmax)
+    constexpr int kPriced = -3;                       // a row beyond the tables whose result lane r already holds (see below)
     int d_K = 0, d_meta = 0, d_i = -1, d_s = -1;      // lane r: what candidate r of this wavefront needs at the end
     RunSteps X = {};
+    RunStepsF32 XF = {};
     bool any_neg = false;
 
     // candidate c = c0 + kWavesPerBlock * r; its row of job j and its counters are reached by stepping pointers
@@ -1057,7 +1236,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     };
 
     if constexpr (kDeferred) {
-        // fp64 grid sweep, in two passes over the wavefront's candidates so that neither pass keeps the
+        // grid sweep (either precision), in two passes over the wavefront's candidates so that neither pass keeps the
         // other's addresses in scalar registers: first the row stage of every candidate (lane r keeps K and
         // nodes | changed of candidate r), then the sweeps, which elect a point per candidate; the points are
         // priced after the loop.
@@ -1156,19 +1335,25 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 any_neg |= neg;
             }
         }
-        X = make_run_steps();      // after the row pass, whose rows in flight use the registers these occupy
+        // after the row pass, whose rows in flight use the registers these occupy
+        if constexpr (F32) XF = make_run_steps_f32();
+        else X = make_run_steps();
         for (int r = 0; r < rows; ++r) {
             const int K = __builtin_amdgcn_readlane(d_K, r);
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
             if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
-            else if (!MEMO && K >= 1) pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near);
+            else if (!MEMO && K >= 1) {
+                if constexpr (F32) pick = sweep_pick_f32<CH, WHOLE>(qf, tb, XF, a.rsf, a.Gm, a.Gs, K, nodes, (LdsFloats)(const float *)r_lds, has_near);
+                else pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near);
+            }
             if (lane == r) {
                 d_i = pick.i;
                 d_s = pick.s;
             }
         }
     } else {
+        // the sampling argmax: one candidate after the other, priced where it is swept
         for (int r = 0; r < a.cand_per_wave; ++r) {
             const int c = c0 + kWavesPerBlock * r;
             if (c >= a.P) break;
@@ -1179,10 +1364,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             if (MEMO && K >= 1 && K <= kTableK) {
                 const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
-            } else if constexpr (CH == 0) {
-                best = sweep_sampled(q, tb.m, a.Gm, a.Gs, K, nodes);
             } else {
-                best = sweep_f32(qf, tb, a.rk, a.Gm, a.Gs, K, nodes);
+                best = sweep_sampled(q, tb.m, a.Gm, a.Gs, K, nodes);
             }
             if (lane == 0) {
                 const size_t pair = (size_t)c * a.J + j;
@@ -1207,17 +1390,24 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         const Job qb = load_job(b.job_params, b.J, j);
         const JobTables tbb = job_tables(b, j);
 
-        // rows with more GPUs than the tables cover: the whole wavefront sweeps them one by one
+        // rows with more GPUs than the tables cover: the whole wavefront sweeps and prices them one by one
+        Best beyond = {0.0, -1, -1};
         unsigned long long pending = __ballot(d_i == kPending);
         while (pending) {
             const int l = __ffsll(pending) - 1;
             pending &= pending - 1;
             const int K = __builtin_amdgcn_readlane(d_K, l);
             const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
-            const Pick pick = sweep_pick<CH, false>(qb, tbb, X, b.rs, b.rk, b.Gm, b.Gs, K, nodes);
+            Best found;
+            if constexpr (F32) {
+                found = sweep_f32(qf, tbb, b.rk, b.Gm, b.Gs, K, nodes);
+            } else {
+                const Pick pick = sweep_pick<CH, false>(qb, tbb, X, b.rs, b.rk, b.Gm, b.Gs, K, nodes);
+                found = price_point(qb, tbb, b.Gm, K, nodes == 1, pick.i, pick.s);
+            }
             if (lane == l) {
-                d_i = pick.i;
-                d_s = pick.s;
+                beyond = found;
+                d_i = kPriced;
             }
         }
         // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
@@ -1230,6 +1420,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             if (MEMO && d_K >= 1 && d_K <= kTableK) {
                 const MemoEntry e = b.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+            } else if (d_i == kPriced) {
+                best = beyond;
+            } else if constexpr (F32) {
+                best = price_point_f32(qf, tbb, b.Gm, d_K, nodes == 1, d_i, d_s);
             } else {
                 best = price_point(qb, tbb, b.Gm, d_K, nodes == 1, d_i, d_s);
             }
@@ -1522,6 +1716,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     a.m_grid = m_grid; a.job_params = job_params;
     a.status = (int32_t *)(ws + L.status);
     a.rs = (double *)(ws + L.rs);
+    a.rsf = (float *)(ws + L.rsf);
     a.rk = (double *)(ws + L.rk);
     a.tg = (double2 *)(ws + L.tg);
     a.lntg = (double *)(ws + L.lntg);
@@ -1649,14 +1844,16 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         launch_job_tables(d, a, !sampled, stream);
         const dim3 job_grid((unsigned)((d->J + kWavesPerBlock - 1) / kWavesPerBlock));
         if (sampled) hipLaunchKernelGGL((jobs_kernel<0, false>), job_grid, dim3(256), 0, stream, a);
-        else if (f32) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
+        else if (f32 && ch == 8) hipLaunchKernelGGL((jobs_kernel<8, true>), job_grid, dim3(256), 0, stream, a);
+        else if (f32) hipLaunchKernelGGL((jobs_kernel<16, true>), job_grid, dim3(256), 0, stream, a);
         else if (ch == 8) hipLaunchKernelGGL((jobs_kernel<8, false>), job_grid, dim3(256), 0, stream, a);
         else if (ch == 16) hipLaunchKernelGGL((jobs_kernel<16, false>), job_grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((jobs_kernel<32, false>), job_grid, dim3(256), 0, stream, a);
         if (memo) {
             const dim3 memo_grid((unsigned)((lt_rows + kWavesPerBlock - 1) / kWavesPerBlock));
             if (sampled) hipLaunchKernelGGL((memo_kernel<0, false>), memo_grid, dim3(256), 0, stream, a);
-            else if (f32) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
+            else if (f32 && ch == 8) hipLaunchKernelGGL((memo_kernel<8, true>), memo_grid, dim3(256), 0, stream, a);
+            else if (f32) hipLaunchKernelGGL((memo_kernel<16, true>), memo_grid, dim3(256), 0, stream, a);
             else if (ch == 8) hipLaunchKernelGGL((memo_kernel<8, false>), memo_grid, dim3(256), 0, stream, a);
             else if (ch == 16) hipLaunchKernelGGL((memo_kernel<16, false>), memo_grid, dim3(256), 0, stream, a);
             else hipLaunchKernelGGL((memo_kernel<32, false>), memo_grid, dim3(256), 0, stream, a);
@@ -1666,17 +1863,18 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool whole = d->Gm % kWave == 0;
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
-#define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1) \
-    hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1>), dim3(pair_blocks), dim3(256), 0, stream, a)
-#define PX_LAUNCH_PAIRS_FP64(CH)                                   \
-    do {                                                           \
-        if (memo && row4) hipLaunchKernelGGL((pairs_kernel<CH, false, true, true, false, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
-        else if (memo && row1) PX_LAUNCH_PAIRS(CH, false, true, true);  \
-        else if (memo) PX_LAUNCH_PAIRS(CH, false, true, false);    \
-        else if (row4 && whole) hipLaunchKernelGGL((pairs_kernel<CH, false, false, true, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
-        else if (row1 && whole) hipLaunchKernelGGL((pairs_kernel<CH, false, false, true, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
-        else if (row1) PX_LAUNCH_PAIRS(CH, false, false, true);    \
-        else PX_LAUNCH_PAIRS(CH, false, false, false);             \
+#define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4) \
+    hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4>), dim3(pair_blocks), dim3(256), 0, stream, a)
+    // the instance for the row length (four rows per load, one row per load, any) and the grid (whole groups of 64 batch sizes or not)
+#define PX_LAUNCH_PAIRS_GRID(CH, F32)                                          \
+    do {                                                                       \
+        if (memo && row4) PX_LAUNCH_PAIRS(CH, F32, true, true, false, true);   \
+        else if (memo && row1) PX_LAUNCH_PAIRS(CH, F32, true, true, false, false); \
+        else if (memo) PX_LAUNCH_PAIRS(CH, F32, true, false, false, false);    \
+        else if (row4 && whole) PX_LAUNCH_PAIRS(CH, F32, false, true, true, true); \
+        else if (row1 && whole) PX_LAUNCH_PAIRS(CH, F32, false, true, true, false); \
+        else if (row1) PX_LAUNCH_PAIRS(CH, F32, false, true, false, false);    \
+        else PX_LAUNCH_PAIRS(CH, F32, false, false, false, false);             \
     } while (0)
     if (memo && !sampled && !f32 && row1 && !row4) {
         // memoised pass over rows of 65 to 256 entries: in memory order
@@ -1686,19 +1884,19 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         else if (ch == 16) hipLaunchKernelGGL(memo_pairs_kernel<16>, memo_pairs_grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL(memo_pairs_kernel<32>, memo_pairs_grid, dim3(256), 0, stream, a);
     } else if (sampled) {
-        if (memo) PX_LAUNCH_PAIRS(0, false, true, false);
-        else PX_LAUNCH_PAIRS(0, false, false, false);
+        if (memo) PX_LAUNCH_PAIRS(0, false, true, false, false, false);
+        else PX_LAUNCH_PAIRS(0, false, false, false, false, false);
     } else if (f32) {
-        if (memo) PX_LAUNCH_PAIRS(8, true, true, false);
-        else PX_LAUNCH_PAIRS(8, true, false, false);
+        if (ch == 8) PX_LAUNCH_PAIRS_GRID(8, true);
+        else PX_LAUNCH_PAIRS_GRID(16, true);
     } else if (ch == 8) {
-        PX_LAUNCH_PAIRS_FP64(8);
+        PX_LAUNCH_PAIRS_GRID(8, false);
     } else if (ch == 16) {
-        PX_LAUNCH_PAIRS_FP64(16);
+        PX_LAUNCH_PAIRS_GRID(16, false);
     } else {
-        PX_LAUNCH_PAIRS_FP64(32);
+        PX_LAUNCH_PAIRS_GRID(32, false);
     }
-#undef PX_LAUNCH_PAIRS_FP64
+#undef PX_LAUNCH_PAIRS_GRID
 #undef PX_LAUNCH_PAIRS
     if (sweep_stop) (void)hipEventRecord(sweep_stop, stream);
     if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);

@@ -30,6 +30,7 @@ struct WorkspaceLayout {
     size_t colpack;   // uint64 [P,N]     per node of each candidate: GPUs asked + multi-node jobs << 40
     // from here on the offsets depend on the grid
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
+    size_t rsf;       // float  [Gs up to a multiple of 32]  the same in fp32
     size_t tg;        // double [J,Gm,2]  T_grad(m_i) and its reciprocal
     size_t lntg;      // double [J,Gm]    ln T_grad(m_i)
     size_t pu;        // double [J,Gm]    phi / m_i
@@ -58,6 +59,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.memo = o;    o = up(o + 16 * J * 2 * kTableK);
     L.colpack = o; o = up(o + 8 * P * (size_t)d.N);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
+    L.rsf = o;     o = up(o + 4 * ((Gs + 31) / 32) * 32);
     L.tg = o;      o = up(o + 16 * J * Gm);
     L.lntg = o;    o = up(o + 8 * J * Gm);
     L.pu = o;      o = up(o + 8 * J * Gm);
