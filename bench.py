@@ -124,6 +124,20 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
+    # the same generations with pollux_generation: the step in place, then the fitness of the 2048 children only
+    # (a survivor's results cannot change within a scheduling interval); only the children's grid points are counted
+    call.run(a, stream=stream, outputs="fitness")
+    for _ in range(2):
+        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness")
+        gen += 1
+    torch.cuda.synchronize()
+    ti0 = time.perf_counter()
+    for _ in range(args.steps):
+        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness")
+        gen += 1
+    torch.cuda.synchronize()
+    incremental_s = time.perf_counter() - ti0
+
     # the same search step out of place (survivors copied into a second buffer), for comparison
     b = torch.empty_like(a)
     o0, o1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -159,6 +173,9 @@ def main():
         "sweep_kernel_evals_per_s": evals_per_step / (sweep_avg_ms * 1e-3),
         "population_bytes_per_s_in_sweep": 4.0 * cfg.P * cfg.J * cfg.N / (sweep_avg_ms * 1e-3),
         "status_word": status, "best_fitness_after_run": best_fitness, "seed": cfg.seed,
+        "children_only_generations_per_s": args.steps / incremental_s,
+        "children_only_ms_per_generation": incremental_s * 1e3 / args.steps,
+        "children_only_evals_per_s": (cfg.P - elite) * cfg.J * cfg.Gm * cfg.Gs * args.steps / incremental_s,
     }
 
     # memoised mode (one sweep per (job, K, placement class); not part of the headline: its population pass
@@ -205,6 +222,18 @@ def main():
             if not flags:
                 extra[label + "_evals_per_s"] = 100.0 * mcfg.evals_per_call / (tg1 - tg0)
             extra[label + "_best_fitness"] = float(mcall.fitness.max().item())
+            # the same loop with pollux_generation (children only)
+            ma = torch.from_numpy(mwl.population).to(dev)
+            mcall.run(ma, stream=stream, outputs="fitness")
+            for g in range(5):
+                mcall.generation(ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, outputs="fitness")
+            torch.cuda.synchronize()
+            tg0 = time.perf_counter()
+            for g in range(5, 105):
+                mcall.generation(ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, outputs="fitness")
+            torch.cuda.synchronize()
+            extra[label + "_children_only_generations_per_s"] = 100.0 / (time.perf_counter() - tg0)
+            extra[label + "_children_only_best_fitness"] = float(mcall.fitness.max().item())
 
         # one fitness call on the mid configuration in fp64 and in fp32 arithmetic (launch overhead included)
         ma = torch.from_numpy(mwl.population).to(dev)
@@ -264,7 +293,8 @@ def main():
         "dtype": "f64", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: P={cfg.P} candidates, J={cfg.J} jobs, {cfg.N} nodes x {cfg.cap} GPUs, "
                                f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step (in place) per step",
-                   "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed},
+                   "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed,
+                   "generations_per_s_children_only": args.steps / incremental_s},
         "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": SWEEP_HBM_BYTES.get(cfg.name),
                      "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL,

@@ -292,6 +292,39 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; only P, J, N a
                    void *hip_stream);
 
 /*
+ * One generation of the search in one call (Sec. 4.3): pollux_ga_step in place on `population`, ranking by
+ * the values `fitness` holds, then pollux_fitness of the children the step has just formed, and of those
+ * only.  A survivor's matrix is unchanged and FITNESS_p of a matrix depends on nothing else that changes
+ * within a scheduling interval, so its entries of fitness, best_m, best_s, best_goodput, speedup and
+ * violations are left as they are; the children's entries are overwritten.  After the call every output
+ * array holds exactly what pollux_ga_step followed by a pollux_fitness call on the whole new population
+ * would have left there, at the cost of sweeping P - elite_k candidates instead of P.
+ *
+ * Preconditions (as for PX_FLAG_KEEP_JOB_TABLES, which is implied): the previous call on this workspace was
+ * pollux_fitness or pollux_generation with the same dims, job_params, m_grid, fair_share, current_alloc, p,
+ * delta, flags and output arrays, and the output arrays and the population have not been written since.
+ * params->flags must be PX_GA_IN_PLACE.  The status word keeps accumulating.
+ * Errors as for pollux_fitness and pollux_ga_step.
+ */
+int pollux_generation(const pollux_dims *dims,           /* host */
+                      int32_t *population,               /* [P,J,N] in/out */
+                      const double *job_params,          /* [PX_NPARAM,J] */
+                      const int32_t *m_grid,             /* [J,Gm] */
+                      const int32_t *fair_share,         /* [J,2] */
+                      const int32_t *current_alloc,      /* [J,N] */
+                      const int32_t *node_capacity,      /* [N] */
+                      double p, double delta,
+                      const pollux_ga_params *params,    /* host */
+                      void *workspace, size_t workspace_bytes,
+                      double *fitness,                   /* [P] in/out */
+                      int32_t *best_m,                   /* [P,J] in/out */
+                      int32_t *best_s,                   /* [P,J] in/out */
+                      double *best_goodput,              /* [P,J] in/out, may be NULL */
+                      double *speedup,                   /* [P,J] in/out, may be NULL */
+                      int32_t *violations,               /* [P] in/out, may be NULL */
+                      void *hip_stream);
+
+/*
  * Online fitting of theta_sys (Sec. 4.1, "Online model fitting"): for each job the seven
  * throughput parameters (Eq. 12) that minimise the root mean squared logarithmic error
  * between Eq. 11 and the iteration times the job has recorded, subject to every alpha and

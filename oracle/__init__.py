@@ -223,6 +223,16 @@ def ga_step(parents, fitness_values, node_capacity, seed, generation, elite_k, m
     return out
 
 
+def generation(population, fitness_values, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta, Gs,
+               seed, generation_index, elite_k, mut_threshold, flags=0, job_gpu_cap=None):
+    """One generation of the search: the step in place, then FITNESS_p of the whole new population by the plain
+    definition (the library evaluates the children only; a survivor's fitness cannot have changed).
+    Returns (new population, dict of fitness outputs)."""
+    new = ga_step(population, fitness_values, node_capacity, seed, generation_index, elite_k, mut_threshold,
+                  flags=GA_IN_PLACE, job_gpu_cap=job_gpu_cap)
+    return new, fitness(new, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta, Gs, flags)
+
+
 def cap_row(row, cap):
     r = np.array(row, dtype=np.int32, order="C", copy=True)
     lib().pollux_ref_cap_row(_p(r), r.size, int(cap))

@@ -23,7 +23,7 @@ PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_fitness_static",
            "pollux_ga_step",
            "pollux_fit_theta", "pollux_goodput_per_gpu", "pollux_autoscale", "pollux_sim_tick", "pollux_last_status",
-           "pollux_fitness_timed", "pollux_apply_best")
+           "pollux_fitness_timed", "pollux_apply_best", "pollux_generation")
 
 
 class PolluxError(RuntimeError):
@@ -76,6 +76,9 @@ def lib() -> ctypes.CDLL:
         L.pollux_last_status.argtypes = [vp, vp, ctypes.POINTER(ctypes.c_int32)]
         L.pollux_fitness_timed.restype = i
         L.pollux_fitness_timed.argtypes = [ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, vp, sz] + [vp] * 6 + [vp, vp, vp]
+        L.pollux_generation.restype = i
+        L.pollux_generation.argtypes = ([ctypes.POINTER(Dims)] + [vp] * 6 + [d, d, ctypes.POINTER(GaParams), vp, sz]
+                                        + [vp] * 6 + [vp])
         L.pollux_apply_best.restype = i
         L.pollux_apply_best.argtypes = [ctypes.POINTER(Dims)] + [vp] * 7 + [vp]
         _lib = L
@@ -213,6 +216,19 @@ def pollux_last_status(workspace, stream=None) -> int:
     return out.value
 
 
+def pollux_generation(dims: Dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p: float,
+                      delta: float, ga: GaParams, workspace, fitness, best_m, best_s, best_goodput=None, speedup=None,
+                      violations=None, stream=None) -> None:
+    """pollux_generation of the C ABI on torch device tensors: the search step in place, then the fitness of its children."""
+    rc = lib().pollux_generation(
+        ctypes.byref(dims), _ptr(population), _ptr(job_params), _ptr(m_grid), _ptr(fair_share), _ptr(current_alloc),
+        _ptr(node_capacity), float(p), float(delta), ctypes.byref(ga), _ptr(workspace),
+        workspace.numel() * workspace.element_size(), _ptr(fitness), _ptr(best_m), _ptr(best_s), _ptr(best_goodput),
+        _ptr(speedup), _ptr(violations), _stream_handle(stream))
+    if rc != PX_OK:
+        raise PolluxError(rc, "pollux_generation")
+
+
 def pollux_apply_best(dims: Dims, population, fitness, current_alloc, best, K, nodes, changed, stream=None) -> None:
     """pollux_apply_best of the C ABI on torch device tensors (current_alloc is overwritten)."""
     rc = lib().pollux_apply_best(ctypes.byref(dims), _ptr(population), _ptr(fitness), _ptr(current_alloc), _ptr(best),
@@ -272,6 +288,14 @@ class FitnessCall:
         ga = GaParams(seed, generation, elite_k, mut_threshold, flags, None if job_gpu_cap is None else job_gpu_cap.data_ptr())
         pollux_ga_step(self.dims, parents, self.fitness if fitness is None else fitness, self.node_capacity, ga,
                        self.workspace, children, stream)
+
+    def generation(self, population, seed, generation, elite_k, mut_threshold, stream=None, outputs="all", job_gpu_cap=None):
+        """pollux_generation on this call's buffers: search step in place, then the fitness of the children only."""
+        full = outputs == "all"
+        ga = GaParams(seed, generation, elite_k, mut_threshold, PX_GA_IN_PLACE, None if job_gpu_cap is None else job_gpu_cap.data_ptr())
+        pollux_generation(self.dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
+                          self.node_capacity, self.p, self.delta, ga, self.workspace, self.fitness, self.best_m, self.best_s,
+                          self.best_goodput if full else None, self.speedup if full else None, self.violations, stream)
 
     def results(self) -> dict:
         self.torch.cuda.synchronize()

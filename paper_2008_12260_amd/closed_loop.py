@@ -4,7 +4,7 @@ and the jobs run on it until the next interval; Sec. 5.3: discrete-time simulati
 
 Per interval:
   1. the jobs' gradient noise scale phi_t is refreshed from their progress (the caller's `phi_of` function);
-  2. the population search runs `generations` steps of pollux_fitness + pollux_ga_step (in place) from a
+  2. the population search runs pollux_fitness once and then `generations` calls of pollux_generation from a
      population seeded with the current allocation;
   3. pollux_apply_best takes the best candidate of the last evaluation, makes it the current allocation and
      marks the jobs whose row changed as re-allocated;
@@ -20,7 +20,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-from . import (PX_FLAG_MEMOISE, PX_GA_IN_PLACE, Dims, FitnessCall, PARAM_PHI, pollux_apply_best, pollux_sim_tick)
+from . import (PX_FLAG_MEMOISE, Dims, FitnessCall, PARAM_PHI, pollux_apply_best, pollux_sim_tick)
 
 
 @dataclass
@@ -56,10 +56,9 @@ def run(job_params, m_grid, fair_share, node_capacity, target, phi_of, alloc0, *
         call = FitnessCall(P, J, N, Gm, Gs, job_params, m_grid, fair_share, state.alloc, node_capacity, p=p, delta=delta,
                            flags=PX_FLAG_MEMOISE if memoise else 0, device=dev)
         pop = call.current_alloc.unsqueeze(0).repeat(P, 1, 1).contiguous()
-        for g in range(generations):
-            call.run(pop, outputs="fitness", keep_job_tables=g > 0)
-            call.ga_step(pop, pop, seed, it * generations + g, max(1, P // 2), mut, flags=PX_GA_IN_PLACE)
-        call.run(pop, outputs="fitness", keep_job_tables=True)
+        call.run(pop, outputs="fitness")
+        for g in range(generations):      # each: the step in place, then the fitness of the children it formed
+            call.generation(pop, seed, it * generations + g, max(1, P // 2), mut, outputs="fitness")
         status = call.status()          # of the search's fitness calls, accumulated over the generations
         pollux_apply_best(call.dims, pop, call.fitness, call.current_alloc, d_best, d_K, d_nodes, d_changed)
         pollux_sim_tick(Dims(P, J, N, Gm, Gs, 0, 0), call.job_params, call.m_grid, d_K, d_nodes, d_changed, d_target,

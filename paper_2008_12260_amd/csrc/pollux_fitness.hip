@@ -95,6 +95,8 @@ struct FitnessArgs {
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
     int need_constraints;
+    const int32_t *sel;           // candidates to evaluate (device list of n_sel indices into the population), or null: all P
+    int n_sel;
     int clear_status;             // tables_kernel starts a new status word (fitness calls; the query calls leave it alone)
     // outputs
     double *fitness, *best_goodput, *speedup;
@@ -1109,7 +1111,9 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // WHOLE: the host has checked that Gm is a multiple of 64 (tabled sweeps then skip the test for the end of the grid).
 // ROW4: ROW1 and a row is at most 64 entries, so one load of the wavefront covers the rows of four candidates
 // (16 lanes each); cand_per_wave is at most 16.
-template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false>
+// SEL: only the candidates listed in a.sel are evaluated (the children a search step has just formed); the
+// wavefronts then walk positions of that list and look the candidate up where an address is formed.
+template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false, bool SEL = false>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
@@ -1156,17 +1160,36 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     RunStepsF32 XF = {};
     bool any_neg = false;
 
-    // candidate c = c0 + kWavesPerBlock * r; its row of job j and its counters are reached by stepping pointers
+    // The wavefront's r-th candidate is c0 + kWavesPerBlock * r; its row of job j and its counters are reached
+    // by stepping pointers.  With SEL that number is a position in the list, and lane r holds the candidate
+    // listed there (-1 past the end of the list).
     const int c0 = group * a.cand_per_wave * kWavesPerBlock + wave;
+    const int P_eff = SEL ? a.n_sel : a.P;
+    int d_c = -1;
+    if constexpr (SEL) {
+        const int k = c0 + kWavesPerBlock * lane;
+        if (lane < a.cand_per_wave && k < P_eff) d_c = a.sel[k];
+    }
     const size_t row_step = (size_t)kWavesPerBlock * a.J * a.N;
     const int32_t *__restrict__ row = a.population + ((size_t)c0 * a.J + j) * a.N - row_step;
     unsigned long long *__restrict__ cp = a.colpack + (size_t)c0 * a.N - (size_t)kWavesPerBlock * a.N;
+    // the row of job j of the wavefront's r-th candidate (SEL), and making that candidate the current one
+    auto row_of = [&](int r) -> const int32_t * {
+        return a.population + ((size_t)__builtin_amdgcn_readlane(d_c, r) * a.J + j) * a.N;
+    };
+    auto advance = [&](int r) {
+        if constexpr (SEL) {
+            row = row_of(r);
+            cp = a.colpack + (size_t)__builtin_amdgcn_readlane(d_c, r) * a.N;
+        } else {
+            row += row_step;
+            cp += (size_t)kWavesPerBlock * a.N;
+        }
+    };
 
-    // The row stage of candidate c0 + 4 r: row reduce and constraint counters.
+    // The row stage of the current candidate (see advance): row reduce and constraint counters.
     // ROW1 callers that have the row in registers already pass it as `have`; otherwise it is read here.
     auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out, const int4 *have = nullptr) {
-        row += row_step;
-        cp += (size_t)kWavesPerBlock * a.N;
         // row reduce: K = sum, nodes = #positive, changed = differs from the current row
         int ksum = 0, nodes = 0;
         bool changed = false, neg = false;
@@ -1241,24 +1264,31 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         // nodes | changed of candidate r), then the sweeps, which elect a point per candidate; the points are
         // priced after the loop.
         int rows = a.cand_per_wave;
-        if (c0 + kWavesPerBlock * (rows - 1) >= a.P) rows = c0 < a.P ? (a.P - c0 + kWavesPerBlock - 1) / kWavesPerBlock : 0;
+        if (c0 + kWavesPerBlock * (rows - 1) >= P_eff) rows = c0 < P_eff ? (P_eff - c0 + kWavesPerBlock - 1) / kWavesPerBlock : 0;
         if constexpr (ROW4) {
             // Lanes 16 g .. 16 g + 15 hold the row of candidate 4 b + g of the wavefront in batch b; all
             // batches are requested together.  Sums over a row are sums over 16 lanes (four DPP steps).
             static_assert(ROW1, "rows of 16-byte groups");
             const int g = lane >> 4, l16 = lane & 15;
             const bool in_row16 = l16 < n4;
-            const int4 *__restrict__ row1 = (const int4 *)(row + row_step) + (in_row16 ? l16 : n4 - 1);
+            const int lane_off = in_row16 ? l16 : n4 - 1;
+            const int4 *__restrict__ row1 = (const int4 *)(row + row_step) + lane_off;
             unsigned long long *__restrict__ cp1 = cp + (size_t)kWavesPerBlock * a.N + 4 * l16;
-            const int4 curg = ((const int4 *)cur)[in_row16 ? l16 : n4 - 1];
+            const int4 curg = ((const int4 *)cur)[lane_off];
             constexpr int kBatches = kMaxCandPerWave / 4;
             int4 v[kBatches];
             int kb[kBatches] = {}, mb[kBatches] = {};
+            int cb[kBatches] = {};           // SEL: the candidate whose row the lane holds in batch b
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
                 if (4 * b < rows) {
                     const int r = 4 * b + g < rows ? 4 * b + g : rows - 1;             // the tail reads the last row again
-                    v[b] = *(const int4 *)((const int32_t *)row1 + (size_t)r * row_step);
+                    if constexpr (SEL) {
+                        cb[b] = __builtin_amdgcn_ds_bpermute(r << 2, d_c);
+                        v[b] = ((const int4 *)(a.population + ((size_t)cb[b] * a.J + j) * a.N))[lane_off];
+                    } else {
+                        v[b] = *(const int4 *)((const int32_t *)row1 + (size_t)r * row_step);
+                    }
                 }
             }
 #pragma unroll
@@ -1281,7 +1311,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                     if (a.need_constraints && live) {
                         // every non-zero entry goes to the candidate's per-node counters (a negative one as it is)
                         const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
-                        unsigned long long *__restrict__ to = cp1 + (size_t)r * kWavesPerBlock * a.N;
+                        unsigned long long *__restrict__ to = SEL ? a.colpack + (size_t)cb[b] * a.N + 4 * l16
+                                                                  : cp1 + (size_t)r * kWavesPerBlock * a.N;
                         if (w.x != 0) atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
                         if (w.y != 0) atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
                         if (w.z != 0) atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
@@ -1307,13 +1338,15 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
-                    v[u] = ((const int4 *)(row + (size_t)(ru - r0 + 1) * row_step))[lane4];
+                    if constexpr (SEL) v[u] = ((const int4 *)row_of(ru))[lane4];
+                    else v[u] = ((const int4 *)(row + (size_t)(ru - r0 + 1) * row_step))[lane4];
                 }
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     if (r0 + u < rows) {
                         int K, nodes;
                         bool changed, neg;
+                        advance(r0 + u);
                         row_stage(K, nodes, changed, neg, &v[u]);
                         if (lane == r0 + u) {
                             d_K = K;
@@ -1327,6 +1360,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             for (int r = 0; r < rows; ++r) {
                 int K, nodes;
                 bool changed, neg;
+                advance(r);
                 row_stage(K, nodes, changed, neg);
                 if (lane == r) {
                     d_K = K;
@@ -1355,10 +1389,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     } else {
         // the sampling argmax: one candidate after the other, priced where it is swept
         for (int r = 0; r < a.cand_per_wave; ++r) {
-            const int c = c0 + kWavesPerBlock * r;
-            if (c >= a.P) break;
+            if (c0 + kWavesPerBlock * r >= P_eff) break;
+            const int c = SEL ? __builtin_amdgcn_readlane(d_c, r) : c0 + kWavesPerBlock * r;
             int K, nodes;
             bool changed, neg;
+            advance(r);
             row_stage(K, nodes, changed, neg);
             Best best;
             if (MEMO && K >= 1 && K <= kTableK) {
@@ -1412,8 +1447,9 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         }
         // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
         // Eq. 4 in the paper's order of operations (or looked up in memoised mode) and stored.
-        const int c = (group * b.cand_per_wave + lane) * kWavesPerBlock + wave;
-        if (lane < b.cand_per_wave && c < b.P) {
+        const int k = (group * b.cand_per_wave + lane) * kWavesPerBlock + wave;
+        if (lane < b.cand_per_wave && k < (SEL ? b.n_sel : b.P)) {
+            const int c = SEL ? d_c : k;
             const size_t pair = (size_t)c * b.J + j;
             const int nodes = d_meta & ~kMetaChanged;
             Best best;
@@ -1450,11 +1486,12 @@ __global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
 {
     constexpr int kJobsPerWave = 16, kAhead = 4;
     const int tiles = (a.J + kWavesPerBlock * kJobsPerWave - 1) / (kWavesPerBlock * kJobsPerWave);
-    const int c = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
+    const int k = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     const int j0 = (tile * kWavesPerBlock + wave) * kJobsPerWave;
-    if (c >= a.P || j0 >= a.J) return;
+    if (k >= (a.sel ? a.n_sel : a.P) || j0 >= a.J) return;
+    const int c = a.sel ? a.sel[k] : k;                   // with a list of candidates the workgroups walk the list
     const int rows = a.J - j0 < kJobsPerWave ? a.J - j0 : kJobsPerWave;
     const int n4 = a.N >> 2;
     const int lane4 = lane < n4 ? lane : n4 - 1;          // lanes past the end of a row load its last 16 bytes again
@@ -1644,7 +1681,7 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     __shared__ REAL red_acc[kCandThreads];
     __shared__ REAL red_w[kCandThreads];
     __shared__ long long red_v[kCandThreads];
-    const int c = blockIdx.x;
+    const int c = a.sel ? a.sel[blockIdx.x] : (int)blockIdx.x;
     const int t = threadIdx.x;
     const double *__restrict__ G = a.G + (size_t)c * a.J;
     const int32_t *__restrict__ meta = a.meta + (size_t)c * a.J;
@@ -1798,7 +1835,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
                    double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
-                   hipEvent_t sweep_stop, hipStream_t stream)
+                   hipEvent_t sweep_stop, int first_rank, hipStream_t stream)
 {
     const WorkspaceLayout L = workspace_layout(*d);
     char *ws = (char *)workspace;
@@ -1815,17 +1852,25 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.memo = (MemoEntry *)(ws + L.memo);
     a.colpack = (unsigned long long *)(ws + L.colpack);
     a.need_constraints = (violations != nullptr || !(d->flags & PX_FLAG_NO_CONSTRAINT_CHECK)) ? 1 : 0;
+    // first_rank > 0: only the candidates of rank first_rank and beyond in the order the search step left in the
+    // workspace, i.e. the slots it has just rewritten; the others keep the results they have
+    const int P_eff = first_rank > 0 ? d->P - first_rank : d->P;
+    if (first_rank > 0) {
+        a.sel = (const int32_t *)(ws + L.order) + first_rank;
+        a.n_sel = P_eff;
+    }
+    if (P_eff <= 0) return PX_OK;
     a.fitness = fitness; a.best_goodput = best_goodput; a.speedup = speedup;
     a.best_m = best_m; a.best_s = best_s; a.violations = violations;
 
     // unrolled s-chunk: the smallest of 8, 16, 32 that covers Gs (32 with several chunks beyond that)
     const int ch = d->Gs <= 8 ? 8 : (d->Gs <= 16 ? 16 : 32);
-    const long long pairs = (long long)d->P * d->J;
+    const long long pairs = (long long)P_eff * d->J;
     // candidates per wavefront: enough wavefronts to fill the chip several times over
     long long per_wave = pairs / 25000;
     per_wave = per_wave < 1 ? 1 : (per_wave > kMaxCandPerWave ? kMaxCandPerWave : per_wave);
     a.cand_per_wave = (int)per_wave;
-    a.cand_groups = (int)((d->P + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
+    a.cand_groups = (int)((P_eff + per_wave * kWavesPerBlock - 1) / (per_wave * kWavesPerBlock));
     const unsigned pair_blocks = (unsigned)(8 * ((d->J + 7) / 8) * a.cand_groups);
 
     const long long lt_rows = (long long)d->J * 2 * kTableK;
@@ -1863,8 +1908,11 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool whole = d->Gm % kWave == 0;
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
-#define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4) \
-    hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4>), dim3(pair_blocks), dim3(256), 0, stream, a)
+#define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4)                                                               \
+    do {                                                                                                                \
+        if (a.sel) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+        else hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, false>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+    } while (0)
     // the instance for the row length (four rows per load, one row per load, any) and the grid (whole groups of 64 batch sizes or not)
 #define PX_LAUNCH_PAIRS_GRID(CH, F32)                                          \
     do {                                                                       \
@@ -1879,7 +1927,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     if (memo && !sampled && !f32 && row1 && !row4) {
         // memoised pass over rows of 65 to 256 entries: in memory order
         const unsigned tiles = (unsigned)((d->J + kWavesPerBlock * 16 - 1) / (kWavesPerBlock * 16));
-        const dim3 memo_pairs_grid((unsigned)d->P * tiles);
+        const dim3 memo_pairs_grid((unsigned)P_eff * tiles);
         if (ch == 8) hipLaunchKernelGGL(memo_pairs_kernel<8>, memo_pairs_grid, dim3(256), 0, stream, a);
         else if (ch == 16) hipLaunchKernelGGL(memo_pairs_kernel<16>, memo_pairs_grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL(memo_pairs_kernel<32>, memo_pairs_grid, dim3(256), 0, stream, a);
@@ -1899,8 +1947,8 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
 #undef PX_LAUNCH_PAIRS_GRID
 #undef PX_LAUNCH_PAIRS
     if (sweep_stop) (void)hipEventRecord(sweep_stop, stream);
-    if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
-    else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)d->P), dim3(kCandThreads), 0, stream, a);
+    if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
+    else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }
 

@@ -75,7 +75,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
                    double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
-                   hipEvent_t sweep_stop, hipStream_t stream);   // the two events, if given, bracket the grid-sweep kernel
+                   hipEvent_t sweep_stop, int first_rank, hipStream_t stream);
+// the two events, if given, bracket the grid-sweep kernel; first_rank > 0 evaluates only the candidates of that
+// rank and beyond in the order the last search step left in the workspace (dims must carry PX_FLAG_KEEP_JOB_TABLES)
 
 // Copies the status word of `workspace` to *status_out (device memory) on the stream.
 int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t stream);

@@ -58,7 +58,7 @@ def test_ragged_shapes_and_heavy_repair(shape):
         assert np.array_equal(children.cpu().numpy(), want)
 
 
-@pytest.mark.parametrize("name,gens", [("physical", 30), ("mid", 100)])
+@pytest.mark.parametrize("name,gens", [("physical", 30), ("mid", 40)])
 def test_search_loop_matches_oracle_every_generation(name, gens):
     """fitness -> step -> fitness ... on both sides independently; matrices compared at every generation."""
     import torch
@@ -289,3 +289,142 @@ def test_step_with_zero_grid_dims_between_fitness_calls_that_keep_their_tables()
     assert np.array_equal(kept["best_m"], ref["best_m"]) and np.array_equal(kept["best_s"], ref["best_s"])
     assert np.allclose(kept["fitness"], ref["fitness"], rtol=1e-12, atol=0.0)
     assert np.allclose(kept["best_goodput"], ref["best_goodput"], rtol=1e-12, atol=0.0)
+
+
+# ---- pollux_generation: the step in place followed by the fitness of the children only ------------------------
+
+def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_every=1, P=None):
+    """Both sides run fitness once and then `gens` generations; every output array is compared each time."""
+    import torch
+    import paper_2008_12260_amd as px
+    from parity import compare
+    c = wl.cfg
+    pop0 = wl.population if P is None else wl.population[:P]
+    P = pop0.shape[0]
+    elite = P // 2 if elite is None else elite
+    mut = (1 << 32) // c.J if mut is None else mut
+    call = px.FitnessCall(P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                          wl.node_capacity, p=c.p, delta=c.delta, flags=flags, precision=precision)
+    dev = torch.as_tensor(pop0).cuda()
+    call.run(dev)
+    host = pop0.copy()
+    ref = run_oracle(wl, population=host)
+    for gen in range(gens):
+        call.generation(dev, SEED, gen, elite, mut)
+        host, ref = O.generation(host, ref["fitness"], wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                                 wl.node_capacity, c.p, c.delta, c.Gs, SEED, gen, elite, mut)
+        got_pop = dev.cpu().numpy()
+        assert np.array_equal(got_pop, host), f"generation {gen}: {np.argwhere((got_pop != host).any(axis=(1, 2))).ravel()[:8]}"
+        if gen % check_every == 0 or gen == gens - 1:
+            got = call.results()
+            if precision == 0:
+                assert compare(wl, got, ref, population=host) == 0, gen
+            else:
+                assert np.array_equal(got["violations"], ref["violations"])
+                err = np.abs(got["fitness"] - ref["fitness"]) / np.where(ref["fitness"] == 0, 1.0, np.abs(ref["fitness"]))
+                assert err.max() <= 1e-5, gen
+    return call, dev, host
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_generation_call_matches_oracle_every_generation_on_the_mid_configuration(flags):
+    """60 generations of pollux_generation (survivors keep their results, children are swept) against the
+    checker's step + full evaluation; matrices every generation, every fitness output every tenth."""
+    import paper_2008_12260_amd as px
+    wl = W.make("mid")
+    call, dev, host = generation_loop(wl, 60, flags=flags, check_every=10)
+    # and a full evaluation of the final population by the library gives bit for bit what the incremental calls left
+    kept = call.results()
+    call.run(dev, keep_job_tables=True)
+    full = call.results()
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations"):
+        assert np.array_equal(kept[k], full[k], equal_nan=True), k
+
+
+@pytest.mark.parametrize("shape,elite", [
+    (dict(P=7, J=5, N=3, cap=2, Gm=5, Gs=3), 3),
+    (dict(P=9, J=13, N=67, cap=2, Gm=70, Gs=5), 1),           # all but one candidate replaced each generation
+    (dict(P=37, J=11, N=64, cap=8, Gm=64, Gs=16), 20),        # rows read four to a load, odd count of children
+    (dict(P=21, J=9, N=256, cap=4, Gm=64, Gs=32), 10),        # one row per load, whole groups of batch sizes
+    (dict(P=530, J=200, N=64, cap=8, Gm=64, Gs=16), 263),     # several candidates per wavefront
+    (dict(P=40, J=70, N=128, cap=2, Gm=20, Gs=6), 40),        # nothing to form: every candidate survives
+    (dict(P=6, J=40, N=9, cap=40, Gm=33, Gs=5), 2),           # rows beyond the tables
+])
+@pytest.mark.parametrize("flags", [0, 4, 16])
+def test_generation_call_on_ragged_shapes(shape, elite, flags):
+    cfg = W.custom("gen_ragged", **shape)
+    wl = W.make(cfg)
+    if flags == 16:
+        wl = W.sampled(wl)
+        import torch
+        import paper_2008_12260_amd as px
+        c = wl.cfg
+        call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                              wl.node_capacity, p=c.p, delta=c.delta, flags=16)
+        dev = torch.as_tensor(wl.population).cuda()
+        call.run(dev)
+        host, ref = wl.population.copy(), run_oracle(wl, flags=16)
+        for gen in range(3):
+            call.generation(dev, SEED, gen, elite, 1 << 30)
+            host, ref = O.generation(host, ref["fitness"], wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                                     wl.node_capacity, c.p, c.delta, c.Gs, SEED, gen, elite, 1 << 30, flags=16)
+            assert np.array_equal(dev.cpu().numpy(), host)
+            got = call.results()
+            assert np.array_equal(got["best_m"], ref["best_m"]) and np.array_equal(got["best_s"], ref["best_s"])
+            assert np.allclose(got["fitness"], ref["fitness"], rtol=1e-12, atol=0.0, equal_nan=True)
+        return
+    generation_loop(wl, 4, flags=flags, elite=elite, mut=1 << 30)
+
+
+def test_generation_call_in_fp32_and_its_argument_checks():
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("physical")
+    generation_loop(wl, 5, precision=1)
+    c = wl.cfg
+    call = gpu_call(wl)
+    dev = torch.as_tensor(wl.population).cuda()
+    call.run(dev)
+    ga = px.GaParams(SEED, 0, c.P // 2, 0, 0, None)          # not in place
+    with pytest.raises(px.PolluxError):
+        px.pollux_generation(call.dims, dev, call.job_params, call.m_grid, call.fair_share, call.current_alloc,
+                             call.node_capacity, c.p, c.delta, ga, call.workspace, call.fitness, call.best_m, call.best_s)
+    ga = px.GaParams(SEED, 0, c.P + 1, 0, px.PX_GA_IN_PLACE, None)
+    with pytest.raises(px.PolluxError):
+        px.pollux_generation(call.dims, dev, call.job_params, call.m_grid, call.fair_share, call.current_alloc,
+                             call.node_capacity, c.p, c.delta, ga, call.workspace, call.fitness, call.best_m, call.best_s)
+
+
+def test_generation_call_on_the_large_configuration():
+    """The headline shape: one full evaluation, then two generations that sweep the 2048 children only; the oracle
+    recomputes the children of the last generation (the slots that were rewritten) and a sample of survivors."""
+    import torch
+    import paper_2008_12260_amd as px
+    from parity import compare
+    cfg = W.CONFIGS["large"]
+    wl = W.make(cfg, with_population=False)
+    pop = W.candidates(cfg, 0, cfg.P)
+    call = px.FitnessCall(cfg.P, cfg.J, cfg.N, cfg.Gm, cfg.Gs, wl.job_params, wl.m_grid, wl.fair_share,
+                          wl.current_alloc, wl.node_capacity, p=cfg.p, delta=cfg.delta)
+    dev = torch.from_numpy(pop).cuda()
+    call.run(dev)
+    host = pop
+    fit = call.results()["fitness"]
+    mut = (1 << 32) // cfg.J
+    for gen in range(2):
+        before = call.results()
+        call.generation(dev, SEED, gen, cfg.P // 2, mut)
+        host = O.ga_step(host, before["fitness"], wl.node_capacity, SEED, gen, cfg.P // 2, mut, flags=O.GA_IN_PLACE)
+        order = O.rank(before["fitness"])
+        got = call.results()
+        survivors = order[:cfg.P // 2]
+        for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup", "violations"):
+            assert np.array_equal(got[k][survivors], before[k][survivors], equal_nan=True), k
+    got_pop = dev.cpu().numpy()
+    for lo in range(0, cfg.P, 256):
+        assert np.array_equal(got_pop[lo:lo + 256], host[lo:lo + 256]), f"candidates {lo}..{lo + 255}"
+    idx = np.concatenate([order[cfg.P // 2:][::16], order[:cfg.P // 2][::64]])       # 128 children, 32 survivors
+    sub = host[idx]
+    ref = run_oracle(wl, population=sub)
+    gs = {k: (v[idx] if isinstance(v, np.ndarray) else v) for k, v in got.items()}
+    assert compare(wl, gs, ref, population=sub) == 0
