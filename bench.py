@@ -25,16 +25,55 @@ if ROOT not in sys.path:
 
 FP64_VECTOR_PEAK_TFLOPS = 78.6      # 256 CUs x 4 SIMDs x 16 lanes x 2 (FMA) x 2.4 GHz
 FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 divisions, each counted as one
-# HBM bytes one launch of the sweep kernel moves on the "large" workload: rocprofv3 FETCH_SIZE (2 068 970 KiB,
-# scaled by 2.0) + WRITE_SIZE (698 395 KiB, scaled by 1.0), the factors taken from a device-to-device copy of known
-# size in the same runs (profiles/pairs_kernel_large.md).  Valid for the kernel those counters were taken on.
-SWEEP_HBM_BYTES = {"large": 2068970 * 1024 * 2.0 + 698395 * 1024 * 1.0}
-# fp64 operations the same kernel executes per launch on "large", from the instruction counters of the same
-# profile: 64 lanes x (ADD_F64 + MUL_F64 + 2 x FMA_F64 wave-instructions)
-SWEEP_EXECUTED_FLOPS = {"large": 64 * (8.7697e6 + 4.9547e7 + 2 * 2.99136e8)}
+# Counter figures of the sweep kernel on the "large" workload, from rocprofv3 runs of this file (summaries and commands
+# under profiles/).  They describe the kernel they were taken on: `source_sha256` is the digest of the library's
+# sources at that time (kernel_source_digest()), and the bench line reports them only while the digest still matches;
+# after any change to the sources they are reported as null until the counters are taken again.
+#   traffic_bytes   HBM bytes per launch: FETCH_SIZE and WRITE_SIZE, each scaled by what the same counter reads for a
+#                   device-to-device copy of known size in the same run
+#   fp64_flops      64 lanes x (ADD_F64 + MUL_F64 + 2 x FMA_F64 wave-instructions) per launch
+#   valu_insts      vector instructions per launch; scan_insts = those of the scan itself (2.25 per grid point)
+#   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
+PROFILED = {
+    "large": None,
+}
 GA_SEED = 0x2008_1226_5EED_0001
 def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
     return (1 << 32) // J
+
+
+def kernel_source_digest():
+    """sha256 over the library's sources and its build script (what the compiled kernels are a function of)."""
+    import hashlib
+    h = hashlib.sha256()
+    base = os.path.join(ROOT, "paper_2008_12260_amd")
+    files = sorted(os.path.join("csrc", f) for f in os.listdir(os.path.join(base, "csrc"))) + ["build.py"]
+    for f in files + [os.path.join("..", "include", "pollux.h")]:
+        h.update(f.encode())
+        h.update(open(os.path.join(base, f), "rb").read())
+    return h.hexdigest()
+
+
+def host_description():
+    model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"cpu_model": model, "nproc": os.cpu_count(), "affinity_cpus": len(os.sched_getaffinity(0))}
+
+
+def compiler_version():
+    import subprocess
+    try:
+        out = subprocess.run([os.environ.get("HIPCC", "/opt/rocm/bin/hipcc"), "--version"], capture_output=True, text=True,
+                             timeout=60).stdout.splitlines()
+        return "; ".join(out[:2])
+    except Exception:
+        return None
 
 
 def cpu_baseline(wl, cfg, target_seconds=30.0):
@@ -62,7 +101,7 @@ def cpu_baseline(wl, cfg, target_seconds=30.0):
         "value": evals / t, "unit": "evals/s", "cores": O.threads(), "kind": "oracle",
         "sample": f"candidates 0..{count - 1} of {cfg.P} (all {cfg.J} jobs, full {cfg.Gm}x{cfg.Gs} grid), "
                   f"fitness + one search step, {t:.2f} s",
-        "seconds": t, "affinity_cpus": len(os.sched_getaffinity(0)),
+        "seconds": t, **host_description(),
         "full_population_seconds_extrapolated": t * cfg.P / count,
     }
 
@@ -235,21 +274,28 @@ def main():
             extra[label + "_children_only_generations_per_s"] = 100.0 / (time.perf_counter() - tg0)
             extra[label + "_children_only_best_fitness"] = float(mcall.fitness.max().item())
 
-        # one fitness call on the mid configuration in fp64 and in fp32 arithmetic (launch overhead included)
+        # one fitness call on the mid configuration at three values of the fairness knob, in fp64 and in fp32
+        # arithmetic (launch overhead included: five to six small kernels per call)
         ma = torch.from_numpy(mwl.population).to(dev)
-        for label, precision in (("mid_fitness_call_fp64_ms", 0), ("mid_fitness_call_fp32_ms", 1)):
-            mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid,
-                                   mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta,
-                                   precision=precision, device=dev)
-            for _ in range(3):
-                mcall.run(ma, stream=stream, outputs="fitness")
-            f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            f0.record(stream)
-            for _ in range(20):
-                mcall.run(ma, stream=stream, outputs="fitness")
-            f1.record(stream)
-            torch.cuda.synchronize()
-            extra[label] = f0.elapsed_time(f1) / 20
+        matrix = {}
+        for pname, precision in (("fp64", 0), ("fp32", 1)):
+            for knob in (-1.0, 0.5, 1.0):
+                mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid,
+                                       mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=knob, delta=mcfg.delta,
+                                       precision=precision, device=dev)
+                for _ in range(3):
+                    mcall.run(ma, stream=stream, outputs="fitness")
+                f0, f1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                f0.record(stream)
+                for _ in range(20):
+                    mcall.run(ma, stream=stream, outputs="fitness")
+                f1.record(stream)
+                torch.cuda.synchronize()
+                matrix[f"{pname}_p={knob:g}"] = f0.elapsed_time(f1) / 20
+        extra["mid_fitness_call_ms"] = matrix
+        extra["mid_fitness_call_fp64_ms"] = matrix["fp64_p=-1"]
+        extra["mid_fitness_call_fp32_ms"] = matrix["fp32_p=-1"]
+        extra["mid_fitness_call_evals_per_s"] = {k: mcfg.evals_per_call / (v * 1e-3) for k, v in matrix.items()}
 
     # the step before the path: theta_sys of all jobs of the workload fitted to synthetic records (Sec. 4.1)
     records = W.observations(cfg, max_obs=48)
@@ -283,6 +329,23 @@ def main():
         extra["closed_loop_mid_ms_per_interval"] = (time.perf_counter() - tl0) * 1e3 / 5
         extra["closed_loop_mid_best_fitness"] = lstate.history[-1]["best_fitness"]
 
+    prof = PROFILED.get(cfg.name)
+    if prof is not None and prof.get("source_sha256") != kernel_source_digest():
+        prof = None                  # the kernels have changed since the counters were taken
+    roofline = {
+        "bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
+        "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": prof["traffic_bytes"] if prof else None,
+        "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL, "avg_launch_ms": sweep_avg_ms,
+        "note": "frac counts the 7 fp64 operations Eq. 4 asks for per grid point; the kernel executes one "
+                "multiply-add and 1.25 other vector instructions per point, see executed_flop_frac and valu_issue_frac",
+        # from the instruction counters: fp64 operations executed, as a fraction of the peak
+        "executed_flop_frac": (prof["fp64_flops"] / (sweep_avg_ms * 1e-3) / 1e12 / FP64_VECTOR_PEAK_TFLOPS) if prof else None,
+        # share of the vector-ALU issue slots of the launch that the scan itself uses: (scan instructions / all vector
+        # instructions) x the fraction of cycles the vector ALUs were busy
+        "valu_issue_frac": (prof["scan_insts"] / prof["valu_insts"] * prof["valu_busy"]) if prof else None,
+    }
+    extra["compiler"] = compiler_version()
+    extra["kernel_source_sha256"] = kernel_source_digest()
     out = {
         "metric": "(m,s) goodput evals/sec + GA generations/sec; % of FP64 VALU peak",
         "value": evals_per_step * args.steps / elapsed,
@@ -295,12 +358,7 @@ def main():
                                f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step (in place) per step",
                    "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed,
                    "generations_per_s_children_only": args.steps / incremental_s},
-        "roofline": {"bound": "alu", "achieved": achieved_tflops, "peak": FP64_VECTOR_PEAK_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved_tflops / FP64_VECTOR_PEAK_TFLOPS, "traffic": SWEEP_HBM_BYTES.get(cfg.name),
-                     "kernel": "px::pairs_kernel", "flops_per_eval": FLOPS_PER_EVAL,
-                     "avg_launch_ms": sweep_avg_ms,
-                     "executed_flop_frac": (SWEEP_EXECUTED_FLOPS[cfg.name] / (sweep_avg_ms * 1e-3) / 1e12 /
-                                            FP64_VECTOR_PEAK_TFLOPS) if cfg.name in SWEEP_EXECUTED_FLOPS else None},
+        "roofline": roofline,
         "extra": extra,
     }
     if not args.no_cpu_baseline:

@@ -338,12 +338,16 @@ int pollux_generation(const pollux_dims *dims,           /* host */
  * none with more than two GPUs, and all four sync parameters while it has none with more
  * than one GPU.
  * The minimiser is a box-constrained damped Gauss-Newton iteration, at most max_iter steps
- * (accepted or rejected) per starting point, one wavefront per job.  It starts from
+ * (accepted or rejected) per starting point, one wavefront per job and starting point.  It starts from
  * theta_init[.,j] when theta_init is given, else from T_min = min_o T_o/(s_o+1) (first record on
  * ties): alpha_grad = T_min/2, beta_grad = T_min/(2 m at that record), alpha_sync = T_min/10,
  * beta_sync = T_min/100, gamma = 2.  The error has several local minima; with n_starts > 1 (at
- * most 5) the iteration is repeated from that start with the four sync parameters scaled by 3,
- * 0.3, 0.3, 3 and gamma set to 1.2, 5, 1.2, 5, and the best end point is kept (the earliest on ties).
+ * most 5) further starts are tried and the best end point is kept (the earliest on ties): starts 2
+ * and 3 first minimise with gamma held at 1 (where Eq. 11 is linear in the alphas and betas) and then
+ * release gamma from 2 and from 5; starts 4 and 5 scale the four sync parameters by 3 and 0.3 and
+ * begin at gamma = 1.2 and 5.  In every start, a sync pair (alpha, beta) that ends at zero, where the
+ * error does not depend on it when gamma > 1, is put back to T_min/10 once and the iteration continued;
+ * the better of the two end points is kept.
  * theta[i*J + j] is parameter i of job j in the order PX_ALPHA_G .. PX_GAMMA, i.e. the first
  * seven rows of job_params; rmsle[j] is the error reached; iterations[j] the steps taken over
  * all starting points.

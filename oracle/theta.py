@@ -20,13 +20,18 @@ Readings
     job on one node has no evidence about the node pair, and plenty about the local one), so it is read as
     alpha_sync^node = beta_sync^node = 0.  With at most one GPU ever used nothing is known about either pair
     and all four are 0.  A parameter a prior fixes stays at 0 through the fit.
-  * Start.  The paper gives no starting point.  From T_min = the smallest recorded T_iter / (s + 1):
-    alpha_grad = T_min / 2, beta_grad = T_min / (2 m at that record), alpha_sync = T_min / 10,
-    beta_sync = T_min / 100, gamma = 2.  Sync parameters must start above 0: at T_sync = 0 and gamma > 1 the
-    derivative of Eq. 10 with respect to T_sync vanishes and a descent method never leaves 0.
-  * Local minima.  The error is not convex; which minimum a local method ends in depends on the method.  The
-    checks against the GPU library therefore pin the objective, the constraints and stationarity exactly and
-    compare the attained minimum statistically ("parity partial" for the choice among local minima).
+  * Start.  The paper gives no starting point, and the error has several local minima, so the checker has a
+    start policy of its own (the GPU library has another; neither is the paper's).  Two base points:
+    "tmin", from T_min = the smallest recorded T_iter / (s + 1): alpha_grad = T_min / 2, beta_grad =
+    T_min / (2 m at that record), alpha_sync = T_min / 10, beta_sync = T_min / 100; and "linear", the
+    non-negative least-squares solution of the model at gamma = 1, where Eq. 11 is linear in the six alphas and
+    betas (relative residuals; scipy's nnls), with every free sync parameter raised to at least T_min / 100.
+    STARTS lists (base, factor on the four sync parameters, gamma) combinations; fit(n_starts = n) runs L-BFGS-B
+    from the first n and keeps the best end point.  Sync parameters must start above 0: at T_sync = 0 and gamma > 1
+    the derivative of Eq. 10 with respect to T_sync vanishes and a descent method never leaves 0.
+  * Local minima.  Which minimum a local method ends in depends on the method and the start.  The checks
+    against the GPU library therefore pin the objective, the constraints and stationarity exactly and compare the
+    attained minimum statistically ("parity partial" for the choice among local minima).
   * Scale.  The unknowns differ by four orders of magnitude (beta_grad ~ 1e-4 s/example, gamma ~ 2), so the
     minimiser works on theta / start (gamma unscaled); the minimum is the same.
 """
@@ -118,6 +123,7 @@ def prior_fixed(K, nodes):
 
 
 def start_point(K, nodes, m, s, T):
+    """The "tmin" base point (see Readings)."""
     m, s, T = (np.asarray(x, np.float64) for x in (m, s, T))
     per_pass = T / (s + 1.0)
     o = int(np.argmin(per_pass))                    # first record attaining the minimum
@@ -127,24 +133,54 @@ def start_point(K, nodes, m, s, T):
     return theta
 
 
-START_VARIANTS = ((1.0, None), (3.0, 1.2), (0.3, 5.0), (0.3, 1.2), (3.0, 5.0))   # (sync parameters x, gamma)
+def linear_start(K, nodes, m, s, T):
+    """The "linear" base point: at gamma = 1 Eq. 10 is T_grad + T_sync, so Eq. 11 is linear in the alphas and betas;
+    their non-negative least-squares fit to the records (relative residuals), gamma = 2 as a placeholder."""
+    from scipy.optimize import nnls
+    K, nodes, m, s, T = (np.asarray(x, np.float64) for x in (K, nodes, m, s, T))
+    one_gpu = K <= 1
+    local = ((~one_gpu) & (nodes == 1)).astype(np.float64)
+    node = ((~one_gpu) & (nodes != 1)).astype(np.float64)
+    A = np.stack([s + 1.0, (s + 1.0) * m, local, local * (K - 2), node, node * (K - 2)], axis=1) / T[:, None]
+    fixed = prior_fixed(K, nodes)
+    free = np.flatnonzero(~fixed[:6])
+    col = np.maximum(np.linalg.norm(A[:, free], axis=0), 1e-300)          # columns differ by orders of magnitude
+    x, _ = nnls(A[:, free] / col, np.ones(T.size))
+    theta = np.zeros(NTHETA)
+    theta[free] = x / col
+    t_min = float(np.min(T / (s + 1.0)))
+    for i in (ALPHA_SL, BETA_SL, ALPHA_SN, BETA_SN):
+        if not fixed[i]:
+            theta[i] = max(theta[i], t_min / 100)
+    if theta[ALPHA_G] + theta[BETA_G] <= 0.0:
+        theta[ALPHA_G] = t_min / 2
+    theta[GAMMA] = 2.0
+    return theta
+
+
+# (base point, factor on the four sync parameters, gamma) of the starts, in the order they are tried
+STARTS = (("tmin", 1.0, 2.0), ("linear", 1.0, 2.0), ("linear", 1.0, 5.0), ("tmin", 4.0, 1.3), ("tmin", 0.25, 4.0),
+          ("linear", 3.0, 1.3), ("tmin", 0.25, 1.3))
 
 
 def fit(K, nodes, m, s, T, start=None, max_iter=2000, n_starts=1):
     """Sec. 4.1: minimise the RMSLE with L-BFGS-B under the box constraints and the priors.
 
-    The error has several local minima; with n_starts > 1 the minimiser is also run from the start with the
-    sync parameters scaled and gamma reset (START_VARIANTS) and the best end point is kept, the earliest on ties.
-    Returns (theta, rmsle, scipy's result object)."""
+    With `start` given, one run from there.  Otherwise the first n_starts entries of STARTS are tried and the best
+    end point is kept, the earliest on ties.  Returns (theta, rmsle, scipy's result object)."""
     K, nodes, m, s, T = (np.asarray(x) for x in (K, nodes, m, s, T))
-    base = start_point(K, nodes, m, s, T) if start is None else np.asarray(start, np.float64).copy()
+    if start is not None:
+        x = np.asarray(start, np.float64).copy()
+        return _fit_from(K, nodes, m, s, T, x, x.copy(), max_iter)
+    bases = {"tmin": start_point(K, nodes, m, s, T)}
     best = None
-    for factor, gamma0 in START_VARIANTS[:n_starts]:
-        x = base.copy()
+    for base_name, factor, gamma0 in STARTS[:n_starts]:
+        if base_name not in bases:
+            bases[base_name] = linear_start(K, nodes, m, s, T)
+        x = bases[base_name].copy()
         x[ALPHA_SL:BETA_SN + 1] *= factor
-        if gamma0 is not None:
-            x[GAMMA] = gamma0
-        out = _fit_from(K, nodes, m, s, T, x, base, max_iter)
+        x[GAMMA] = gamma0
+        out = _fit_from(K, nodes, m, s, T, x, bases[base_name], max_iter)
         if best is None or out[1] < best[1]:
             best = out
     return best

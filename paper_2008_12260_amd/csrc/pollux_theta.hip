@@ -260,71 +260,114 @@ __global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
 
     // The error has several local minima (and a flat spot at T_sync = 0 when gamma > 1), so the iteration is
     // run from a few starting points, one per wavefront, and the best end point is kept (the first one on
-    // ties): the start itself, then the sync parameters scaled by 3 or 0.3 with gamma = 1.2 or 5.
+    // ties).  Start 0 is the start itself.  Starts 1 and 2 first minimise with gamma held at 1, where
+    // Eq. 11 is linear in the alphas and betas, then release gamma from 2 and from 5 with the sync
+    // parameters raised to at least a tenth of their starting values.  Starts 3 and 4 scale the sync
+    // parameters by 3 and 0.3 and begin at gamma = 1.2 and 5.
     {
-        const double sync_factor = (k == 0) ? 1.0 : ((k == 1 || k == 4) ? 3.0 : 0.3);
-        const double gamma0 = (k == 0) ? start[PX_GAMMA] : ((k & 1) ? 1.2 : 5.0);
+        const bool two_phase = k == 1 || k == 2;
+        const double sync_factor = (k == 3) ? 3.0 : (k == 4 ? 0.3 : 1.0);
+        const double gamma0 = (k == 0) ? start[PX_GAMMA] : (k == 1 ? 2.0 : (k == 3 ? 1.2 : 5.0));
+        // the default starting values of the sync parameters, in the units of z (used where one has to leave zero)
+        const double sync_a = (t_min / 10.0), sync_b = (t_min / 100.0);
         double z[kTheta];
 #pragma unroll
         for (int i = 0; i < kTheta; ++i) {
             double v = start[i];
             if (i >= PX_ALPHA_SL && i <= PX_BETA_SN) v *= sync_factor;
-            if (i == PX_GAMMA) v = gamma0;
+            if (i == PX_GAMMA) v = two_phase ? 1.0 : gamma0;
             v /= scale[i];
             z[i] = v < lo[i] ? lo[i] : (v > hi[i] ? hi[i] : v);
         }
 
-        Normal cur = normal_equations(f, j, n, z, scale);
-        double lambda = 1e-3;
+        Normal cur;
         int it = 0;
-        while (it < f.max_iter && cur.sse > 0.0) {
-            ++it;
-            unsigned held = prior;
-#pragma unroll
-            for (int i = 0; i < kTheta; ++i) {
-                if ((z[i] <= lo[i] && cur.g[i] > 0.0) || (z[i] >= hi[i] && cur.g[i] < 0.0)) held |= 1u << i;
-            }
-            // a free variable that sits on a bound and would be pushed across it joins the held set
-            double step[kTheta];
-            bool solved = false;
-            for (int pass = 0; pass < kTheta + 1; ++pass) {
-                solved = damped_step(cur, lambda, held, step);
-                if (!solved) break;
-                unsigned more = 0u;
+        // The damped Gauss-Newton iteration from z, until it converges or the budget of steps is spent;
+        // the variables in `hold` stay where they are.  Leaves the end point in z and its sums in cur.
+        auto descend = [&](unsigned hold) {
+            cur = normal_equations(f, j, n, z, scale);
+            double lambda = 1e-3;
+            while (it < f.max_iter && cur.sse > 0.0) {
+                ++it;
+                unsigned held = hold;
 #pragma unroll
                 for (int i = 0; i < kTheta; ++i) {
-                    if (!((held >> i) & 1u) && ((z[i] <= lo[i] && step[i] < 0.0) || (z[i] >= hi[i] && step[i] > 0.0))) more |= 1u << i;
+                    if ((z[i] <= lo[i] && cur.g[i] > 0.0) || (z[i] >= hi[i] && cur.g[i] < 0.0)) held |= 1u << i;
                 }
-                if (!more) break;
-                held |= more;
-            }
-            if (!solved) {
-                lambda *= 10.0;
-                if (lambda > 1e15) break;
-                continue;
-            }
-            double zn[kTheta];
-            double moved = 0.0;
+                // a free variable that sits on a bound and would be pushed across it joins the held set
+                double step[kTheta];
+                bool solved = false;
+                for (int pass = 0; pass < kTheta + 1; ++pass) {
+                    solved = damped_step(cur, lambda, held, step);
+                    if (!solved) break;
+                    unsigned more = 0u;
 #pragma unroll
-            for (int i = 0; i < kTheta; ++i) {
-                double v = ((held >> i) & 1u) ? z[i] : z[i] + step[i];
-                v = v < lo[i] ? lo[i] : (v > hi[i] ? hi[i] : v);
-                zn[i] = v;
-                const double rel = fabs(v - z[i]) / (fabs(z[i]) + 1e-12);
-                moved = rel > moved ? rel : moved;
-            }
-            if (moved == 0.0) break;
-            const Normal trial = normal_equations(f, j, n, zn, scale);
-            if (trial.sse < cur.sse) {
-                const double gain = (cur.sse - trial.sse) / cur.sse;
+                    for (int i = 0; i < kTheta; ++i) {
+                        if (!((held >> i) & 1u) && ((z[i] <= lo[i] && step[i] < 0.0) || (z[i] >= hi[i] && step[i] > 0.0))) more |= 1u << i;
+                    }
+                    if (!more) break;
+                    held |= more;
+                }
+                if (!solved) {
+                    lambda *= 10.0;
+                    if (lambda > 1e15) break;
+                    continue;
+                }
+                double zn[kTheta];
+                double moved = 0.0;
 #pragma unroll
-                for (int i = 0; i < kTheta; ++i) z[i] = zn[i];
-                cur = trial;
-                lambda = lambda * 0.2 > 1e-15 ? lambda * 0.2 : 1e-15;
-                if (gain < 1e-13 && moved < 1e-9) break;
-            } else {
-                lambda *= 5.0;
-                if (lambda > 1e15 || moved < 1e-15) break;
+                for (int i = 0; i < kTheta; ++i) {
+                    double v = ((held >> i) & 1u) ? z[i] : z[i] + step[i];
+                    v = v < lo[i] ? lo[i] : (v > hi[i] ? hi[i] : v);
+                    zn[i] = v;
+                    const double rel = fabs(v - z[i]) / (fabs(z[i]) + 1e-12);
+                    moved = rel > moved ? rel : moved;
+                }
+                if (moved == 0.0) break;
+                const Normal trial = normal_equations(f, j, n, zn, scale);
+                if (trial.sse < cur.sse) {
+                    const double gain = (cur.sse - trial.sse) / cur.sse;
+#pragma unroll
+                    for (int i = 0; i < kTheta; ++i) z[i] = zn[i];
+                    cur = trial;
+                    lambda = lambda * 0.2 > 1e-15 ? lambda * 0.2 : 1e-15;
+                    if (gain < 1e-13 && moved < 1e-9) break;
+                } else {
+                    lambda *= 5.0;
+                    if (lambda > 1e15 || moved < 1e-15) break;
+                }
+            }
+        };
+
+        if (two_phase) {
+            descend(prior | (1u << PX_GAMMA));
+            z[PX_GAMMA] = gamma0;
+#pragma unroll
+            for (int i = PX_ALPHA_SL; i <= PX_BETA_SN; ++i) {
+                const double least = 0.1 * ((i == PX_ALPHA_SL || i == PX_ALPHA_SN) ? sync_a : sync_b) / scale[i];
+                if (!((prior >> i) & 1u) && z[i] < least) z[i] = least;
+            }
+        }
+        descend(prior);
+        // A sync pair that has ended at zero may only be stuck there: with T_sync = 0 and gamma > 1 the error
+        // does not feel the pair at all (the flat spot).  It is put back to its default starting value once, the
+        // others staying where they are, and the iteration is continued; the better end point is kept.
+#pragma unroll
+        for (int pair = 0; pair < 2; ++pair) {
+            const int ia = pair == 0 ? PX_ALPHA_SL : PX_ALPHA_SN, ib = ia + 1;
+            const bool stuck = !((prior >> ia) & 1u) && z[ia] == 0.0 && (((prior >> ib) & 1u) || z[ib] == 0.0);
+            if (stuck && it < f.max_iter && cur.sse > 0.0) {
+                double z_before[kTheta];
+#pragma unroll
+                for (int i = 0; i < kTheta; ++i) z_before[i] = z[i];
+                const double sse_before = cur.sse;
+                z[ia] = sync_a / scale[ia];
+                descend(prior);
+                if (!(cur.sse < sse_before)) {
+#pragma unroll
+                    for (int i = 0; i < kTheta; ++i) z[i] = z_before[i];
+                    cur.sse = sse_before;
+                }
             }
         }
         if (lane == 0) {

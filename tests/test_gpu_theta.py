@@ -7,8 +7,9 @@ are compared as follows:
   * bounds and exploration priors hold exactly;
   * the library's end point is a minimum for the checker too: L-BFGS-B started there gains less than 1e-6;
   * started from the checker's end point, the library never ends worse, and typically ends at the same error;
-  * over a workload, the library's error is within 0.1 % of the checker's, or lower, for at least 90 % of jobs;
-  * records generated from known parameters are reproduced to rounding.
+  * over a workload, the library's error is within 0.1 % of the best of the checker's seven starts (a start
+    policy of its own, see oracle/theta.py), or lower, for at least 97 % of jobs;
+  * records generated from known parameters are reproduced to rounding, every job.
 """
 import numpy as np
 import pytest
@@ -54,13 +55,15 @@ def test_fit_on_generated_records(name):
     close = 0
     for j in range(J):
         r = job_records(ob, j)
-        # the reported error is the checker's error function at the reported parameters
-        assert abs(TH.rmsle(theta[:, j], *r) - err[j]) <= 1e-12 * err[j]
+        # the reported error is the checker's error function at the reported parameters (a job with fewer records
+        # than parameters is fitted exactly: both errors are then rounding noise around 1e-16)
+        assert abs(TH.rmsle(theta[:, j], *r) - err[j]) <= 1e-12 * err[j] + 1e-14
         # priors
         assert np.all(theta[TH.prior_fixed(r[0], r[1]), j] == 0.0)
-        want = TH.fit(*r, n_starts=3)[1]
+        want = TH.fit(*r, n_starts=7)[1]
         close += err[j] <= want * 1.001 + 1e-12
-    assert close >= 0.9 * J, f"only {close} of {J} fits are as good as the checker's"
+    print(f"{name}: {close} of {J} fits within 0.1 % of the checker's best or lower")
+    assert close >= 0.97 * J, f"only {close} of {J} fits are as good as the checker's"
 
 
 def test_end_points_are_minima_for_the_checker_too():
@@ -99,7 +102,7 @@ def test_exact_records_are_reproduced():
     ob = pack(recs, 128)                                                    # more than one record per lane
     got = px.fit_theta(ob, max_iter=300, n_starts=3)
     good = got["rmsle"] < 1e-9
-    assert good.sum() >= 36, got["rmsle"]
+    assert good.all(), got["rmsle"]
     for j in np.flatnonzero(good):
         K, nodes, m, s, T = recs[j]
         assert np.max(np.abs(TH.t_iter(got["theta"][:, j], K, nodes, m, s)[0] / T - 1.0)) < 1e-7
@@ -154,7 +157,7 @@ def test_bounds_bind_where_the_unconstrained_fit_would_leave_the_box():
     ts = np.where(K > 1, 0.05 + 0.01 * (K - 2), 0.0)
     dear = s * tg + np.where(K > 1, 1.6 * (tg + ts), tg)
     ob = pack([(K, nodes, m, s, fast), (K, nodes, m, s, dear)], 64)
-    got = px.fit_theta(ob, max_iter=300, n_starts=3)
+    got = px.fit_theta(ob, max_iter=300, n_starts=5)       # the best corner of the first job is reached from the fifth start only
     th = got["theta"]
     assert np.all(th[:6] >= 0.0) and np.all(th[6] >= 1.0) and np.all(th[6] <= 10.0)
     assert th[6, 1] == 1.0                                              # gamma pressed against its lower bound
