@@ -361,9 +361,9 @@ typedef double Double2 __attribute__((ext_vector_type(2)));
 
 constexpr int kRun = 16;
 constexpr int runs_of(int CH) { return CH > kRun ? CH / kRun : 1; }
-// Chunks of 32 tag per group of four positions; the shorter ones tag every position (twelve instructions per
-// four points, and nothing left to find afterwards: quicker for few counts per batch size).
-constexpr bool grouped_tags(int CH) { return CH >= 32; }
+// Chunks of 16 and 32 tag per group of four positions; chunks of 8 tag every position (twelve instructions per
+// four points, and less to find afterwards: quicker for very few counts per batch size).
+constexpr bool grouped_tags(int CH) { return CH >= 16; }
 
 // The addends that are not inline constants (3, 5 .. 15) in vector registers.  Made once
 // per kernel through an opaque statement, so that they stay in registers instead of being formed
@@ -583,36 +583,45 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                     g_star = s0 / kPerTag + (__double2loint(w) & 31);
                 }
             }
-            int s_star = g_star;
+            // The keys of the scan carry index bits in their low mantissa bits, so what the scan has found is the
+            // argmin up to values that agree to 2^-47; w is convex, so only neighbouring counts can agree that
+            // closely, and the true argmin lies next to what the scan found.  The order of neighbours is known
+            // exactly: w(s+1) < w(s) precisely when C > (s+1)(s+2), both sides exact in fp64.  With
+            // U[t] = t (t+1) (U[0] = -1, so that the result never falls below 0) the argmin over all counts is the
+            // number of t >= 0 with C > U[t], less one; only the t around the scan's result need to be looked at.
+            int s_star;
             if constexpr (grouped_tags(CH)) {
-                // inside that group: its four values once more (relative to the group's first count), each with
-                // its position in the low bits
-                Double2 r01, r23;
+                // the scan names a group of four counts 4 g .. 4 g + 3: the argmin is 4 g - 1 plus the number of
+                // t = 4 g .. 4 g + 4 with C > U[t]
+                const int t0 = 4 * g_star;
+                s_star = t0 - 1;
                 if (has_near) {
-                    r01 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star);
-                    r23 = *(const Double2 __attribute__((address_space(3))) *)(near + 4 * g_star + 2);
+                    // two, two and one at a time, each read issued after the previous comparison (the opaque
+                    // statements tie the address to the running count): five values held at once would cost
+                    // the kernel registers it does not have
+                    LdsDoubles u = near + kNearRecips + t0;
+                    const Double2 a01 = *(const Double2 __attribute__((address_space(3))) *)u;
+                    s_star += (C > a01.x ? 1 : 0) + (C > a01.y ? 1 : 0);
+                    asm volatile("" : "+v"(s_star), "+v"(u));
+                    const Double2 a23 = *(const Double2 __attribute__((address_space(3))) *)(u + 2);
+                    s_star += (C > a23.x ? 1 : 0) + (C > a23.y ? 1 : 0);
+                    asm volatile("" : "+v"(s_star), "+v"(u));
+                    s_star += C > u[4] ? 1 : 0;
                 } else {
-                    r01 = *(const Double2 *)(rs + 4 * g_star);
-                    r23 = *(const Double2 *)(rs + 4 * g_star + 2);
+                    const double td = (double)t0;
+                    s_star += (C > (t0 > 0 ? px_fma(td, td, td) : -1.0) ? 1 : 0);
+                    s_star += (C > px_fma(td, td, px_fma(3.0, td, 2.0)) ? 1 : 0);
+                    s_star += (C > px_fma(td, td, px_fma(5.0, td, 6.0)) ? 1 : 0);
+                    s_star += (C > px_fma(td, td, px_fma(7.0, td, 12.0)) ? 1 : 0);
+                    s_star += (C > px_fma(td, td, px_fma(9.0, td, 20.0)) ? 1 : 0);
                 }
-                const double k0 = tagged<0>(C * r01.x), k1 = tagged<1>(px_fma(C, r01.y, 1.0));
-                const double k2 = tagged<2>(px_fma(C, r23.x, 2.0)), k3 = tagged<3>(px_fma(C, r23.y, X.x[3]));
-                double kk;
-                asm("v_min_f64 %0, %1, %2\n\t"
-                    "v_min_f64 %0, %0, %3\n\t"
-                    "v_min_f64 %0, %0, %4"
-                    : "=&v"(kk)
-                    : "v"(k0), "v"(k1), "v"(k2), "v"(k3));
-                s_star = 4 * g_star + (__double2loint(kk) & 3);
-            }
-            // The keys of the scan carry index bits, so two neighbouring counts whose values agree to 2^-47 may
-            // have been taken in the wrong order (convexity rules out any other near-tie).  The order of
-            // neighbours is known exactly: w(s+1) < w(s) precisely when C > (s+1)(s+2), both sides exact in fp64.
-            {
-                double t_lo, t_hi;                 // s (s+1) and (s+1)(s+2) at s = s_star; -1 for s = 0, so that it never moves below 0
+            } else {
+                // the scan names a count: one step down or up if its neighbour is better
+                s_star = g_star;
+                double t_lo, t_hi;
                 if (has_near) {
-                    const Double2 t = *(const Double2 __attribute__((address_space(3))) *)(near + kNearRecips + 2 * s_star);
-                    t_lo = t.x; t_hi = t.y;
+                    t_lo = near[kNearRecips + s_star];
+                    t_hi = near[kNearRecips + s_star + 1];
                 } else {
                     const double sd = (double)s_star;
                     t_lo = s_star > 0 ? px_fma(sd, sd, sd) : -1.0;
@@ -1123,8 +1132,8 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
-    // behind them, per count s, the pair s (s+1), (s+1)(s+2) that decides the order of neighbouring counts (sweep_pick)
-    __shared__ __align__(16) double r_lds[3 * kNearRecips];
+    // behind them U[t] = t (t+1), U[0] = -1: what decides the order of neighbouring counts (sweep_pick)
+    __shared__ __align__(16) double r_lds[2 * kNearRecips + 8];
     bool has_near = false;
     if constexpr (CH != 0 && !MEMO) {
         if (a.gs_pad <= kNearRecips) {
@@ -1133,9 +1142,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                     ((float *)r_lds)[t] = a.rsf[t];
                 } else {
                     r_lds[t] = a.rs[t];
-                    const double sd = (double)t;
-                    r_lds[kNearRecips + 2 * t] = t > 0 ? sd * (sd + 1.0) : -1.0;
-                    r_lds[kNearRecips + 2 * t + 1] = (sd + 1.0) * (sd + 2.0);
+                    for (int e = t; e < a.gs_pad + 8; e += a.gs_pad) {
+                        const double ed = (double)e;
+                        r_lds[kNearRecips + e] = e > 0 ? ed * (ed + 1.0) : -1.0;
+                    }
                 }
             }
             __syncthreads();
