@@ -21,8 +21,9 @@
 //                     per-candidate, per-node counters with integer atomics
 //   candidates_kernel per candidate (one workgroup): SPEEDUP, penalty, constraint
 //                     check from those counters and the generalized mean
-// With PX_FLAG_MEMOISE, memo_kernel sweeps once per (job, placement class, K <= 64) and the population pass
-// (pairs_kernel, or memo_pairs_kernel for rows of 65 to 256 nodes) looks the result up.
+// With PX_FLAG_MEMOISE, memo_kernel sweeps once per (job, placement class, K <= 64) and the population pass looks
+// the result up: pairs_kernel, or for rows of 65 to 256 nodes memo_candidates_kernel, which takes a whole candidate
+// per workgroup and finishes its fitness as well (no per-pair scratch, no candidates_kernel).
 // With PX_FLAG_SAMPLE_M the sweep is replaced by sweep_sampled (Sec. 4.3), the kernels
 // instantiated with CH = 0, and last_kernel is not launched.
 //
@@ -93,6 +94,7 @@ struct FitnessArgs {
     int gs_pad;                   // Gs rounded up to a multiple of 32: length of rs
     int32_t *running, *meta;
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
+    int32_t *redo;                // [P] memoised mode: candidates left to the second instance of memo_candidates_kernel
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
     int need_constraints;
     const int32_t *sel;           // candidates to evaluate (device list of n_sel indices into the population), or null: all P
@@ -1483,112 +1485,6 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
     }
 }
 
-// ---- memoised mode, candidate by candidate ------------------------------------------------
-// With the sweeps looked up (PX_FLAG_MEMOISE) a pair costs its row reduce only, so the pass is bound by
-// reading the population.  This kernel walks it in memory order: a workgroup takes 64 consecutive jobs of one
-// candidate (64 KB of consecutive rows at N = 256), a wavefront 16 of them, four rows of the candidate and of
-// the current allocation requested together; lane r then finishes the pair of the wavefront's r-th job, so the
-// results of a wavefront are consecutive in memory too.  Launched when rows are 16-byte groups of 65 to 256
-// entries (shorter rows: pairs_kernel with four rows per load).  A row with more GPUs than the memo table
-// covers is swept here by the whole wavefront (rare).
-template <int CH>
-__global__ void __launch_bounds__(256) memo_pairs_kernel(FitnessArgs a)
-{
-    constexpr int kJobsPerWave = 16, kAhead = 4;
-    const int tiles = (a.J + kWavesPerBlock * kJobsPerWave - 1) / (kWavesPerBlock * kJobsPerWave);
-    const int k = (int)(blockIdx.x / (unsigned)tiles), tile = (int)(blockIdx.x % (unsigned)tiles);
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = lane_id();
-    const int j0 = (tile * kWavesPerBlock + wave) * kJobsPerWave;
-    if (k >= (a.sel ? a.n_sel : a.P) || j0 >= a.J) return;
-    const int c = a.sel ? a.sel[k] : k;                   // with a list of candidates the workgroups walk the list
-    const int rows = a.J - j0 < kJobsPerWave ? a.J - j0 : kJobsPerWave;
-    const int n4 = a.N >> 2;
-    const int lane4 = lane < n4 ? lane : n4 - 1;          // lanes past the end of a row load its last 16 bytes again
-    const unsigned long long in_row = __ballot(lane < n4);
-    const int4 *__restrict__ rowp = (const int4 *)(a.population + ((size_t)c * a.J + j0) * a.N) + lane4;
-    const int4 *__restrict__ curp = (const int4 *)(a.current_alloc + (size_t)j0 * a.N) + lane4;
-    unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
-    int d_K = 0, d_meta = 0;                              // lane r: K and nodes | changed of job j0 + r
-    bool any_neg = false;
-
-    // Two buffers of kAhead rows: the next batch is requested before the current one is worked on, so that
-    // requests are in flight all the time.
-    auto request = [&](int r0, int4 (&v)[kAhead], int4 (&cv)[kAhead]) {
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            const int ru = r0 + u < rows ? r0 + u : rows - 1;                 // the tail reads the last row again
-            v[u] = rowp[(size_t)ru * n4];
-            cv[u] = curp[(size_t)ru * n4];
-        }
-    };
-    auto work = [&](int r0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
-#pragma unroll
-        for (int u = 0; u < kAhead; ++u) {
-            if (r0 + u < rows) {
-                const int4 w = v[u], was = cv[u];
-                const int part = (w.x + w.y) + (w.z + w.w);
-                const int K = wave_sum(lane < n4 ? part : 0);
-                const int nodes = __popcll(__ballot(w.x > 0) & in_row) + __popcll(__ballot(w.y > 0) & in_row) +
-                                  __popcll(__ballot(w.z > 0) & in_row) + __popcll(__ballot(w.w > 0) & in_row);
-                const bool changed = ((__ballot(w.x != was.x) | __ballot(w.y != was.y) | __ballot(w.z != was.z) | __ballot(w.w != was.w)) & in_row) != 0;
-                any_neg |= (__ballot((w.x | w.y | w.z | w.w) < 0) & in_row) != 0;
-                if (a.need_constraints && lane < n4) {
-                    // every non-zero entry goes to the candidate's per-node counters (a negative one as it is)
-                    const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
-                    unsigned long long *__restrict__ to = cp + 4 * lane;
-                    if (w.x != 0) atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
-                    if (w.y != 0) atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
-                    if (w.z != 0) atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
-                    if (w.w != 0) atomicAdd(&to[3], (unsigned long long)(long long)w.w + (w.w > 0 ? one_job : 0ull));
-                }
-                if (lane == r0 + u) {
-                    d_K = K;
-                    d_meta = nodes | (changed ? kMetaChanged : 0);
-                }
-            }
-        }
-    };
-    static_assert(kJobsPerWave == 4 * kAhead, "four batches, unrolled below");
-    int4 v0[kAhead], c0v[kAhead], v1[kAhead], c1v[kAhead];
-    request(0, v0, c0v);
-    if (kAhead < rows) request(kAhead, v1, c1v);
-    work(0, v0, c0v);
-    if (2 * kAhead < rows) request(2 * kAhead, v0, c0v);
-    if (kAhead < rows) work(kAhead, v1, c1v);
-    if (3 * kAhead < rows) request(3 * kAhead, v1, c1v);
-    if (2 * kAhead < rows) work(2 * kAhead, v0, c0v);
-    if (3 * kAhead < rows) work(3 * kAhead, v1, c1v);
-
-    // rows beyond the memo table: swept and priced here
-    Best beyond = {0.0, -1, -1};
-    unsigned long long pending = __ballot(lane < rows && d_K > kTableK);
-    while (pending) {
-        const int l = __ffsll(pending) - 1;
-        pending &= pending - 1;
-        const int K = __builtin_amdgcn_readlane(d_K, l);
-        const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
-        const Best b = sweep<CH>(load_job(a.job_params, a.J, j0 + l), job_tables(a, j0 + l), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
-        if (lane == l) beyond = b;
-    }
-    if (lane < rows) {
-        const int j = j0 + lane;
-        const size_t pair = (size_t)c * a.J + j;
-        const int nodes = d_meta & ~kMetaChanged;
-        Best best = beyond;
-        if (d_K >= 1 && d_K <= kTableK) {
-            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
-            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
-        }
-        a.G[pair] = best.goodput;
-        a.meta[pair] = d_meta;
-        a.best_m[pair] = best.m;
-        a.best_s[pair] = best.s;
-        if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-    }
-    if (any_neg && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
-}
-
 // ---- the argmax alone, for the consumers outside the search ----------------------------
 // One wavefront per query (job, K, nodes): the same sweep and pricing as a (candidate, job) pair.
 //   per_gpu mode   query (j, n), n = 0..max_nodes: column 0 is the job on one GPU, column n >= 1
@@ -1747,6 +1643,191 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     }
 }
 
+// ---- memoised mode, one workgroup per candidate ---------------------------------------------------
+// With the sweeps looked up a candidate costs the reading of its matrix and little else, so one workgroup
+// takes the whole candidate: it walks the matrix in memory order (four wavefronts, 64 consecutive rows each
+// per round of 256 jobs, four rows and the matching rows of the current allocation requested at a time, the
+// next four before the current ones are worked on), keeps the per-node counters of the constraint check in
+// LDS (integer atomics: order-independent), and thread t finishes the pairs of jobs t, t + 256, ...: looks the
+// sweep's result up, forms SPEEDUP (Eq. 15) with the penalty and its term of the generalized mean (Eq. 14).
+// The terms are summed exactly as candidates_kernel sums them (thread t over its jobs in ascending order, then
+// the same tree), so the fitness is bit-identical to the plain mode's.  Nothing but the results leaves the
+// chip.  For rows of 16-byte groups of at most 256 nodes, fp64, grid sweeps (not the sampling argmax).  A row
+// with more GPUs than the memo table covers is swept here by its wavefront (rare).
+// BEYOND = false: the instance for the common case.  A candidate with a row beyond the memo table is left
+// alone and flagged in a.redo[c]; the instance with BEYOND = true is launched after it, returns at once for
+// the candidates that are done and treats the flagged ones in full, sweeps included.  Split because the sweep
+// costs the kernel twice the registers of everything else in it.
+template <int CH, bool BEYOND>
+__global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessArgs a)
+{
+    static_assert(kCandThreads == 4 * kWave, "thread t of the workgroup is lane t % 64 of wavefront t / 64");
+    constexpr int kAhead = 4;
+    __shared__ unsigned long long node_lds[4 * kWave];       // per node: GPUs asked + multi-node jobs << 40, as colpack
+    __shared__ double red_acc[kCandThreads];
+    __shared__ double red_w[kCandThreads];
+    __shared__ long long red_v[kCandThreads];
+    __shared__ int found_beyond;
+    const int c = a.sel ? a.sel[blockIdx.x] : (int)blockIdx.x;
+    if constexpr (BEYOND) {
+        if (!a.redo[c]) return;
+    }
+    const int t = threadIdx.x;
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int n4 = a.N >> 2;
+    const int lane4 = lane < n4 ? lane : n4 - 1;          // lanes past the end of a row load its last 16 bytes again
+    const unsigned long long in_row = __ballot(lane < n4);
+    const double *__restrict__ wt = a.job_params + (size_t)PX_WEIGHT * a.J;
+    node_lds[t] = 0ull;
+    if (t == 0) found_beyond = 0;
+    __syncthreads();
+
+    double acc = 0.0, wsum = 0.0;
+    bool any_neg = false;
+    for (int j0 = 0; j0 < a.J; j0 += kCandThreads) {
+        const int jw = j0 + kWave * wave;                   // this wavefront's first job of the round
+        const int rows = a.J - jw < kWave ? (a.J - jw > 0 ? a.J - jw : 0) : kWave;
+        int d_K = 0, d_meta = 0;                            // lane r: K and nodes | changed of job jw + r
+        if (rows > 0) {
+            const int4 *__restrict__ rowp = (const int4 *)(a.population + ((size_t)c * a.J + jw) * a.N) + lane4;
+            const int4 *__restrict__ curp = (const int4 *)(a.current_alloc + (size_t)jw * a.N) + lane4;
+            auto request = [&](int r0, int4 (&v)[kAhead]) {
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
+                    v[u] = rowp[(size_t)ru * n4];
+                }
+            };
+            // The rows of the current allocation come from L2 (1 KB per job, shared by all candidates).  They are
+            // requested when their batch is about to be worked on, not a batch ahead, which saves the registers of a
+            // second buffer, but BEFORE the next batch of the population is requested: loads complete in order, so
+            // waiting for them then leaves that next batch in flight.
+            auto request_current = [&](int r0, int4 (&cv)[kAhead]) {
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) cv[u] = curp[(size_t)(r0 + u < rows ? r0 + u : rows - 1) * n4];
+            };
+            auto work = [&](int r0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    if (r0 + u < rows) {
+                        const int4 w = v[u], was = cv[u];
+                        const int part = (w.x + w.y) + (w.z + w.w);
+                        const int K = wave_sum(lane < n4 ? part : 0);
+                        const int nodes = __popcll(__ballot(w.x > 0) & in_row) + __popcll(__ballot(w.y > 0) & in_row) +
+                                          __popcll(__ballot(w.z > 0) & in_row) + __popcll(__ballot(w.w > 0) & in_row);
+                        const bool changed = ((__ballot(w.x != was.x) | __ballot(w.y != was.y) | __ballot(w.z != was.z) | __ballot(w.w != was.w)) & in_row) != 0;
+                        any_neg |= (__ballot((w.x | w.y | w.z | w.w) < 0) & in_row) != 0;
+                        if (a.need_constraints && lane < n4 && (w.x | w.y | w.z | w.w) != 0) {
+                            // The few lanes that hold a non-zero entry (a job sits on few nodes) add their four
+                            // entries to the per-node counters, zeros included (a negative entry as it is): one
+                            // branch per row instead of one per entry.
+                            const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
+                            unsigned long long *to = node_lds + 4 * lane;
+                            atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
+                            atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
+                            atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
+                            atomicAdd(&to[3], (unsigned long long)(long long)w.w + (w.w > 0 ? one_job : 0ull));
+                        }
+                        if (lane == r0 + u) {
+                            d_K = K;
+                            d_meta = nodes | (changed ? kMetaChanged : 0);
+                        }
+                    }
+                }
+            };
+            // two buffers of kAhead rows: requests are in flight all the time
+            int4 v0[kAhead], v1[kAhead], cv[kAhead];
+            request(0, v0);
+            for (int r0 = 0; r0 < rows; r0 += 2 * kAhead) {
+                request_current(r0, cv);
+                if (r0 + kAhead < rows) request(r0 + kAhead, v1);
+                work(r0, v0, cv);
+                if (r0 + kAhead < rows) {
+                    request_current(r0 + kAhead, cv);
+                    if (r0 + 2 * kAhead < rows) request(r0 + 2 * kAhead, v0);
+                    work(r0 + kAhead, v1, cv);
+                }
+            }
+        }
+        // rows beyond the memo table: swept and priced by the whole wavefront (BEYOND), or the candidate is left to
+        // the instance that can
+        Best beyond = {0.0, -1, -1};
+        unsigned long long pending = __ballot(lane < rows && d_K > kTableK);
+        if constexpr (BEYOND) {
+            while (pending) {
+                const int l = __ffsll(pending) - 1;
+                pending &= pending - 1;
+                const int K = __builtin_amdgcn_readlane(d_K, l);
+                const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
+                const Best b = sweep<CH>(load_job(a.job_params, a.J, jw + l), job_tables(a, jw + l), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+                if (lane == l) beyond = b;
+            }
+        } else if (pending) {
+            if (lane == 0) found_beyond = 1;
+        }
+        // thread t finishes the pair of job j0 + t
+        if (lane < rows) {
+            const int j = jw + lane;
+            const size_t pair = (size_t)c * a.J + j;
+            const int nodes = d_meta & ~kMetaChanged;
+            Best best = beyond;
+            if (d_K >= 1 && d_K <= kTableK) {
+                const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
+                best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+            }
+            a.best_m[pair] = best.m;
+            a.best_s[pair] = best.s;
+            if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+            // SPEEDUP (Eq. 15) with the re-allocation penalty, and the job's term of Eq. 14
+            const double d = a.denom[j];
+            double s_j = d > 0 ? best.goodput / d : 0.0;
+            if (d_meta & kMetaChanged) s_j = s_j * a.factor[j];
+            if (a.speedup) a.speedup[pair] = s_j;
+            acc += pmean_term(s_j, wt[j], a.p);
+            wsum += wt[j];
+        }
+    }
+    red_acc[t] = acc;
+    red_w[t] = wsum;
+    __syncthreads();                                        // the counters of all wavefronts are complete
+    if constexpr (!BEYOND) {
+        // (the outputs written so far for a flagged candidate are written again, in full, by the other instance)
+        if (t == 0) a.redo[c] = found_beyond;
+        if (found_beyond) return;
+    }
+    if (__ballot(any_neg) != 0ull && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
+
+    // constraint check: per node, multi-node jobs beyond the first and GPUs beyond capacity
+    long long v = 0;
+    if (a.need_constraints && t < a.N) {
+        const long long x = (long long)node_lds[t];
+        const long long asked = (x << 24) >> 24;              // low 40 bits, sign-extended
+        const long long distributed = (x - asked) >> 40;
+        if (distributed > 1) v += distributed - 1;
+        const long long over = asked - (long long)a.node_capacity[t];
+        if (over > 0) v += over;
+    }
+    red_v[t] = v;
+    __syncthreads();
+    for (int half = kCandThreads / 2; half > 0; half >>= 1) {
+        if (t < half) {
+            red_acc[t] += red_acc[t + half];
+            red_w[t] += red_w[t + half];
+            red_v[t] += red_v[t + half];
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        const double mean = red_acc[0] / red_w[0];
+        double f = pmean_finish(mean, a.p);
+        const long long V = red_v[0];
+        if (a.violations) a.violations[c] = (int32_t)(V > 0x7FFFFFFF ? 0x7FFFFFFF : V);
+        if (V > 0 && !(a.flags & PX_FLAG_NO_CONSTRAINT_CHECK)) f = -(double)V;
+        a.fitness[c] = f;
+    }
+}
+
 }  // namespace px
 
 // ---- host side -----------------------------------------------------------------
@@ -1860,6 +1941,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.G = (double *)(ws + L.G);
     a.meta = (int32_t *)(ws + L.meta);
     a.memo = (MemoEntry *)(ws + L.memo);
+    a.redo = (int32_t *)(ws + L.redo);
     a.colpack = (unsigned long long *)(ws + L.colpack);
     a.need_constraints = (violations != nullptr || !(d->flags & PX_FLAG_NO_CONSTRAINT_CHECK)) ? 1 : 0;
     // first_rank > 0: only the candidates of rank first_rank and beyond in the order the search step left in the
@@ -1935,12 +2017,19 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         else PX_LAUNCH_PAIRS(CH, F32, false, false, false, false);             \
     } while (0)
     if (memo && !sampled && !f32 && row1 && !row4) {
-        // memoised pass over rows of 65 to 256 entries: in memory order
-        const unsigned tiles = (unsigned)((d->J + kWavesPerBlock * 16 - 1) / (kWavesPerBlock * 16));
-        const dim3 memo_pairs_grid((unsigned)P_eff * tiles);
-        if (ch == 8) hipLaunchKernelGGL(memo_pairs_kernel<8>, memo_pairs_grid, dim3(256), 0, stream, a);
-        else if (ch == 16) hipLaunchKernelGGL(memo_pairs_kernel<16>, memo_pairs_grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL(memo_pairs_kernel<32>, memo_pairs_grid, dim3(256), 0, stream, a);
+        // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, fitness included
+        const dim3 memo_grid((unsigned)P_eff);
+#define PX_LAUNCH_MEMO_CANDIDATES(CH)                                                                                 \
+    do {                                                                                                              \
+        hipLaunchKernelGGL((memo_candidates_kernel<CH, false>), memo_grid, dim3(kCandThreads), 0, stream, a);         \
+        hipLaunchKernelGGL((memo_candidates_kernel<CH, true>), memo_grid, dim3(kCandThreads), 0, stream, a);          \
+    } while (0)
+        if (ch == 8) PX_LAUNCH_MEMO_CANDIDATES(8);
+        else if (ch == 16) PX_LAUNCH_MEMO_CANDIDATES(16);
+        else PX_LAUNCH_MEMO_CANDIDATES(32);
+#undef PX_LAUNCH_MEMO_CANDIDATES
+        if (sweep_stop) (void)hipEventRecord(sweep_stop, stream);
+        return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
     } else if (sampled) {
         if (memo) PX_LAUNCH_PAIRS(0, false, true, false, false, false);
         else PX_LAUNCH_PAIRS(0, false, false, false, false, false);

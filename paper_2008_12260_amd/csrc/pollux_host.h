@@ -20,6 +20,7 @@ constexpr int kTableK = 64;
 struct WorkspaceLayout {
     size_t status;    // int32 status word
     size_t order;     // int32  [P]       candidates by rank (search step)
+    size_t redo;      // int32  [P]       memoised mode: candidates with a row beyond the memo table
     size_t rk;        // double [256]     1/K
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
@@ -50,6 +51,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
     L.order = o;   o = up(o + 4 * P);
+    L.redo = o;    o = up(o + 4 * P);
     L.rk = o;      o = up(o + 8 * 256);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);
