@@ -1739,15 +1739,26 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
             // two buffers of kAhead rows: requests are in flight all the time
             int4 v0[kAhead], v1[kAhead], cv[kAhead];
             request(0, v0);
+            // (the fences keep the compiler from issuing the requests in another order)
+            auto fence = [] {
+                asm volatile("" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            };
             for (int r0 = 0; r0 < rows; r0 += 2 * kAhead) {
                 request_current(r0, cv);
+                fence();
                 if (r0 + kAhead < rows) request(r0 + kAhead, v1);
+                fence();
                 work(r0, v0, cv);
                 if (r0 + kAhead < rows) {
+                    fence();
                     request_current(r0 + kAhead, cv);
+                    fence();
                     if (r0 + 2 * kAhead < rows) request(r0 + 2 * kAhead, v0);
+                    fence();
                     work(r0 + kAhead, v1, cv);
                 }
+                fence();
             }
         }
         // rows beyond the memo table: swept and priced by the whole wavefront (BEYOND), or the candidate is left to
