@@ -35,7 +35,14 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_insts      vector instructions per launch; scan_insts = those of the scan itself (2.25 per grid point)
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
-    "large": None,
+    "large": {
+        "source_sha256": "9c70abd79909579c9225f83ba5f9d0a645b0d8c34c61d198ae1b59bcee20edf1",
+        "traffic_bytes": 2_068_600 * 1024 * 2 + 697_760 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "fp64_flops": 64 * (8.8881e6 + 4.1625e7 + 2 * 2.7480e8),
+        "valu_insts": 1.1032e9,
+        "scan_insts": 2.25 * 1.6777e10 / 64,
+        "valu_busy": 1.1172e9 * 4 / 1024 / (3.9478e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+    },
 }
 GA_SEED = 0x2008_1226_5EED_0001
 def mut_threshold(J):               # mutation probability 1/J per job: about one move per child
