@@ -95,6 +95,9 @@ struct FitnessArgs {
     int32_t *running, *meta;
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
     int32_t *redo;                // [P] memoised mode: candidates left to the second instance of memo_candidates_kernel
+    unsigned long long *curmask;  // [J] rows of at most 256 entries in 16-byte groups: bit g set when group g of the job's
+                                  // current row holds a non-zero entry (jobs_kernel)
+    int32_t *zeros;               // 64 zero bytes (jobs_kernel): what lanes read where the current row holds nothing
     unsigned long long *colpack;  // [P,N] per node: GPUs asked (low 40 bits, signed) + multi-node jobs present << 40
     int need_constraints;
     const int32_t *sel;           // candidates to evaluate (device list of n_sel indices into the population), or null: all P
@@ -1067,6 +1070,16 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
     }
     const long long total = wave_sum(csum);
     if (__ballot(neg) != 0) st |= PX_ST_NEG_ALLOC;
+    // which 16-byte groups of the current row hold anything (rows that one 16-byte load per lane covers)
+    unsigned long long groups = 0ull;
+    if ((a.N & 3) == 0 && a.N <= 4 * kWave) {
+        bool any = false;
+        if (lane < (a.N >> 2)) {
+            const int32_t *g = a.current_alloc + (size_t)j * a.N + 4 * lane;
+            any = (g[0] | g[1] | g[2] | g[3]) != 0;
+        }
+        groups = __ballot(any);
+    }
     // denominator of Eq. 15: the same sweep at the fair-share allocation
     Best fair;
     if constexpr (CH == 0)
@@ -1081,8 +1094,10 @@ __global__ void __launch_bounds__(256) jobs_kernel(FitnessArgs a)
         a.denom[j] = fair.goodput;
         a.factor[j] = (!(a.flags & PX_FLAG_NO_REALLOC_PENALTY) && total > 0) ? factor : 1.0;
         a.running[j] = total > 0;
+        a.curmask[j] = groups;
         if (st) atomicOr(a.status, st);
     }
+    if (j == 0 && lane < 16) a.zeros[lane] = 0;
 }
 
 // ---- memoised mode ---------------------------------------------------------------
@@ -1699,13 +1714,24 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                     v[u] = rowp[(size_t)ru * n4];
                 }
             };
-            // The rows of the current allocation come from L2 (1 KB per job, shared by all candidates).  They are
-            // requested when their batch is about to be worked on, not a batch ahead, which saves the registers of a
-            // second buffer, but BEFORE the next batch of the population is requested: loads complete in order, so
-            // waiting for them then leaves that next batch in flight.
+            // The rows of the current allocation come from L2 (shared by all candidates), and only the lanes whose
+            // 16-byte group of the current row holds anything read it (a.curmask, a scalar per row: a job sits on few
+            // nodes, so that is a lane or two); all other lanes read one block of zeros, which is what the current
+            // row holds there: a few cache lines per row through the vector cache instead of 1 KB.  Every lane
+            // loads either way, so the number of loads in flight is the same on every path and the waits can be
+            // exact.  The rows are requested when their batch is about to be worked on, not a batch ahead, which
+            // saves the registers of a second buffer, but BEFORE the next batch of the population is requested:
+            // loads complete in order, so waiting for them then leaves that next batch in flight.
+            // (the masks through the scalar cache: a vector load would make every use wait for all loads in flight)
+            typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
+            const ScalarMasks maskp = (ScalarMasks)a.curmask + jw;
+            const int4 *__restrict__ zerop = (const int4 *)a.zeros;
             auto request_current = [&](int r0, int4 (&cv)[kAhead]) {
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) cv[u] = curp[(size_t)(r0 + u < rows ? r0 + u : rows - 1) * n4];
+                for (int u = 0; u < kAhead; ++u) {
+                    const int ru = r0 + u < rows ? r0 + u : rows - 1;
+                    cv[u] = *(((maskp[ru] >> lane) & 1ull) ? curp + (size_t)ru * n4 : zerop);
+                }
             };
             auto work = [&](int r0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
 #pragma unroll
@@ -1736,7 +1762,9 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                     }
                 }
             };
-            // two buffers of kAhead rows: requests are in flight all the time
+            // Two buffers of kAhead rows: requests are in flight all the time.  A request past the end of the
+            // wavefront's rows reads its last row again (nothing works on it), so that every pass through the
+            // loop issues the same loads in the same order and each wait leaves exactly the next batch in flight.
             int4 v0[kAhead], v1[kAhead], cv[kAhead];
             request(0, v0);
             // (the fences keep the compiler from issuing the requests in another order)
@@ -1747,17 +1775,15 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
             for (int r0 = 0; r0 < rows; r0 += 2 * kAhead) {
                 request_current(r0, cv);
                 fence();
-                if (r0 + kAhead < rows) request(r0 + kAhead, v1);
+                request(r0 + kAhead, v1);
                 fence();
                 work(r0, v0, cv);
-                if (r0 + kAhead < rows) {
-                    fence();
-                    request_current(r0 + kAhead, cv);
-                    fence();
-                    if (r0 + 2 * kAhead < rows) request(r0 + 2 * kAhead, v0);
-                    fence();
-                    work(r0 + kAhead, v1, cv);
-                }
+                fence();
+                request_current(r0 + kAhead, cv);
+                fence();
+                request(r0 + 2 * kAhead, v0);
+                fence();
+                work(r0 + kAhead, v1, cv);
                 fence();
             }
         }
@@ -1953,6 +1979,8 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     a.meta = (int32_t *)(ws + L.meta);
     a.memo = (MemoEntry *)(ws + L.memo);
     a.redo = (int32_t *)(ws + L.redo);
+    a.curmask = (unsigned long long *)(ws + L.curmask);
+    a.zeros = (int32_t *)(ws + L.zeros);
     a.colpack = (unsigned long long *)(ws + L.colpack);
     a.need_constraints = (violations != nullptr || !(d->flags & PX_FLAG_NO_CONSTRAINT_CHECK)) ? 1 : 0;
     // first_rank > 0: only the candidates of rank first_rank and beyond in the order the search step left in the

@@ -21,6 +21,8 @@ struct WorkspaceLayout {
     size_t status;    // int32 status word
     size_t order;     // int32  [P]       candidates by rank (search step)
     size_t redo;      // int32  [P]       memoised mode: candidates with a row beyond the memo table
+    size_t curmask;   // uint64 [J]       16-byte groups of the job's current row that hold a non-zero entry
+    size_t zeros;     // 64 zero bytes
     size_t rk;        // double [256]     1/K
     size_t denom;     // double [J]       fair-share goodput
     size_t factor;    // double [J]       re-allocation factor
@@ -52,6 +54,8 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.status = o;  o = up(o + 256);
     L.order = o;   o = up(o + 4 * P);
     L.redo = o;    o = up(o + 4 * P);
+    L.curmask = o; o = up(o + 8 * J);
+    L.zeros = o;   o = up(o + 64);
     L.rk = o;      o = up(o + 8 * 256);
     L.denom = o;   o = up(o + 8 * J);
     L.factor = o;  o = up(o + 8 * J);

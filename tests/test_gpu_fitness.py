@@ -329,6 +329,51 @@ def test_memoised_mode_on_rows_of_65_to_256_nodes(shape):
     assert compare(wl, g, r, population=pop) == 0
 
 
+@pytest.mark.parametrize("N", [68, 128, 256])
+def test_memoised_mode_tells_changed_rows_from_unchanged_ones(N):
+    """The re-allocation penalty hinges on whether a row equals the job's current row.  Candidates built from the
+    current allocation itself: unchanged; the same nodes with other counts; a GPU moved to the neighbouring node
+    (same 16-byte group of the row, or the next group); moved to the far end of the row; a job that holds
+    nothing now and gets GPUs; a job that holds GPUs now and gets none.  Plain and memoised mode, against the
+    oracle's SPEEDUP (the factor is far from 1 for these jobs)."""
+    cfg = W.custom("changed_rows", P=8, J=70, N=N, cap=8, Gm=20, Gs=6)
+    wl = W.make(cfg)
+    cur = wl.current_alloc.copy()
+    cur[5] = 0                                              # job 5 holds nothing now
+    jp = wl.job_params.copy()
+    jp[11] = 600.0                                          # T_j: young jobs, so that the penalty is large
+    jp[12] = 3.0                                            # R_j
+    pop = np.repeat(cur[None], cfg.P, 0).copy()
+    rng = np.random.default_rng(5)
+    changed = np.zeros((cfg.P, cfg.J), bool)
+    for j in range(cfg.J):
+        occ = np.flatnonzero(cur[j])
+        if len(occ) == 0:
+            continue
+        n = int(occ[0])
+        pop[1, j, n] += 1                                   # same nodes, another count
+        to = n + 1 if n + 1 < N and cur[j, n + 1] == 0 else n
+        pop[2, j, n] -= 1; pop[2, j, to] += 1               # one GPU to the next node
+        far = N - 1 - n if cur[j, N - 1 - n] == 0 else n
+        pop[3, j, n] -= 1; pop[3, j, far] += 1              # one GPU to the mirrored node
+        pop[4, j] = 0                                       # gets nothing
+        pop[6, j] = np.roll(cur[j], 4)                      # every entry one 16-byte group further
+        if rng.uniform() < 0.5:
+            pop[7, j] = np.roll(cur[j], 1)
+    pop[5, 5, 3] = 2                                        # the job that holds nothing now gets GPUs
+    changed = (pop != cur[None]).any(2)
+    assert changed[1:5].mean() > 0.9 and not changed[0].any()
+    r = run_oracle(wl, population=pop, current=cur, job_params=jp, flags=2)
+    for flags in (2, 2 | 4):                                # constraint check off: the matrices overload nodes
+        g = run_gpu(wl, population=pop, current=cur, job_params=jp, flags=flags)
+        assert compare(wl, g, r, population=pop, job_params=jp) == 0
+    # and the penalty is what tells the rows apart: unchanged rows score the plain ratio
+    plain = run_oracle(wl, population=pop, current=pop[0], job_params=jp, flags=2 | 1)
+    live = cur.sum(1) > 0
+    assert np.array_equal(r["speedup"][0], plain["speedup"][0])
+    assert np.all(r["speedup"][1][live] < plain["speedup"][1][live])
+
+
 def test_memoised_mode_with_rows_beyond_the_table_and_in_fp32():
     cfg = W.custom("bigK", P=6, J=40, N=9, cap=40, Gm=33, Gs=5)      # K up to 160: beyond the 64-entry table
     wl = W.make(cfg)
