@@ -34,7 +34,7 @@
 extern "C" {
 #endif
 
-#define POLLUX_VERSION 104
+#define POLLUX_VERSION 105
 
 typedef struct {
     int32_t P;         /* candidates in the population                          */
@@ -159,8 +159,9 @@ int pollux_fitness(const pollux_dims *dims,              /* host */
                    double p, double delta,               /* fairness knob; re-allocation delay [s], >= 0 */
                    void *workspace, size_t workspace_bytes,
                    double *fitness,                      /* [P] out */
-                   int32_t *best_m,                      /* [P,J] out: m* (the batch size, not its index), -1 if none */
-                   int32_t *best_s,                      /* [P,J] out: s*, -1 if none */
+                   int32_t *best_m,                      /* [P,J] out: m* (the batch size, not its index), -1 if none;
+                                                            may be NULL together with best_s (a search needs only fitness) */
+                   int32_t *best_s,                      /* [P,J] out: s*, -1 if none; NULL exactly when best_m is */
                    double *best_goodput,                 /* [P,J] out, may be NULL */
                    double *speedup,                      /* [P,J] out, may be NULL: SPEEDUP_j (Eq. 15) after the penalty */
                    int32_t *violations,                  /* [P] out, may be NULL: V */
@@ -219,8 +220,8 @@ int pollux_fitness_static(const pollux_dims *dims,       /* host */
                           const int32_t *node_capacity,  /* [N] */
                           double p, double delta,
                           double *fitness,               /* [P] out */
-                          int32_t *best_m,               /* [P,J] out */
-                          int32_t *best_s,               /* [P,J] out */
+                          int32_t *best_m,               /* [P,J] out, may be NULL together with best_s */
+                          int32_t *best_s,               /* [P,J] out, NULL exactly when best_m is */
                           double *best_goodput,          /* [P,J] out, may be NULL */
                           double *speedup,               /* [P,J] out, may be NULL */
                           int32_t *violations,           /* [P] out, may be NULL */
@@ -317,8 +318,8 @@ int pollux_generation(const pollux_dims *dims,           /* host */
                       const pollux_ga_params *params,    /* host */
                       void *workspace, size_t workspace_bytes,
                       double *fitness,                   /* [P] in/out */
-                      int32_t *best_m,                   /* [P,J] in/out */
-                      int32_t *best_s,                   /* [P,J] in/out */
+                      int32_t *best_m,                   /* [P,J] in/out, may be NULL together with best_s */
+                      int32_t *best_s,                   /* [P,J] in/out, NULL exactly when best_m is */
                       double *best_goodput,              /* [P,J] in/out, may be NULL */
                       double *speedup,                   /* [P,J] in/out, may be NULL */
                       int32_t *violations,               /* [P] in/out, may be NULL */

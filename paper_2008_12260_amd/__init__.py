@@ -268,12 +268,15 @@ class FitnessCall:
         self.violations = torch.empty(P, dtype=torch.int32, device=dev)
 
     def run(self, population, stream=None, outputs="all", keep_job_tables=False, sweep_events=None):
-        full = outputs == "all"
+        """outputs: "all"; "argmax" (fitness, violations, best_m, best_s); "fitness" (fitness and violations only)."""
+        assert outputs in ("all", "argmax", "fitness")
+        full, argmax = outputs == "all", outputs != "fitness"
         dims = self.dims
         if keep_job_tables:
             dims = Dims(dims.P, dims.J, dims.N, dims.Gm, dims.Gs, dims.precision, dims.flags | PX_FLAG_KEEP_JOB_TABLES)
         pollux_fitness(dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
-                       self.node_capacity, self.p, self.delta, self.workspace, self.fitness, self.best_m, self.best_s,
+                       self.node_capacity, self.p, self.delta, self.workspace, self.fitness,
+                       self.best_m if argmax else None, self.best_s if argmax else None,
                        self.best_goodput if full else None, self.speedup if full else None, self.violations,
                        stream, sweep_events)
 
@@ -291,10 +294,12 @@ class FitnessCall:
 
     def generation(self, population, seed, generation, elite_k, mut_threshold, stream=None, outputs="all", job_gpu_cap=None):
         """pollux_generation on this call's buffers: search step in place, then the fitness of the children only."""
-        full = outputs == "all"
+        assert outputs in ("all", "argmax", "fitness")
+        full, argmax = outputs == "all", outputs != "fitness"
         ga = GaParams(seed, generation, elite_k, mut_threshold, PX_GA_IN_PLACE, None if job_gpu_cap is None else job_gpu_cap.data_ptr())
         pollux_generation(self.dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
-                          self.node_capacity, self.p, self.delta, ga, self.workspace, self.fitness, self.best_m, self.best_s,
+                          self.node_capacity, self.p, self.delta, ga, self.workspace, self.fitness,
+                          self.best_m if argmax else None, self.best_s if argmax else None,
                           self.best_goodput if full else None, self.speedup if full else None, self.violations, stream)
 
     def results(self) -> dict:

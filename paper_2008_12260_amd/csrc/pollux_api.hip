@@ -117,7 +117,7 @@ int fitness_call(const pollux_dims *dims, const int32_t *population, const doubl
 {
     if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
     if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !fitness ||
-        !best_m || !best_s)
+        (best_m == nullptr) != (best_s == nullptr))
         return PX_E_INVALID_ARG;
     if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
     int rc = check_workspace(dims, workspace, workspace_bytes);
@@ -161,7 +161,7 @@ int pollux_fitness_static(const pollux_dims *dims, const int32_t *population, co
 {
     if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
     if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !fitness ||
-        !best_m || !best_s)
+        (best_m == nullptr) != (best_s == nullptr))
         return PX_E_INVALID_ARG;
     if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
     // the problem must fit the library's array: checked on the host, before any device is touched
@@ -211,7 +211,7 @@ int pollux_generation(const pollux_dims *dims, int32_t *population, const double
 {
     if (!dims_ok(dims, true)) return PX_E_INVALID_ARG;
     if (!population || !job_params || !m_grid || !fair_share || !current_alloc || !node_capacity || !params || !fitness ||
-        !best_m || !best_s)
+        (best_m == nullptr) != (best_s == nullptr))
         return PX_E_INVALID_ARG;
     if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
     if (params->elite_k < 1u || params->elite_k > (uint32_t)dims->P) return PX_E_INVALID_ARG;

@@ -1433,8 +1433,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
                 const size_t pair = (size_t)c * a.J + j;
                 a.G[pair] = best.goodput;
                 a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
-                a.best_m[pair] = best.m;
-                a.best_s[pair] = best.s;
+                if (a.best_m) {
+                    a.best_m[pair] = best.m;
+                    a.best_s[pair] = best.s;
+                }
                 if (a.best_goodput) a.best_goodput[pair] = best.goodput;
                 if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
             }
@@ -1492,8 +1494,10 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
             }
             b.G[pair] = best.goodput;
             b.meta[pair] = d_meta;
-            b.best_m[pair] = best.m;
-            b.best_s[pair] = best.s;
+            if (b.best_m) {
+                b.best_m[pair] = best.m;
+                b.best_s[pair] = best.s;
+            }
             if (b.best_goodput) b.best_goodput[pair] = best.goodput;
         }
         if (any_neg && lane == 0) atomicOr(b.status, PX_ST_NEG_ALLOC);
@@ -1662,23 +1666,30 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
 // With the sweeps looked up a candidate costs the reading of its matrix and little else, so one workgroup
 // takes the whole candidate: it walks the matrix in memory order (four wavefronts, 64 consecutive rows each
 // per round of 256 jobs, four rows and the matching rows of the current allocation requested at a time, the
-// next four before the current ones are worked on), keeps the per-node counters of the constraint check in
-// LDS (integer atomics: order-independent), and thread t finishes the pairs of jobs t, t + 256, ...: looks the
-// sweep's result up, forms SPEEDUP (Eq. 15) with the penalty and its term of the generalized mean (Eq. 14).
-// The terms are summed exactly as candidates_kernel sums them (thread t over its jobs in ascending order, then
-// the same tree), so the fitness is bit-identical to the plain mode's.  Nothing but the results leaves the
-// chip.  For rows of 16-byte groups of at most 256 nodes, fp64, grid sweeps (not the sampling argmax).  A row
-// with more GPUs than the memo table covers is swept here by its wavefront (rare).
-// BEYOND = false: the instance for the common case.  A candidate with a row beyond the memo table is left
-// alone and flagged in a.redo[c]; the instance with BEYOND = true is launched after it, returns at once for
-// the candidates that are done and treats the flagged ones in full, sweeps included.  Split because the sweep
-// costs the kernel twice the registers of everything else in it.
+// next four before the current ones are worked on, from one round straight into the next), keeps the per-node
+// counters of the constraint check in LDS (integer atomics: order-independent) and K, nodes and the changed flag
+// of every row in LDS as well.  After up to 1024 jobs the workgroup stops reading, and thread t finishes the
+// pairs of jobs t, t + 256, ... of those: looks the sweep's result up, forms SPEEDUP (Eq. 15) with the penalty
+// and its term of the generalized mean (Eq. 14).  (Finishing per round instead, between the requests, left the
+// memory system idle a tenth of the time.)  The terms are summed exactly as candidates_kernel sums them (thread
+// t over its jobs in ascending order, then the same tree), so the fitness is bit-identical to the plain mode's.
+// Nothing but the results leaves the chip.  For rows of 16-byte groups of at most 256 nodes, fp64, grid sweeps
+// (not the sampling argmax).
+// BEYOND = false: the instance for the common case.  A candidate with a row of more GPUs than the memo table
+// covers is left alone and flagged in a.redo[c]; the instance with BEYOND = true is launched after it, returns at
+// once for the candidates that are done and treats the flagged ones in full, such rows swept by their wavefront.
+// Split because the sweep costs the kernel twice the registers of everything else in it.
+constexpr int kMemoChunkJobs = 4 * kCandThreads;    // jobs between two finishing steps
+
 template <int CH, bool BEYOND>
 __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessArgs a)
 {
     static_assert(kCandThreads == 4 * kWave, "thread t of the workgroup is lane t % 64 of wavefront t / 64");
     constexpr int kAhead = 4;
+    static_assert(kWave % (2 * kAhead) == 0, "a pass of the request loop never straddles two rounds");
     __shared__ unsigned long long node_lds[4 * kWave];       // per node: GPUs asked + multi-node jobs << 40, as colpack
+    __shared__ int2 row_lds[kMemoChunkJobs];                  // per job of the chunk: K, nodes | changed flag
+    __shared__ MemoEntry beyond_lds[BEYOND ? kMemoChunkJobs : 1];   // per job of the chunk with K beyond the table: its sweep
     __shared__ double red_acc[kCandThreads];
     __shared__ double red_w[kCandThreads];
     __shared__ long long red_v[kCandThreads];
@@ -1700,18 +1711,22 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
 
     double acc = 0.0, wsum = 0.0;
     bool any_neg = false;
-    for (int j0 = 0; j0 < a.J; j0 += kCandThreads) {
-        const int jw = j0 + kWave * wave;                   // this wavefront's first job of the round
-        const int rows = a.J - jw < kWave ? (a.J - jw > 0 ? a.J - jw : 0) : kWave;
-        int d_K = 0, d_meta = 0;                            // lane r: K and nodes | changed of job jw + r
+    for (int jc = 0; jc < a.J; jc += kMemoChunkJobs) {
+        const int chunk_jobs = a.J - jc < kMemoChunkJobs ? a.J - jc : kMemoChunkJobs;
+        // Row q of this wavefront in the chunk is job  jc + (q / 64) * 256 + 64 * wave + q % 64  (position in the
+        // chunk: the same without jc); the wavefront has `rows` of them.
+        int tail = chunk_jobs % kCandThreads - kWave * wave;
+        tail = tail < 0 ? 0 : (tail > kWave ? kWave : tail);
+        const int rows = kWave * (chunk_jobs / kCandThreads) + tail;
+        auto place = [&](int q) { return (q >> 6) * kCandThreads + kWave * wave + (q & (kWave - 1)); };
         if (rows > 0) {
-            const int4 *__restrict__ rowp = (const int4 *)(a.population + ((size_t)c * a.J + jw) * a.N) + lane4;
-            const int4 *__restrict__ curp = (const int4 *)(a.current_alloc + (size_t)jw * a.N) + lane4;
-            auto request = [&](int r0, int4 (&v)[kAhead]) {
+            const int4 *__restrict__ rowp = (const int4 *)(a.population + ((size_t)c * a.J + jc) * a.N) + lane4;
+            const int4 *__restrict__ curp = (const int4 *)(a.current_alloc + (size_t)jc * a.N) + lane4;
+            auto request = [&](int q0, int4 (&v)[kAhead]) {
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
-                    const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
-                    v[u] = rowp[(size_t)ru * n4];
+                    const int q = q0 + u < rows ? q0 + u : rows - 1;               // the tail reads the last row again
+                    v[u] = rowp[(size_t)place(q) * n4];
                 }
             };
             // The rows of the current allocation come from L2 (shared by all candidates), and only the lanes whose
@@ -1724,19 +1739,20 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
             // loads complete in order, so waiting for them then leaves that next batch in flight.
             // (the masks through the scalar cache: a vector load would make every use wait for all loads in flight)
             typedef const unsigned long long __attribute__((address_space(4))) *ScalarMasks;
-            const ScalarMasks maskp = (ScalarMasks)a.curmask + jw;
+            const ScalarMasks maskp = (ScalarMasks)a.curmask + jc;
             const int4 *__restrict__ zerop = (const int4 *)a.zeros;
-            auto request_current = [&](int r0, int4 (&cv)[kAhead]) {
+            auto request_current = [&](int q0, int4 (&cv)[kAhead]) {
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
-                    const int ru = r0 + u < rows ? r0 + u : rows - 1;
-                    cv[u] = *(((maskp[ru] >> lane) & 1ull) ? curp + (size_t)ru * n4 : zerop);
+                    const int at = place(q0 + u < rows ? q0 + u : rows - 1);
+                    cv[u] = *(((maskp[at] >> lane) & 1ull) ? curp + (size_t)at * n4 : zerop);
                 }
             };
-            auto work = [&](int r0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
+            int d_K = 0, d_meta = 0;                        // lane r: K and nodes | changed of row q with q % 64 = r
+            auto work = [&](int q0, const int4 (&v)[kAhead], const int4 (&cv)[kAhead]) {
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
-                    if (r0 + u < rows) {
+                    if (q0 + u < rows) {
                         const int4 w = v[u], was = cv[u];
                         const int part = (w.x + w.y) + (w.z + w.w);
                         const int K = wave_sum(lane < n4 ? part : 0);
@@ -1755,7 +1771,7 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                             atomicAdd(&to[2], (unsigned long long)(long long)w.z + (w.z > 0 ? one_job : 0ull));
                             atomicAdd(&to[3], (unsigned long long)(long long)w.w + (w.w > 0 ? one_job : 0ull));
                         }
-                        if (lane == r0 + u) {
+                        if (lane == ((q0 + u) & (kWave - 1))) {
                             d_K = K;
                             d_meta = nodes | (changed ? kMetaChanged : 0);
                         }
@@ -1772,49 +1788,76 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                 asm volatile("" ::: "memory");
                 __builtin_amdgcn_sched_barrier(0);
             };
-            for (int r0 = 0; r0 < rows; r0 += 2 * kAhead) {
-                request_current(r0, cv);
+            for (int q0 = 0; q0 < rows; q0 += 2 * kAhead) {
+                request_current(q0, cv);
                 fence();
-                request(r0 + kAhead, v1);
+                request(q0 + kAhead, v1);
                 fence();
-                work(r0, v0, cv);
+                work(q0, v0, cv);
                 fence();
-                request_current(r0 + kAhead, cv);
+                request_current(q0 + kAhead, cv);
                 fence();
-                request(r0 + 2 * kAhead, v0);
+                request(q0 + 2 * kAhead, v0);
                 fence();
-                work(r0 + kAhead, v1, cv);
+                work(q0 + kAhead, v1, cv);
                 fence();
+                // a round of 64 rows (or the last, shorter one) is complete: lane r puts its row's figures away
+                const int next = q0 + 2 * kAhead;
+                if ((next & (kWave - 1)) == 0 || next >= rows) {
+                    const int first = q0 & ~(kWave - 1);
+                    const int in_round = rows - first < kWave ? rows - first : kWave;
+                    const int at = place(first) + lane;
+                    if (lane < in_round) row_lds[at] = make_int2(d_K, d_meta);
+                    // rows beyond the memo table: swept and priced by the whole wavefront (BEYOND), or the candidate
+                    // is left to the instance that can
+                    unsigned long long pending = __ballot(lane < in_round && d_K > kTableK);
+                    if constexpr (BEYOND) {
+                        while (pending) {
+                            const int l = __ffsll(pending) - 1;
+                            pending &= pending - 1;
+                            const int K = __builtin_amdgcn_readlane(d_K, l);
+                            const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
+                            const int j = jc + place(first) + l;
+                            const Best b = sweep<CH>(load_job(a.job_params, a.J, j), job_tables(a, j), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+                            if (lane == l) {
+                                MemoEntry e;
+                                e.goodput = b.goodput; e.m = b.m; e.s = b.s;
+                                beyond_lds[at] = e;
+                            }
+                        }
+                    } else if (pending) {
+                        if (lane == 0) found_beyond = 1;
+                    }
+                }
             }
         }
-        // rows beyond the memo table: swept and priced by the whole wavefront (BEYOND), or the candidate is left to
-        // the instance that can
-        Best beyond = {0.0, -1, -1};
-        unsigned long long pending = __ballot(lane < rows && d_K > kTableK);
-        if constexpr (BEYOND) {
-            while (pending) {
-                const int l = __ffsll(pending) - 1;
-                pending &= pending - 1;
-                const int K = __builtin_amdgcn_readlane(d_K, l);
-                const int nodes = __builtin_amdgcn_readlane(d_meta, l) & ~kMetaChanged;
-                const Best b = sweep<CH>(load_job(a.job_params, a.J, jw + l), job_tables(a, jw + l), a.rs, a.rk, a.Gm, a.Gs, K, nodes);
-                if (lane == l) beyond = b;
+        __syncthreads();                                    // the chunk's rows are all put away
+        if constexpr (!BEYOND) {
+            // (the outputs written so far for a flagged candidate are written again, in full, by the other instance)
+            if (found_beyond) {
+                if (t == 0) a.redo[c] = 1;
+                return;
             }
-        } else if (pending) {
-            if (lane == 0) found_beyond = 1;
         }
-        // thread t finishes the pair of job j0 + t
-        if (lane < rows) {
-            const int j = jw + lane;
+        // thread t finishes the pairs of jobs jc + t, jc + t + 256, ...
+        for (int at = t; at < chunk_jobs; at += kCandThreads) {
+            const int j = jc + at;
             const size_t pair = (size_t)c * a.J + j;
+            const int2 row = row_lds[at];
+            const int d_K = row.x, d_meta = row.y;
             const int nodes = d_meta & ~kMetaChanged;
-            Best best = beyond;
+            Best best = {0.0, -1, -1};
             if (d_K >= 1 && d_K <= kTableK) {
                 const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+            } else if (BEYOND && d_K > kTableK) {
+                const MemoEntry e = beyond_lds[at];
+                best.goodput = e.goodput; best.m = e.m; best.s = e.s;
             }
-            a.best_m[pair] = best.m;
-            a.best_s[pair] = best.s;
+            if (a.best_m) {
+                a.best_m[pair] = best.m;
+                a.best_s[pair] = best.s;
+            }
             if (a.best_goodput) a.best_goodput[pair] = best.goodput;
             // SPEEDUP (Eq. 15) with the re-allocation penalty, and the job's term of Eq. 14
             const double d = a.denom[j];
@@ -1824,14 +1867,12 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
             acc += pmean_term(s_j, wt[j], a.p);
             wsum += wt[j];
         }
+        __syncthreads();                                    // before the next chunk's rows take their places
     }
     red_acc[t] = acc;
     red_w[t] = wsum;
-    __syncthreads();                                        // the counters of all wavefronts are complete
     if constexpr (!BEYOND) {
-        // (the outputs written so far for a flagged candidate are written again, in full, by the other instance)
-        if (t == 0) a.redo[c] = found_beyond;
-        if (found_beyond) return;
+        if (t == 0) a.redo[c] = 0;
     }
     if (__ballot(any_neg) != 0ull && lane == 0) atomicOr(a.status, PX_ST_NEG_ALLOC);
 

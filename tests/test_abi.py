@@ -23,7 +23,7 @@ def test_library_exports_every_declared_symbol():
     L = px.lib()
     for n in names:
         assert getattr(L, n) is not None
-    assert px.version() == 104
+    assert px.version() == 105
     assert px.strerror(0) == "success" and "workspace" in px.strerror(px.PX_E_WORKSPACE)
     assert px.strerror(-99) == "unknown error code"
 
@@ -59,6 +59,10 @@ def test_entry_points_reject_bad_arguments_without_a_device():
     assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
     bad = list(args); bad[9] = 16
     assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_WORKSPACE
+    bad = list(args); bad[11] = null                       # best_m without best_s (args[10] is fitness)
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
+    bad = list(args); bad[12] = null
+    assert L.pollux_fitness(ctypes.byref(d), *bad) == px.PX_E_INVALID_ARG
     d0 = px.Dims(16, 8, 4, 0, 8, 0, 0)
     assert L.pollux_fitness(ctypes.byref(d0), *args) == px.PX_E_INVALID_ARG
     d_big = px.Dims(16, 8, 4, 1 << 20, 1 << 13, 0, 0)       # a job's lane-mask table would pass 2^31 bytes

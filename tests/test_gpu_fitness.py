@@ -273,8 +273,12 @@ def test_large_config_full_population_in_the_benchmark_launch_shape():
     call = px.FitnessCall(cfg.P, cfg.J, cfg.N, cfg.Gm, cfg.Gs, wl.job_params, wl.m_grid, wl.fair_share,
                           wl.current_alloc, wl.node_capacity, p=cfg.p, delta=cfg.delta)
     dpop = torch.from_numpy(pop).cuda()
-    call.run(dpop, outputs="fitness")           # as bench.py calls it: no per-pair goodput or speedup written
-    lean = {k: v.copy() for k, v in call.results().items() if k in ("fitness", "best_m", "best_s", "violations")}
+    call.run(dpop, outputs="fitness")           # as a search loop calls it: nothing per pair written
+    lean = {k: v.copy() for k, v in call.results().items() if k in ("fitness", "violations")}
+    call.run(dpop, outputs="argmax")            # as bench.py's headline loop calls it: no per-pair goodput or speedup
+    lean.update({k: v.copy() for k, v in call.results().items() if k in ("best_m", "best_s")})
+    for k in ("fitness", "violations"):
+        assert np.array_equal(lean[k], call.results()[k], equal_nan=True), k
     call.run(dpop)
     g = call.results()
     for k, v in lean.items():
@@ -309,7 +313,9 @@ def test_memoised_mode_gives_the_same_results(name):
 
 @pytest.mark.parametrize("shape", [dict(P=7, J=70, N=128, cap=2, Gm=20, Gs=6),          # a second, partly filled tile of jobs
                                    dict(P=5, J=21, N=68, cap=40, Gm=33, Gs=5),          # K beyond the memo table
-                                   dict(P=3, J=130, N=256, cap=8, Gm=64, Gs=32)])
+                                   dict(P=3, J=130, N=256, cap=8, Gm=64, Gs=32),
+                                   dict(P=3, J=1100, N=68, cap=40, Gm=8, Gs=4),          # more jobs than one finishing step takes
+                                   dict(P=2, J=2051, N=72, cap=30, Gm=5, Gs=3)])
 def test_memoised_mode_on_rows_of_65_to_256_nodes(shape):
     """These rows take the memoised pass that walks the population candidate by candidate; negative entries in a
     few rows as well (flagged, counted as they are)."""
@@ -324,6 +330,8 @@ def test_memoised_mode_on_rows_of_65_to_256_nodes(shape):
     pop[0, 1, 3] = -1
     pop[cfg.P - 1, cfg.J - 1, cfg.N - 1] = -2
     pop[cfg.P - 1, cfg.J - 1, 0] += 4
+    pop[cfg.P - 1, cfg.J - 2, 2] += 70                    # and two rows with more GPUs than the memo table covers
+    pop[1, cfg.J // 2, cfg.N - 2] += 90
     g, r = run_gpu(wl, population=pop, flags=4), run_oracle(wl, population=pop)
     assert g["status"] & 8 and r["status"] & 8
     assert compare(wl, g, r, population=pop) == 0

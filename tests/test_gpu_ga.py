@@ -244,7 +244,7 @@ def test_search_loop_in_the_benchmark_shape_matches_oracle_every_generation(flag
     mut = (1 << 32) // c.J
     first_best = None
     for gen in range(100):
-        call.run(dev, outputs="fitness", keep_job_tables=gen > 0)
+        call.run(dev, outputs="argmax", keep_job_tables=gen > 0)
         ref = run_oracle(wl, population=host)
         if gen % 10 == 0 or gen == 99:
             got = call.results()
@@ -428,3 +428,35 @@ def test_generation_call_on_the_large_configuration():
     ref = run_oracle(wl, population=sub)
     gs = {k: (v[idx] if isinstance(v, np.ndarray) else v) for k, v in got.items()}
     assert compare(wl, gs, ref, population=sub) == 0
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+@pytest.mark.parametrize("shape", [None, dict(P=12, J=70, N=128, cap=2, Gm=20, Gs=6)])
+def test_generations_that_write_fitness_only(flags, shape):
+    """A search needs only fitness: with best_m and best_s left out (NULL) the generations form the same matrices and
+    the same fitness and violation counts, and nothing is written per pair."""
+    import torch
+    import paper_2008_12260_amd as px
+    wl = W.make("physical") if shape is None else W.make(W.custom("fitness_only", **shape))
+    c = wl.cfg
+    calls, pops = [], []
+    for outputs in ("all", "fitness"):
+        call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
+                              wl.node_capacity, p=c.p, delta=c.delta, flags=flags)
+        for t in (call.best_m, call.best_s):
+            t.fill_(-7)
+        call.best_goodput.fill_(-7.0)
+        call.speedup.fill_(-7.0)
+        dev = torch.as_tensor(wl.population).cuda()
+        call.run(dev, outputs=outputs)
+        for gen in range(20):
+            call.generation(dev, SEED, gen, c.P // 2, (1 << 32) // c.J, outputs=outputs)
+        calls.append(call.results())
+        pops.append(dev.cpu().numpy())
+    assert np.array_equal(pops[0], pops[1])
+    for k in ("fitness", "violations"):
+        assert np.array_equal(calls[0][k], calls[1][k], equal_nan=True), k
+    assert calls[0]["status"] == calls[1]["status"]
+    for k in ("best_m", "best_s", "best_goodput", "speedup"):
+        assert np.all(calls[1][k] == -7), k
+    assert np.all(calls[0]["best_s"] >= -1)
