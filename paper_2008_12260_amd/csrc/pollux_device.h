@@ -89,6 +89,13 @@ __device__ __forceinline__ int row16_sum(int v)
     return v;
 }
 
+// Smallest value in the lane's row of 16 lanes, returned in every lane of that row.
+__device__ __forceinline__ unsigned row16_min(unsigned v)
+{
+    PX_DPP_ROW_REDUCE("v_min_u32_dpp", v);
+    return v;
+}
+
 __device__ __forceinline__ int wave_sum(int v)
 {
     PX_DPP_REDUCE("v_add_u32_dpp", v);

@@ -520,6 +520,73 @@ __device__ __forceinline__ double sweep_chunk_plain(double tg, double A0s, doubl
     return kmin;
 }
 
+// The accumulation count with the smallest w(s) = s + C / (s + 1) among s = 0, 1, ... (all counts of the grid,
+// rounded up to whole chunks: the reciprocals are padded), equal values to the lower count, for the lane's own C >= 0.
+// near: a copy of the reciprocals in LDS with the thresholds U[t] = t (t+1) behind them, when has_near.
+template <int CH>
+__device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDoubles rsc, int Gs, LdsDoubles near, bool has_near)
+{
+    // the argmin of w over all counts (its group of four, where keys carry groups): low bits of the smallest key, chunk by chunk
+    double wmin = scan_chunk<CH>(C, X, rsc);
+    constexpr int kPerTag = grouped_tags(CH) ? 4 : 1;
+    int g_star = __double2loint(wmin) & 31;
+    for (int s0 = CH; s0 < Gs; s0 += CH) {
+        const double w = scan_chunk<CH>(C, X, rsc + s0);
+        const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
+        if (moved < wmin) {
+            wmin = moved;
+            g_star = s0 / kPerTag + (__double2loint(w) & 31);
+        }
+    }
+    // The keys of the scan carry index bits in their low mantissa bits, so what the scan has found is the
+    // argmin up to values that agree to 2^-47; w is convex, so only neighbouring counts can agree that
+    // closely, and the true argmin lies next to what the scan found.  The order of neighbours is known
+    // exactly: w(s+1) < w(s) precisely when C > (s+1)(s+2), both sides exact in fp64.  With
+    // U[t] = t (t+1) (U[0] = -1, so that the result never falls below 0) the argmin over all counts is the
+    // number of t >= 0 with C > U[t], less one; only the t around the scan's result need to be looked at.
+    int s_star;
+    if constexpr (grouped_tags(CH)) {
+        // the scan names a group of four counts 4 g .. 4 g + 3: the argmin is 4 g - 1 plus the number of
+        // t = 4 g .. 4 g + 4 with C > U[t]
+        const int t0 = 4 * g_star;
+        s_star = t0 - 1;
+        if (has_near) {
+            // two, two and one at a time, each read issued after the previous comparison (the opaque
+            // statements tie the address to the running count): five values held at once would cost
+            // the kernel registers it does not have
+            LdsDoubles u = near + kNearRecips + t0;
+            const Double2 a01 = *(const Double2 __attribute__((address_space(3))) *)u;
+            s_star += (C > a01.x ? 1 : 0) + (C > a01.y ? 1 : 0);
+            asm volatile("" : "+v"(s_star), "+v"(u));
+            const Double2 a23 = *(const Double2 __attribute__((address_space(3))) *)(u + 2);
+            s_star += (C > a23.x ? 1 : 0) + (C > a23.y ? 1 : 0);
+            asm volatile("" : "+v"(s_star), "+v"(u));
+            s_star += C > u[4] ? 1 : 0;
+        } else {
+            const double td = (double)t0;
+            s_star += (C > (t0 > 0 ? px_fma(td, td, td) : -1.0) ? 1 : 0);
+            s_star += (C > px_fma(td, td, px_fma(3.0, td, 2.0)) ? 1 : 0);
+            s_star += (C > px_fma(td, td, px_fma(5.0, td, 6.0)) ? 1 : 0);
+            s_star += (C > px_fma(td, td, px_fma(7.0, td, 12.0)) ? 1 : 0);
+            s_star += (C > px_fma(td, td, px_fma(9.0, td, 20.0)) ? 1 : 0);
+        }
+    } else {
+        // the scan names a count: one step down or up if its neighbour is better
+        s_star = g_star;
+        double t_lo, t_hi;
+        if (has_near) {
+            t_lo = near[kNearRecips + s_star];
+            t_hi = near[kNearRecips + s_star + 1];
+        } else {
+            const double sd = (double)s_star;
+            t_lo = s_star > 0 ? px_fma(sd, sd, sd) : -1.0;
+            t_hi = px_fma(sd, sd, px_fma(3.0, sd, 2.0));
+        }
+        s_star = C <= t_lo ? s_star - 1 : (C > t_hi ? s_star + 1 : s_star);
+    }
+    return s_star;
+}
+
 // The grid point a sweep elects: index into the job's batch-size grid and accumulation
 // count; i = -1 when no point is feasible.
 struct Pick {
@@ -575,65 +642,8 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active && s_lo <= s_hi;
-            // the argmin of w over all counts (its group of four, where keys carry groups): low bits of the smallest key, chunk by chunk
             const double C = B0 * tgr.y;
-            double wmin = scan_chunk<CH>(C, X, rsc);
-            constexpr int kPerTag = grouped_tags(CH) ? 4 : 1;
-            int g_star = __double2loint(wmin) & 31;
-            for (int s0 = CH; s0 < Gs; s0 += CH) {
-                const double w = scan_chunk<CH>(C, X, rsc + s0);
-                const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
-                if (moved < wmin) {
-                    wmin = moved;
-                    g_star = s0 / kPerTag + (__double2loint(w) & 31);
-                }
-            }
-            // The keys of the scan carry index bits in their low mantissa bits, so what the scan has found is the
-            // argmin up to values that agree to 2^-47; w is convex, so only neighbouring counts can agree that
-            // closely, and the true argmin lies next to what the scan found.  The order of neighbours is known
-            // exactly: w(s+1) < w(s) precisely when C > (s+1)(s+2), both sides exact in fp64.  With
-            // U[t] = t (t+1) (U[0] = -1, so that the result never falls below 0) the argmin over all counts is the
-            // number of t >= 0 with C > U[t], less one; only the t around the scan's result need to be looked at.
-            int s_star;
-            if constexpr (grouped_tags(CH)) {
-                // the scan names a group of four counts 4 g .. 4 g + 3: the argmin is 4 g - 1 plus the number of
-                // t = 4 g .. 4 g + 4 with C > U[t]
-                const int t0 = 4 * g_star;
-                s_star = t0 - 1;
-                if (has_near) {
-                    // two, two and one at a time, each read issued after the previous comparison (the opaque
-                    // statements tie the address to the running count): five values held at once would cost
-                    // the kernel registers it does not have
-                    LdsDoubles u = near + kNearRecips + t0;
-                    const Double2 a01 = *(const Double2 __attribute__((address_space(3))) *)u;
-                    s_star += (C > a01.x ? 1 : 0) + (C > a01.y ? 1 : 0);
-                    asm volatile("" : "+v"(s_star), "+v"(u));
-                    const Double2 a23 = *(const Double2 __attribute__((address_space(3))) *)(u + 2);
-                    s_star += (C > a23.x ? 1 : 0) + (C > a23.y ? 1 : 0);
-                    asm volatile("" : "+v"(s_star), "+v"(u));
-                    s_star += C > u[4] ? 1 : 0;
-                } else {
-                    const double td = (double)t0;
-                    s_star += (C > (t0 > 0 ? px_fma(td, td, td) : -1.0) ? 1 : 0);
-                    s_star += (C > px_fma(td, td, px_fma(3.0, td, 2.0)) ? 1 : 0);
-                    s_star += (C > px_fma(td, td, px_fma(5.0, td, 6.0)) ? 1 : 0);
-                    s_star += (C > px_fma(td, td, px_fma(7.0, td, 12.0)) ? 1 : 0);
-                    s_star += (C > px_fma(td, td, px_fma(9.0, td, 20.0)) ? 1 : 0);
-                }
-            } else {
-                // the scan names a count: one step down or up if its neighbour is better
-                s_star = g_star;
-                double t_lo, t_hi;
-                if (has_near) {
-                    t_lo = near[kNearRecips + s_star];
-                    t_hi = near[kNearRecips + s_star + 1];
-                } else {
-                    const double sd = (double)s_star;
-                    t_lo = s_star > 0 ? px_fma(sd, sd, sd) : -1.0;
-                    t_hi = px_fma(sd, sd, px_fma(3.0, sd, 2.0));
-                }
-                s_star = C <= t_lo ? s_star - 1 : (C > t_hi ? s_star + 1 : s_star);
-            }
+            const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
@@ -696,6 +706,61 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     const int wl = __ffsll(winners) - 1;
     const int wwhere = __builtin_amdgcn_readlane(where, wl);
     return Pick{(wwhere >> 16) * kWave + wl, wwhere & 0xFFFF};
+}
+
+// The same election for four (job, K, nodes) at once, one per row of 16 lanes, for small grids, where a sweep per
+// wavefront spends more on its cross-lane steps than on the grid: every row of 16 lanes calls this with its own
+// K (1 .. kTableK) and its own one_node (the same in all 16 lanes of a row; the job is the same for the whole
+// wavefront), lane l of a row takes batch sizes l, l + 16, ..., and every lane of a row returns the row's
+// result: (i << 16) | s of the feasible point with the smallest h, equal values to the lowest (i, s), or -1 when
+// the row has no feasible point.  Per (K, batch size) the arithmetic is that of sweep_pick, instruction for
+// instruction, so both elect the same point.
+template <int CH>
+__device__ __forceinline__ int sweep_pick_rows(const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
+                                               const double *__restrict__ rk, int Gm, int Gs, int K, bool one_node,
+                                               LdsDoubles near, bool has_near)
+{
+    const int l16 = lane_id() & 15;
+    const double rK = rk[K];                              // kTableK < kRecipTable
+    // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
+    const unsigned lrow = (unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm;
+    const unsigned srow = (unsigned)(K - 1) * (unsigned)Gm;
+    double kbest = __builtin_inf();   // smallest h seen by this lane
+    int where = 0;                    // its (i << 16) | s
+    const ScalarDoubles rsc = (ScalarDoubles)rs;
+    for (int i0 = 0; i0 < Gm; i0 += 16) {
+        const int i = i0 + l16;
+        const bool active = i < Gm;
+        const unsigned il = (unsigned)(active ? i : Gm - 1);
+        const double2 tgr = tb.tg[il];
+        const double tg = tgr.x;
+        const double last = tb.lt[lrow + il];
+        const double u = tb.pu[il] * rK;
+        const double A0 = px_fma(u, tg, last);
+        const double B0 = (last - tg) * u;
+        const int bounds = tb.srange[srow + il];
+        const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
+        const bool feasible = active && s_lo <= s_hi;
+        const double C = B0 * tgr.y;
+        const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
+        // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
+        int s_c = s_star < s_hi ? s_star : s_hi;
+        s_c = s_c > s_lo ? s_c : s_lo;
+        const double r_c = has_near ? near[s_c] : rs[s_c];
+        const double w_c = px_fma(C, r_c, (double)s_c);
+        const double key = px_fma(tg, w_c, A0);
+        if (feasible && key < kbest) {
+            kbest = key;
+            where = (i << 16) | s_c;
+        }
+    }
+    // Positive doubles order like their bit patterns: three unsigned minima over the row, the high words, the
+    // low words among the lanes that hold the smallest high word, and (i, s) among the lanes that hold both.
+    const unsigned hi = (unsigned)__double2hiint(kbest), lo = (unsigned)__double2loint(kbest);
+    const unsigned hmin = row16_min(hi);
+    const unsigned lmin = row16_min(hi == hmin ? lo : 0xFFFFFFFFu);
+    const unsigned first = row16_min(hi == hmin && lo == lmin ? (unsigned)where : 0x7FFFFFFFu);
+    return hmin >= 0x7FF00000u ? -1 : (int)first;             // every lane of the row still holds +inf: no point
 }
 
 template <int CH>
@@ -1399,7 +1464,35 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         // after the row pass, whose rows in flight use the registers these occupy
         if constexpr (F32) XF = make_run_steps_f32();
         else X = make_run_steps();
-        for (int r = 0; r < rows; ++r) {
+        // Short rows come with small grids: there the sweeps go four candidates at a time, one per row of 16 lanes.
+        constexpr bool kRows = ROW4 && !F32 && !MEMO && CH <= 16;
+        if constexpr (kRows) {
+            const int g = lane >> 4;
+            for (int b = 0; 4 * b < rows; ++b) {
+                // lane r holds K and nodes of candidate r; this lane's row works on candidate 4 b + g
+                const int r = 4 * b + g;
+                const int K = __builtin_amdgcn_ds_bpermute(r << 2, d_K);
+                const int nodes = __builtin_amdgcn_ds_bpermute(r << 2, d_meta) & ~kMetaChanged;
+                const int K_in = K < 1 ? 1 : (K > kTableK ? kTableK : K);
+                const int found = sweep_pick_rows<CH>(tb, X, a.rs, a.rk, a.Gm, a.Gs, K_in, nodes == 1, (LdsDoubles)r_lds, has_near);
+                int pi = found < 0 ? -1 : found >> 16, ps = found < 0 ? -1 : found & 0xFFFF;
+                if (K > kTableK) {                           // rare: swept after the loop, outside the hot path
+                    pi = kPending;
+                    ps = -1;
+                } else if (K < 1 || r >= rows) {
+                    pi = -1;
+                    ps = -1;
+                }
+                // lane 4 b + g' takes over what row g' has found
+                const int from = ((lane & 3) * 16) << 2;
+                const int ti = __builtin_amdgcn_ds_bpermute(from, pi), ts = __builtin_amdgcn_ds_bpermute(from, ps);
+                if ((lane >> 2) == b) {
+                    d_i = ti;
+                    d_s = ts;
+                }
+            }
+        }
+        for (int r = 0; !kRows && r < rows; ++r) {
             const int K = __builtin_amdgcn_readlane(d_K, r);
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
