@@ -8,6 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpollux_hip.so")
+BUILD_INFO = LIB + ".buildinfo"     # one line: the compiler that built LIB (written beside it, read by bench.py)
 SOURCES = ["pollux_api.hip", "pollux_fitness.hip", "pollux_ga.hip", "pollux_theta.hip"]
 
 HIPCC_FLAGS = [
@@ -39,8 +40,10 @@ def build(verbose: bool = False, save_temps: str | None = None) -> str:
         print(f"({len(lines) - len(other)} host-pass notices about -packed-fp32-ops dropped)", flush=True)
     if run.returncode != 0:
         raise subprocess.CalledProcessError(run.returncode, cmd)
+    version = subprocess.run([hipcc, "--version"], capture_output=True, text=True).stdout.splitlines()
+    with open(BUILD_INFO, "w") as f:
+        f.write("; ".join(v for v in version[:2]) + "\n")
     if verbose:
-        version = subprocess.run([hipcc, "--version"], capture_output=True, text=True).stdout.splitlines()
         print("compiler:", "; ".join(v for v in version[:2]), flush=True)
     return LIB
 
