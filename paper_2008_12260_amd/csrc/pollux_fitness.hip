@@ -2145,7 +2145,11 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     // The per-node counters start every call at zero.  A call that uses them leaves them at zero again
     // (candidates_kernel clears what it reads), so a call that keeps the job tables, whose caller guarantees an
     // untouched workspace and unchanged dimensions, does not clear them once more.
-    if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
+    const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
+    const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
+    // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, counters in LDS, fitness included
+    const bool candidate_pass = memo && !sampled && !f32 && row1 && !row4;
+    if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES) && !candidate_pass) {
         long long zb = ((long long)d->P * d->N + 255) / 256;
         hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
     }
@@ -2170,9 +2174,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         }
     }
     if (sweep_start) (void)hipEventRecord(sweep_start, stream);
-    const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool whole = d->Gm % kWave == 0;
-    const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
 #define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4)                                                               \
     do {                                                                                                                \
         if (a.sel) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
@@ -2189,8 +2191,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         else if (row1) PX_LAUNCH_PAIRS(CH, F32, false, true, false, false);    \
         else PX_LAUNCH_PAIRS(CH, F32, false, false, false, false);             \
     } while (0)
-    if (memo && !sampled && !f32 && row1 && !row4) {
-        // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, fitness included
+    if (candidate_pass) {
         const dim3 memo_grid((unsigned)P_eff);
 #define PX_LAUNCH_MEMO_CANDIDATES(CH)                                                                                 \
     do {                                                                                                              \
