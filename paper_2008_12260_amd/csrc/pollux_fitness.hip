@@ -1204,8 +1204,13 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // (16 lanes each); cand_per_wave is at most 16.
 // SEL: only the candidates listed in a.sel are evaluated (the children a search step has just formed); the
 // wavefronts then walk positions of that list and look the candidate up where an address is formed.
+// Eight wavefronts per SIMD (64 registers); the instances that sweep four candidates at a time (rows_at_a_time)
+// take six (80 registers), which is what they need without spilling, and are no slower for it.
+constexpr bool rows_at_a_time(int CH, bool F32, bool MEMO, bool ROW4) { return ROW4 && !F32 && !MEMO && CH != 0 && CH <= 16; }
+
 template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false, bool SEL = false>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) pairs_kernel(FitnessArgs a)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(rows_at_a_time(CH, F32, MEMO, ROW4) ? 6 : 8)))
+pairs_kernel(FitnessArgs a)
 {
     const int xcd = blockIdx.x & 7, slot = blockIdx.x >> 3;
     const int j = (slot / a.cand_groups) * 8 + xcd;
@@ -1465,7 +1470,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(8))) p
         if constexpr (F32) XF = make_run_steps_f32();
         else X = make_run_steps();
         // Short rows come with small grids: there the sweeps go four candidates at a time, one per row of 16 lanes.
-        constexpr bool kRows = ROW4 && !F32 && !MEMO && CH <= 16;
+        constexpr bool kRows = rows_at_a_time(CH, F32, MEMO, ROW4);
         if constexpr (kRows) {
             const int g = lane >> 4;
             for (int b = 0; 4 * b < rows; ++b) {
