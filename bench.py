@@ -36,12 +36,12 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "9c70abd79909579c9225f83ba5f9d0a645b0d8c34c61d198ae1b59bcee20edf1",
-        "traffic_bytes": 2_068_600 * 1024 * 2 + 697_760 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "source_sha256": "68e135eecc66cc1f362088ac9b491040cb7a41f8d15a8b9abbf1e1a12e8122fa",
+        "traffic_bytes": 2_068_696 * 1024 * 2 + 649_763 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
         "fp64_flops": 64 * (8.8881e6 + 4.1625e7 + 2 * 2.7480e8),
-        "valu_insts": 1.1032e9,
+        "valu_insts": 1.1030e9,
         "scan_insts": 2.25 * 1.6777e10 / 64,
-        "valu_busy": 1.1172e9 * 4 / 1024 / (3.9478e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+        "valu_busy": 1.1170e9 * 4 / 1024 / (3.9944e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
     },
 }
 GA_SEED = 0x2008_1226_5EED_0001
