@@ -210,7 +210,7 @@ int pollux_fitness_timed(const pollux_dims *dims, const int32_t *population, con
  * (pollux_last_status does not apply: there is no workspace to name).
  * All other arguments, results and error codes as for pollux_fitness.
  */
-#define POLLUX_STATIC_SCRATCH_BYTES (32u << 20)
+#define POLLUX_STATIC_SCRATCH_BYTES (64u << 20)
 int pollux_fitness_static(const pollux_dims *dims,       /* host */
                           const int32_t *population,     /* [P,J,N] */
                           const double *job_params,      /* [PX_NPARAM,J] */

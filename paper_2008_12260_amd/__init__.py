@@ -129,7 +129,7 @@ def pollux_fitness(dims: Dims, population, job_params, m_grid, fair_share, curre
         raise PolluxError(rc, "pollux_fitness")
 
 
-STATIC_SCRATCH_BYTES = 32 << 20
+STATIC_SCRATCH_BYTES = 64 << 20
 
 
 def pollux_fitness_static(dims: Dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity,

@@ -90,6 +90,7 @@ struct FitnessArgs {
     double *rs, *rk, *lntg, *pu, *qh5, *ql5, *lt, *denom, *factor, *G;
     float *rsf;                   // 1/(s+1) in fp32, as long as rs
     double2 *tg;                  // [J,Gm] (T_grad, 1 / T_grad)
+    double2 *ca;                  // [J,2,kTableK,Gm] (C, A0) of the sweep per (job, one node?, K, grid point) (see last_kernel)
     int32_t *srange;              // [J,kTableK,Gm] feasible accumulation counts per (job, K, grid point) (see last_kernel)
     int gs_pad;                   // Gs rounded up to a multiple of 32: length of rs
     int32_t *running, *meta;
@@ -247,6 +248,10 @@ __device__ __forceinline__ void feasible_range(double ql5, double qh5, double rK
 // prepares T_sync and its logarithm for the r-th of them.  The rows of the "several nodes"
 // class also write the feasible accumulation counts of (job, K, i), which do not depend on
 // the class: srange[j][K-1][i] = first | last << 16, first > last when there is none.
+// Beside lt[row][i] the wavefront writes ca[row][i] = (C, A0), the two terms the sweep needs of (job, class, K, i):
+//     h(m_i, s) = A0 + T_grad (s + C / (s + 1)),   u = phi / (K m_i),   A0 = last + u T_grad,   C = (last - T_grad) u / T_grad,
+// formed here once instead of by every (candidate, job) pair; A0 = +inf where no accumulation count is feasible, so
+// such a batch size never wins an election.
 constexpr int kLastRows = 8;
 static_assert(kTableK % kLastRows == 0, "the rows of a wavefront belong to one job and class");
 
@@ -275,22 +280,29 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
         t[r].inv_gamma = mine.inv_gamma;
         t[r].mode = __builtin_amdgcn_readlane(mine.mode, r);
     }
-    const size_t o = (size_t)j * a.Gm;
-    for (int i = lane; i < a.Gm; i += kWave) {
-        const double tg = a.tg[o + i].x, lntg = a.lntg[o + i];
+    double rK[kLastRows];
 #pragma unroll
-        for (int r = 0; r < kLastRows; ++r) a.lt[(size_t)(row0 + r) * a.Gm + i] = last_pass(t[r], tg, lntg);
-    }
-    if (one_node) return;
+    for (int r = 0; r < kLastRows; ++r) rK[r] = a.rk[K0 + r];
+    const size_t o = (size_t)j * a.Gm;
     int32_t *__restrict__ out = a.srange + ((size_t)j * kTableK + (size_t)(K0 - 1)) * a.Gm;
     for (int i = lane; i < a.Gm; i += kWave) {
+        const double2 tgr = a.tg[o + i];
+        const double tg = tgr.x, lntg = a.lntg[o + i], pu = a.pu[o + i];
         const double ql5 = a.ql5[o + i], qh5 = a.qh5[o + i];
 #pragma unroll
         for (int r = 0; r < kLastRows; ++r) {
+            const double last = last_pass(t[r], tg, lntg);
+            a.lt[(size_t)(row0 + r) * a.Gm + i] = last;
             int s_lo, s_hi;
-            feasible_range(ql5, qh5, a.rk[K0 + r], a.Gs, s_lo, s_hi);
-            if (s_lo > s_hi || s_hi < 0) { s_lo = 1; s_hi = 0; }
-            out[(size_t)r * a.Gm + i] = s_lo | (s_hi << 16);
+            feasible_range(ql5, qh5, rK[r], a.Gs, s_lo, s_hi);
+            const bool none = s_lo > s_hi || s_hi < 0;
+            if (none) { s_lo = 1; s_hi = 0; }
+            if (!one_node) out[(size_t)r * a.Gm + i] = s_lo | (s_hi << 16);
+            // what the sweep needs of (job, class, K, i): h(m_i, s) = A0 + T_grad (s + C / (s+1))
+            const double u = pu * rK[r];
+            const double A0 = px_fma(u, tg, last);
+            const double B0 = (last - tg) * u;
+            a.ca[(size_t)(row0 + r) * a.Gm + i] = double2{B0 * tgr.y, none ? __builtin_inf() : A0};
         }
     }
 }
@@ -307,6 +319,7 @@ struct JobTables {
     const double2 *__restrict__ tg;   // (T_grad, 1 / T_grad)
     const double *__restrict__ lntg, *__restrict__ pu, *__restrict__ qh5, *__restrict__ ql5;
     const double *__restrict__ lt;    // rows of this job in the last-pass table
+    const double2 *__restrict__ ca;   // rows of this job in the table of (C, A0)
     const int32_t *__restrict__ srange;   // feasible accumulation counts of this job, [kTableK, Gm]
 };
 
@@ -611,7 +624,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     const double rK = K < kRecipTable ? ((ScalarDoubles)rk)[K] : 1.0 / (double)K;
     const bool one_node = nodes == 1;
     // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
-    const double *__restrict__ lrow = tb.lt + (unsigned)((one_node ? kTableK : 0) + (TABLED ? K - 1 : 0)) * (unsigned)Gm;
+    const double2 *__restrict__ carow = tb.ca + (unsigned)((one_node ? kTableK : 0) + (TABLED ? K - 1 : 0)) * (unsigned)Gm;
     const int32_t *__restrict__ srow = tb.srange + (unsigned)(TABLED ? K - 1 : 0) * (unsigned)Gm;
     SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
@@ -627,22 +640,16 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const int il = active ? i : Gm - 1;
         // a uniform base plus a 32-bit byte offset per lane: the address needs no 64-bit vector arithmetic
         const unsigned at = (unsigned)il * 8u;
-        const double2 tgr = *(const double2 *)((const char *)tb.tg + 2u * at);
-        const double tg = tgr.x;
-        double last;
-        if constexpr (TABLED) last = *(const double *)((const char *)lrow + at);
-        else last = last_pass(st, tg, tb.lntg[il]);
-        const double u = *(const double *)((const char *)tb.pu + at) * rK;
-        const double A0 = px_fma(u, tg, last);
-        const double B0 = (last - tg) * u;
         double key = __builtin_inf();    // h of this batch size at its best feasible count s_c
         int s_c = 0;
         bool feasible;
         if constexpr (TABLED) {
+            const double tg = *(const double *)((const char *)tb.tg + 2u * at);
+            const double2 car = *(const double2 *)((const char *)carow + 2u * at);
+            const double C = car.x, A0 = car.y;     // A0 = +inf when the batch size has no feasible count
             const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
-            feasible = active && s_lo <= s_hi;
-            const double C = B0 * tgr.y;
+            feasible = active;
             const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
@@ -651,6 +658,12 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             const double w_c = px_fma(C, r_c, (double)s_c);
             key = px_fma(tg, w_c, A0);
         } else {
+            const double2 tgr = *(const double2 *)((const char *)tb.tg + 2u * at);
+            const double tg = tgr.x;
+            const double last = last_pass(st, tg, tb.lntg[il]);
+            const double u = *(const double *)((const char *)tb.pu + at) * rK;
+            const double A0 = px_fma(u, tg, last);
+            const double B0 = (last - tg) * u;
             int s_lo = 1, s_hi = 0;
             feasible_range(tb.ql5[il], tb.qh5[il], rK, Gs, s_lo, s_hi);
             if (!active) s_hi = -1;
@@ -721,7 +734,6 @@ __device__ __forceinline__ int sweep_pick_rows(const JobTables &tb, const RunSte
                                                LdsDoubles near, bool has_near)
 {
     const int l16 = lane_id() & 15;
-    const double rK = rk[K];                              // kTableK < kRecipTable
     // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
     const unsigned lrow = (unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm;
     const unsigned srow = (unsigned)(K - 1) * (unsigned)Gm;
@@ -730,18 +742,13 @@ __device__ __forceinline__ int sweep_pick_rows(const JobTables &tb, const RunSte
     const ScalarDoubles rsc = (ScalarDoubles)rs;
     for (int i0 = 0; i0 < Gm; i0 += 16) {
         const int i = i0 + l16;
-        const bool active = i < Gm;
-        const unsigned il = (unsigned)(active ? i : Gm - 1);
-        const double2 tgr = tb.tg[il];
-        const double tg = tgr.x;
-        const double last = tb.lt[lrow + il];
-        const double u = tb.pu[il] * rK;
-        const double A0 = px_fma(u, tg, last);
-        const double B0 = (last - tg) * u;
+        const bool feasible = i < Gm;
+        const unsigned il = (unsigned)(feasible ? i : Gm - 1);
+        const double tg = tb.tg[il].x;
+        const double2 car = tb.ca[lrow + il];
+        const double C = car.x, A0 = car.y;         // A0 = +inf when the batch size has no feasible count
         const int bounds = tb.srange[srow + il];
         const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
-        const bool feasible = active && s_lo <= s_hi;
-        const double C = B0 * tgr.y;
         const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
         // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
         int s_c = s_star < s_hi ? s_star : s_hi;
@@ -801,7 +808,8 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 {
     const size_t o = (size_t)j * a.Gm;
     return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
-                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.srange + (size_t)j * kTableK * a.Gm};
+                     a.lt + (size_t)j * 2 * kTableK * a.Gm, a.ca + (size_t)j * 2 * kTableK * a.Gm,
+                     a.srange + (size_t)j * kTableK * a.Gm};
 }
 
 // ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
@@ -2028,6 +2036,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     a.qh5 = (double *)(ws + L.qh5);
     a.ql5 = (double *)(ws + L.ql5);
     a.lt = (double *)(ws + L.lt);
+    a.ca = (double2 *)(ws + L.ca);
     a.srange = (int32_t *)(ws + L.srange);
     a.gs_pad = ((d->Gs + 31) / 32) * 32;
     return a;

@@ -40,6 +40,7 @@ struct WorkspaceLayout {
     size_t qh5;       // double [J,Gm]    floor(M_max / m_i) + 1/2
     size_t ql5;       // double [J,Gm]    ceil(M0 / m_i) - 1/2
     size_t lt;        // double [J,2,kTableK,Gm]  last pass of Eq. 10 by (job, one node?, K)
+    size_t ca;        // double [J,2,kTableK,Gm,2]  the sweep's (C, A0) by (job, one node?, K, grid point)
     size_t srange;    // int32  [J,kTableK,Gm]  feasible accumulation counts of grid point i with K GPUs:
                       //                  first | last << 16 (first > last: none)
     size_t total;
@@ -72,6 +73,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.qh5 = o;     o = up(o + 8 * J * Gm);
     L.ql5 = o;     o = up(o + 8 * J * Gm);
     L.lt = o;      o = up(o + 8 * J * 2 * kTableK * Gm);
+    L.ca = o;      o = up(o + 16 * J * 2 * kTableK * Gm);
     L.srange = o;  o = up(o + 4 * J * kTableK * Gm);
     L.total = o;
     return L;
