@@ -260,6 +260,9 @@ class FitnessCall:
         assert self.fair_share.shape == (J, 2) and self.current_alloc.shape == (J, N) and self.node_capacity.shape == (N,)
         self.workspace = torch.empty(workspace_size(self.dims), dtype=torch.uint8, device=dev)
         assert self.workspace.data_ptr() % 256 == 0
+        if os.environ.get("POLLUX_POISON_WORKSPACE"):
+            # for tests: nothing in the library may depend on what a fresh workspace holds (0xFF bytes read as NaN / -1)
+            self.workspace.fill_(0xFF)
         self.fitness = torch.empty(P, dtype=torch.float64, device=dev)
         self.best_m = torch.empty((P, J), dtype=torch.int32, device=dev)
         self.best_s = torch.empty((P, J), dtype=torch.int32, device=dev)

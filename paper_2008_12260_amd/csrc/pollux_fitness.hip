@@ -92,6 +92,7 @@ struct FitnessArgs {
     double2 *tg;                  // [J,Gm] (T_grad, 1 / T_grad)
     double2 *ca;                  // [J,2,kTableK,Gm] (C, A0) of the sweep per (job, one node?, K, grid point) (see last_kernel)
     int32_t *srange;              // [J,kTableK,Gm] feasible accumulation counts per (job, K, grid point) (see last_kernel)
+    int32_t *k1;                  // one word: the rows of the "one node" class are tabled for K <= *k1 only (tables_kernel)
     int gs_pad;                   // Gs rounded up to a multiple of 32: length of rs
     int32_t *running, *meta;
     MemoEntry *memo;              // [J,2,kTableK] best point per (job, one node?, K), memoised mode only
@@ -160,6 +161,26 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
 {
     const int t = blockIdx.x * blockDim.x + threadIdx.x;
     if (t == 0 && a.clear_status) *a.status = 0;
+    if (blockIdx.x == 0) {
+        // A job that sits on one node holds at most that node's GPUs, so the tables of the "one node" class stop at
+        // the largest capacity (all of kTableK when the call names no capacities); a row that claims more on one
+        // node, which no valid allocation does, is swept in place like a row beyond the tables.
+        __shared__ int cap_lds[256];
+        int c = 0;
+        if (a.node_capacity) {
+            for (int n = threadIdx.x; n < a.N; n += 256) {
+                const int v = a.node_capacity[n];
+                c = v > c ? v : c;
+            }
+        }
+        cap_lds[threadIdx.x] = c;
+        __syncthreads();
+        for (int half = 128; half > 0; half >>= 1) {
+            if ((int)threadIdx.x < half) cap_lds[threadIdx.x] = cap_lds[threadIdx.x] > cap_lds[threadIdx.x + half] ? cap_lds[threadIdx.x] : cap_lds[threadIdx.x + half];
+            __syncthreads();
+        }
+        if (threadIdx.x == 0) *a.k1 = (a.node_capacity && cap_lds[0] < kTableK) ? cap_lds[0] : kTableK;
+    }
     const int rs_len = ((a.Gs + 31) / 32) * 32;
     if (t < rs_len) {
         a.rs[t] = 1.0 / (double)(t + 1);
@@ -243,6 +264,12 @@ __device__ __forceinline__ void feasible_range(double ql5, double qh5, double rK
     s_hi = s_hi < Gs - 1 ? s_hi : Gs - 1;
 }
 
+// Whether the tables hold the row of (K, class): K = 1 .. kTableK for several nodes, 1 .. k1 for one node.
+__device__ __forceinline__ bool tabled_row(int K, bool one_node, int k1)
+{
+    return K <= (one_node ? k1 : kTableK);
+}
+
 // lt[row][i] for every grid point i, row index ((j * 2 + one_node) * kTableK + (K - 1)).
 // One wavefront fills kLastRows rows of one (job, placement class): their inputs are read once and lane r
 // prepares T_sync and its logarithm for the r-th of them.  The rows of the "several nodes"
@@ -268,6 +295,7 @@ __global__ void __launch_bounds__(256) last_kernel(FitnessArgs a)
     const int K0 = (int)(row0 % kTableK) + 1;
     const bool one_node = ((row0 / kTableK) & 1) != 0;
     const int j = (int)(row0 / (2 * kTableK));
+    if (one_node && K0 > *a.k1) return;             // no row of this wavefront is ever looked up
     const Job q = load_job(a.job_params, a.J, j);
     const int lane = lane_id();
     const SyncTerm mine = sync_term(q, K0 + (lane < kLastRows ? lane : 0), one_node);
@@ -321,6 +349,7 @@ struct JobTables {
     const double *__restrict__ lt;    // rows of this job in the last-pass table
     const double2 *__restrict__ ca;   // rows of this job in the table of (C, A0)
     const int32_t *__restrict__ srange;   // feasible accumulation counts of this job, [kTableK, Gm]
+    int k1;                               // rows of the "one node" class are tabled for K <= k1
 };
 
 // Wave-wide argmax of non-negative goodput values g (0 = the lane has no point): positive
@@ -778,7 +807,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     nodes = __builtin_amdgcn_readfirstlane(nodes);
     if (K <= 0) return Pick{-1, -1};
     const RunSteps X = make_run_steps();
-    if (K <= kTableK) return sweep_pick<CH, true>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
+    if (tabled_row(K, nodes == 1, tb.k1)) return sweep_pick<CH, true>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
     return sweep_pick<CH, false>(q, tb, X, rs, rk, Gm, Gs, K, nodes);
 }
 
@@ -790,7 +819,7 @@ __device__ __forceinline__ Best price_point(const Job &q, const JobTables &tb, i
     const int m = tb.m[i];
     const double tg = tb.tg[i].x;
     double last;
-    if (K <= kTableK) last = tb.lt[(unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm + (unsigned)i];
+    if (tabled_row(K, one_node, tb.k1)) last = tb.lt[(unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm + (unsigned)i];
     else last = last_pass(sync_term(q, K, one_node), tg, tb.lntg[i]);
     return Best{goodput_point(q, (double)K * (double)m, tg, last, s), m, s};
 }
@@ -809,7 +838,7 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
     const size_t o = (size_t)j * a.Gm;
     return JobTables{a.m_grid + o, a.tg + o, a.lntg + o, a.pu + o, a.qh5 + o, a.ql5 + o,
                      a.lt + (size_t)j * 2 * kTableK * a.Gm, a.ca + (size_t)j * 2 * kTableK * a.Gm,
-                     a.srange + (size_t)j * kTableK * a.Gm};
+                     a.srange + (size_t)j * kTableK * a.Gm, __builtin_amdgcn_readfirstlane(*a.k1)};
 }
 
 // ---- argmax by sampling total batch sizes (Sec. 4.3) -------------------------------
@@ -892,7 +921,7 @@ __device__ __forceinline__ Best sweep_f32(const JobF32 &q, const JobTables &tb, 
     float ts = 0.0f;                                                          // Eq. 9
     if (K > 1) ts = (nodes == 1) ? q.alpha_sl + q.beta_sl * (float)(K - 2) : q.alpha_sn + q.beta_sn * (float)(K - 2);
     // Eq. 10 for K within the tables: the fp64 table of last_kernel, rounded to fp32 (two powf per batch size otherwise)
-    const bool tabled = K <= kTableK;
+    const bool tabled = tabled_row(K, nodes == 1, tb.k1);
     const double *__restrict__ lrow = tb.lt + (unsigned)((nodes == 1 ? kTableK : 0) + (tabled ? K - 1 : 0)) * (unsigned)Gm;
     const float tsg = (!tabled && ts != 0.0f && q.gamma != 1.0f) ? powf(ts, q.gamma) : 0.0f;
 
@@ -1098,7 +1127,7 @@ __device__ __forceinline__ Best sweep_any_f32(const JobF32 &q, const JobTables &
     K = __builtin_amdgcn_readfirstlane(K);
     nodes = __builtin_amdgcn_readfirstlane(nodes);
     if (K <= 0) return Best{0.0, -1, -1};
-    if (K > kTableK) return sweep_f32(q, tb, rk, Gm, Gs, K, nodes);
+    if (!tabled_row(K, nodes == 1, tb.k1)) return sweep_f32(q, tb, rk, Gm, Gs, K, nodes);
     const Pick pick = sweep_pick_f32<CH, false>(q, tb, make_run_steps_f32(), rsf, Gm, Gs, K, nodes);
     return price_point_f32(q, tb, Gm, K, nodes == 1, pick.i, pick.s);
 }
@@ -1188,6 +1217,7 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
     const int K = (int)(row % kTableK) + 1;
     const int nodes = ((row / kTableK) & 1) ? 1 : 2;
     const int j = (int)(row / (2 * kTableK));
+    if (nodes == 1 && K > *a.k1) return;            // never looked up (tabled_row)
     Best best;
     if constexpr (CH == 0) best = sweep_sampled(load_job(a.job_params, a.J, j), a.m_grid + (size_t)j * a.Gm, a.Gm, a.Gs, K, nodes);
     else if constexpr (F32) best = sweep_any_f32<CH>(load_job_f32(a.job_params, a.J, j), job_tables(a, j), a.rsf, a.rk, a.Gm, a.Gs, K, nodes);
@@ -1486,10 +1516,11 @@ pairs_kernel(FitnessArgs a)
                 const int r = 4 * b + g;
                 const int K = __builtin_amdgcn_ds_bpermute(r << 2, d_K);
                 const int nodes = __builtin_amdgcn_ds_bpermute(r << 2, d_meta) & ~kMetaChanged;
-                const int K_in = K < 1 ? 1 : (K > kTableK ? kTableK : K);
-                const int found = sweep_pick_rows<CH>(tb, X, a.rs, a.rk, a.Gm, a.Gs, K_in, nodes == 1, (LdsDoubles)r_lds, has_near);
+                const bool within = tabled_row(K, nodes == 1, tb.k1);
+                const int K_in = (K < 1 || !within) ? 1 : K;
+                const int found = sweep_pick_rows<CH>(tb, X, a.rs, a.rk, a.Gm, a.Gs, K_in, nodes == 1 && within, (LdsDoubles)r_lds, has_near);
                 int pi = found < 0 ? -1 : found >> 16, ps = found < 0 ? -1 : found & 0xFFFF;
-                if (K > kTableK) {                           // rare: swept after the loop, outside the hot path
+                if (K >= 1 && !within) {                     // rare: swept after the loop, outside the hot path
                     pi = kPending;
                     ps = -1;
                 } else if (K < 1 || r >= rows) {
@@ -1509,7 +1540,7 @@ pairs_kernel(FitnessArgs a)
             const int K = __builtin_amdgcn_readlane(d_K, r);
             const int nodes = __builtin_amdgcn_readlane(d_meta, r) & ~kMetaChanged;
             Pick pick = {-1, -1};
-            if (K > kTableK) pick.i = kPending;          // rare: swept after the loop, outside the hot path
+            if (K >= 1 && !tabled_row(K, nodes == 1, tb.k1)) pick.i = kPending;   // rare: swept after the loop, outside the hot path
             else if (!MEMO && K >= 1) {
                 if constexpr (F32) pick = sweep_pick_f32<CH, WHOLE>(qf, tb, XF, a.rsf, a.Gm, a.Gs, K, nodes, (LdsFloats)(const float *)r_lds, has_near);
                 else pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near);
@@ -1529,7 +1560,7 @@ pairs_kernel(FitnessArgs a)
             advance(r);
             row_stage(K, nodes, changed, neg);
             Best best;
-            if (MEMO && K >= 1 && K <= kTableK) {
+            if (MEMO && K >= 1 && tabled_row(K, nodes == 1, tb.k1)) {
                 const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
             } else {
@@ -1588,7 +1619,7 @@ pairs_kernel(FitnessArgs a)
             const size_t pair = (size_t)c * b.J + j;
             const int nodes = d_meta & ~kMetaChanged;
             Best best;
-            if (MEMO && d_K >= 1 && d_K <= kTableK) {
+            if (MEMO && d_K >= 1 && tabled_row(d_K, nodes == 1, tbb.k1)) {
                 const MemoEntry e = b.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
             } else if (d_i == kPriced) {
@@ -1811,6 +1842,7 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
     const int lane4 = lane < n4 ? lane : n4 - 1;          // lanes past the end of a row load its last 16 bytes again
     const unsigned long long in_row = __ballot(lane < n4);
     const double *__restrict__ wt = a.job_params + (size_t)PX_WEIGHT * a.J;
+    const int k1 = __builtin_amdgcn_readfirstlane(*a.k1);
     node_lds[t] = 0ull;
     if (t == 0) found_beyond = 0;
     __syncthreads();
@@ -1916,7 +1948,7 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                     if (lane < in_round) row_lds[at] = make_int2(d_K, d_meta);
                     // rows beyond the memo table: swept and priced by the whole wavefront (BEYOND), or the candidate
                     // is left to the instance that can
-                    unsigned long long pending = __ballot(lane < in_round && d_K > kTableK);
+                    unsigned long long pending = __ballot(lane < in_round && !tabled_row(d_K, (d_meta & ~kMetaChanged) == 1, k1));
                     if constexpr (BEYOND) {
                         while (pending) {
                             const int l = __ffsll(pending) - 1;
@@ -1953,10 +1985,10 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
             const int d_K = row.x, d_meta = row.y;
             const int nodes = d_meta & ~kMetaChanged;
             Best best = {0.0, -1, -1};
-            if (d_K >= 1 && d_K <= kTableK) {
+            if (d_K >= 1 && tabled_row(d_K, nodes == 1, k1)) {
                 const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (d_K - 1)];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
-            } else if (BEYOND && d_K > kTableK) {
+            } else if (BEYOND && d_K >= 1) {
                 const MemoEntry e = beyond_lds[at];
                 best.goodput = e.goodput; best.m = e.m; best.s = e.s;
             }
@@ -2038,6 +2070,7 @@ static FitnessArgs job_level_args(const pollux_dims *d, const double *job_params
     a.lt = (double *)(ws + L.lt);
     a.ca = (double2 *)(ws + L.ca);
     a.srange = (int32_t *)(ws + L.srange);
+    a.k1 = (int32_t *)(ws + L.k1);
     a.gs_pad = ((d->Gs + 31) / 32) * 32;
     return a;
 }

@@ -19,6 +19,7 @@ constexpr int kTableK = 64;
 // whatever grid dimensions the former is given.
 struct WorkspaceLayout {
     size_t status;    // int32 status word
+    size_t k1;        // int32            the tables of the "one node" class cover K <= this (largest node capacity)
     size_t order;     // int32  [P]       candidates by rank (search step)
     size_t redo;      // int32  [P]       memoised mode: candidates with a row beyond the memo table
     size_t curmask;   // uint64 [J]       16-byte groups of the job's current row that hold a non-zero entry
@@ -53,6 +54,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     size_t o = 0;
     const size_t P = (size_t)d.P, J = (size_t)d.J, Gm = (size_t)(d.Gm > 0 ? d.Gm : 1), Gs = (size_t)(d.Gs > 0 ? d.Gs : 1);
     L.status = o;  o = up(o + 256);
+    L.k1 = o;      o = up(o + 256);
     L.order = o;   o = up(o + 4 * P);
     L.redo = o;    o = up(o + 4 * P);
     L.curmask = o; o = up(o + 8 * J);

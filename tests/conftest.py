@@ -8,6 +8,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+# every workspace the binding allocates in a test starts as 0xFF bytes (NaN, -1), so that a kernel that reads a
+# section before anything has written it cannot pass by finding the values an earlier call left there
+os.environ.setdefault("POLLUX_POISON_WORKSPACE", "1")
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

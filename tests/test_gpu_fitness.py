@@ -393,6 +393,37 @@ def test_memoised_mode_with_rows_beyond_the_table_and_in_fp32():
         assert np.array_equal(a[k], b[k], equal_nan=True), k
 
 
+@pytest.mark.parametrize("name", ["physical", "mid"])
+def test_rows_that_claim_more_gpus_on_one_node_than_any_node_has(name):
+    """The tables of the one-node class stop at the largest node capacity; a row beyond it (which no valid
+    allocation has) is swept in place.  Plain, memoised, sampling and fp32 calls on a population with many such
+    rows, next to ordinary ones, at every count up to the tables' end and beyond."""
+    from parity import rel_err
+    wl = W.make(name)
+    c = wl.cfg
+    pop = wl.population[:48].copy()
+    cap = int(wl.node_capacity.max())
+    rng = np.random.default_rng(7)
+    for cand in range(0, pop.shape[0], 2):
+        for j in rng.choice(c.J, size=c.J // 3, replace=False):
+            pop[cand, j] = 0
+            pop[cand, j, rng.integers(c.N)] = rng.integers(cap + 1, 70)          # one node, up to beyond kTableK
+    ref = run_oracle(wl, population=pop)
+    assert ref["violations"].max() > 0
+    assert compare(wl, run_gpu(wl, population=pop), ref, population=pop) == 0
+    assert compare(wl, run_gpu(wl, population=pop, flags=4), ref, population=pop) == 0
+    sw = W.sampled(wl)
+    sref = run_oracle(sw, population=pop, flags=16)
+    assert compare(sw, run_gpu(sw, population=pop, flags=16), sref, population=pop, sampled=True) == 0
+    assert compare(sw, run_gpu(sw, population=pop, flags=16 | 4), sref, population=pop, sampled=True) == 0
+    g = run_gpu(wl, population=pop, precision=1)
+    for k in ("best_goodput", "speedup"):
+        assert rel_err(g[k], ref[k]).max() <= 1e-5, k
+    gm = run_gpu(wl, population=pop, precision=1, flags=4)
+    for k in ("fitness", "best_m", "best_s", "best_goodput", "speedup"):
+        assert np.array_equal(g[k], gm[k], equal_nan=True), k
+
+
 def test_keep_job_tables_reuses_the_job_level_work():
     """PX_FLAG_KEEP_JOB_TABLES: a second call on the same workspace with another population skips the job-level
     kernels and must give what a full call gives."""
