@@ -60,6 +60,21 @@ __device__ __forceinline__ double uniform_f64(double v)
                             __builtin_amdgcn_readfirstlane(__double2loint(v)));
 }
 
+// One recorded tuple in the form the iteration uses it.
+struct Record {
+    int K, nodes;
+    double md, sd, lnT;
+};
+
+__device__ __forceinline__ Record load_record(const FitArgs &f, size_t at)
+{
+    Record r;
+    r.K = f.K[at]; r.nodes = f.nodes[at];
+    r.md = (double)f.m[at]; r.sd = (double)f.s[at];
+    r.lnT = px_log(f.T[at]);
+    return r;
+}
+
 // SUM r^2, J^T r and J^T J of one job at theta = z * scale.
 struct Normal {
     double sse;
@@ -67,8 +82,10 @@ struct Normal {
     double a[kPacked];
 };
 
+// mine: the record of lane l when the job has at most 64 of them (held: read once per job, kept in registers
+// over all iterations); otherwise the records are read from memory in every evaluation.
 __device__ __forceinline__ Normal normal_equations(const FitArgs &f, int j, int n, const double (&z)[kTheta],
-                                                   const double (&scale)[kTheta])
+                                                   const double (&scale)[kTheta], const Record &mine, bool held_records)
 {
     const int lane = lane_id();
     double th[kTheta];
@@ -85,9 +102,10 @@ __device__ __forceinline__ Normal normal_equations(const FitArgs &f, int j, int 
 
     const size_t base = (size_t)j * f.max_obs;
     for (int o = lane; o < n; o += kWave) {
-        const int K = f.K[base + o], nodes = f.nodes[base + o];
-        const double md = (double)f.m[base + o], sd = (double)f.s[base + o];
-        const double lnT = px_log(f.T[base + o]);
+        const Record rec = held_records ? mine : load_record(f, base + o);
+        const int K = rec.K, nodes = rec.nodes;
+        const double md = rec.md, sd = rec.sd;
+        const double lnT = rec.lnT;
         double tg = th[PX_ALPHA_G] + th[PX_BETA_G] * md;                                  // Eq. 8
         tg = tg > kTgradFloor ? tg : kTgradFloor;
         const bool local = K > 1 && nodes == 1, node = K > 1 && nodes != 1;
@@ -156,6 +174,8 @@ __device__ __forceinline__ bool damped_step(const Normal &q, double lambda, unsi
         l[i * (i + 1) / 2 + i] = hi ? 1.0 : dii + lambda * (dii > 1e-300 ? dii : 1e-300);
         b[i] = hi ? 0.0 : -q.g[i];
     }
+    // (one division per pivot: the entries below it and both substitutions multiply by its reciprocal)
+    double inv[kTheta];
     bool ok = true;
 #pragma unroll
     for (int i = 0; i < kTheta; ++i) {
@@ -167,8 +187,9 @@ __device__ __forceinline__ bool damped_step(const Normal &q, double lambda, unsi
             if (k == i) {
                 if (!(s > 0.0)) { ok = false; s = 1.0; }
                 l[i * (i + 1) / 2 + i] = sqrt(s);
+                inv[i] = 1.0 / l[i * (i + 1) / 2 + i];
             } else {
-                l[i * (i + 1) / 2 + k] = s / l[k * (k + 1) / 2 + k];
+                l[i * (i + 1) / 2 + k] = s * inv[k];
             }
         }
     }
@@ -178,14 +199,14 @@ __device__ __forceinline__ bool damped_step(const Normal &q, double lambda, unsi
         double s = b[i];
 #pragma unroll
         for (int t = 0; t < i; ++t) s = px_fma(-l[i * (i + 1) / 2 + t], b[t], s);
-        b[i] = s / l[i * (i + 1) / 2 + i];
+        b[i] = s * inv[i];
     }
 #pragma unroll
     for (int i = kTheta - 1; i >= 0; --i) {
         double s = b[i];
 #pragma unroll
         for (int t = i + 1; t < kTheta; ++t) s = px_fma(-l[t * (t + 1) / 2 + i], x[t], s);
-        x[i] = s / l[i * (i + 1) / 2 + i];
+        x[i] = s * inv[i];
     }
     return ok;
 }
@@ -233,6 +254,10 @@ __global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
         best = __hiloint2double((int)hmin, (int)lmin);
     }
     const double t_min = uniform_f64(best);
+    // the usual case, at most one record per lane: each lane keeps its record for the whole fit
+    const bool held_records = n <= kWave;
+    Record mine = {1, 1, 1.0, 0.0, 0.0};
+    if (held_records && lane < n) mine = load_record(f, base + lane);
     const double m_at = (double)f.m[base + (size_t)__builtin_amdgcn_readfirstlane(best_o)];
 
     // priors (Sec. 4.1, "Prior-driven exploration"): parameters without evidence are held at zero
@@ -285,7 +310,7 @@ __global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
         // The damped Gauss-Newton iteration from z, until it converges or the budget of steps is spent;
         // the variables in `hold` stay where they are.  Leaves the end point in z and its sums in cur.
         auto descend = [&](unsigned hold) {
-            cur = normal_equations(f, j, n, z, scale);
+            cur = normal_equations(f, j, n, z, scale, mine, held_records);
             double lambda = 1e-3;
             while (it < f.max_iter && cur.sse > 0.0) {
                 ++it;
@@ -324,7 +349,7 @@ __global__ void __launch_bounds__(64 * kMaxStarts) fit_theta_kernel(FitArgs f)
                     moved = rel > moved ? rel : moved;
                 }
                 if (moved == 0.0) break;
-                const Normal trial = normal_equations(f, j, n, zn, scale);
+                const Normal trial = normal_equations(f, j, n, zn, scale, mine, held_records);
                 if (trial.sse < cur.sse) {
                     const double gain = (cur.sse - trial.sse) / cur.sse;
 #pragma unroll
