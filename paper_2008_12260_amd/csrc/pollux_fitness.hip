@@ -757,26 +757,26 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
 // result: (i << 16) | s of the feasible point with the smallest h, equal values to the lowest (i, s), or -1 when
 // the row has no feasible point.  Per (K, batch size) the arithmetic is that of sweep_pick, instruction for
 // instruction, so both elect the same point.
-template <int CH>
+template <int CH, bool WHOLE>
 __device__ __forceinline__ int sweep_pick_rows(const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
-                                               const double *__restrict__ rk, int Gm, int Gs, int K, bool one_node,
-                                               LdsDoubles near, bool has_near)
+                                               int Gm, int Gs, int K, bool one_node, LdsDoubles near, bool has_near)
 {
     const int l16 = lane_id() & 15;
-    // offsets inside one job's tables fit 32 bits (Gm <= 2^20)
-    const unsigned lrow = (unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm;
-    const unsigned srow = (unsigned)(K - 1) * (unsigned)Gm;
+    // Byte offsets inside one job's tables fit 32 bits (Gm <= 2^20, 2 * kTableK rows of 16 bytes per batch size): a
+    // uniform base plus a 32-bit offset per lane, so that no address needs 64-bit vector arithmetic.
+    const unsigned ca_row = (unsigned)((one_node ? kTableK : 0) + K - 1) * (unsigned)Gm * 16u;
+    const unsigned s_row = (unsigned)(K - 1) * (unsigned)Gm * 4u;
     double kbest = __builtin_inf();   // smallest h seen by this lane
     int where = 0;                    // its (i << 16) | s
     const ScalarDoubles rsc = (ScalarDoubles)rs;
     for (int i0 = 0; i0 < Gm; i0 += 16) {
         const int i = i0 + l16;
-        const bool feasible = i < Gm;
+        const bool feasible = WHOLE || i < Gm;       // WHOLE: Gm is a multiple of 64, so no lane runs past the grid
         const unsigned il = (unsigned)(feasible ? i : Gm - 1);
-        const double tg = tb.tg[il].x;
-        const double2 car = tb.ca[lrow + il];
+        const double tg = *(const double *)((const char *)tb.tg + 16u * il);
+        const double2 car = *(const double2 *)((const char *)tb.ca + (ca_row + 16u * il));
         const double C = car.x, A0 = car.y;         // A0 = +inf when the batch size has no feasible count
-        const int bounds = tb.srange[srow + il];
+        const int bounds = *(const int32_t *)((const char *)tb.srange + (s_row + 4u * il));
         const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
         const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
         // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
@@ -1518,7 +1518,7 @@ pairs_kernel(FitnessArgs a)
                 const int nodes = __builtin_amdgcn_ds_bpermute(r << 2, d_meta) & ~kMetaChanged;
                 const bool within = tabled_row(K, nodes == 1, tb.k1);
                 const int K_in = (K < 1 || !within) ? 1 : K;
-                const int found = sweep_pick_rows<CH>(tb, X, a.rs, a.rk, a.Gm, a.Gs, K_in, nodes == 1 && within, (LdsDoubles)r_lds, has_near);
+                const int found = sweep_pick_rows<CH, WHOLE>(tb, X, a.rs, a.Gm, a.Gs, K_in, nodes == 1 && within, (LdsDoubles)r_lds, has_near);
                 int pi = found < 0 ? -1 : found >> 16, ps = found < 0 ? -1 : found & 0xFFFF;
                 if (K >= 1 && !within) {                     // rare: swept after the loop, outside the hot path
                     pi = kPending;
