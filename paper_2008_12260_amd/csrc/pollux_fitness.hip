@@ -5,9 +5,9 @@
 // Sec. 4.1 (Eq. 13), SPEEDUP / FITNESS_p, re-allocation penalty and
 // interference avoidance Sec. 4.2 (Eq. 14-15).
 //
-// Kernels (one call = six launches on the caller's stream)
+// Kernels (one call = five launches on the caller's stream)
 //   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), 1/T_grad, ln T_grad, phi/m and
-//                     the feasibility bounds; reciprocals; clears the status word
+//                     the feasibility bounds; reciprocals; clears the status word and the per-node counters
 //   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
 //                     per eight rows): T_sync (Eq. 9) and, for every batch size of the grid,
 //                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
@@ -105,6 +105,7 @@ struct FitnessArgs {
     const int32_t *sel;           // candidates to evaluate (device list of n_sel indices into the population), or null: all P
     int n_sel;
     int clear_status;             // tables_kernel starts a new status word (fitness calls; the query calls leave it alone)
+    int clear_counters;           // tables_kernel clears colpack (fitness calls whose population pass keeps the counters in memory)
     // outputs
     double *fitness, *best_goodput, *speedup;
     int32_t *best_m, *best_s, *violations;
@@ -187,6 +188,11 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
         a.rsf[t] = 1.0f / (float)(t + 1);
     }
     if (t < kRecipTable) a.rk[t] = t > 0 ? 1.0 / (double)t : 0.0;
+    if (a.clear_counters) {
+        // the per-candidate, per-node counters of the constraint check start the call at zero
+        const size_t n = (size_t)a.P * a.N;
+        for (size_t i = (size_t)t; i < n; i += (size_t)gridDim.x * blockDim.x) a.colpack[i] = 0ull;
+    }
     if (t < a.J * a.Gm) {
         const int j = t / a.Gm;
         const int mi = a.m_grid[t];
@@ -209,15 +215,6 @@ __global__ void __launch_bounds__(256) tables_kernel(FitnessArgs a)
         a.pu[t] = mi > 0 ? a.job_params[(size_t)PX_PHI * a.J + j] / m : 0.0;
         a.qh5[t] = qh + 0.5;
         a.ql5[t] = ql - 0.5;
-    }
-}
-
-// Clears the per-candidate, per-node counters of the constraint check.
-__global__ void __launch_bounds__(256) zero_counters_kernel(FitnessArgs a)
-{
-    const size_t n = (size_t)a.P * a.N;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) {
-        a.colpack[i] = 0ull;
     }
 }
 
@@ -2196,10 +2193,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
     // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, counters in LDS, fitness included
     const bool candidate_pass = memo && !sampled && !f32 && row1 && !row4;
-    if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES) && !candidate_pass) {
-        long long zb = ((long long)d->P * d->N + 255) / 256;
-        hipLaunchKernelGGL(zero_counters_kernel, dim3((unsigned)(zb > 4096 ? 4096 : zb)), dim3(256), 0, stream, a);
-    }
+    a.clear_counters = candidate_pass ? 0 : 1;       // done by tables_kernel, i.e. not by a call that keeps the job tables
     if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         // everything that depends on the jobs only (not on the population)
         launch_job_tables(d, a, !sampled, stream);
