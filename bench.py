@@ -244,6 +244,24 @@ def main():
     extra["memoised_population_bytes_per_s"] = 4.0 * cfg.P * cfg.J * cfg.N / (extra["memoised_fitness_call_ms"] * 1e-3)
     del mcall_memo
 
+    # the argmax by sampling total batch sizes (Sec. 4.3): Gm evaluations of Eq. 4 per pair instead of Gm x Gs; its
+    # own figure, not part of the headline (the grid row of a job then lists total batch sizes)
+    swl = W.sampled(wl)
+    scall = px.FitnessCall(cfg.P, cfg.J, cfg.N, cfg.Gm, cfg.Gs, swl.job_params, swl.m_grid, swl.fair_share,
+                           swl.current_alloc, swl.node_capacity, p=cfg.p, delta=cfg.delta,
+                           flags=px.PX_FLAG_SAMPLE_M, device=dev)
+    for _ in range(2):
+        scall.run(a, stream=stream)
+    s0, s1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s0.record(stream)
+    for _ in range(5):
+        scall.run(a, stream=stream)
+    s1.record(stream)
+    torch.cuda.synchronize()
+    extra["sampled_fitness_call_ms"] = s0.elapsed_time(s1) / 5
+    extra["sampled_evals_per_s"] = cfg.P * cfg.J * cfg.Gm / (extra["sampled_fitness_call_ms"] * 1e-3)
+    del scall, swl
+
     if not args.no_ga_loop:
         # the search loop on the mid configuration: 100 generations, fitness + step each; job tables are kept
         # between generations (the jobs do not change within a scheduling interval).  Timed twice: with the
