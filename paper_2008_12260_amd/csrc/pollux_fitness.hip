@@ -845,17 +845,6 @@ __device__ __forceinline__ JobTables job_tables(const FitnessArgs &a, int j)
 // arithmetic; the point is then priced with Eq. 4 in the paper's order of operations
 // (T_grad, its logarithm and the last pass of Eq. 10 are formed here, m is not on a grid).
 // Gm evaluations per call instead of Gm * Gs.  Ties go to the lowest i.
-// ceil(n / d) for integers 1 <= n, d < 2^52 held in doubles: the quotient from a reciprocal, put right by its exact
-// remainder (every intermediate is an integer below 2^53, so the products and differences are exact).  rd = 1 / d to
-// within a few units in the last place.
-__device__ __forceinline__ double ceil_div_exact(double n, double d, double rd)
-{
-    double qd = floor(n * rd);
-    const double r = px_fma(-qd, d, n);              // n - qd d, exact
-    qd = r < 0.0 ? qd - 1.0 : (r >= d ? qd + 1.0 : qd);
-    return px_fma(-qd, d, n) > 0.0 ? qd + 1.0 : qd;
-}
-
 __device__ __forceinline__ Best sweep_sampled(const Job &q, const int32_t *__restrict__ M_list, int Gm, int Gs, int K,
                                               int nodes)
 {
@@ -865,36 +854,28 @@ __device__ __forceinline__ Best sweep_sampled(const Job &q, const int32_t *__res
     const double M0 = q.jp[(size_t)PX_M0 * q.J + q.j], Mmax = q.jp[(size_t)PX_MMAX * q.J + q.j];
     const double m_mem_d = q.jp[(size_t)PX_M_MEM * q.J + q.j];
     if (!(m_mem_d >= 1.0 && m_mem_d <= 2147483647.0)) return Best{0.0, -1, -1};
-    // examples one pass over K GPUs can hold: an integer below 2^62; a list entry is below 2^31, so a pass that
-    // holds 2^31 or more needs no accumulation whatever the entry, and below that the division is exact in fp64
-    const double Kd = (double)K;
-    const double per_pass = Kd * floor(m_mem_d);
-    const bool one_pass = per_pass >= 2147483648.0;
-    const double r_pass = px_div(1.0, per_pass);
+    const long long per_pass = (long long)K * (long long)m_mem_d;     // examples one pass over K GPUs can hold
     const SyncTerm st = sync_term(q, K, nodes == 1);
+    const double Kd = (double)K;
 
     double gbest = 0.0;
     int ibest = 0x7FFFFFFF, m_best = -1, s_best = -1;
     for (int i0 = 0; i0 < Gm; i0 += kWave) {
         const int i = i0 + lane;
         if (i >= Gm) continue;
-        const int Mi = M_list[i];
-        if (Mi <= 0) continue;
-        const double M = (double)Mi;
-        // s: the smallest accumulation count whose per-GPU batch fits the memory bound, ceil(M / per_pass) - 1
-        const double sd = one_pass ? 0.0 : ceil_div_exact(M, per_pass, r_pass) - 1.0;
-        if (sd > (double)(Gs - 1)) continue;
-        // m = ceil(M / (K (s+1))), 1 <= m <= m_mem
-        const double ks = Kd * (sd + 1.0);                             // below 2^31 * 2^14
-        const double md = ceil_div_exact(M, ks, px_div(1.0, ks));
-        const double Km = Kd * md;
-        const double Mrun = Km * (sd + 1.0);
+        const long long M = M_list[i];
+        if (M <= 0) continue;
+        const long long s = (M + per_pass - 1) / per_pass - 1;
+        if (s > (long long)(Gs - 1)) continue;
+        const long long ks = (long long)K * (s + 1);
+        const long long m = (M + ks - 1) / ks;                         // 1 <= m <= m_mem
+        const double Km = Kd * (double)m;
+        const double Mrun = Km * (double)(s + 1);
         if (Mrun < M0 || Mrun > Mmax) continue;
-        const double tg = alpha_g + beta_g * md;                       // Eq. 8
+        const double tg = alpha_g + beta_g * (double)m;                // Eq. 8
         const double last = last_pass(st, tg, st.mode == 2 ? px_log(tg) : 0.0);
-        const int s = (int)sd;
-        const double g = goodput_point(q, Km, tg, last, s);
-        if (g > gbest) { gbest = g; ibest = i; m_best = (int)md; s_best = s; }
+        const double g = goodput_point(q, Km, tg, last, (int)s);
+        if (g > gbest) { gbest = g; ibest = i; m_best = (int)m; s_best = (int)s; }
     }
     return wave_argmax(gbest, ibest, m_best, s_best);
 }
