@@ -183,6 +183,18 @@ def main():
         gen += 1
     torch.cuda.synchronize()
     incremental_s = time.perf_counter() - ti0
+    # and with PX_GA_INHERIT_ROWS: of the children, only the rows a move or a repair has changed are read back and
+    # swept; an unchanged row takes over its parent's results (same matrices, same fitness, a few sweeps per child)
+    for _ in range(2):
+        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=True)
+        gen += 1
+    torch.cuda.synchronize()
+    th0 = time.perf_counter()
+    for _ in range(args.steps):
+        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=True)
+        gen += 1
+    torch.cuda.synchronize()
+    inherited_s = time.perf_counter() - th0
 
     # the same search step out of place (survivors copied into a second buffer), for comparison
     b = torch.empty_like(a)
@@ -222,6 +234,8 @@ def main():
         "children_only_generations_per_s": args.steps / incremental_s,
         "children_only_ms_per_generation": incremental_s * 1e3 / args.steps,
         "children_only_evals_per_s": (cfg.P - elite) * cfg.J * cfg.Gm * cfg.Gs * args.steps / incremental_s,
+        "changed_rows_only_generations_per_s": args.steps / inherited_s,
+        "changed_rows_only_ms_per_generation": inherited_s * 1e3 / args.steps,
     }
 
     # memoised mode (one sweep per (job, K, placement class); not part of the headline: its population pass
@@ -301,6 +315,18 @@ def main():
             torch.cuda.synchronize()
             extra[label + "_children_only_generations_per_s"] = 100.0 / (time.perf_counter() - tg0)
             extra[label + "_children_only_best_fitness"] = float(mcall.fitness.max().item())
+            # and with PX_GA_INHERIT_ROWS (only the rows a move or a repair has changed are swept)
+            ma = torch.from_numpy(mwl.population).to(dev)
+            mcall.run(ma, stream=stream, outputs="fitness")
+            for g in range(5):
+                mcall.generation(ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, outputs="fitness", inherit_rows=True)
+            torch.cuda.synchronize()
+            tg0 = time.perf_counter()
+            for g in range(5, 105):
+                mcall.generation(ma, GA_SEED, g, mcfg.P // 2, mut, stream=stream, outputs="fitness", inherit_rows=True)
+            torch.cuda.synchronize()
+            extra[label + "_changed_rows_only_generations_per_s"] = 100.0 / (time.perf_counter() - tg0)
+            extra[label + "_changed_rows_only_best_fitness"] = float(mcall.fitness.max().item())
 
         # one fitness call on the mid configuration at three values of the fairness knob, in fp64 and in fp32
         # arithmetic (launch overhead included: five to six small kernels per call)
@@ -385,7 +411,8 @@ def main():
         "config": {"workload": f"{cfg.name}: P={cfg.P} candidates, J={cfg.J} jobs, {cfg.N} nodes x {cfg.cap} GPUs, "
                                f"grid {cfg.Gm}x{cfg.Gs}, p={cfg.p}, fitness + one search step (in place) per step",
                    "evals_per_step": evals_per_step, "generations_per_s": args.steps / elapsed,
-                   "generations_per_s_children_only": args.steps / incremental_s},
+                   "generations_per_s_children_only": args.steps / incremental_s,
+                   "generations_per_s_changed_rows_only": args.steps / inherited_s},
         "roofline": roofline,
         "extra": extra,
     }

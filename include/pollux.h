@@ -239,10 +239,18 @@ typedef struct {
 } pollux_ga_params;
 
 enum {
-    PX_GA_IN_PLACE = 1   /* children == parents: child c (c >= elite_k) overwrites the candidate of rank c, which
+    PX_GA_IN_PLACE = 1,  /* children == parents: child c (c >= elite_k) overwrites the candidate of rank c, which
                             did not survive, and the survivors stay where they are.  The new population holds the
                             same matrices as the out-of-place call, child c in slot order[c] instead of slot c,
                             and half of the traffic: survivors are neither read nor written. */
+    PX_GA_INHERIT_ROWS = 2
+                         /* pollux_generation only, with PX_GA_IN_PLACE: a row of a child that is a verbatim copy
+                            of its parent's row (no move drawn for it, not touched by a repair) takes over the
+                            parent's results for that row instead of being swept again: Eq. 13 sees a row only
+                            through the job, its GPU count and whether it sits on one node, and the parent is a
+                            survivor whose results the output arrays still hold.  Only the rows a move or a repair
+                            has changed are read back and swept.  Results are what the call gives without the
+                            flag; the work per generation drops from a sweep per (child, job) to a few per child. */
 };
 
 /*
@@ -304,7 +312,12 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; only P, J, N a
  * Preconditions (as for PX_FLAG_KEEP_JOB_TABLES, which is implied): the previous call on this workspace was
  * pollux_fitness or pollux_generation with the same dims, job_params, m_grid, fair_share, current_alloc, p,
  * delta, flags and output arrays, and the output arrays and the population have not been written since.
- * params->flags must be PX_GA_IN_PLACE.  The status word keeps accumulating.
+ * params->flags must be PX_GA_IN_PLACE, optionally with PX_GA_INHERIT_ROWS (which needs P * J < 2^31).  The
+ * status word keeps accumulating.
+ * With PX_GA_INHERIT_ROWS a child whose matrix was formed the ordinary way (no negative entry met, every node
+ * brought within its capacity, the per-node lists on chip large enough) satisfies both constraints by
+ * construction and is given violations = 0 without its matrix being read again; any other child is evaluated in
+ * full.
  * Errors as for pollux_fitness and pollux_ga_step.
  */
 int pollux_generation(const pollux_dims *dims,           /* host */

@@ -18,6 +18,7 @@ PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1
 PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
 PX_FLAG_SAMPLE_M = 16
 PX_GA_IN_PLACE = 1
+PX_GA_INHERIT_ROWS = 2
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8
 
 EXPORTS = ("pollux_version", "pollux_strerror", "pollux_workspace_size", "pollux_fitness", "pollux_fitness_static",
@@ -295,11 +296,14 @@ class FitnessCall:
         pollux_ga_step(self.dims, parents, self.fitness if fitness is None else fitness, self.node_capacity, ga,
                        self.workspace, children, stream)
 
-    def generation(self, population, seed, generation, elite_k, mut_threshold, stream=None, outputs="all", job_gpu_cap=None):
-        """pollux_generation on this call's buffers: search step in place, then the fitness of the children only."""
+    def generation(self, population, seed, generation, elite_k, mut_threshold, stream=None, outputs="all", job_gpu_cap=None,
+                   inherit_rows=False):
+        """pollux_generation on this call's buffers: search step in place, then the fitness of the children only.
+        inherit_rows: PX_GA_INHERIT_ROWS (rows a child holds unchanged take over their parent's results)."""
         assert outputs in ("all", "argmax", "fitness")
         full, argmax = outputs == "all", outputs != "fitness"
-        ga = GaParams(seed, generation, elite_k, mut_threshold, PX_GA_IN_PLACE, None if job_gpu_cap is None else job_gpu_cap.data_ptr())
+        ga = GaParams(seed, generation, elite_k, mut_threshold, PX_GA_IN_PLACE | (PX_GA_INHERIT_ROWS if inherit_rows else 0),
+                      None if job_gpu_cap is None else job_gpu_cap.data_ptr())
         pollux_generation(self.dims, population, self.job_params, self.m_grid, self.fair_share, self.current_alloc,
                           self.node_capacity, self.p, self.delta, ga, self.workspace, self.fitness,
                           self.best_m if argmax else None, self.best_s if argmax else None,

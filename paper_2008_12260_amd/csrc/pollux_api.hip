@@ -126,7 +126,7 @@ int fitness_call(const pollux_dims *dims, const int32_t *population, const doubl
     if (rc != PX_OK) return rc;
     return px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
                               workspace, fitness, best_m, best_s, best_goodput, speedup, violations, sweep_start,
-                              sweep_stop, 0, (hipStream_t)hip_stream);
+                              sweep_stop, 0, false, (hipStream_t)hip_stream);
 }
 
 }  // namespace
@@ -173,7 +173,7 @@ int pollux_fitness_static(const pollux_dims *dims, const int32_t *population, co
     rc = static_scratch(dev, &ws);
     if (rc != PX_OK) return rc;
     rc = px::launch_fitness(dims, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
-                            ws, fitness, best_m, best_s, best_goodput, speedup, violations, nullptr, nullptr, 0,
+                            ws, fitness, best_m, best_s, best_goodput, speedup, violations, nullptr, nullptr, 0, false,
                             (hipStream_t)hip_stream);
     if (rc != PX_OK) return rc;
     return status ? px::launch_copy_status(ws, status, (hipStream_t)hip_stream) : PX_OK;
@@ -199,7 +199,7 @@ int pollux_ga_step(const pollux_dims *dims, const int32_t *parents, const double
     if (rc != PX_OK) return rc;
     rc = check_device();
     if (rc != PX_OK) return rc;
-    return px::launch_ga_step(dims, parents, fitness, node_capacity, params, workspace, children,
+    return px::launch_ga_step(dims, parents, fitness, node_capacity, params, workspace, children, false,
                               (hipStream_t)hip_stream);
 }
 
@@ -215,19 +215,24 @@ int pollux_generation(const pollux_dims *dims, int32_t *population, const double
         return PX_E_INVALID_ARG;
     if (!isfinite(p) || !isfinite(delta) || delta < 0.0) return PX_E_INVALID_ARG;
     if (params->elite_k < 1u || params->elite_k > (uint32_t)dims->P) return PX_E_INVALID_ARG;
-    if (params->flags != (uint32_t)PX_GA_IN_PLACE) return PX_E_INVALID_ARG;       // the step is in place by definition here
+    // the step is in place by definition here
+    if (params->flags != (uint32_t)PX_GA_IN_PLACE && params->flags != (uint32_t)(PX_GA_IN_PLACE | PX_GA_INHERIT_ROWS))
+        return PX_E_INVALID_ARG;
+    const bool inherit_rows = (params->flags & PX_GA_INHERIT_ROWS) != 0;
+    if (inherit_rows && (long long)dims->P * dims->J > 0x7FFFFFFFll) return PX_E_INVALID_ARG;   // a pair index and a flag share a word
     if (!px::ga_shapes_fit(dims->J, dims->N)) return PX_E_INVALID_ARG;
     int rc = check_workspace(dims, workspace, workspace_bytes);
     if (rc != PX_OK) return rc;
     rc = check_device();
     if (rc != PX_OK) return rc;
-    rc = px::launch_ga_step(dims, population, fitness, node_capacity, params, workspace, population, (hipStream_t)hip_stream);
+    rc = px::launch_ga_step(dims, population, fitness, node_capacity, params, workspace, population, inherit_rows,
+                            (hipStream_t)hip_stream);
     if (rc != PX_OK) return rc;
     pollux_dims kept = *dims;
     kept.flags |= PX_FLAG_KEEP_JOB_TABLES;
     return px::launch_fitness(&kept, population, job_params, m_grid, fair_share, current_alloc, node_capacity, p, delta,
                               workspace, fitness, best_m, best_s, best_goodput, speedup, violations, nullptr, nullptr,
-                              (int)params->elite_k, (hipStream_t)hip_stream);
+                              (int)params->elite_k, inherit_rows, (hipStream_t)hip_stream);
 }
 
 int pollux_apply_best(const pollux_dims *dims, const int32_t *population, const double *fitness, int32_t *current_alloc,

@@ -104,6 +104,10 @@ struct FitnessArgs {
     int need_constraints;
     const int32_t *sel;           // candidates to evaluate (device list of n_sel indices into the population), or null: all P
     int n_sel;
+    // row inheritance (pollux_generation with PX_GA_INHERIT_ROWS; written by the search step, see GaArgs)
+    const int32_t *src_row;       // [n_sel, J] the candidate whose row j the listed child holds unchanged, or -1
+    const int32_t *odd;           // [n_sel] the listed child is to be evaluated in full
+    int32_t *dirty_count, *dirty; // rows to sweep: their number, and pair index (candidate * J + job) | odd << 31 of each
     int clear_status;             // tables_kernel starts a new status word (fitness calls; the query calls leave it alone)
     int clear_counters;           // tables_kernel clears colpack (fitness calls whose population pass keeps the counters in memory)
     // outputs
@@ -1796,6 +1800,100 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
     }
 }
 
+// ---- row inheritance (pollux_generation with PX_GA_INHERIT_ROWS) ----------------------------------
+// The search step has left, per child it formed and per job, the candidate whose row the child holds unchanged
+// (a survivor: its results are in place), or -1.  Eq. 13, the re-allocation flag and everything else the fitness
+// takes from a row depend on the row, the job and the current allocation only, so an unchanged row takes over the
+// results of its source; the rows a move or a repair has changed are listed for dirty_rows_kernel.  A child the
+// step has flagged (a.odd: it may hold a negative entry or violate a constraint) lists all its rows, with the flag
+// that makes dirty_rows_kernel feed the per-node counters too; every other child satisfies both constraints by
+// construction and its counters stay at zero.  One workgroup per listed child; candidates_kernel follows as usual.
+__global__ void __launch_bounds__(256) inherit_kernel(FitnessArgs a)
+{
+    const int k = blockIdx.x;
+    const int slot = a.sel[k];
+    const bool odd = a.odd[k] != 0;
+    const int32_t *__restrict__ src = a.src_row + (size_t)k * a.J;
+    for (int j = threadIdx.x; j < a.J; j += 256) {
+        const int s = odd ? -1 : src[j];
+        const size_t to = (size_t)slot * a.J + j;
+        if (s >= 0) {
+            const size_t from = (size_t)s * a.J + j;
+            a.G[to] = a.G[from];
+            a.meta[to] = a.meta[from];
+            if (a.best_m) {
+                a.best_m[to] = a.best_m[from];
+                a.best_s[to] = a.best_s[from];
+            }
+            if (a.best_goodput) a.best_goodput[to] = a.best_goodput[from];
+        } else {
+            a.dirty[atomicAdd(a.dirty_count, 1)] = (int32_t)((uint32_t)to | (odd ? 0x80000000u : 0u));
+        }
+    }
+}
+
+// One wavefront per listed row at a time: row reduce, the sweep (or the look-up in memoised mode) and the pricing
+// of a (candidate, job) pair, as pairs_kernel does them; for a row of a flagged child also its entries to the
+// per-node counters.  The list is short (a few rows per child), so the plain forms of the sweep do.
+template <int CH, bool F32>
+__global__ void __launch_bounds__(256) dirty_rows_kernel(FitnessArgs a)
+{
+    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+    const int lane = lane_id();
+    const int total = __builtin_amdgcn_readfirstlane(*a.dirty_count);
+    const bool memo = (a.flags & PX_FLAG_MEMOISE) != 0;
+    for (int i = blockIdx.x * kWavesPerBlock + wave; i < total; i += gridDim.x * kWavesPerBlock) {
+        const int entry = __builtin_amdgcn_readfirstlane(a.dirty[i]);
+        const bool odd = entry < 0;
+        const int pair = entry & 0x7FFFFFFF;
+        const int c = pair / a.J, j = pair - c * a.J;
+        const int32_t *__restrict__ row = a.population + (size_t)pair * a.N;
+        const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
+        int ksum = 0, nodes = 0;
+        bool changed = false, neg = false;
+        for (int n0 = 0; n0 < a.N; n0 += kWave) {
+            const int n = n0 + lane;
+            const int v = n < a.N ? row[n] : 0;
+            const int cv = n < a.N ? cur[n] : 0;
+            ksum += v;
+            nodes += __popcll(__ballot(v > 0));
+            changed |= __ballot(v != cv) != 0;
+            neg |= __ballot(v < 0) != 0;
+        }
+        const int K = wave_sum(ksum);
+        if (odd && a.need_constraints) {
+            const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
+            unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
+            for (int n = lane; n < a.N; n += kWave) {
+                const int v = row[n];
+                if (v != 0) atomicAdd(&cp[n], (unsigned long long)(long long)v + (v > 0 ? one_job : 0ull));
+            }
+        }
+        const JobTables tb = job_tables(a, j);
+        Best best;
+        if (memo && K >= 1 && tabled_row(K, nodes == 1, tb.k1)) {
+            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
+            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
+        } else if constexpr (CH == 0) {
+            best = sweep_sampled(load_job(a.job_params, a.J, j), tb.m, a.Gm, a.Gs, K, nodes);
+        } else if constexpr (F32) {
+            best = sweep_any_f32<CH>(load_job_f32(a.job_params, a.J, j), tb, a.rsf, a.rk, a.Gm, a.Gs, K, nodes);
+        } else {
+            best = sweep<CH>(load_job(a.job_params, a.J, j), tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
+        }
+        if (lane == 0) {
+            a.G[pair] = best.goodput;
+            a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
+            if (a.best_m) {
+                a.best_m[pair] = best.m;
+                a.best_s[pair] = best.s;
+            }
+            if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+            if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
+        }
+    }
+}
+
 // ---- memoised mode, one workgroup per candidate ---------------------------------------------------
 // With the sweeps looked up a candidate costs the reading of its matrix and little else, so one workgroup
 // takes the whole candidate: it walks the matrix in memory order (four wavefronts, 64 consecutive rows each
@@ -1994,6 +2092,9 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                 a.best_s[pair] = best.s;
             }
             if (a.best_goodput) a.best_goodput[pair] = best.goodput;
+            // (what a later generation that inherits rows reads of this pair)
+            a.G[pair] = best.goodput;
+            a.meta[pair] = d_meta;
             // SPEEDUP (Eq. 15) with the re-allocation penalty, and the job's term of Eq. 14
             const double d = a.denom[j];
             double s_j = d > 0 ? best.goodput / d : 0.0;
@@ -2141,7 +2242,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
                    double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
-                   hipEvent_t sweep_stop, int first_rank, hipStream_t stream)
+                   hipEvent_t sweep_stop, int first_rank, bool inherit_rows, hipStream_t stream)
 {
     const WorkspaceLayout L = workspace_layout(*d);
     char *ws = (char *)workspace;
@@ -2193,7 +2294,29 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
     // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, counters in LDS, fitness included
     const bool candidate_pass = memo && !sampled && !f32 && row1 && !row4;
-    a.clear_counters = candidate_pass ? 0 : 1;       // done by tables_kernel, i.e. not by a call that keeps the job tables
+    if (inherit_rows && first_rank > 0) {
+        // the children of the step that has just run: unchanged rows take over their source's results, the others
+        // are swept one by one, then SPEEDUP and the generalized mean per child as usual
+        a.src_row = (const int32_t *)(ws + L.src_row);
+        a.odd = (const int32_t *)(ws + L.odd);
+        a.dirty_count = (int32_t *)(ws + L.dirty_count);
+        a.dirty = (int32_t *)(ws + L.dirty);
+        hipLaunchKernelGGL(inherit_kernel, dim3((unsigned)P_eff), dim3(256), 0, stream, a);
+        // enough wavefronts that each takes one or two rows even when a tenth of the rows is listed
+        long long db = pairs / 32;
+        db = db < 256 ? 256 : (db > 4096 ? 4096 : db);
+        const dim3 dirty_grid((unsigned)db);
+        if (sampled) hipLaunchKernelGGL((dirty_rows_kernel<0, false>), dirty_grid, dim3(256), 0, stream, a);
+        else if (f32 && ch == 8) hipLaunchKernelGGL((dirty_rows_kernel<8, true>), dirty_grid, dim3(256), 0, stream, a);
+        else if (f32) hipLaunchKernelGGL((dirty_rows_kernel<16, true>), dirty_grid, dim3(256), 0, stream, a);
+        else if (ch == 8) hipLaunchKernelGGL((dirty_rows_kernel<8, false>), dirty_grid, dim3(256), 0, stream, a);
+        else if (ch == 16) hipLaunchKernelGGL((dirty_rows_kernel<16, false>), dirty_grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((dirty_rows_kernel<32, false>), dirty_grid, dim3(256), 0, stream, a);
+        if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
+        else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
+        return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
+    }
+    a.clear_counters = 1;       // done by tables_kernel, i.e. not by a call that keeps the job tables
     if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         // everything that depends on the jobs only (not on the population)
         launch_job_tables(d, a, !sampled, stream);

@@ -52,6 +52,13 @@ struct GaArgs {
     uint32_t key0, key1, generation, elite_k, mut_threshold;
     int max_entries;   // capacity of the per-node entry lists in LDS
     int in_place;      // children == parents: only children c >= elite_k are formed, child c goes to slot order[c]
+    // Row inheritance (in place only; all three null otherwise).  Child c = elite_k + k:
+    int32_t *src_row;      // [P - elite_k, J]: the candidate whose row j the child holds unchanged, or -1 if a move or a
+                           // repair has changed the row
+    int32_t *odd;          // [P - elite_k]: 1 if the child may violate a constraint or hold a negative entry (a negative
+                           // entry was met, a node could not be brought within its capacity, or the node lists
+                           // overflowed), so that nothing about it may be taken for granted
+    int32_t *dirty_count;  // one word, set to zero by the step: the rows to be swept are counted there afterwards
 };
 
 // ---- rank ----------------------------------------------------------------------
@@ -61,6 +68,7 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int c = blockIdx.x * 4 + wave;           // one wavefront per candidate, lanes over the others
+    if (a.dirty_count && blockIdx.x == 0 && threadIdx.x == 0) *a.dirty_count = 0;
     if (c >= a.P) return;
     const int lane = lane_id();
     double f = a.fitness[c];
@@ -204,6 +212,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
 {
     extern __shared__ __align__(16) unsigned char ga_lds[];
     __shared__ int count, n_dist, n_ent;
+    __shared__ int odd;             // see GaArgs::odd
     __shared__ unsigned long long keep;
 
     const int c = a.in_place ? (int)(blockIdx.x + a.elite_k) : (int)blockIdx.x;
@@ -229,7 +238,9 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
 
     const GaShared sh = carve_shared(ga_lds, a.J, a.N, a.max_entries);
     for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1; }
-    if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; }
+    if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; odd = 0; }
+    // row inheritance: where the child's rows come from (see GaArgs)
+    int32_t *__restrict__ src_row = a.src_row ? a.src_row + (size_t)(c - (int)a.elite_k) * a.J : nullptr;
 
     // ---- step A ----
     // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1, decx[j] = the
@@ -248,15 +259,18 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         sh.decx[j] = (int32_t)x;
     }
     const U4 pr = philox4x32_10(a.generation, (uint32_t)c, 0u, kTagParent, a.key0, a.key1);
-    const int32_t *__restrict__ pa = a.parents + (size_t)a.order[below(pr.x, a.elite_k)] * JN;
+    const int cand_a = a.order[below(pr.x, a.elite_k)];
     // half of the children have a single parent (mutation only)
-    const int32_t *__restrict__ pb = (pr.z & 1u) ? pa : a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
+    const int cand_b = (pr.z & 1u) ? cand_a : a.order[below(pr.y, a.elite_k)];
+    const int32_t *__restrict__ pa = a.parents + (size_t)cand_a * JN;
+    const int32_t *__restrict__ pb = a.parents + (size_t)cand_b * JN;
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
     __syncthreads();
 
     // a positive entry of the child: per-node total and node list
     auto record = [&](int j, int n, int32_t v) {
         atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
+        if (v < 0) odd = 1;
         if (v > 0) {
             const int e = atomicAdd(&n_ent, 1);
             if (e < a.max_entries) {
@@ -290,6 +304,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
             if (plain && l16 == 0) {
                 sh.nodes_of[j] = nodes;
                 if (nodes >= 2) sh.dist[atomicAdd(&n_dist, 1)] = j;
+                if (src_row) src_row[j] = (d & 1) ? cand_b : cand_a;
             }
         }
     }
@@ -399,6 +414,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         }
         if (lane == 0) sh.nodes_of[j] = nodes;
         if (nodes >= 2 && lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
+        if (src_row && lane == 0) src_row[j] = (move < 0 && !over_limit) ? ((d & 1) ? cand_b : cand_a) : -1;
     }
     __syncthreads();
 
@@ -424,12 +440,15 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                 const int j = sh.ent_j[pick];
                 sh.ent_v[pick] = (int32_t)(have - take);
                 child[(size_t)j * a.N + n] = (int32_t)(have - take);
+                if (src_row) src_row[j] = -1;
                 excess -= take;
                 if (take == have) atomicSub(&sh.nodes_of[j], 1);
                 last = pick_dist;
             }
+            if (excess > 0) odd = 1;                        // nothing left to take away: the node stays over its capacity
         }
         __syncthreads();
+        if (a.odd && tid == 0) a.odd[c - (int)a.elite_k] = odd;     // final: step C only removes entries
         // ---- step C on the node lists ----
         // which multi-node jobs each node holds now (later removals can only take some away)
         for (int n = tid; n < a.N; n += kGaThreads) {
@@ -470,6 +489,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                         const int keeper = (int)(0xFFFFFFFFu - (uint32_t)((unsigned long long)key & 0xFFFFFFFFull));
                         if (multi && j != keeper) {
                             child[(size_t)j * a.N + n] = 0;
+                            if (src_row) src_row[j] = -1;
                             sh.nodes_of[j] -= 1;
                         }
                     }
@@ -490,6 +510,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                             const int j = sh.ent_j[e];
                             if (j != keeper && sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
                                 child[(size_t)j * a.N + n] = 0;
+                                if (src_row) src_row[j] = -1;
                                 sh.nodes_of[j] -= 1;
                             }
                         }
@@ -501,6 +522,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     }
 
     // ---- dense fallback: step B on columns read from memory ----
+    if (a.odd && tid == 0) a.odd[c - (int)a.elite_k] = 1;       // evaluated in full afterwards: src_row is not kept up
     for (int n = tid; n < a.N; n += kGaThreads) {
         long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
         if (excess <= 0) continue;
@@ -632,7 +654,7 @@ int launch_apply_best(const pollux_dims *d, const int32_t *population, const dou
 }
 
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
-                   const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream)
+                   const pollux_ga_params *ga, void *workspace, int32_t *children, bool inherit_rows, hipStream_t stream)
 {
     const WorkspaceLayout L = workspace_layout(*d);
     GaArgs a;
@@ -646,6 +668,12 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     a.generation = ga->generation; a.elite_k = ga->elite_k; a.mut_threshold = ga->mut_threshold;
     a.in_place = (ga->flags & PX_GA_IN_PLACE) ? 1 : 0;
     a.max_entries = ga_max_entries(d->J);
+    a.src_row = nullptr; a.odd = nullptr; a.dirty_count = nullptr;
+    if (inherit_rows && a.in_place) {
+        a.src_row = (int32_t *)((char *)workspace + L.src_row);
+        a.odd = (int32_t *)((char *)workspace + L.odd);
+        a.dirty_count = (int32_t *)((char *)workspace + L.dirty_count);
+    }
 
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);

@@ -32,6 +32,11 @@ struct WorkspaceLayout {
     size_t meta;      // int32  [P,J]     nodes occupied by the row | changed flag
     size_t memo;      // 16 bytes [J,2,kTableK]  best point per (job, one node?, K) in memoised mode
     size_t colpack;   // uint64 [P,N]     per node of each candidate: GPUs asked + multi-node jobs << 40
+    // row inheritance of pollux_generation (child k = the candidate of rank elite_k + k)
+    size_t src_row;   // int32  [P,J]     the candidate whose row j child k holds unchanged, or -1
+    size_t odd;       // int32  [P]       child k may violate a constraint: nothing about it is taken for granted
+    size_t dirty_count;  // int32         rows to sweep
+    size_t dirty;     // int32  [P,J]     those rows: pair index (candidate * J + job) | odd << 31
     // from here on the offsets depend on the grid
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
     size_t rsf;       // float  [Gs up to a multiple of 32]  the same in fp32
@@ -67,6 +72,10 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.meta = o;    o = up(o + 4 * P * J);
     L.memo = o;    o = up(o + 16 * J * 2 * kTableK);
     L.colpack = o; o = up(o + 8 * P * (size_t)d.N);
+    L.src_row = o; o = up(o + 4 * P * J);
+    L.odd = o;     o = up(o + 4 * P);
+    L.dirty_count = o; o = up(o + 256);
+    L.dirty = o;   o = up(o + 4 * P * J);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
     L.rsf = o;     o = up(o + 4 * ((Gs + 31) / 32) * 32);
     L.tg = o;      o = up(o + 16 * J * Gm);
@@ -85,15 +94,19 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
                    const int32_t *fair_share, const int32_t *current_alloc, const int32_t *node_capacity, double p,
                    double delta, void *workspace, double *fitness, int32_t *best_m, int32_t *best_s,
                    double *best_goodput, double *speedup, int32_t *violations, hipEvent_t sweep_start,
-                   hipEvent_t sweep_stop, int first_rank, hipStream_t stream);
+                   hipEvent_t sweep_stop, int first_rank, bool inherit_rows, hipStream_t stream);
 // the two events, if given, bracket the grid-sweep kernel; first_rank > 0 evaluates only the candidates of that
-// rank and beyond in the order the last search step left in the workspace (dims must carry PX_FLAG_KEEP_JOB_TABLES)
+// rank and beyond in the order the last search step left in the workspace (dims must carry PX_FLAG_KEEP_JOB_TABLES);
+// inherit_rows (with first_rank > 0, after launch_ga_step with inherit_rows): rows a child holds unchanged take over
+// their parent's results, only the others are swept
 
 // Copies the status word of `workspace` to *status_out (device memory) on the stream.
 int launch_copy_status(const void *workspace, int32_t *status_out, hipStream_t stream);
 
 int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *fitness, const int32_t *node_capacity,
-                   const pollux_ga_params *ga, void *workspace, int32_t *children, hipStream_t stream);
+                   const pollux_ga_params *ga, void *workspace, int32_t *children, bool inherit_rows, hipStream_t stream);
+// inherit_rows (in place only): the step also leaves, in the workspace, where every row of every child comes from
+// (WorkspaceLayout::src_row, odd) and clears the count of rows to sweep, for launch_fitness with inherit_rows
 
 // True when the search step's per-job and per-node bookkeeping for J jobs and N nodes fits the LDS of a workgroup.
 bool ga_shapes_fit(int J, int N);

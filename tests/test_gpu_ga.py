@@ -293,13 +293,13 @@ def test_step_with_zero_grid_dims_between_fitness_calls_that_keep_their_tables()
 
 # ---- pollux_generation: the step in place followed by the fitness of the children only ------------------------
 
-def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_every=1, P=None):
+def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_every=1, P=None, inherit=False, pop=None):
     """Both sides run fitness once and then `gens` generations; every output array is compared each time."""
     import torch
     import paper_2008_12260_amd as px
     from parity import compare
     c = wl.cfg
-    pop0 = wl.population if P is None else wl.population[:P]
+    pop0 = (wl.population if pop is None else pop) if P is None else wl.population[:P]
     P = pop0.shape[0]
     elite = P // 2 if elite is None else elite
     mut = (1 << 32) // c.J if mut is None else mut
@@ -310,7 +310,7 @@ def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_
     host = pop0.copy()
     ref = run_oracle(wl, population=host)
     for gen in range(gens):
-        call.generation(dev, SEED, gen, elite, mut)
+        call.generation(dev, SEED, gen, elite, mut, inherit_rows=inherit)
         host, ref = O.generation(host, ref["fitness"], wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
                                  wl.node_capacity, c.p, c.delta, c.Gs, SEED, gen, elite, mut)
         got_pop = dev.cpu().numpy()
@@ -326,13 +326,15 @@ def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_
     return call, dev, host
 
 
+@pytest.mark.parametrize("inherit", [False, True])
 @pytest.mark.parametrize("flags", [0, 4])
-def test_generation_call_matches_oracle_every_generation_on_the_mid_configuration(flags):
-    """60 generations of pollux_generation (survivors keep their results, children are swept) against the
-    checker's step + full evaluation; matrices every generation, every fitness output every tenth."""
+def test_generation_call_matches_oracle_every_generation_on_the_mid_configuration(flags, inherit):
+    """60 generations of pollux_generation (survivors keep their results, children are swept, or with
+    PX_GA_INHERIT_ROWS only their changed rows) against the checker's step + full evaluation; matrices every
+    generation, every fitness output every tenth."""
     import paper_2008_12260_amd as px
     wl = W.make("mid")
-    call, dev, host = generation_loop(wl, 60, flags=flags, check_every=10)
+    call, dev, host = generation_loop(wl, 60, flags=flags, check_every=10, inherit=inherit)
     # and a full evaluation of the final population by the library gives bit for bit what the incremental calls left
     kept = call.results()
     call.run(dev, keep_job_tables=True)
@@ -350,8 +352,9 @@ def test_generation_call_matches_oracle_every_generation_on_the_mid_configuratio
     (dict(P=40, J=70, N=128, cap=2, Gm=20, Gs=6), 40),        # nothing to form: every candidate survives
     (dict(P=6, J=40, N=9, cap=40, Gm=33, Gs=5), 2),           # rows beyond the tables
 ])
+@pytest.mark.parametrize("inherit", [False, True])
 @pytest.mark.parametrize("flags", [0, 4, 16])
-def test_generation_call_on_ragged_shapes(shape, elite, flags):
+def test_generation_call_on_ragged_shapes(shape, elite, flags, inherit):
     cfg = W.custom("gen_ragged", **shape)
     wl = W.make(cfg)
     if flags == 16:
@@ -365,7 +368,7 @@ def test_generation_call_on_ragged_shapes(shape, elite, flags):
         call.run(dev)
         host, ref = wl.population.copy(), run_oracle(wl, flags=16)
         for gen in range(3):
-            call.generation(dev, SEED, gen, elite, 1 << 30)
+            call.generation(dev, SEED, gen, elite, 1 << 30, inherit_rows=inherit)
             host, ref = O.generation(host, ref["fitness"], wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
                                      wl.node_capacity, c.p, c.delta, c.Gs, SEED, gen, elite, 1 << 30, flags=16)
             assert np.array_equal(dev.cpu().numpy(), host)
@@ -373,7 +376,7 @@ def test_generation_call_on_ragged_shapes(shape, elite, flags):
             assert np.array_equal(got["best_m"], ref["best_m"]) and np.array_equal(got["best_s"], ref["best_s"])
             assert np.allclose(got["fitness"], ref["fitness"], rtol=1e-12, atol=0.0, equal_nan=True)
         return
-    generation_loop(wl, 4, flags=flags, elite=elite, mut=1 << 30)
+    generation_loop(wl, 4, flags=flags, elite=elite, mut=1 << 30, inherit=inherit)
 
 
 def test_generation_call_in_fp32_and_its_argument_checks():
@@ -381,6 +384,7 @@ def test_generation_call_in_fp32_and_its_argument_checks():
     import paper_2008_12260_amd as px
     wl = W.make("physical")
     generation_loop(wl, 5, precision=1)
+    generation_loop(wl, 5, precision=1, inherit=True)
     c = wl.cfg
     call = gpu_call(wl)
     dev = torch.as_tensor(wl.population).cuda()
@@ -395,7 +399,8 @@ def test_generation_call_in_fp32_and_its_argument_checks():
                              call.node_capacity, c.p, c.delta, ga, call.workspace, call.fitness, call.best_m, call.best_s)
 
 
-def test_generation_call_on_the_large_configuration():
+@pytest.mark.parametrize("inherit", [False, True])
+def test_generation_call_on_the_large_configuration(inherit):
     """The headline shape: one full evaluation, then two generations that sweep the 2048 children only; the oracle
     recomputes the children of the last generation (the slots that were rewritten) and a sample of survivors."""
     import torch
@@ -413,7 +418,7 @@ def test_generation_call_on_the_large_configuration():
     mut = (1 << 32) // cfg.J
     for gen in range(2):
         before = call.results()
-        call.generation(dev, SEED, gen, cfg.P // 2, mut)
+        call.generation(dev, SEED, gen, cfg.P // 2, mut, inherit_rows=inherit)
         host = O.ga_step(host, before["fitness"], wl.node_capacity, SEED, gen, cfg.P // 2, mut, flags=O.GA_IN_PLACE)
         order = O.rank(before["fitness"])
         got = call.results()
@@ -430,9 +435,10 @@ def test_generation_call_on_the_large_configuration():
     assert compare(wl, gs, ref, population=sub) == 0
 
 
+@pytest.mark.parametrize("inherit", [False, True])
 @pytest.mark.parametrize("flags", [0, 4])
 @pytest.mark.parametrize("shape", [None, dict(P=12, J=70, N=128, cap=2, Gm=20, Gs=6)])
-def test_generations_that_write_fitness_only(flags, shape):
+def test_generations_that_write_fitness_only(flags, shape, inherit):
     """A search needs only fitness: with best_m and best_s left out (NULL) the generations form the same matrices and
     the same fitness and violation counts, and nothing is written per pair."""
     import torch
@@ -450,7 +456,7 @@ def test_generations_that_write_fitness_only(flags, shape):
         dev = torch.as_tensor(wl.population).cuda()
         call.run(dev, outputs=outputs)
         for gen in range(20):
-            call.generation(dev, SEED, gen, c.P // 2, (1 << 32) // c.J, outputs=outputs)
+            call.generation(dev, SEED, gen, c.P // 2, (1 << 32) // c.J, outputs=outputs, inherit_rows=inherit)
         calls.append(call.results())
         pops.append(dev.cpu().numpy())
     assert np.array_equal(pops[0], pops[1])
@@ -460,3 +466,25 @@ def test_generations_that_write_fitness_only(flags, shape):
     for k in ("best_m", "best_s", "best_goodput", "speedup"):
         assert np.all(calls[1][k] == -7), k
     assert np.all(calls[0]["best_s"] >= -1)
+
+
+@pytest.mark.parametrize("flags", [0, 4])
+def test_inherited_rows_with_children_that_cannot_be_taken_for_granted(flags):
+    """PX_GA_INHERIT_ROWS on populations whose children the step flags: matrices dense enough to overflow the
+    per-node lists on chip (the column path of the repairs), parents with negative entries; and a node without
+    capacity.  Such children are evaluated in full; everything must equal the checker's step + full evaluation,
+    violation counts and the status word included."""
+    cfg = W.custom("odd_children", P=24, J=40, N=64, cap=4, Gm=64, Gs=16)
+    wl = W.make(cfg)
+    rng = np.random.default_rng(11)
+    dense = wl.population.copy()
+    dense[::3] = (rng.random(dense[::3].shape) < 0.4).astype(np.int32) * rng.integers(1, 3, dense[::3].shape, dtype=np.int32)
+    assert (dense[0] > 0).sum() > 512                                   # more entries than the lists of this shape hold
+    generation_loop(wl, 4, flags=flags, mut=1 << 29, inherit=True, pop=dense)
+    negative = wl.population.copy()
+    negative[:, ::5, 3] = -1            # in every candidate, so that the (accumulating) status word and the checker's agree
+    generation_loop(wl, 4, flags=flags, mut=1 << 29, inherit=True, pop=negative)
+    import dataclasses
+    cap = wl.node_capacity.copy()
+    cap[5] = 0
+    generation_loop(dataclasses.replace(wl, node_capacity=cap), 4, flags=flags, mut=1 << 29, inherit=True)
