@@ -283,7 +283,7 @@ def main():
         mcfg = W.CONFIGS["mid"]
         mwl = W.make(mcfg)
         for label, flags, mut in (("ga_loop_mid", 0, mut_threshold(mcfg.J)),
-                                  ("ga_loop_mid_memoised", px.PX_FLAG_MEMOISE, mut_threshold(mcfg.J)),
+                                  ("ga_loop_mid_memoised", px.PX_FLAG_MEMOISE | px.PX_FLAG_PAIR_RESULTS, mut_threshold(mcfg.J)),
                                   ("ga_loop_mid_mutation_1_in_8", 0, 1 << 29)):
             mcall = px.FitnessCall(mcfg.P, mcfg.J, mcfg.N, mcfg.Gm, mcfg.Gs, mwl.job_params, mwl.m_grid,
                                    mwl.fair_share, mwl.current_alloc, mwl.node_capacity, p=mcfg.p, delta=mcfg.delta,

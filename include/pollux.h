@@ -60,10 +60,15 @@ enum {
                                          and that nothing but this library has written to the workspace,
                                          as in the generations of one scheduling interval.  The status word is
                                          then not cleared and keeps accumulating. */
-    PX_FLAG_SAMPLE_M = 16             /* the argmax of Eq. 13 by the sampling procedure of Sec. 4.3 instead of the
+    PX_FLAG_SAMPLE_M = 16,            /* the argmax of Eq. 13 by the sampling procedure of Sec. 4.3 instead of the
                                          dense grid: m_grid[j,*] then holds candidate TOTAL batch sizes M, and for
                                          each one s is the smallest count with which the per-GPU batch fits
                                          PX_M_MEM; see pollux_fitness.  fp64 only. */
+    PX_FLAG_PAIR_RESULTS = 32         /* with PX_FLAG_MEMOISE: the call also leaves the goodput and the node count of
+                                         every (candidate, job) pair in the workspace, which pollux_generation with
+                                         PX_GA_INHERIT_ROWS reads (calls without PX_FLAG_MEMOISE leave them anyway;
+                                         a memoised call on rows of 65 to 256 nodes otherwise keeps them on chip,
+                                         and the 12 bytes per pair cost it about a twentieth of its time). */
 };
 
 /* Rows of job_params[PX_NPARAM][J] (structure of arrays, fp64).
@@ -312,8 +317,9 @@ int pollux_ga_step(const pollux_dims *dims,              /* host; only P, J, N a
  * Preconditions (as for PX_FLAG_KEEP_JOB_TABLES, which is implied): the previous call on this workspace was
  * pollux_fitness or pollux_generation with the same dims, job_params, m_grid, fair_share, current_alloc, p,
  * delta, flags and output arrays, and the output arrays and the population have not been written since.
- * params->flags must be PX_GA_IN_PLACE, optionally with PX_GA_INHERIT_ROWS (which needs P * J < 2^31).  The
- * status word keeps accumulating.
+ * params->flags must be PX_GA_IN_PLACE, optionally with PX_GA_INHERIT_ROWS (with PX_FLAG_MEMOISE in dims that
+ * needs PX_FLAG_PAIR_RESULTS there too, in this call and in the calls before it).  The status word keeps
+ * accumulating.
  * With PX_GA_INHERIT_ROWS a child whose matrix was formed the ordinary way (no negative entry met, every node
  * brought within its capacity, the per-node lists on chip large enough) satisfies both constraints by
  * construction and is given violations = 0 without its matrix being read again; any other child is evaluated in

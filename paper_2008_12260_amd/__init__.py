@@ -17,6 +17,7 @@ PARAM_PHI = 7            # row of job_params that holds the gradient noise scale
 PX_OK, PX_E_INVALID_ARG, PX_E_WORKSPACE, PX_E_UNSUPPORTED_ARCH, PX_E_HIP = 0, -1, -2, -3, -4
 PX_FLAG_NO_REALLOC_PENALTY, PX_FLAG_NO_CONSTRAINT_CHECK, PX_FLAG_MEMOISE, PX_FLAG_KEEP_JOB_TABLES = 1, 2, 4, 8
 PX_FLAG_SAMPLE_M = 16
+PX_FLAG_PAIR_RESULTS = 32
 PX_GA_IN_PLACE = 1
 PX_GA_INHERIT_ROWS = 2
 PX_ST_BAD_PARAM, PX_ST_ZERO_FAIR, PX_ST_BAD_RESTART, PX_ST_NEG_ALLOC = 1, 2, 4, 8

@@ -219,7 +219,8 @@ int pollux_generation(const pollux_dims *dims, int32_t *population, const double
     if (params->flags != (uint32_t)PX_GA_IN_PLACE && params->flags != (uint32_t)(PX_GA_IN_PLACE | PX_GA_INHERIT_ROWS))
         return PX_E_INVALID_ARG;
     const bool inherit_rows = (params->flags & PX_GA_INHERIT_ROWS) != 0;
-    if (inherit_rows && (long long)dims->P * dims->J > 0x7FFFFFFFll) return PX_E_INVALID_ARG;   // a pair index and a flag share a word
+    // the per-pair results a memoised call leaves in the workspace only on request
+    if (inherit_rows && (dims->flags & PX_FLAG_MEMOISE) && !(dims->flags & PX_FLAG_PAIR_RESULTS)) return PX_E_INVALID_ARG;
     if (!px::ga_shapes_fit(dims->J, dims->N)) return PX_E_INVALID_ARG;
     int rc = check_workspace(dims, workspace, workspace_bytes);
     if (rc != PX_OK) return rc;

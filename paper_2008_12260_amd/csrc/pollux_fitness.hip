@@ -1913,7 +1913,8 @@ __global__ void __launch_bounds__(256) dirty_rows_kernel(FitnessArgs a)
 // Split because the sweep costs the kernel twice the registers of everything else in it.
 constexpr int kMemoChunkJobs = 4 * kCandThreads;    // jobs between two finishing steps
 
-template <int CH, bool BEYOND>
+// PAIRS: the goodput and the node count of every pair are also left in the workspace (PX_FLAG_PAIR_RESULTS).
+template <int CH, bool BEYOND, bool PAIRS>
 __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessArgs a)
 {
     static_assert(kCandThreads == 4 * kWave, "thread t of the workgroup is lane t % 64 of wavefront t / 64");
@@ -2092,9 +2093,11 @@ __global__ void __launch_bounds__(kCandThreads) memo_candidates_kernel(FitnessAr
                 a.best_s[pair] = best.s;
             }
             if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-            // (what a later generation that inherits rows reads of this pair)
-            a.G[pair] = best.goodput;
-            a.meta[pair] = d_meta;
+            if constexpr (PAIRS) {
+                // what a later generation that inherits rows reads of this pair
+                a.G[pair] = best.goodput;
+                a.meta[pair] = d_meta;
+            }
             // SPEEDUP (Eq. 15) with the re-allocation penalty, and the job's term of Eq. 14
             const double d = a.denom[j];
             double s_j = d > 0 ? best.goodput / d : 0.0;
@@ -2316,7 +2319,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
         return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
     }
-    a.clear_counters = 1;       // done by tables_kernel, i.e. not by a call that keeps the job tables
+    // done by tables_kernel, i.e. not by a call that keeps the job tables; the candidate pass keeps its counters on chip
+    // and leaves those in memory alone, unless generations that inherit rows (and read them) are to follow
+    a.clear_counters = (candidate_pass && !(d->flags & PX_FLAG_PAIR_RESULTS)) ? 0 : 1;
     if (!(d->flags & PX_FLAG_KEEP_JOB_TABLES)) {
         // everything that depends on the jobs only (not on the population)
         launch_job_tables(d, a, !sampled, stream);
@@ -2359,8 +2364,13 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         const dim3 memo_grid((unsigned)P_eff);
 #define PX_LAUNCH_MEMO_CANDIDATES(CH)                                                                                 \
     do {                                                                                                              \
-        hipLaunchKernelGGL((memo_candidates_kernel<CH, false>), memo_grid, dim3(kCandThreads), 0, stream, a);         \
-        hipLaunchKernelGGL((memo_candidates_kernel<CH, true>), memo_grid, dim3(kCandThreads), 0, stream, a);          \
+        if (d->flags & PX_FLAG_PAIR_RESULTS) {                                                                        \
+            hipLaunchKernelGGL((memo_candidates_kernel<CH, false, true>), memo_grid, dim3(kCandThreads), 0, stream, a); \
+            hipLaunchKernelGGL((memo_candidates_kernel<CH, true, true>), memo_grid, dim3(kCandThreads), 0, stream, a); \
+        } else {                                                                                                      \
+            hipLaunchKernelGGL((memo_candidates_kernel<CH, false, false>), memo_grid, dim3(kCandThreads), 0, stream, a); \
+            hipLaunchKernelGGL((memo_candidates_kernel<CH, true, false>), memo_grid, dim3(kCandThreads), 0, stream, a); \
+        }                                                                                                             \
     } while (0)
         if (ch == 8) PX_LAUNCH_MEMO_CANDIDATES(8);
         else if (ch == 16) PX_LAUNCH_MEMO_CANDIDATES(16);

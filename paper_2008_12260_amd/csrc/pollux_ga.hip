@@ -207,8 +207,10 @@ __device__ __forceinline__ unsigned long long holder_key(int32_t v, int j)
 }
 
 // FOUR: the host has checked that rows are 16-byte groups of at most 64 nodes and no per-job GPU limit is given.
-template <bool FOUR>
-__global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
+// INHERIT: the step also records where every row of the child comes from (GaArgs::src_row, odd); an instance of its
+// own, so that the plain step pays nothing for it (a few scalar registers more would cost it a workgroup per CU).
+template <bool FOUR, bool INHERIT>
+__global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96))) generation_kernel(GaArgs a)
 {
     extern __shared__ __align__(16) unsigned char ga_lds[];
     __shared__ int count, n_dist, n_ent;
@@ -240,7 +242,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1; }
     if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; odd = 0; }
     // row inheritance: where the child's rows come from (see GaArgs)
-    int32_t *__restrict__ src_row = a.src_row ? a.src_row + (size_t)(c - (int)a.elite_k) * a.J : nullptr;
+    int32_t *__restrict__ src_row = INHERIT ? a.src_row + (size_t)(c - (int)a.elite_k) * a.J : nullptr;
 
     // ---- step A ----
     // decisions of every row, one thread per job: dec[j] = source parent | (move + 1) << 1, decx[j] = the
@@ -259,18 +261,22 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         sh.decx[j] = (int32_t)x;
     }
     const U4 pr = philox4x32_10(a.generation, (uint32_t)c, 0u, kTagParent, a.key0, a.key1);
-    const int cand_a = a.order[below(pr.x, a.elite_k)];
+    const int32_t *__restrict__ pa = a.parents + (size_t)a.order[below(pr.x, a.elite_k)] * JN;
     // half of the children have a single parent (mutation only)
-    const int cand_b = (pr.z & 1u) ? cand_a : a.order[below(pr.y, a.elite_k)];
-    const int32_t *__restrict__ pa = a.parents + (size_t)cand_a * JN;
-    const int32_t *__restrict__ pb = a.parents + (size_t)cand_b * JN;
+    const int32_t *__restrict__ pb = (pr.z & 1u) ? pa : a.parents + (size_t)a.order[below(pr.y, a.elite_k)] * JN;
+    // the two parents as candidates (what src_row names)
+    int cand_a = 0, cand_b = 0;
+    if constexpr (INHERIT) {
+        cand_a = a.order[below(pr.x, a.elite_k)];
+        cand_b = (pr.z & 1u) ? cand_a : a.order[below(pr.y, a.elite_k)];
+    }
     const bool vec4 = (a.N & 3) == 0 && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
     __syncthreads();
 
     // a positive entry of the child: per-node total and node list
     auto record = [&](int j, int n, int32_t v) {
         atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
-        if (v < 0) odd = 1;
+        if (INHERIT && v < 0) odd = 1;
         if (v > 0) {
             const int e = atomicAdd(&n_ent, 1);
             if (e < a.max_entries) {
@@ -304,7 +310,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
             if (plain && l16 == 0) {
                 sh.nodes_of[j] = nodes;
                 if (nodes >= 2) sh.dist[atomicAdd(&n_dist, 1)] = j;
-                if (src_row) src_row[j] = (d & 1) ? cand_b : cand_a;
+                if (INHERIT) src_row[j] = (d & 1) ? cand_b : cand_a;
             }
         }
     }
@@ -414,7 +420,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
         }
         if (lane == 0) sh.nodes_of[j] = nodes;
         if (nodes >= 2 && lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
-        if (src_row && lane == 0) src_row[j] = (move < 0 && !over_limit) ? ((d & 1) ? cand_b : cand_a) : -1;
+        if (INHERIT && lane == 0) src_row[j] = (move < 0 && !over_limit) ? ((d & 1) ? cand_b : cand_a) : -1;
     }
     __syncthreads();
 
@@ -440,15 +446,15 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                 const int j = sh.ent_j[pick];
                 sh.ent_v[pick] = (int32_t)(have - take);
                 child[(size_t)j * a.N + n] = (int32_t)(have - take);
-                if (src_row) src_row[j] = -1;
+                if (INHERIT) src_row[j] = -1;
                 excess -= take;
                 if (take == have) atomicSub(&sh.nodes_of[j], 1);
                 last = pick_dist;
             }
-            if (excess > 0) odd = 1;                        // nothing left to take away: the node stays over its capacity
+            if (INHERIT && excess > 0) odd = 1;             // nothing left to take away: the node stays over its capacity
         }
         __syncthreads();
-        if (a.odd && tid == 0) a.odd[c - (int)a.elite_k] = odd;     // final: step C only removes entries
+        if (INHERIT && tid == 0) a.odd[c - (int)a.elite_k] = odd;   // final: step C only removes entries
         // ---- step C on the node lists ----
         // which multi-node jobs each node holds now (later removals can only take some away)
         for (int n = tid; n < a.N; n += kGaThreads) {
@@ -489,7 +495,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                         const int keeper = (int)(0xFFFFFFFFu - (uint32_t)((unsigned long long)key & 0xFFFFFFFFull));
                         if (multi && j != keeper) {
                             child[(size_t)j * a.N + n] = 0;
-                            if (src_row) src_row[j] = -1;
+                            if (INHERIT) src_row[j] = -1;
                             sh.nodes_of[j] -= 1;
                         }
                     }
@@ -510,7 +516,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
                             const int j = sh.ent_j[e];
                             if (j != keeper && sh.ent_v[e] > 0 && sh.nodes_of[j] >= 2) {
                                 child[(size_t)j * a.N + n] = 0;
-                                if (src_row) src_row[j] = -1;
+                                if (INHERIT) src_row[j] = -1;
                                 sh.nodes_of[j] -= 1;
                             }
                         }
@@ -522,7 +528,7 @@ __global__ void __launch_bounds__(kGaThreads) generation_kernel(GaArgs a)
     }
 
     // ---- dense fallback: step B on columns read from memory ----
-    if (a.odd && tid == 0) a.odd[c - (int)a.elite_k] = 1;       // evaluated in full afterwards: src_row is not kept up
+    if (INHERIT && tid == 0) a.odd[c - (int)a.elite_k] = 1;     // evaluated in full afterwards: src_row is not kept up
     for (int n = tid; n < a.N; n += kGaThreads) {
         long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
         if (excess <= 0) continue;
@@ -678,24 +684,30 @@ int launch_ga_step(const pollux_dims *d, const int32_t *parents, const double *f
     hipLaunchKernelGGL(rank_kernel, dim3((unsigned)((d->P + 3) / 4)), dim3(256), 0, stream, a);
     const size_t lds = ga_shared_bytes(d->J, d->N);
     const bool four = (d->N & 3) == 0 && d->N <= kWave && !a.job_gpu_cap && (((uintptr_t)a.parents | (uintptr_t)a.children) & 15) == 0;
+    const bool inherit = a.src_row != nullptr;
+    const int instance = (four ? 1 : 0) + (inherit ? 2 : 0);
+    const void *kernels[4] = {(const void *)generation_kernel<false, false>, (const void *)generation_kernel<true, false>,
+                              (const void *)generation_kernel<false, true>, (const void *)generation_kernel<true, true>};
     if (lds > 48 * 1024) {
         // Beyond 48 KB a kernel must be allowed its dynamic LDS explicitly.  The allowance is raised per kernel
         // instance and device, and only when a call needs more than any earlier one did.
         static std::mutex lock;
-        static size_t allowed[2][kGaDevices];
+        static size_t allowed[4][kGaDevices];
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kGaDevices) return PX_E_HIP;
         std::lock_guard<std::mutex> hold(lock);
-        if (allowed[four ? 1 : 0][dev] < lds) {
-            const void *kernel = four ? (const void *)generation_kernel<true> : (const void *)generation_kernel<false>;
-            if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return PX_E_HIP;
-            allowed[four ? 1 : 0][dev] = lds;
+        if (allowed[instance][dev] < lds) {
+            if (hipFuncSetAttribute(kernels[instance], hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return PX_E_HIP;
+            allowed[instance][dev] = lds;
         }
     }
     const unsigned children_formed = a.in_place ? (unsigned)d->P - ga->elite_k : (unsigned)d->P;
     if (children_formed > 0) {
-        if (four) hipLaunchKernelGGL(generation_kernel<true>, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
-        else hipLaunchKernelGGL(generation_kernel<false>, dim3(children_formed), dim3(kGaThreads), lds, stream, a);
+        const dim3 grid(children_formed), block(kGaThreads);
+        if (instance == 0) hipLaunchKernelGGL((generation_kernel<false, false>), grid, block, lds, stream, a);
+        else if (instance == 1) hipLaunchKernelGGL((generation_kernel<true, false>), grid, block, lds, stream, a);
+        else if (instance == 2) hipLaunchKernelGGL((generation_kernel<false, true>), grid, block, lds, stream, a);
+        else hipLaunchKernelGGL((generation_kernel<true, true>), grid, block, lds, stream, a);
     }
     return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
 }

@@ -303,6 +303,8 @@ def generation_loop(wl, gens, flags=0, precision=0, elite=None, mut=None, check_
     P = pop0.shape[0]
     elite = P // 2 if elite is None else elite
     mut = (1 << 32) // c.J if mut is None else mut
+    if inherit and (flags & px.PX_FLAG_MEMOISE):
+        flags |= px.PX_FLAG_PAIR_RESULTS           # a memoised call keeps its per-pair results only on request
     call = px.FitnessCall(P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
                           wl.node_capacity, p=c.p, delta=c.delta, flags=flags, precision=precision)
     dev = torch.as_tensor(pop0).cuda()
@@ -445,6 +447,8 @@ def test_generations_that_write_fitness_only(flags, shape, inherit):
     import paper_2008_12260_amd as px
     wl = W.make("physical") if shape is None else W.make(W.custom("fitness_only", **shape))
     c = wl.cfg
+    if inherit and flags:
+        flags |= px.PX_FLAG_PAIR_RESULTS
     calls, pops = [], []
     for outputs in ("all", "fitness"):
         call = px.FitnessCall(c.P, c.J, c.N, c.Gm, c.Gs, wl.job_params, wl.m_grid, wl.fair_share, wl.current_alloc,
