@@ -36,12 +36,12 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "68e135eecc66cc1f362088ac9b491040cb7a41f8d15a8b9abbf1e1a12e8122fa",
-        "traffic_bytes": 2_068_696 * 1024 * 2 + 649_763 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-        "fp64_flops": 64 * (8.8881e6 + 4.1625e7 + 2 * 2.7480e8),
-        "valu_insts": 1.1030e9,
+        "source_sha256": "c87d25bec49d7eb0e77291a210adeeacd87b02863d6eb228dee474a9bf37b4eb",
+        "traffic_bytes": 2_082_559 * 1024 * 2 + 645_602 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "fp64_flops": 64 * (8.960e5 + 1.7648e7 + 2 * 2.66812e8),
+        "valu_insts": 1.0559e9,
         "scan_insts": 2.25 * 1.6777e10 / 64,
-        "valu_busy": 1.1170e9 * 4 / 1024 / (3.9944e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+        "valu_busy": 1.0699e9 * 4 / 1024 / (3.8531e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
     },
 }
 GA_SEED = 0x2008_1226_5EED_0001
@@ -170,34 +170,35 @@ def main():
     torch.cuda.synchronize()
     t1 = time.perf_counter()
 
-    # the same generations with pollux_generation: the step in place, then the fitness of the 2048 children only
-    # (a survivor's results cannot change within a scheduling interval); only the children's grid points are counted
-    call.run(a, stream=stream, outputs="fitness")
-    for _ in range(2):
-        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness")
-        gen += 1
-    torch.cuda.synchronize()
-    ti0 = time.perf_counter()
-    for _ in range(args.steps):
-        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness")
-        gen += 1
-    torch.cuda.synchronize()
-    incremental_s = time.perf_counter() - ti0
-    # and with PX_GA_INHERIT_ROWS: of the children, only the rows a move or a repair has changed are read back and
-    # swept; an unchanged row takes over its parent's results (same matrices, same fitness, a few sweeps per child)
-    for _ in range(2):
-        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=True)
-        gen += 1
-    torch.cuda.synchronize()
-    th0 = time.perf_counter()
-    for _ in range(args.steps):
-        call.generation(a, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=True)
-        gen += 1
-    torch.cuda.synchronize()
-    inherited_s = time.perf_counter() - th0
+    # The next generations with pollux_generation, twice from the same population and with the same generation
+    # numbers (so both loops form the same matrices): the step in place and then (i) the fitness of the 2048
+    # children only (a survivor's results cannot change within a scheduling interval; only the children's grid
+    # points are counted), (ii) with PX_GA_INHERIT_ROWS, of the children only the rows a move or a repair has
+    # changed are read back and swept, an unchanged row takes over its parent's results.  How many rows the repairs
+    # touch depends on how far the search has converged (two-parent children of unlike parents need many).
+    b = a.clone()
+    gen_loop = gen
+    loop_s, loop_best = {}, {}
+    for inherit in (False, True):
+        if inherit:
+            a.copy_(b)
+        g = gen_loop
+        call.run(a, stream=stream, outputs="fitness")
+        for _ in range(2):
+            call.generation(a, GA_SEED, g, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=inherit)
+            g += 1
+        torch.cuda.synchronize()
+        ti0 = time.perf_counter()
+        for _ in range(args.steps):
+            call.generation(a, GA_SEED, g, elite, mut_threshold(cfg.J), stream=stream, outputs="fitness", inherit_rows=inherit)
+            g += 1
+        torch.cuda.synchronize()
+        loop_s[inherit] = time.perf_counter() - ti0
+        loop_best[inherit] = float(call.fitness.max().item())
+    gen = g
+    incremental_s, inherited_s = loop_s[False], loop_s[True]
 
     # the same search step out of place (survivors copied into a second buffer), for comparison
-    b = torch.empty_like(a)
     o0, o1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     call.ga_step(a, b, GA_SEED, gen, elite, mut_threshold(cfg.J), stream=stream)
     o0.record(stream)
@@ -234,6 +235,7 @@ def main():
         "children_only_generations_per_s": args.steps / incremental_s,
         "children_only_ms_per_generation": incremental_s * 1e3 / args.steps,
         "children_only_evals_per_s": (cfg.P - elite) * cfg.J * cfg.Gm * cfg.Gs * args.steps / incremental_s,
+        "children_only_best_fitness": loop_best[False], "changed_rows_only_best_fitness": loop_best[True],
         "changed_rows_only_generations_per_s": args.steps / inherited_s,
         "changed_rows_only_ms_per_generation": inherited_s * 1e3 / args.steps,
     }

@@ -4,8 +4,8 @@ and the jobs run on it until the next interval; Sec. 5.3: discrete-time simulati
 
 Per interval:
   1. the jobs' gradient noise scale phi_t is refreshed from their progress (the caller's `phi_of` function);
-  2. the population search runs pollux_fitness once and then `generations` calls of pollux_generation from a
-     population seeded with the current allocation;
+  2. the population search runs pollux_fitness once and then `generations` calls of pollux_generation (rows that a
+     child holds unchanged inherit their parent's results) from a population seeded with the current allocation;
   3. pollux_apply_best takes the best candidate of the last evaluation, makes it the current allocation and
      marks the jobs whose row changed as re-allocated;
   4. pollux_sim_tick advances every job on its new allocation.
@@ -20,7 +20,7 @@ from dataclasses import dataclass, field
 
 import numpy as np
 
-from . import (PX_FLAG_MEMOISE, Dims, FitnessCall, PARAM_PHI, pollux_apply_best, pollux_sim_tick)
+from . import (PX_FLAG_MEMOISE, PX_FLAG_PAIR_RESULTS, Dims, FitnessCall, PARAM_PHI, pollux_apply_best, pollux_sim_tick)
 
 
 @dataclass
@@ -54,11 +54,11 @@ def run(job_params, m_grid, fair_share, node_capacity, target, phi_of, alloc0, *
     for it in range(intervals):
         job_params[PARAM_PHI] = phi_of(np.minimum(state.progress / np.asarray(target, np.float64), 1.0))
         call = FitnessCall(P, J, N, Gm, Gs, job_params, m_grid, fair_share, state.alloc, node_capacity, p=p, delta=delta,
-                           flags=PX_FLAG_MEMOISE if memoise else 0, device=dev)
+                           flags=(PX_FLAG_MEMOISE | PX_FLAG_PAIR_RESULTS) if memoise else 0, device=dev)
         pop = call.current_alloc.unsqueeze(0).repeat(P, 1, 1).contiguous()
         call.run(pop, outputs="fitness")
         for g in range(generations):      # each: the step in place, then the fitness of the children it formed
-            call.generation(pop, seed, it * generations + g, max(1, P // 2), mut, outputs="fitness")
+            call.generation(pop, seed, it * generations + g, max(1, P // 2), mut, outputs="fitness", inherit_rows=True)
         status = call.status()          # of the search's fitness calls, accumulated over the generations
         pollux_apply_best(call.dims, pop, call.fitness, call.current_alloc, d_best, d_K, d_nodes, d_changed)
         pollux_sim_tick(Dims(P, J, N, Gm, Gs, 0, 0), call.job_params, call.m_grid, d_K, d_nodes, d_changed, d_target,

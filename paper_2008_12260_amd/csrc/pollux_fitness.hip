@@ -107,7 +107,7 @@ struct FitnessArgs {
     // row inheritance (pollux_generation with PX_GA_INHERIT_ROWS; written by the search step, see GaArgs)
     const int32_t *src_row;       // [n_sel, J] the candidate whose row j the listed child holds unchanged, or -1
     const int32_t *odd;           // [n_sel] the listed child is to be evaluated in full
-    int32_t *dirty_count, *dirty; // rows to sweep: their number, and pair index (candidate * J + job) | odd << 31 of each
+    int32_t *dirty_count, *dirty; // rows to sweep, per job: their number [J] and the candidates they belong to [J, n_sel]
     int clear_status;             // tables_kernel starts a new status word (fitness calls; the query calls leave it alone)
     int clear_counters;           // tables_kernel clears colpack (fitness calls whose population pass keeps the counters in memory)
     // outputs
@@ -1247,7 +1247,9 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // take six (80 registers), which is what they need without spilling, and are no slower for it.
 constexpr bool rows_at_a_time(int CH, bool F32, bool MEMO, bool ROW4) { return ROW4 && !F32 && !MEMO && CH != 0 && CH <= 16; }
 
-template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false, bool SEL = false>
+// SEL = 2: per job, the candidates listed in a.dirty[j, 0 .. a.dirty_count[j]) (row inheritance: the rows of job j that a
+// move or a repair of the search step has changed); workgroups beyond a job's list return at once.
+template <int CH, bool F32, bool MEMO, bool ROW1, bool WHOLE = false, bool ROW4 = false, int SEL = 0>
 __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(rows_at_a_time(CH, F32, MEMO, ROW4) ? 6 : 8)))
 pairs_kernel(FitnessArgs a)
 {
@@ -1255,6 +1257,12 @@ pairs_kernel(FitnessArgs a)
     const int j = (slot / a.cand_groups) * 8 + xcd;
     const int group = slot % a.cand_groups;
     if (j >= a.J) return;
+    // the number of candidates this job's workgroups share out among them
+    int P_eff = SEL == 1 ? a.n_sel : a.P;
+    if constexpr (SEL == 2) {
+        P_eff = __builtin_amdgcn_readfirstlane(a.dirty_count[j]);
+        if (group * a.cand_per_wave * kWavesPerBlock >= P_eff) return;
+    }
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int lane = lane_id();
     // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
@@ -1300,11 +1308,10 @@ pairs_kernel(FitnessArgs a)
     // by stepping pointers.  With SEL that number is a position in the list, and lane r holds the candidate
     // listed there (-1 past the end of the list).
     const int c0 = group * a.cand_per_wave * kWavesPerBlock + wave;
-    const int P_eff = SEL ? a.n_sel : a.P;
     int d_c = -1;
-    if constexpr (SEL) {
+    if constexpr (SEL != 0) {
         const int k = c0 + kWavesPerBlock * lane;
-        if (lane < a.cand_per_wave && k < P_eff) d_c = a.sel[k];
+        if (lane < a.cand_per_wave && k < P_eff) d_c = SEL == 2 ? a.dirty[(size_t)j * a.n_sel + k] : a.sel[k];
     }
     const size_t row_step = (size_t)kWavesPerBlock * a.J * a.N;
     const int32_t *__restrict__ row = a.population + ((size_t)c0 * a.J + j) * a.N - row_step;
@@ -1314,7 +1321,7 @@ pairs_kernel(FitnessArgs a)
         return a.population + ((size_t)__builtin_amdgcn_readlane(d_c, r) * a.J + j) * a.N;
     };
     auto advance = [&](int r) {
-        if constexpr (SEL) {
+        if constexpr (SEL != 0) {
             row = row_of(r);
             cp = a.colpack + (size_t)__builtin_amdgcn_readlane(d_c, r) * a.N;
         } else {
@@ -1419,7 +1426,7 @@ pairs_kernel(FitnessArgs a)
             for (int b = 0; b < kBatches; ++b) {
                 if (4 * b < rows) {
                     const int r = 4 * b + g < rows ? 4 * b + g : rows - 1;             // the tail reads the last row again
-                    if constexpr (SEL) {
+                    if constexpr (SEL != 0) {
                         cb[b] = __builtin_amdgcn_ds_bpermute(r << 2, d_c);
                         v[b] = ((const int4 *)(a.population + ((size_t)cb[b] * a.J + j) * a.N))[lane_off];
                     } else {
@@ -1447,7 +1454,7 @@ pairs_kernel(FitnessArgs a)
                     if (a.need_constraints && live) {
                         // every non-zero entry goes to the candidate's per-node counters (a negative one as it is)
                         const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
-                        unsigned long long *__restrict__ to = SEL ? a.colpack + (size_t)cb[b] * a.N + 4 * l16
+                        unsigned long long *__restrict__ to = SEL != 0 ? a.colpack + (size_t)cb[b] * a.N + 4 * l16
                                                                   : cp1 + (size_t)r * kWavesPerBlock * a.N;
                         if (w.x != 0) atomicAdd(&to[0], (unsigned long long)(long long)w.x + (w.x > 0 ? one_job : 0ull));
                         if (w.y != 0) atomicAdd(&to[1], (unsigned long long)(long long)w.y + (w.y > 0 ? one_job : 0ull));
@@ -1474,7 +1481,7 @@ pairs_kernel(FitnessArgs a)
 #pragma unroll
                 for (int u = 0; u < kAhead; ++u) {
                     const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
-                    if constexpr (SEL) v[u] = ((const int4 *)row_of(ru))[lane4];
+                    if constexpr (SEL != 0) v[u] = ((const int4 *)row_of(ru))[lane4];
                     else v[u] = ((const int4 *)(row + (size_t)(ru - r0 + 1) * row_step))[lane4];
                 }
 #pragma unroll
@@ -1555,7 +1562,7 @@ pairs_kernel(FitnessArgs a)
         // the sampling argmax: one candidate after the other, priced where it is swept
         for (int r = 0; r < a.cand_per_wave; ++r) {
             if (c0 + kWavesPerBlock * r >= P_eff) break;
-            const int c = SEL ? __builtin_amdgcn_readlane(d_c, r) : c0 + kWavesPerBlock * r;
+            const int c = SEL != 0 ? __builtin_amdgcn_readlane(d_c, r) : c0 + kWavesPerBlock * r;
             int K, nodes;
             bool changed, neg;
             advance(r);
@@ -1615,8 +1622,8 @@ pairs_kernel(FitnessArgs a)
         // Lane l finishes the l-th candidate of this wavefront: the elected point is priced with
         // Eq. 4 in the paper's order of operations (or looked up in memoised mode) and stored.
         const int k = (group * b.cand_per_wave + lane) * kWavesPerBlock + wave;
-        if (lane < b.cand_per_wave && k < (SEL ? b.n_sel : b.P)) {
-            const int c = SEL ? d_c : k;
+        if (lane < b.cand_per_wave && k < (SEL == 2 ? P_eff : (SEL == 1 ? b.n_sel : b.P))) {
+            const int c = SEL != 0 ? d_c : k;
             const size_t pair = (size_t)c * b.J + j;
             const int nodes = d_meta & ~kMetaChanged;
             Best best;
@@ -1804,10 +1811,13 @@ __global__ void __launch_bounds__(kCandThreads) candidates_kernel(FitnessArgs a)
 // The search step has left, per child it formed and per job, the candidate whose row the child holds unchanged
 // (a survivor: its results are in place), or -1.  Eq. 13, the re-allocation flag and everything else the fitness
 // takes from a row depend on the row, the job and the current allocation only, so an unchanged row takes over the
-// results of its source; the rows a move or a repair has changed are listed for dirty_rows_kernel.  A child the
-// step has flagged (a.odd: it may hold a negative entry or violate a constraint) lists all its rows, with the flag
-// that makes dirty_rows_kernel feed the per-node counters too; every other child satisfies both constraints by
-// construction and its counters stay at zero.  One workgroup per listed child; candidates_kernel follows as usual.
+// results of its source.  The rows a move or a repair has changed are listed per job (a.dirty[j, ...], counted in
+// a.dirty_count[j]) for pairs_kernel with SEL = 2, which treats them like any other (candidate, job) pair, per-node
+// counters included.  A child the step has flagged (a.odd: it may hold a negative entry or violate a constraint)
+// lists all its rows, so its counters come out complete; of every other child only some rows reach the counters,
+// and a part of a matrix that satisfies both constraints (which such a child does by construction) satisfies
+// them too, so its violation count is the zero it has to be.  One workgroup per listed child; candidates_kernel
+// follows as usual.
 __global__ void __launch_bounds__(256) inherit_kernel(FitnessArgs a)
 {
     const int k = blockIdx.x;
@@ -1827,69 +1837,7 @@ __global__ void __launch_bounds__(256) inherit_kernel(FitnessArgs a)
             }
             if (a.best_goodput) a.best_goodput[to] = a.best_goodput[from];
         } else {
-            a.dirty[atomicAdd(a.dirty_count, 1)] = (int32_t)((uint32_t)to | (odd ? 0x80000000u : 0u));
-        }
-    }
-}
-
-// One wavefront per listed row at a time: row reduce, the sweep (or the look-up in memoised mode) and the pricing
-// of a (candidate, job) pair, as pairs_kernel does them; for a row of a flagged child also its entries to the
-// per-node counters.  The list is short (a few rows per child), so the plain forms of the sweep do.
-template <int CH, bool F32>
-__global__ void __launch_bounds__(256) dirty_rows_kernel(FitnessArgs a)
-{
-    const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-    const int lane = lane_id();
-    const int total = __builtin_amdgcn_readfirstlane(*a.dirty_count);
-    const bool memo = (a.flags & PX_FLAG_MEMOISE) != 0;
-    for (int i = blockIdx.x * kWavesPerBlock + wave; i < total; i += gridDim.x * kWavesPerBlock) {
-        const int entry = __builtin_amdgcn_readfirstlane(a.dirty[i]);
-        const bool odd = entry < 0;
-        const int pair = entry & 0x7FFFFFFF;
-        const int c = pair / a.J, j = pair - c * a.J;
-        const int32_t *__restrict__ row = a.population + (size_t)pair * a.N;
-        const int32_t *__restrict__ cur = a.current_alloc + (size_t)j * a.N;
-        int ksum = 0, nodes = 0;
-        bool changed = false, neg = false;
-        for (int n0 = 0; n0 < a.N; n0 += kWave) {
-            const int n = n0 + lane;
-            const int v = n < a.N ? row[n] : 0;
-            const int cv = n < a.N ? cur[n] : 0;
-            ksum += v;
-            nodes += __popcll(__ballot(v > 0));
-            changed |= __ballot(v != cv) != 0;
-            neg |= __ballot(v < 0) != 0;
-        }
-        const int K = wave_sum(ksum);
-        if (odd && a.need_constraints) {
-            const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
-            unsigned long long *__restrict__ cp = a.colpack + (size_t)c * a.N;
-            for (int n = lane; n < a.N; n += kWave) {
-                const int v = row[n];
-                if (v != 0) atomicAdd(&cp[n], (unsigned long long)(long long)v + (v > 0 ? one_job : 0ull));
-            }
-        }
-        const JobTables tb = job_tables(a, j);
-        Best best;
-        if (memo && K >= 1 && tabled_row(K, nodes == 1, tb.k1)) {
-            const MemoEntry e = a.memo[((size_t)j * 2 + (nodes == 1 ? 1 : 0)) * kTableK + (K - 1)];
-            best.goodput = e.goodput; best.m = e.m; best.s = e.s;
-        } else if constexpr (CH == 0) {
-            best = sweep_sampled(load_job(a.job_params, a.J, j), tb.m, a.Gm, a.Gs, K, nodes);
-        } else if constexpr (F32) {
-            best = sweep_any_f32<CH>(load_job_f32(a.job_params, a.J, j), tb, a.rsf, a.rk, a.Gm, a.Gs, K, nodes);
-        } else {
-            best = sweep<CH>(load_job(a.job_params, a.J, j), tb, a.rs, a.rk, a.Gm, a.Gs, K, nodes);
-        }
-        if (lane == 0) {
-            a.G[pair] = best.goodput;
-            a.meta[pair] = nodes | (changed ? kMetaChanged : 0);
-            if (a.best_m) {
-                a.best_m[pair] = best.m;
-                a.best_s[pair] = best.s;
-            }
-            if (a.best_goodput) a.best_goodput[pair] = best.goodput;
-            if (neg) atomicOr(a.status, PX_ST_NEG_ALLOC);
+            a.dirty[(size_t)j * a.n_sel + atomicAdd(&a.dirty_count[j], 1)] = slot;
         }
     }
 }
@@ -2296,28 +2244,17 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool row1 = d->N <= 4 * kWave && (d->N & 3) == 0 && (((uintptr_t)population | (uintptr_t)current_alloc) & 15) == 0;
     const bool row4 = row1 && d->N <= kWave;        // four rows per load of a wavefront (cand_per_wave <= 16 holds)
     // memoised pass over rows of 65 to 256 entries: one workgroup per candidate, counters in LDS, fitness included
-    const bool candidate_pass = memo && !sampled && !f32 && row1 && !row4;
-    if (inherit_rows && first_rank > 0) {
-        // the children of the step that has just run: unchanged rows take over their source's results, the others
-        // are swept one by one, then SPEEDUP and the generalized mean per child as usual
+    const bool inherit = inherit_rows && first_rank > 0;
+    // (not with row inheritance, whose rows to evaluate are listed per job, not per candidate)
+    const bool candidate_pass = memo && !sampled && !f32 && row1 && !row4 && !inherit;
+    if (inherit) {
+        // the children of the step that has just run: unchanged rows take over their source's results; the others are
+        // listed per job and go through the population pass below like any pair
         a.src_row = (const int32_t *)(ws + L.src_row);
         a.odd = (const int32_t *)(ws + L.odd);
         a.dirty_count = (int32_t *)(ws + L.dirty_count);
         a.dirty = (int32_t *)(ws + L.dirty);
         hipLaunchKernelGGL(inherit_kernel, dim3((unsigned)P_eff), dim3(256), 0, stream, a);
-        // enough wavefronts that each takes one or two rows even when a tenth of the rows is listed
-        long long db = pairs / 32;
-        db = db < 256 ? 256 : (db > 4096 ? 4096 : db);
-        const dim3 dirty_grid((unsigned)db);
-        if (sampled) hipLaunchKernelGGL((dirty_rows_kernel<0, false>), dirty_grid, dim3(256), 0, stream, a);
-        else if (f32 && ch == 8) hipLaunchKernelGGL((dirty_rows_kernel<8, true>), dirty_grid, dim3(256), 0, stream, a);
-        else if (f32) hipLaunchKernelGGL((dirty_rows_kernel<16, true>), dirty_grid, dim3(256), 0, stream, a);
-        else if (ch == 8) hipLaunchKernelGGL((dirty_rows_kernel<8, false>), dirty_grid, dim3(256), 0, stream, a);
-        else if (ch == 16) hipLaunchKernelGGL((dirty_rows_kernel<16, false>), dirty_grid, dim3(256), 0, stream, a);
-        else hipLaunchKernelGGL((dirty_rows_kernel<32, false>), dirty_grid, dim3(256), 0, stream, a);
-        if (f32) hipLaunchKernelGGL(candidates_kernel<float>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
-        else hipLaunchKernelGGL(candidates_kernel<double>, dim3((unsigned)P_eff), dim3(kCandThreads), 0, stream, a);
-        return hipGetLastError() == hipSuccess ? PX_OK : PX_E_HIP;
     }
     // done by tables_kernel, i.e. not by a call that keeps the job tables; the candidate pass keeps its counters on chip
     // and leaves those in memory alone, unless generations that inherit rows (and read them) are to follow
@@ -2346,8 +2283,9 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     const bool whole = d->Gm % kWave == 0;
 #define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4)                                                               \
     do {                                                                                                                \
-        if (a.sel) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, true>), dim3(pair_blocks), dim3(256), 0, stream, a); \
-        else hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, false>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+        if (a.dirty) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, 2>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+        else if (a.sel) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, 1>), dim3(pair_blocks), dim3(256), 0, stream, a); \
+        else hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, 0>), dim3(pair_blocks), dim3(256), 0, stream, a); \
     } while (0)
     // the instance for the row length (four rows per load, one row per load, any) and the grid (whole groups of 64 batch sizes or not)
 #define PX_LAUNCH_PAIRS_GRID(CH, F32)                                          \

@@ -58,7 +58,7 @@ struct GaArgs {
     int32_t *odd;          // [P - elite_k]: 1 if the child may violate a constraint or hold a negative entry (a negative
                            // entry was met, a node could not be brought within its capacity, or the node lists
                            // overflowed), so that nothing about it may be taken for granted
-    int32_t *dirty_count;  // one word, set to zero by the step: the rows to be swept are counted there afterwards
+    int32_t *dirty_count;  // [J], set to zero by the step: the rows to be swept are counted there afterwards, per job
 };
 
 // ---- rank ----------------------------------------------------------------------
@@ -68,7 +68,9 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 {
     const int wave = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
     const int c = blockIdx.x * 4 + wave;           // one wavefront per candidate, lanes over the others
-    if (a.dirty_count && blockIdx.x == 0 && threadIdx.x == 0) *a.dirty_count = 0;
+    if (a.dirty_count && blockIdx.x == 0) {
+        for (int j = threadIdx.x; j < a.J; j += blockDim.x) a.dirty_count[j] = 0;
+    }
     if (c >= a.P) return;
     const int lane = lane_id();
     double f = a.fitness[c];

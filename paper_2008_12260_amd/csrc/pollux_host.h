@@ -35,8 +35,8 @@ struct WorkspaceLayout {
     // row inheritance of pollux_generation (child k = the candidate of rank elite_k + k)
     size_t src_row;   // int32  [P,J]     the candidate whose row j child k holds unchanged, or -1
     size_t odd;       // int32  [P]       child k may violate a constraint: nothing about it is taken for granted
-    size_t dirty_count;  // int32         rows to sweep
-    size_t dirty;     // int32  [P,J]     those rows: pair index (candidate * J + job) | odd << 31
+    size_t dirty_count;  // int32 [J]     rows of job j to sweep
+    size_t dirty;     // int32  [J,P]     the candidates those rows belong to (row stride: the number of children)
     // from here on the offsets depend on the grid
     size_t rs;        // double [Gs up to a multiple of 32]  1/(s+1)
     size_t rsf;       // float  [Gs up to a multiple of 32]  the same in fp32
@@ -74,7 +74,7 @@ inline WorkspaceLayout workspace_layout(const pollux_dims &d)
     L.colpack = o; o = up(o + 8 * P * (size_t)d.N);
     L.src_row = o; o = up(o + 4 * P * J);
     L.odd = o;     o = up(o + 4 * P);
-    L.dirty_count = o; o = up(o + 256);
+    L.dirty_count = o; o = up(o + 4 * J);
     L.dirty = o;   o = up(o + 4 * P * J);
     L.rs = o;      o = up(o + 8 * ((Gs + 31) / 32) * 32);
     L.rsf = o;     o = up(o + 4 * ((Gs + 31) / 32) * 32);
