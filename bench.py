@@ -36,12 +36,12 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "c87d25bec49d7eb0e77291a210adeeacd87b02863d6eb228dee474a9bf37b4eb",
-        "traffic_bytes": 2_082_559 * 1024 * 2 + 645_602 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
-        "fp64_flops": 64 * (8.960e5 + 1.7648e7 + 2 * 2.66812e8),
-        "valu_insts": 1.0559e9,
+        "source_sha256": "2810147e4a6b9b8651922799268ad459df13ef29765fc6ef79ee5c9d1a33e677",
+        "traffic_bytes": 2_081_291 * 1024 * 2 + 645_602 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
+        "fp64_flops": 64 * (8.960e5 + 1.7635e7 + 2 * 2.66600e8),
+        "valu_insts": 1.0551e9,
         "scan_insts": 2.25 * 1.6777e10 / 64,
-        "valu_busy": 1.0699e9 * 4 / 1024 / (3.8531e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+        "valu_busy": 1.0691e9 * 4 / 1024 / (3.8043e7 / 8),              # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
     },
 }
 GA_SEED = 0x2008_1226_5EED_0001
