@@ -199,8 +199,8 @@ int pollux_fitness_timed(const pollux_dims *dims, const int32_t *population, con
  * kernels.
  *
  * Limit: pollux_workspace_size(dims) must not exceed POLLUX_STATIC_SCRATCH_BYTES, otherwise
- * PX_E_WORKSPACE is returned before anything is launched (32 MiB holds, for example, 1000
- * candidates x 200 jobs x 64 nodes with a 64 x 16 grid).
+ * PX_E_WORKSPACE is returned before anything is launched (64 MiB holds, for example, 1000
+ * candidates x 200 jobs x 64 nodes with a 64 x 16 grid, which needs 46 MiB).
  *
  * Every call on a GPU uses that GPU's one array: two calls that overlap in time on one GPU
  * (different streams or threads) race and give undefined results; calls on one stream, or

@@ -52,7 +52,7 @@ def assert_same(want, got):
 
 def test_two_calls_in_a_row_the_second_on_a_smaller_problem():
     import paper_2008_12260_amd as px
-    big = W.make("mid")                       # 19.4 MiB of scratch: most of the array
+    big = W.make("mid")                       # 46 MiB of scratch: most of the array
     assert px.workspace_size(px.Dims(big.cfg.P, big.cfg.J, big.cfg.N, big.cfg.Gm, big.cfg.Gs, 0, 0)) <= px.STATIC_SCRATCH_BYTES
     spoiled = big.population.copy()
     spoiled[::7] *= 3                         # many nodes over capacity: the per-node counters are exercised
