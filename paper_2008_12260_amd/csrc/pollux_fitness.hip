@@ -1824,20 +1824,42 @@ __global__ void __launch_bounds__(256) inherit_kernel(FitnessArgs a)
     const int slot = a.sel[k];
     const bool odd = a.odd[k] != 0;
     const int32_t *__restrict__ src = a.src_row + (size_t)k * a.J;
-    for (int j = threadIdx.x; j < a.J; j += 256) {
-        const int s = odd ? -1 : src[j];
-        const size_t to = (size_t)slot * a.J + j;
-        if (s >= 0) {
-            const size_t from = (size_t)s * a.J + j;
-            a.G[to] = a.G[from];
-            a.meta[to] = a.meta[from];
-            if (a.best_m) {
-                a.best_m[to] = a.best_m[from];
-                a.best_s[to] = a.best_s[from];
+    // four jobs per thread and pass: the sources first, then all the reads that depend on them, then the stores
+    constexpr int kJobs = 4;
+    for (int j0 = threadIdx.x; j0 < a.J; j0 += kJobs * 256) {
+        int s[kJobs];
+#pragma unroll
+        for (int u = 0; u < kJobs; ++u) {
+            const int j = j0 + u * 256;
+            s[u] = (j < a.J && !odd) ? src[j] : -1;
+        }
+        double g[kJobs], bg[kJobs];
+        int32_t mt[kJobs], bm[kJobs], bs[kJobs];
+#pragma unroll
+        for (int u = 0; u < kJobs; ++u) {
+            const size_t from = (size_t)(s[u] >= 0 ? s[u] : slot) * a.J + (j0 + u * 256 < a.J ? j0 + u * 256 : 0);
+            g[u] = a.G[from];
+            mt[u] = a.meta[from];
+            bm[u] = a.best_m ? a.best_m[from] : 0;
+            bs[u] = a.best_m ? a.best_s[from] : 0;
+            bg[u] = a.best_goodput ? a.best_goodput[from] : 0.0;
+        }
+#pragma unroll
+        for (int u = 0; u < kJobs; ++u) {
+            const int j = j0 + u * 256;
+            if (j >= a.J) continue;
+            const size_t to = (size_t)slot * a.J + j;
+            if (s[u] >= 0) {
+                a.G[to] = g[u];
+                a.meta[to] = mt[u];
+                if (a.best_m) {
+                    a.best_m[to] = bm[u];
+                    a.best_s[to] = bs[u];
+                }
+                if (a.best_goodput) a.best_goodput[to] = bg[u];
+            } else {
+                a.dirty[(size_t)j * a.n_sel + atomicAdd(&a.dirty_count[j], 1)] = slot;
             }
-            if (a.best_goodput) a.best_goodput[to] = a.best_goodput[from];
-        } else {
-            a.dirty[(size_t)j * a.n_sel + atomicAdd(&a.dirty_count[j], 1)] = slot;
         }
     }
 }
