@@ -7,12 +7,14 @@
 //
 // Kernels (one call = five launches on the caller's stream)
 //   tables_kernel     per job and grid point: T_grad(m) (Eq. 8), 1/T_grad, ln T_grad, phi/m and
-//                     the feasibility bounds; reciprocals; clears the status word and the per-node counters
+//                     the feasibility bounds; reciprocals; the largest node capacity; clears the status
+//                     word and the per-node counters
 //   last_kernel       per job, placement class and GPU count K <= 64 (one wavefront
-//                     per eight rows): T_sync (Eq. 9) and, for every batch size of the grid,
-//                     the last pass of Eq. 10, (T_grad^g + T_sync^g)^(1/g).  That
-//                     term depends on the allocation only through K and on whether
-//                     the job sits on one node, so it is shared by the population;
+//                     per eight rows; the "one node" class only up to the largest node capacity):
+//                     T_sync (Eq. 9) and, for every batch size of the grid, the last pass of Eq. 10,
+//                     (T_grad^g + T_sync^g)^(1/g), and the two terms C and A0 the sweep needs of it.
+//                     They depend on the allocation only through K and on whether the job sits on
+//                     one node, so they are shared by the population;
 //                     also the feasible accumulation counts per (job, K, batch size)
 //   jobs_kernel       per job (one wavefront): parameter checks, restart factor,
 //                     fair-share goodput (denominator of Eq. 15)
@@ -26,6 +28,9 @@
 // per workgroup and finishes its fitness as well (no per-pair scratch, no candidates_kernel).
 // With PX_FLAG_SAMPLE_M the sweep is replaced by sweep_sampled (Sec. 4.3), the kernels
 // instantiated with CH = 0, and last_kernel is not launched.
+// For pollux_generation the population pass takes a list of candidates (the children of the search step), or,
+// with PX_GA_INHERIT_ROWS, per job the list of rows the step has changed, after inherit_kernel has given every
+// unchanged row the results of the row it was copied from.
 //
 // How one wavefront sweeps the grid of a (candidate, job) pair.  Lane l owns
 // the batch sizes m_i, i = l, l+64, ...; it walks s = 0..Gs-1.  Dividing Eq. 4
@@ -42,8 +47,8 @@
 // that result after its low five mantissa bits have been replaced by the index of the group (so
 // the minimum carries the group it came from and equal values resolve to the earlier group; the
 // perturbation is 2^-47 relative).  The s inside the winning group is found once per lane
-// afterwards, from the group's four values formed again with their position in the low bits
-// (equal values: the smaller s).  w is convex in s
+// afterwards by an exact comparison: w(s+1) < w(s) precisely when C > (s+1)(s+2), so the argmin is
+// a count of thresholds below C (scan_argmin; equal values: the smaller s).  w is convex in s
 // (C >= 0), so the feasible optimum sits at the scan's argmin clamped to s_lo..s_hi; h is
 // formed there once per lane and group of 64 batch sizes.  The wave then takes the
 // smallest h (equal values: lowest flat index), and the elected point is evaluated
