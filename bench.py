@@ -36,7 +36,7 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "6ea24d878fdd9c9635f9708e7056a9416a62c7351288d9f4428df5a8ac339035",
+        "source_sha256": "d30be7c784267b25f5412abf2f3503590d93645cbf50ffa7a969c75c37ce8bed",
         "traffic_bytes": 2_081_291 * 1024 * 2 + 645_602 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0
         "fp64_flops": 64 * (8.960e5 + 1.7635e7 + 2 * 2.66600e8),
         "valu_insts": 1.0551e9,
