@@ -135,6 +135,21 @@ def test_the_newer_entry_points_reject_bad_arguments_without_a_device():
     ga = px.GaParams(1, 0, 8, 0, 2)                                    # unknown search flag
     dd = px.Dims(16, 8, 4, 32, 8, 0, 0)
     assert L.pollux_ga_step(ctypes.byref(dd), fake, fake, fake, ctypes.byref(ga), fake, 1 << 30, ctypes.c_void_p(0x90000000), null) == px.PX_E_INVALID_ARG
+    # pollux_generation: in place always; rows are inherited only in place, and of a memoised call only when it was
+    # asked to leave its per-pair results in the workspace
+    def generation(dims, flags):
+        g = px.GaParams(1, 0, 8, 0, flags, None)
+        return L.pollux_generation(ctypes.byref(dims), *([fake] * 6), -1.0, 30.0, ctypes.byref(g), null, 0, *([fake] * 6), null)
+    assert generation(dd, 0) == px.PX_E_INVALID_ARG
+    assert generation(dd, px.PX_GA_INHERIT_ROWS) == px.PX_E_INVALID_ARG
+    assert generation(dd, px.PX_GA_IN_PLACE | 4) == px.PX_E_INVALID_ARG
+    memo = px.Dims(16, 8, 4, 32, 8, 0, px.PX_FLAG_MEMOISE)
+    assert generation(memo, px.PX_GA_IN_PLACE | px.PX_GA_INHERIT_ROWS) == px.PX_E_INVALID_ARG
+    # (valid flags get as far as the workspace check)
+    assert generation(dd, px.PX_GA_IN_PLACE) == px.PX_E_WORKSPACE
+    assert generation(dd, px.PX_GA_IN_PLACE | px.PX_GA_INHERIT_ROWS) == px.PX_E_WORKSPACE
+    memo_pairs = px.Dims(16, 8, 4, 32, 8, 0, px.PX_FLAG_MEMOISE | px.PX_FLAG_PAIR_RESULTS)
+    assert generation(memo_pairs, px.PX_GA_IN_PLACE | px.PX_GA_INHERIT_ROWS) == px.PX_E_WORKSPACE
 
 
 def test_shapes_whose_bookkeeping_does_not_fit_on_chip_are_rejected():
