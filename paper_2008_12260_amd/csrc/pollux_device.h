@@ -50,6 +50,32 @@ __device__ __forceinline__ long long wave_broadcast(long long v, int src)
     return ((long long)hi << 32) | (long long)(unsigned)lo;
 }
 
+// `into` with the value of lane LANE replaced by `value` (the same in every lane: it is read from a scalar register).
+template <int LANE>
+__device__ __forceinline__ int write_lane(int into, int value)
+{
+    asm("v_writelane_b32 %0, %1, %2" : "+v"(into) : "s"(value), "n"(LANE));
+    return into;
+}
+
+// The same for a lane number 0 .. 7 that is a constant once the caller's loop is unrolled.
+__device__ __forceinline__ int write_lane8(int into, int value, int lane)
+{
+    switch (lane) {
+    case 0: return write_lane<0>(into, value);
+    case 1: return write_lane<1>(into, value);
+    case 2: return write_lane<2>(into, value);
+    case 3: return write_lane<3>(into, value);
+    case 4: return write_lane<4>(into, value);
+    case 5: return write_lane<5>(into, value);
+    case 6: return write_lane<6>(into, value);
+    default: return write_lane<7>(into, value);
+    }
+}
+
+// Every lane receives the value of the lane eight below it in its row of 16 lanes; the lower eight lanes of a row receive 0.
+__device__ __forceinline__ int row16_up8(int v) { return __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, true); }   // row_shr:8
+
 template <int STEP = 0>
 __device__ __forceinline__ long long wave_sum(long long v)
 {

@@ -599,17 +599,15 @@ __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDo
         const int t0 = 4 * g_star;
         s_star = t0 - 1;
         if (has_near) {
-            // two, two and one at a time, each read issued after the previous comparison (the opaque
-            // statements tie the address to the running count): five values held at once would cost
-            // the kernel registers it does not have
+            // all five requested together: three reads in a row cost three LDS round trips per batch size, and after
+            // the scan the registers its values occupied are free
             LdsDoubles u = near + kNearRecips + t0;
             const Double2 a01 = *(const Double2 __attribute__((address_space(3))) *)u;
-            s_star += (C > a01.x ? 1 : 0) + (C > a01.y ? 1 : 0);
-            asm volatile("" : "+v"(s_star), "+v"(u));
             const Double2 a23 = *(const Double2 __attribute__((address_space(3))) *)(u + 2);
+            const double a4 = u[4];
+            s_star += (C > a01.x ? 1 : 0) + (C > a01.y ? 1 : 0);
             s_star += (C > a23.x ? 1 : 0) + (C > a23.y ? 1 : 0);
-            asm volatile("" : "+v"(s_star), "+v"(u));
-            s_star += C > u[4] ? 1 : 0;
+            s_star += C > a4 ? 1 : 0;
         } else {
             const double td = (double)t0;
             s_star += (C > (t0 > 0 ? px_fma(td, td, td) : -1.0) ? 1 : 0);
@@ -673,16 +671,22 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         const int i = i0 + lane;
         const bool active = WHOLE || i < Gm;
         const int il = active ? i : Gm - 1;
-        // a uniform base plus a 32-bit byte offset per lane: the address needs no 64-bit vector arithmetic
+        // a uniform base plus a 32-bit byte offset per lane: the address needs no 64-bit vector arithmetic;
+        // the offsets of the 16-byte and the 4-byte entries are one shift-and-add each on the lane number
         const unsigned at = (unsigned)il * 8u;
+        // (the opaque statement keeps the two shifted counters on the scalar unit)
+        unsigned i16 = (unsigned)i0 << 4, i4 = (unsigned)i0 << 2;
+        asm("" : "+s"(i16), "+s"(i4));
+        const unsigned at16 = WHOLE ? ((unsigned)lane << 4) + i16 : (unsigned)il * 16u;
+        const unsigned at4 = WHOLE ? ((unsigned)lane << 2) + i4 : (unsigned)il * 4u;
         double key = __builtin_inf();    // h of this batch size at its best feasible count s_c
         int s_c = 0;
         bool feasible;
         if constexpr (TABLED) {
-            const double tg = *(const double *)((const char *)tb.tg + 2u * at);
-            const double2 car = *(const double2 *)((const char *)carow + 2u * at);
+            const double tg = *(const double *)((const char *)tb.tg + at16);
+            const double2 car = *(const double2 *)((const char *)carow + at16);
             const double C = car.x, A0 = car.y;     // A0 = +inf when the batch size has no feasible count
-            const int bounds = *(const int32_t *)((const char *)srow + (at >> 1));
+            const int bounds = *(const int32_t *)((const char *)srow + at4);
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active;
             const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
@@ -1274,13 +1278,22 @@ pairs_kernel(FitnessArgs a)
     // behind them U[t] = t (t+1), U[0] = -1: what decides the order of neighbouring counts (sweep_pick)
     __shared__ __align__(16) double r_lds[2 * kNearRecips + 8];
     bool has_near = false;
-    if constexpr (CH != 0 && !MEMO) {
-        if (a.gs_pad <= kNearRecips) {
-            for (int t = threadIdx.x; t < a.gs_pad; t += blockDim.x) {
+    // (the instances that read one row per wavefront load fill the table after they have requested their first rows)
+    constexpr bool kRowsFirst = CH != 0 && ROW1 && !ROW4;
+    // every thread brings one entry, formed by the same division as the entry of a.rs (tables_kernel): no load, so
+    // storing it waits for nothing that is on its way from memory
+    static_assert(kNearRecips <= kWavesPerBlock * kWave, "one entry per thread");
+    const bool near_fits = CH != 0 && !MEMO && a.gs_pad <= kNearRecips;
+    const double near_d = 1.0 / (double)((int)threadIdx.x + 1);
+    const float near_f = 1.0f / (float)((int)threadIdx.x + 1);
+    auto fill_near = [&]() {
+        if (near_fits) {
+            const int t = threadIdx.x;
+            if (t < a.gs_pad) {
                 if constexpr (F32) {
-                    ((float *)r_lds)[t] = a.rsf[t];
+                    ((float *)r_lds)[t] = near_f;
                 } else {
-                    r_lds[t] = a.rs[t];
+                    r_lds[t] = near_d;
                     for (int e = t; e < a.gs_pad + 8; e += a.gs_pad) {
                         const double ed = (double)e;
                         r_lds[kNearRecips + e] = e > 0 ? ed * (ed + 1.0) : -1.0;
@@ -1290,7 +1303,8 @@ pairs_kernel(FitnessArgs a)
             __syncthreads();
             has_near = true;
         }
-    }
+    };
+    if constexpr (!kRowsFirst) fill_near();
     const Job q = load_job(a.job_params, a.J, j);
     JobF32 qf = {};
     if constexpr (F32) qf = load_job_f32(a.job_params, a.J, j);
@@ -1336,8 +1350,11 @@ pairs_kernel(FitnessArgs a)
     };
 
     // The row stage of the current candidate (see advance): row reduce and constraint counters.
-    // ROW1 callers that have the row in registers already pass it as `have`; otherwise it is read here.
-    auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out, const int4 *have = nullptr) {
+    // ROW1 callers that have the row in registers already pass it as `have`; otherwise it is read here.  Callers
+    // that have the row's sum already pass it as `K_have`, with `in_range` when they know that the row has no
+    // negative entry.
+    auto row_stage = [&](int &K_out, int &nodes_out, bool &changed_out, bool &neg_out, const int4 *have = nullptr,
+                         const int *K_have = nullptr, int in_range = 0) {
         // row reduce: K = sum, nodes = #positive, changed = differs from the current row
         int ksum = 0, nodes = 0;
         bool changed = false, neg = false;
@@ -1345,12 +1362,14 @@ pairs_kernel(FitnessArgs a)
         if constexpr (ROW1) {
             const int4 v = have ? *have : ((const int4 *)row)[lane4];
             v0 = v;
-            const int part = (v.x + v.y) + (v.z + v.w);
-            ksum = lane < n4 ? part : 0;
+            if (!K_have) {
+                const int part = (v.x + v.y) + (v.z + v.w);
+                ksum = lane < n4 ? part : 0;
+            }
             nodes = __popcll(__ballot(v.x > 0) & in_row) + __popcll(__ballot(v.y > 0) & in_row) +
                     __popcll(__ballot(v.z > 0) & in_row) + __popcll(__ballot(v.w > 0) & in_row);
             changed = ((__ballot(v.x != cur0.x) | __ballot(v.y != cur0.y) | __ballot(v.z != cur0.z) | __ballot(v.w != cur0.w)) & in_row) != 0;
-            neg = (__ballot((v.x | v.y | v.z | v.w) < 0) & in_row) != 0;
+            if (in_range == 0) neg = (__ballot((v.x | v.y | v.z | v.w) < 0) & in_row) != 0;
         } else if (vec4) {
             const int4 *__restrict__ row4 = (const int4 *)row;
             const int4 *__restrict__ cur4 = (const int4 *)cur;
@@ -1380,12 +1399,16 @@ pairs_kernel(FitnessArgs a)
                 neg |= __ballot(v < 0) != 0;
             }
         }
-        const int K = wave_sum(ksum);
+        const int K = K_have ? *K_have : wave_sum(ksum);
 
         // constraint check, part one: the row's non-zero entries (a job sits on few nodes) go to the
         // candidate's per-node counters; a multi-node job also counts once on each of its nodes.
         // One 64-bit integer atomic per entry: the result does not depend on the order of arrival.
-        if (a.need_constraints) {
+        // (the flags of this stage are kept as integers in scalar registers: the compiler otherwise carries a
+        // truth value across the branches as a lane mask that it rebuilds with two vector instructions)
+        int need = __builtin_amdgcn_readfirstlane(a.need_constraints);
+        asm volatile("" : "+s"(need));
+        if (need != 0) {
             const unsigned long long one_job = nodes >= 2 ? kPackJob : 0ull;
             if ((ROW1 || (vec4 && a.N <= 4 * kWave)) && !neg) {
                 // the row is still in registers and has no negative entry
@@ -1479,31 +1502,84 @@ pairs_kernel(FitnessArgs a)
                 }
             }
         } else if constexpr (ROW1) {
-            // eight rows are requested together: their latencies overlap
+            // eight rows are requested together: their latencies overlap.  The last eight come first: a stretch leaves
+            // what its candidates need in lanes 0 .. 7, and the lanes move up by eight before the next stretch
             constexpr int kAhead = 8;
-            for (int r0 = 0; r0 < rows; r0 += kAhead) {
-                int4 v[kAhead];
+            static_assert(kMaxCandPerWave <= 2 * kAhead, "two stretches at most (the lanes move inside a row of 16)");
+            const int r_last = (rows - 1) & ~(kAhead - 1);
+            int at_row = -1;          // the candidate (of this wavefront) that `row` and `cp` point at
+            int4 v[kAhead];
+            const int32_t *__restrict__ row_first = row + row_step;       // the row of the wavefront's candidate 0 (SEL == 0)
+            auto request = [&](int r, int4 &to) {
+                const int ru = r < rows ? r : rows - 1;                   // the tail reads the last row again
+                if constexpr (SEL != 0) to = ((const int4 *)row_of(ru))[lane4];
+                else to = ((const int4 *)(row_first + (size_t)ru * row_step))[lane4];
+            };
+            // the rows of the first stretch are on their way while the workgroup fills its table in LDS
+            if (r_last >= 0) {
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
-                    const int ru = r0 + u < rows ? r0 + u : rows - 1;             // the tail reads the last row again
-                    if constexpr (SEL != 0) v[u] = ((const int4 *)row_of(ru))[lane4];
-                    else v[u] = ((const int4 *)(row + (size_t)(ru - r0 + 1) * row_step))[lane4];
+                for (int u = 0; u < kAhead; ++u) request(r_last + u, v[u]);
+            }
+            fill_near();
+            // One stretch; with NEXT its rows' registers are handed on to the rows of the stretch below it, two at a
+            // time.  (Written out once per stretch instead of as a loop, so that every wait names the loads it needs.)
+            auto stretch = [&](int r0, auto hand_on) {
+                if constexpr (SEL == 0) {
+                    // advance() steps from one candidate to the next: start one before the stretch
+                    const ptrdiff_t step = r0 - 1 - at_row;
+                    row += step * (ptrdiff_t)row_step;
+                    cp += step * (ptrdiff_t)kWavesPerBlock * a.N;
+                    at_row = (r0 + kAhead < rows ? r0 + kAhead : rows) - 1;
                 }
+                // The sums of two rows come out of one reduction, 16 bits each, when every entry of both lies in
+                // 0 .. 255 (a row of 256 such entries sums to less than 2^16), which the rows of any valid
+                // population do; otherwise each row is summed on its own.
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
+                for (int u = 0; u < kAhead; u += 2) {
                     if (r0 + u < rows) {
-                        int K, nodes;
-                        bool changed, neg;
-                        advance(r0 + u);
-                        row_stage(K, nodes, changed, neg, &v[u]);
-                        if (lane == r0 + u) {
-                            d_K = K;
-                            d_meta = nodes | (changed ? kMetaChanged : 0);
+                        const int4 &va = v[u], &vb = v[u + 1];
+                        int wide = (__ballot((unsigned)(((va.x | va.y) | (va.z | va.w)) | ((vb.x | vb.y) | (vb.z | vb.w))) > 255u) & in_row) != 0 ? 1 : 0;
+                        wide = __builtin_amdgcn_readfirstlane(wide);
+                        asm volatile("" : "+s"(wide));
+                        const int part_a = lane < n4 ? (va.x + va.y) + (va.z + va.w) : 0;
+                        const int part_b = lane < n4 ? (vb.x + vb.y) + (vb.z + vb.w) : 0;
+                        int K2[2];
+                        if (wide == 0) {
+                            const int both = wave_sum(part_a + (part_b << 16));
+                            K2[0] = both & 0xFFFF;
+                            K2[1] = (int)((unsigned)both >> 16);
+                        } else {
+                            K2[0] = wave_sum(part_a);
+                            K2[1] = wave_sum(part_b);
                         }
-                        any_neg |= neg;
+#pragma unroll
+                        for (int e = 0; e < 2; ++e) {
+                            if (r0 + u + e < rows) {
+                                int K, nodes;
+                                bool changed, neg;
+                                advance(r0 + u + e);
+                                row_stage(K, nodes, changed, neg, &v[u + e], &K2[e], wide ^ 1);
+                                // lane r keeps what candidate r needs (see above)
+                                d_K = write_lane8(d_K, K, u + e);
+                                d_meta = write_lane8(d_meta, nodes | (changed ? kMetaChanged : 0), u + e);
+                                any_neg |= neg;
+                            }
+                        }
+                    }
+                    // the rows of the next stretch take the registers this pair has left: they are on their way
+                    // while the rest of this stretch is worked on
+                    if constexpr (decltype(hand_on)::value) {
+                        request(r0 - kAhead + u, v[u]);
+                        request(r0 - kAhead + u + 1, v[u + 1]);
                     }
                 }
+            };
+            if (r_last >= kAhead) {
+                stretch(r_last, std::true_type());
+                d_K = row16_up8(d_K);
+                d_meta = row16_up8(d_meta);
             }
+            if (r_last >= 0) stretch(0, std::false_type());
         } else {
             for (int r = 0; r < rows; ++r) {
                 int K, nodes;
