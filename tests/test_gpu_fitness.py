@@ -173,6 +173,29 @@ def test_negative_entries_in_rows_of_at_most_64_nodes(shape, flags):
     assert compare(wl, g, r, population=pop) == 0
 
 
+@pytest.mark.parametrize("flags", [0, 4])
+def test_out_of_range_entries_in_rows_of_65_to_256_nodes(flags):
+    """Rows of 65 to 256 nodes are read one to a wavefront load, and the sums of two rows come out of one
+    reduction while every entry lies in 0 .. 255.  Negative entries and entries far beyond that range (invalid
+    input, flagged or counted as violations) take the other path: planted in the first and in the second row of
+    a pair, in both rows, in the first and in the last eight candidates of a wavefront and in the ragged tail
+    of the population; K, the node count and the per-node totals follow the plain definitions, as in the oracle."""
+    cfg = W.custom("wide132", P=2003, J=200, N=132, cap=8, Gm=64, Gs=8)
+    wl = W.make(cfg)
+    pop = wl.population.copy()
+    rng = np.random.default_rng(11)
+    # the candidates of one wavefront are 4 apart: 0, 4, 8, ... are its candidates 0, 1, 2, ...
+    for cand, value in ((0, -2), (12, 300), (16, 70000), (20, -1), (36, 256), (40, -3), (44, 1000), (60, -1),
+                        (61, 255), (65, -2), (cfg.P - 1, 400), (cfg.P - 2, -1)):
+        for j in rng.choice(cfg.J, size=5, replace=False):
+            n = int(rng.integers(cfg.N))
+            pop[cand, j, n] = value
+            pop[cand, j, (n + 7) % cfg.N] += 2
+    g, r = run_gpu(wl, population=pop, flags=flags), run_oracle(wl, population=pop)
+    assert g["status"] & 8 and r["status"] & 8
+    assert compare(wl, g, r, population=pop) == 0
+
+
 def test_a_job_without_gradient_time_is_flagged_and_leaves_the_other_jobs_alone():
     """alpha_grad = beta_grad = 0 (T_grad = 0, outside the model's domain): status bit on both sides, the
     call completes, and every other job's elected point and goodput still match the oracle."""
