@@ -1278,8 +1278,8 @@ pairs_kernel(FitnessArgs a)
     // behind them U[t] = t (t+1), U[0] = -1: what decides the order of neighbouring counts (sweep_pick)
     __shared__ __align__(16) double r_lds[2 * kNearRecips + 8];
     bool has_near = false;
-    // (the instances that read one row per wavefront load fill the table after they have requested their first rows)
-    constexpr bool kRowsFirst = CH != 0 && ROW1 && !ROW4;
+    // (the instances whose rows fit one 16-byte load per lane fill the table after they have requested their first rows)
+    constexpr bool kRowsFirst = CH != 0 && ROW1;
     // every thread brings one entry, formed by the same division as the entry of a.rs (tables_kernel): no load, so
     // storing it waits for nothing that is on its way from memory
     static_assert(kNearRecips <= kWavesPerBlock * kWave, "one entry per thread");
@@ -1462,6 +1462,7 @@ pairs_kernel(FitnessArgs a)
                     }
                 }
             }
+            fill_near();        // while the rows are on their way
 #pragma unroll
             for (int b = 0; b < kBatches; ++b) {
                 if (4 * b < rows) {
