@@ -1254,6 +1254,11 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // wavefronts then walk positions of that list and look the candidate up where an address is formed.
 // Eight wavefronts per SIMD (64 registers); the instances that sweep four candidates at a time (rows_at_a_time)
 // take six (80 registers), which is what they need without spilling, and are no slower for it.
+// Order of a wavefront's work (ROW1): request its first rows; fill the workgroup's table in LDS (entries formed
+// in registers, so nothing waits for memory) and meet the other wavefronts; reduce the rows two at a time, and
+// hand the registers of each finished pair to the rows of the next stretch of eight; then the sweeps of its
+// candidates, one after the other; then prices and stores.  What a wavefront spends waiting at its start is
+// time the vector ALU has one wavefront fewer to draw on, so memory is asked as early as the addresses are known.
 constexpr bool rows_at_a_time(int CH, bool F32, bool MEMO, bool ROW4) { return ROW4 && !F32 && !MEMO && CH != 0 && CH <= 16; }
 
 // SEL = 2: per job, the candidates listed in a.dirty[j, 0 .. a.dirty_count[j]) (row inheritance: the rows of job j that a
