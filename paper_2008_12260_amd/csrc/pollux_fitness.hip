@@ -1582,6 +1582,9 @@ pairs_kernel(FitnessArgs a)
             };
             if (r_last >= kAhead) {
                 stretch(r_last, std::true_type());
+                // (write_lane is an opaque statement: the two wait states a DPP read needs after a vector write of its
+                // source are put here by hand, whatever the compiler schedules in between)
+                asm volatile("s_nop 1" : "+v"(d_K), "+v"(d_meta));
                 d_K = row16_up8(d_K);
                 d_meta = row16_up8(d_meta);
             }
