@@ -122,6 +122,13 @@ struct FitnessArgs {
 
 constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
 constexpr int kNearRecips = 256;          // pairs kernel: reciprocals kept in LDS when Gs (rounded up to 32) is at most this
+// pairs kernel: the table rows (one per (placement class, K)) that most of a workgroup's pairs read are staged in LDS,
+// behind the reciprocals and thresholds: T_grad per batch size, then per row the (C, A0) pairs and the feasible ranges
+constexpr int kStageGm = 128;             // staged rows hold grids of at most this many batch sizes
+constexpr int kStageRows = 5;             // rows staged at most (17.6 KB of LDS per workgroup with the rest: eight workgroups per CU)
+constexpr int kStageRowDoubles = 2 * kStageGm + kStageGm / 2;
+constexpr int kStageBase = 2 * kNearRecips + 8;
+constexpr int kStageDoubles = kStageGm + kStageRows * kStageRowDoubles;
 constexpr int kPending = -2;             // pairs kernel: grid index of a row whose sweep is still to be done
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
@@ -647,9 +654,10 @@ struct Pick {
 template <int CH, bool TABLED, bool WHOLE = false>
 __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, const RunSteps &X, const double *__restrict__ rs,
                                            const double *__restrict__ rk, int Gm, int Gs, int K, int nodes,
-                                           LdsDoubles near = nullptr, bool has_near = false)
+                                           LdsDoubles near = nullptr, bool has_near = false, int staged_row = -1)
 {
     // near: a copy of rs in LDS (quicker to read per lane) when has_near
+    // staged_row: where in `near` the terms of this (class, K) are staged (TABLED and WHOLE; see kStageBase), or -1
     const int lane = lane_id();
     K = __builtin_amdgcn_readfirstlane(K);        // the same in every lane (see above): kept in scalar registers
     nodes = __builtin_amdgcn_readfirstlane(nodes);
@@ -683,10 +691,21 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         int s_c = 0;
         bool feasible;
         if constexpr (TABLED) {
-            const double tg = *(const double *)((const char *)tb.tg + at16);
-            const double2 car = *(const double2 *)((const char *)carow + at16);
-            const double C = car.x, A0 = car.y;     // A0 = +inf when the batch size has no feasible count
-            const int bounds = *(const int32_t *)((const char *)srow + at4);
+            double tg, C, A0;                        // A0 = +inf when the batch size has no feasible count
+            int bounds;
+            if (WHOLE && staged_row >= 0) {
+                const Double2 car = *(const Double2 __attribute__((address_space(3))) *)(near + staged_row + 2 * il);
+                C = car.x;
+                A0 = car.y;
+                tg = near[kStageBase + il];
+                bounds = ((const int __attribute__((address_space(3))) *)(near + staged_row + 2 * kStageGm))[il];
+            } else {
+                tg = *(const double *)((const char *)tb.tg + at16);
+                const double2 car = *(const double2 *)((const char *)carow + at16);
+                C = car.x;
+                A0 = car.y;
+                bounds = *(const int32_t *)((const char *)srow + at4);
+            }
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active;
             const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
@@ -1281,7 +1300,12 @@ pairs_kernel(FitnessArgs a)
     const int lane = lane_id();
     // the reciprocals 1/(s+1) also in LDS when they fit: the clamped count of a lane reads its own entry
     // behind them U[t] = t (t+1), U[0] = -1: what decides the order of neighbouring counts (sweep_pick)
-    __shared__ __align__(16) double r_lds[2 * kNearRecips + 8];
+    // kStage: behind them the table rows most of the workgroup's pairs read (see kStageBase); stage_votes counts, per
+    // (class, K), the pairs of the workgroup that read the row
+    constexpr bool kStage = CH != 0 && !F32 && !MEMO && ROW1 && !ROW4 && WHOLE;
+    __shared__ __align__(16) double r_lds[2 * kNearRecips + 8 + (kStage ? kStageDoubles : 0)];
+    __shared__ int stage_votes[kStage ? 2 * kTableK : 1];
+    const bool stage_on = kStage && a.Gm <= kStageGm;
     bool has_near = false;
     // (the instances whose rows fit one 16-byte load per lane fill the table after they have requested their first rows)
     constexpr bool kRowsFirst = CH != 0 && ROW1;
@@ -1305,9 +1329,10 @@ pairs_kernel(FitnessArgs a)
                     }
                 }
             }
-            __syncthreads();
-            has_near = true;
         }
+        if (stage_on && threadIdx.x < 2 * kTableK) stage_votes[threadIdx.x] = 0;
+        if (near_fits || stage_on) __syncthreads();
+        has_near = near_fits;
     };
     if constexpr (!kRowsFirst) fill_near();
     const Job q = load_job(a.job_params, a.J, j);
@@ -1602,6 +1627,57 @@ pairs_kernel(FitnessArgs a)
                 any_neg |= neg;
             }
         }
+        if constexpr (kStage) {
+            if (stage_on) {
+                // Which rows to stage: every pair of the workgroup votes for the row it will read, and every
+                // wavefront takes, from the same counts (so all four agree), the rows with two votes or more: those
+                // of the "one node" class first, fewer GPUs first, which is where allocations concentrate.  Lane r then notes, in the place where the count elected for its
+                // candidate will go, where that candidate's row is staged (-1: not staged).
+                const int my_nodes = d_meta & ~kMetaChanged;
+                const bool votes = lane < rows && d_K >= 1 && tabled_row(d_K, my_nodes == 1, tb.k1);
+                const int my_row = (my_nodes == 1 ? kTableK : 0) + d_K - 1;
+                if (votes) atomicAdd(&stage_votes[my_row], 1);
+                __syncthreads();
+                unsigned long long several = __ballot(stage_votes[lane] >= 2), one = __ballot(stage_votes[lane + kWave] >= 2);
+                int staged[kStageRows];
+                const int t = threadIdx.x;
+                double2 ca_in[kStageRows];
+                int range_in[kStageRows];
+                double tg_in = 0.0;
+                if (t < a.Gm) tg_in = tb.tg[t].x;
+#pragma unroll
+                for (int e = 0; e < kStageRows; ++e) {
+                    staged[e] = -1;
+                    if (one != 0ull) {
+                        staged[e] = kTableK + __builtin_ctzll(one);
+                        one &= one - 1ull;
+                    } else if (several != 0ull) {
+                        staged[e] = __builtin_ctzll(several);
+                        several &= several - 1ull;
+                    }
+                    if (staged[e] >= 0) {
+                        // threads 0 .. Gm-1 bring the (C, A0) pairs of the row, threads Gm .. 2 Gm - 1 its feasible ranges
+                        if (t < a.Gm) ca_in[e] = tb.ca[(size_t)staged[e] * a.Gm + t];
+                        else if (t < 2 * a.Gm) range_in[e] = tb.srange[(size_t)(staged[e] & (kTableK - 1)) * a.Gm + (t - a.Gm)];
+                        if (votes && my_row == staged[e]) d_s = kStageBase + kStageGm + e * kStageRowDoubles;
+                    }
+                }
+                if (t < a.Gm) r_lds[kStageBase + t] = tg_in;
+#pragma unroll
+                for (int e = 0; e < kStageRows; ++e) {
+                    if (staged[e] >= 0) {
+                        double *row_lds = r_lds + kStageBase + kStageGm + e * kStageRowDoubles;
+                        if (t < a.Gm) {
+                            row_lds[2 * t] = ca_in[e].x;
+                            row_lds[2 * t + 1] = ca_in[e].y;
+                        } else if (t < 2 * a.Gm) {
+                            ((int *)(row_lds + 2 * kStageGm))[t - a.Gm] = range_in[e];
+                        }
+                    }
+                }
+                __syncthreads();
+            }
+        }
         // after the row pass, whose rows in flight use the registers these occupy
         if constexpr (F32) XF = make_run_steps_f32();
         else X = make_run_steps();
@@ -1641,7 +1717,8 @@ pairs_kernel(FitnessArgs a)
             if (K >= 1 && !tabled_row(K, nodes == 1, tb.k1)) pick.i = kPending;   // rare: swept after the loop, outside the hot path
             else if (!MEMO && K >= 1) {
                 if constexpr (F32) pick = sweep_pick_f32<CH, WHOLE>(qf, tb, XF, a.rsf, a.Gm, a.Gs, K, nodes, (LdsFloats)(const float *)r_lds, has_near);
-                else pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near);
+                else pick = sweep_pick<CH, true, WHOLE>(q, tb, X, a.rs, a.rk, a.Gm, a.Gs, K, nodes, (LdsDoubles)r_lds, has_near,
+                                                        kStage ? __builtin_amdgcn_readlane(d_s, r) : -1);
             }
             if (lane == r) {
                 d_i = pick.i;
