@@ -123,12 +123,14 @@ struct FitnessArgs {
 constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
 constexpr int kNearRecips = 256;          // pairs kernel: reciprocals kept in LDS when Gs (rounded up to 32) is at most this
 // pairs kernel: the table rows (one per (placement class, K)) that most of a workgroup's pairs read are staged in LDS,
-// behind the reciprocals and thresholds: T_grad per batch size, then per row the (C, A0) pairs and the feasible ranges
+// behind the reciprocals and thresholds: (T_grad, 1 / T_grad) per batch size as in memory, then per row the (C, A0)
+// pairs and the feasible ranges.  16-byte entries throughout, so that a lane's addresses are its number times 16
+// (or times 4 for the ranges) plus a uniform offset, as they are for the tables in memory.
 constexpr int kStageGm = 128;             // staged rows hold grids of at most this many batch sizes
-constexpr int kStageRows = 5;             // rows staged at most (17.6 KB of LDS per workgroup with the rest: eight workgroups per CU)
+constexpr int kStageRows = 4;             // rows staged at most (16.6 KB of LDS per workgroup with the rest: eight workgroups per CU)
 constexpr int kStageRowDoubles = 2 * kStageGm + kStageGm / 2;
 constexpr int kStageBase = 2 * kNearRecips + 8;
-constexpr int kStageDoubles = kStageGm + kStageRows * kStageRowDoubles;
+constexpr int kStageDoubles = 2 * kStageGm + kStageRows * kStageRowDoubles;
 constexpr int kPending = -2;             // pairs kernel: grid index of a row whose sweep is still to be done
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
 
@@ -694,11 +696,16 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             double tg, C, A0;                        // A0 = +inf when the batch size has no feasible count
             int bounds;
             if (WHOLE && staged_row >= 0) {
-                const Double2 car = *(const Double2 __attribute__((address_space(3))) *)(near + staged_row + 2 * il);
+                // (uniform byte offsets kept on the scalar unit, as above)
+                typedef const char __attribute__((address_space(3))) *LdsBytes;
+                unsigned o_ca = i16 + 8u * (unsigned)staged_row, o_tg = i16 + 8u * (unsigned)kStageBase;
+                unsigned o_range = i4 + 8u * (unsigned)(staged_row + 2 * kStageGm);
+                asm("" : "+s"(o_ca), "+s"(o_tg), "+s"(o_range));
+                const Double2 car = *(const Double2 __attribute__((address_space(3))) *)((LdsBytes)near + (((unsigned)lane << 4) + o_ca));
                 C = car.x;
                 A0 = car.y;
-                tg = near[kStageBase + il];
-                bounds = ((const int __attribute__((address_space(3))) *)(near + staged_row + 2 * kStageGm))[il];
+                tg = *(LdsDoubles)((LdsBytes)near + (((unsigned)lane << 4) + o_tg));
+                bounds = *(const int __attribute__((address_space(3))) *)((LdsBytes)near + (((unsigned)lane << 2) + o_range));
             } else {
                 tg = *(const double *)((const char *)tb.tg + at16);
                 const double2 car = *(const double2 *)((const char *)carow + at16);
@@ -1278,6 +1285,11 @@ __global__ void __launch_bounds__(256) memo_kernel(FitnessArgs a)
 // hand the registers of each finished pair to the rows of the next stretch of eight; then the sweeps of its
 // candidates, one after the other; then prices and stores.  What a wavefront spends waiting at its start is
 // time the vector ALU has one wavefront fewer to draw on, so memory is asked as early as the addresses are known.
+// Between row pass and sweeps (grids of at most 128 batch sizes, whole groups of 64): the workgroup's 64 pairs
+// share one job and mostly a handful of (placement class, GPU count) rows of its tables, so each pair votes for
+// its row, the rows with two votes or more (four at most) are copied to LDS once, and the sweeps of those pairs
+// read (C, A0), T_grad and the feasible range from there.  Three vector-memory loads per lane and group of 64
+// batch sizes were what kept the texture addresser two thirds busy and the vector ALU waiting.
 constexpr bool rows_at_a_time(int CH, bool F32, bool MEMO, bool ROW4) { return ROW4 && !F32 && !MEMO && CH != 0 && CH <= 16; }
 
 // SEL = 2: per job, the candidates listed in a.dirty[j, 0 .. a.dirty_count[j]) (row inheritance: the rows of job j that a
@@ -1643,8 +1655,8 @@ pairs_kernel(FitnessArgs a)
                 const int t = threadIdx.x;
                 double2 ca_in[kStageRows];
                 int range_in[kStageRows];
-                double tg_in = 0.0;
-                if (t < a.Gm) tg_in = tb.tg[t].x;
+                double2 tg_in = {0.0, 0.0};
+                if (t < a.Gm) tg_in = tb.tg[t];
 #pragma unroll
                 for (int e = 0; e < kStageRows; ++e) {
                     staged[e] = -1;
@@ -1659,14 +1671,17 @@ pairs_kernel(FitnessArgs a)
                         // threads 0 .. Gm-1 bring the (C, A0) pairs of the row, threads Gm .. 2 Gm - 1 its feasible ranges
                         if (t < a.Gm) ca_in[e] = tb.ca[(size_t)staged[e] * a.Gm + t];
                         else if (t < 2 * a.Gm) range_in[e] = tb.srange[(size_t)(staged[e] & (kTableK - 1)) * a.Gm + (t - a.Gm)];
-                        if (votes && my_row == staged[e]) d_s = kStageBase + kStageGm + e * kStageRowDoubles;
+                        if (votes && my_row == staged[e]) d_s = kStageBase + 2 * kStageGm + e * kStageRowDoubles;
                     }
                 }
-                if (t < a.Gm) r_lds[kStageBase + t] = tg_in;
+                if (t < a.Gm) {
+                    r_lds[kStageBase + 2 * t] = tg_in.x;
+                    r_lds[kStageBase + 2 * t + 1] = tg_in.y;
+                }
 #pragma unroll
                 for (int e = 0; e < kStageRows; ++e) {
                     if (staged[e] >= 0) {
-                        double *row_lds = r_lds + kStageBase + kStageGm + e * kStageRowDoubles;
+                        double *row_lds = r_lds + kStageBase + 2 * kStageGm + e * kStageRowDoubles;
                         if (t < a.Gm) {
                             row_lds[2 * t] = ca_in[e].x;
                             row_lds[2 * t + 1] = ca_in[e].y;
