@@ -317,9 +317,8 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
         }
     }
 
-    for (int j = wave; j < a.J; j += waves) {
-        const int d = __builtin_amdgcn_readfirstlane(sh.dec[j]);
-        if (FOUR && (d >> 1) == 0) continue;
+    // one row by one wavefront: the move (if any), the job's GPU limit, the copy, the bookkeeping
+    auto row_by_wavefront = [&](int j, int d) {
         const int32_t *__restrict__ src = ((d & 1) ? pb : pa) + (size_t)j * a.N;
         int32_t *__restrict__ dst = child + (size_t)j * a.N;
         const int move = ((d >> 1) & 3) - 1;
@@ -423,6 +422,24 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
         if (lane == 0) sh.nodes_of[j] = nodes;
         if (nodes >= 2 && lane == 0) sh.dist[atomicAdd(&n_dist, 1)] = j;
         if (INHERIT && lane == 0) src_row[j] = (move < 0 && !over_limit) ? ((d & 1) ? cand_b : cand_a) : -1;
+    };
+    if constexpr (FOUR) {
+        // only the rows with a move are left: every wavefront reads the decisions 64 at a time and takes, of the rows
+        // that have one, those whose number is its own modulo the number of wavefronts (a few per child: walking
+        // all rows to find them cost one LDS round trip per row)
+        static_assert(kGaThreads / kWave == 8, "the pattern below picks every eighth row");
+        for (int jb = 0; jb < a.J; jb += kWave) {
+            const int jj = jb + lane;
+            const int dd = jj < a.J ? sh.dec[jj] : 0;
+            unsigned long long mine = __ballot((dd >> 1) != 0) & (0x0101010101010101ull << wave);
+            while (mine != 0ull) {
+                const int b = __builtin_ctzll(mine);
+                mine &= mine - 1ull;
+                row_by_wavefront(jb + b, __builtin_amdgcn_readlane(dd, b));
+            }
+        }
+    } else {
+        for (int j = wave; j < a.J; j += waves) row_by_wavefront(j, __builtin_amdgcn_readfirstlane(sh.dec[j]));
     }
     __syncthreads();
 
