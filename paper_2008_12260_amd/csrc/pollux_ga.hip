@@ -122,6 +122,13 @@ __global__ void __launch_bounds__(256) rank_kernel(GaArgs a)
 //         that list two or more, four lanes looking at a node's entries together.
 // When a matrix has more positive entries than the lists hold (dense matrices) steps
 // B and C run the same rules on columns read from memory instead.
+// Matrices of at most 64 nodes (the instances with FOUR) keep, instead of the lists, an array of
+// entries per node (kNodeCap each; more: the column path).  Step B then gives half a wavefront to a
+// node: lane k holds its k-th entry, and what a job gives up, min(its GPUs, the excess less the
+// GPUs of the jobs before it in the cyclic order), needs a sum over the entries with a smaller
+// cyclic distance, which every lane forms for itself: no walk, no second pass.  Step C lists the
+// multi-node entries of every node from the arrays, and the wavefront that takes the nodes in order
+// holds the listed entries of sixteen nodes in registers, four lanes a node.
 //
 // A workgroup re-reads global memory written by its own wavefronts only in that
 // fallback; __syncthreads() orders those accesses (one CU, one L1).
@@ -137,12 +144,19 @@ inline int ga_max_entries(int J)
 }
 
 constexpr int kNodeSlots = 4;       // multi-node entries listed per node for step C (more: that node's list is walked)
+// Rows of at most 64 nodes (the instances with FOUR): instead of the lists every node keeps its entries as an array,
+// which 32 lanes read together, so that neither repair walks anything.  A node with more entries than its array
+// holds sends the child down the column path.
+constexpr int kNodeCap = 32;
+constexpr int kArrayNodes = 64;     // the arrays exist for matrices of at most this many nodes
 
 struct GaShared {
     unsigned long long *colsum;
     int32_t *nodes_of, *colcnt, *dist, *dec, *decx, *head;
     int32_t *ent_j, *ent_v, *ent_next;
     uint16_t *slot;                 // [N, kNodeSlots] entry indices; shares the memory of dec / decx, which step A is done with
+    // N <= kArrayNodes only: entries per node; per node and position the job and its GPUs there
+    int32_t *ncnt, *arr_j, *arr_v;
 };
 
 __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int N, int max_entries)
@@ -160,12 +174,16 @@ __device__ __forceinline__ GaShared carve_shared(unsigned char *base, int J, int
     sh.ent_next = sh.ent_v + max_entries;
     // 2 * kNodeSlots bytes per node: inside dec / decx (8 bytes per job) when J >= N, else behind the entry arrays
     sh.slot = J >= N ? (uint16_t *)sh.dec : (uint16_t *)(sh.ent_next + max_entries);
+    sh.ncnt = sh.ent_next + max_entries + (J >= N ? 0 : (2 * kNodeSlots * N) / 4);
+    sh.arr_j = sh.ncnt + N;
+    sh.arr_v = sh.arr_j + N * kNodeCap;
     return sh;
 }
 
 inline size_t ga_shared_bytes(int J, int N)
 {
-    return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J) + (J >= N ? 0 : 2 * kNodeSlots * (size_t)N);
+    return 16 * (size_t)N + 16 * (size_t)J + 12 * (size_t)ga_max_entries(J) + (J >= N ? 0 : 2 * kNodeSlots * (size_t)N) +
+           (N <= kArrayNodes ? 4 * (size_t)N + 8 * (size_t)N * kNodeCap : 0);
 }
 
 // What a workgroup may use: the 160 KB of a compute unit less the kernel's few static variables, rounded down.
@@ -217,6 +235,7 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
     extern __shared__ __align__(16) unsigned char ga_lds[];
     __shared__ int count, n_dist, n_ent;
     __shared__ int odd;             // see GaArgs::odd
+    __shared__ int spill;           // FOUR: a node has more entries than its array holds
     __shared__ unsigned long long keep;
 
     const int c = a.in_place ? (int)(blockIdx.x + a.elite_k) : (int)blockIdx.x;
@@ -241,8 +260,11 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
     }
 
     const GaShared sh = carve_shared(ga_lds, a.J, a.N, a.max_entries);
-    for (int n = tid; n < a.N; n += kGaThreads) { sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1; }
-    if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; odd = 0; }
+    for (int n = tid; n < a.N; n += kGaThreads) {
+        sh.colsum[n] = 0ull; sh.colcnt[n] = 0; sh.head[n] = -1;
+        if constexpr (FOUR) sh.ncnt[n] = 0;
+    }
+    if (tid == 0) { count = 0; n_dist = 0; n_ent = 0; keep = 0ull; odd = 0; spill = 0; }
     // row inheritance: where the child's rows come from (see GaArgs)
     int32_t *__restrict__ src_row = INHERIT ? a.src_row + (size_t)(c - (int)a.elite_k) * a.J : nullptr;
 
@@ -280,11 +302,21 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
         atomicAdd(&sh.colsum[n], (unsigned long long)(long long)v);
         if (INHERIT && v < 0) odd = 1;
         if (v > 0) {
-            const int e = atomicAdd(&n_ent, 1);
-            if (e < a.max_entries) {
-                sh.ent_j[e] = j;
-                sh.ent_v[e] = v;
-                sh.ent_next[e] = atomicExch(&sh.head[n], e);
+            if constexpr (FOUR) {
+                const int k = atomicAdd(&sh.ncnt[n], 1);
+                if (k < kNodeCap) {
+                    sh.arr_j[n * kNodeCap + k] = j;
+                    sh.arr_v[n * kNodeCap + k] = v;
+                } else {
+                    spill = 1;
+                }
+            } else {
+                const int e = atomicAdd(&n_ent, 1);
+                if (e < a.max_entries) {
+                    sh.ent_j[e] = j;
+                    sh.ent_v[e] = v;
+                    sh.ent_next[e] = atomicExch(&sh.head[n], e);
+                }
             }
         }
     };
@@ -443,7 +475,143 @@ __global__ void __launch_bounds__(kGaThreads) __attribute__((amdgpu_num_sgpr(96)
     }
     __syncthreads();
 
-    if (n_ent <= a.max_entries) {
+    if constexpr (FOUR) {
+      if (spill == 0) {
+        static_assert(kNodeCap == 32 && kWave == 64 && kArrayNodes == 64 && kGaThreads == 512,
+                      "a half of a wavefront per node, four nodes per half");
+        const int half = lane >> 5, k = lane & 31;
+        // the entries this lane looks after: the k-th of nodes 2 wave + half, + 16, + 32, + 48
+        int ej[4], ev[4], en[4], have[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            en[r] = 16 * r + 2 * wave + half;
+            ej[r] = 0;
+            ev[r] = 0;
+            have[r] = en[r] < a.N ? sh.ncnt[en[r]] : 0;
+            if (k < have[r]) {
+                ej[r] = sh.arr_j[en[r] * kNodeCap + k];
+                ev[r] = sh.arr_v[en[r] * kNodeCap + k];
+            }
+        }
+        // ---- step B on the node arrays.  In the cyclic order from the drawn start a job gives up
+        // min(its GPUs, what is still to take after the jobs before it), and "before it" is a sum over the
+        // entries with a smaller distance: every lane forms its own, no walk, no second pass.
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int n = en[r];
+            const long long excess = n < a.N ? (long long)sh.colsum[n] - (long long)a.node_capacity[n] : 0ll;
+            const bool over = excess > 0;
+            if (__ballot(over) == 0ull) continue;
+            int dist = 0x7FFFFFFF;                      // cyclic distance of the job from the start; no job: last
+            if (over && ev[r] > 0) {
+                const U4 rr = philox4x32_10(a.generation, (uint32_t)c, (uint32_t)n, kTagRepair, a.key0, a.key1);
+                const int j0 = (int)below(rr.x, (uint32_t)a.J);
+                dist = ej[r] >= j0 ? ej[r] - j0 : ej[r] - j0 + a.J;
+            }
+            long long before = 0, present = 0;
+            const int most = max(__builtin_amdgcn_readlane(have[r], 0), __builtin_amdgcn_readlane(have[r], 32));
+            for (int i = 0; i < most; ++i) {
+                const int from = ((lane & 32) + i) << 2;
+                const int di = __builtin_amdgcn_ds_bpermute(from, dist), vi = __builtin_amdgcn_ds_bpermute(from, ev[r]);
+                if (di != 0x7FFFFFFF) {
+                    present += vi;
+                    if (di < dist) before += vi;
+                }
+            }
+            const long long room = excess - before;
+            if (dist != 0x7FFFFFFF && room > 0) {
+                const int32_t left = (long long)ev[r] <= room ? 0 : (int32_t)((long long)ev[r] - room);
+                ev[r] = left;
+                child[(size_t)ej[r] * a.N + n] = left;
+                if (INHERIT) src_row[ej[r]] = -1;
+                if (left == 0) atomicSub(&sh.nodes_of[ej[r]], 1);
+            }
+            if (INHERIT && over && present < excess) odd = 1;     // nothing left to take away: the node stays over its capacity
+        }
+        __syncthreads();
+        if (INHERIT && tid == 0) a.odd[c - (int)a.elite_k] = odd;   // final: step C only removes entries
+        // ---- step C on the node arrays: first the listing, which multi-node jobs each node holds now (their positions
+        // in the node's array, up to kNodeSlots of them) ...
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const bool multi = ev[r] > 0 && sh.nodes_of[ej[r]] >= 2;
+            const unsigned long long both = __ballot(multi);
+            const unsigned mine = half ? (unsigned)(both >> 32) : (unsigned)both;
+            const int pos = __popc(mine & ((1u << k) - 1u));
+            if (multi && pos < kNodeSlots) sh.slot[en[r] * kNodeSlots + pos] = (uint16_t)(en[r] * kNodeCap + k);
+            if (en[r] < a.N && k == 0) sh.colcnt[en[r]] = __popc(mine);
+            // (step B's outcome, for the walk below of a node that lists more than kNodeSlots)
+            if (k < have[r]) sh.arr_v[en[r] * kNodeCap + k] = ev[r];
+        }
+        __syncthreads();
+        if (wave != 0) return;
+        // ... then one wavefront takes the nodes in ascending order, 16 at a time: four lanes hold a node's listed
+        // entries, so a node that lists two or more costs one look at its jobs' node counts (which the nodes before
+        // it may have lowered), a maximum over four lanes and the writes.
+        for (int n0 = 0; n0 < a.N; n0 += 16) {
+            const int n = n0 + (lane >> 2), q = lane & 3;
+            const int listed_n = n < a.N ? sh.colcnt[n] : 0;
+            int j = 0;
+            int32_t v = 0;
+            const bool has = q < listed_n && q < kNodeSlots;
+            if (has) {
+                const int at = sh.slot[n * kNodeSlots + q];
+                j = sh.arr_j[at];
+                v = sh.arr_v[at];
+            }
+            unsigned long long conflicts = __ballot(q == 0 && listed_n > 1);
+            while (conflicts != 0ull) {
+                const int first = __builtin_ctzll(conflicts);          // the node's first lane
+                conflicts &= conflicts - 1ull;
+                const int nn = n0 + (first >> 2);
+                const int listed = __builtin_amdgcn_readlane(listed_n, first);
+                if (listed <= kNodeSlots) {
+                    const bool multi = has && (lane >> 2) == (first >> 2) && sh.nodes_of[j] >= 2;
+                    if (__popcll(__ballot(multi)) > 1) {
+                        long long key = multi ? (long long)holder_key(v, j) : 0ll;      // below 2^63: v is positive
+                        long long other = exchange<0>(key);
+                        key = other > key ? other : key;
+                        other = exchange<1>(key);
+                        key = other > key ? other : key;                                  // the four lanes agree
+                        const int keeper = (int)(0xFFFFFFFFu - (uint32_t)((unsigned long long)key & 0xFFFFFFFFull));
+                        if (multi && j != keeper) {
+                            child[(size_t)j * a.N + nn] = 0;
+                            if (INHERIT) src_row[j] = -1;
+                            sh.nodes_of[j] -= 1;
+                        }
+                    }
+                } else if (lane == 0) {
+                    const int entries = sh.ncnt[nn];
+                    int cnt = 0;
+                    unsigned long long best = 0ull;
+                    for (int t = 0; t < entries; ++t) {
+                        const int jt = sh.arr_j[nn * kNodeCap + t];
+                        const int32_t vt = sh.arr_v[nn * kNodeCap + t];
+                        if (vt > 0 && sh.nodes_of[jt] >= 2) {
+                            cnt++;
+                            const unsigned long long key = holder_key(vt, jt);
+                            best = key > best ? key : best;
+                        }
+                    }
+                    if (cnt > 1) {
+                        const int keeper = (int)(0xFFFFFFFFu - (uint32_t)(best & 0xFFFFFFFFull));
+                        for (int t = 0; t < entries; ++t) {
+                            const int jt = sh.arr_j[nn * kNodeCap + t];
+                            if (jt != keeper && sh.arr_v[nn * kNodeCap + t] > 0 && sh.nodes_of[jt] >= 2) {
+                                child[(size_t)jt * a.N + nn] = 0;
+                                if (INHERIT) src_row[jt] = -1;
+                                sh.nodes_of[jt] -= 1;
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        return;
+      }
+    }
+
+    if (!FOUR && n_ent <= a.max_entries) {
         // ---- step B on the node lists ----
         for (int n = tid; n < a.N; n += kGaThreads) {
             long long excess = (long long)sh.colsum[n] - (long long)a.node_capacity[n];
