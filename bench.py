@@ -36,12 +36,12 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "f91a3d7bb791948a649a91a9ea8b25fd5b42ed8816717aa377d61c347e7b9db0",
-        "traffic_bytes": 2_079_571 * 1024 * 2 + 693_035 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
+        "source_sha256": "484aa9376afa71c45a827e67d62c5c03233fb4cb7e8c6d5e9dac6c52a27b021a",
+        "traffic_bytes": 2_079_567 * 1024 * 2 + 692_906 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
         "fp64_flops": 64 * (8.960e5 + 1.770e7 + 2 * 2.670e8),
         "valu_insts": 1.04635e9,
         "scan_insts": 2.25 * 1.6777e10 / 64,
-        "valu_busy": 1.06451e9 * 4 / 1024 / (3.65034e7 / 8),           # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+        "valu_busy": 1.06451e9 * 4 / 1024 / (3.66939e7 / 8),           # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
     },
 }
 GA_SEED = 0x2008_1226_5EED_0001
