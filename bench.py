@@ -36,7 +36,7 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "484aa9376afa71c45a827e67d62c5c03233fb4cb7e8c6d5e9dac6c52a27b021a",
+        "source_sha256": "de09ebcb9b20d7a2554e775e977c3f13c75e368c8ebc5cdc97b55a1ad4433c8e",
         "traffic_bytes": 2_079_567 * 1024 * 2 + 692_906 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
         "fp64_flops": 64 * (8.960e5 + 1.770e7 + 2 * 2.670e8),
         "valu_insts": 1.04635e9,

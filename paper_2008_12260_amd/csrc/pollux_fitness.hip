@@ -1564,8 +1564,8 @@ pairs_kernel(FitnessArgs a)
                 for (int u = 0; u < kAhead; ++u) request(r_last + u, v[u]);
             }
             fill_near();
-            // One stretch; with NEXT its rows' registers are handed on to the rows of the stretch below it, two at a
-            // time.  (Written out once per stretch instead of as a loop, so that every wait names the loads it needs.)
+            // One stretch; with hand_on the registers of its rows are handed on to the rows of the stretch below it, two
+            // at a time.  (Written out once per stretch instead of as a loop, so that every wait names the loads it needs.)
             auto stretch = [&](int r0, auto hand_on) {
                 if constexpr (SEL == 0) {
                     // advance() steps from one candidate to the next: start one before the stretch
@@ -1643,8 +1643,9 @@ pairs_kernel(FitnessArgs a)
             if (stage_on) {
                 // Which rows to stage: every pair of the workgroup votes for the row it will read, and every
                 // wavefront takes, from the same counts (so all four agree), the rows with two votes or more: those
-                // of the "one node" class first, fewer GPUs first, which is where allocations concentrate.  Lane r then notes, in the place where the count elected for its
-                // candidate will go, where that candidate's row is staged (-1: not staged).
+                // of the "one node" class first, fewer GPUs first, which is where allocations concentrate.  Lane r
+                // then notes, in the register where the count elected for its candidate will go, where that
+                // candidate's row is staged (-1: not staged).
                 const int my_nodes = d_meta & ~kMetaChanged;
                 const bool votes = lane < rows && d_K >= 1 && tabled_row(d_K, my_nodes == 1, tb.k1);
                 const int my_row = (my_nodes == 1 ? kTableK : 0) + d_K - 1;
