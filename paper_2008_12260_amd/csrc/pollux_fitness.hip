@@ -122,6 +122,9 @@ struct FitnessArgs {
 
 constexpr unsigned long long kPackJob = 1ull << 40;   // one multi-node job in a colpack word
 constexpr int kNearRecips = 256;          // pairs kernel: reciprocals kept in LDS when Gs (rounded up to 32) is at most this
+// The fp64 table in LDS (in doubles): per count s the pair (1 / (s + 1), s), so that one read brings both operands of
+// w(s) = s + C / (s + 1) at the clamped count; behind the pairs the thresholds U[t] = t (t + 1).
+constexpr int kNearU = 2 * kNearRecips;
 // pairs kernel: the table rows (one per (placement class, K)) that most of a workgroup's pairs read are staged in LDS,
 // behind the reciprocals and thresholds: (T_grad, 1 / T_grad) per batch size as in memory, then per row the (C, A0)
 // pairs and the feasible ranges.  16-byte entries throughout, so that a lane's addresses are its number times 16
@@ -129,7 +132,7 @@ constexpr int kNearRecips = 256;          // pairs kernel: reciprocals kept in L
 constexpr int kStageGm = 128;             // staged rows hold grids of at most this many batch sizes
 constexpr int kStageRows = 4;             // rows staged at most (16.6 KB of LDS per workgroup with the rest: eight workgroups per CU)
 constexpr int kStageRowDoubles = 2 * kStageGm + kStageGm / 2;
-constexpr int kStageBase = 2 * kNearRecips + 8;
+constexpr int kStageBase = kNearU + kNearRecips + 8;
 constexpr int kStageDoubles = 2 * kStageGm + kStageRows * kStageRowDoubles;
 constexpr int kPending = -2;             // pairs kernel: grid index of a row whose sweep is still to be done
 constexpr int kMetaChanged = 1 << 30;   // meta[pair] = nodes | (row differs from current ? kMetaChanged : 0)
@@ -610,7 +613,7 @@ __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDo
         if (has_near) {
             // all five requested together: three reads in a row cost three LDS round trips per batch size, and after
             // the scan the registers its values occupied are free
-            LdsDoubles u = near + kNearRecips + t0;
+            LdsDoubles u = near + kNearU + t0;
             const Double2 a01 = *(const Double2 __attribute__((address_space(3))) *)u;
             const Double2 a23 = *(const Double2 __attribute__((address_space(3))) *)(u + 2);
             const double a4 = u[4];
@@ -630,8 +633,8 @@ __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDo
         s_star = g_star;
         double t_lo, t_hi;
         if (has_near) {
-            t_lo = near[kNearRecips + s_star];
-            t_hi = near[kNearRecips + s_star + 1];
+            t_lo = near[kNearU + s_star];
+            t_hi = near[kNearU + s_star + 1];
         } else {
             const double sd = (double)s_star;
             t_lo = s_star > 0 ? px_fma(sd, sd, sd) : -1.0;
@@ -719,8 +722,16 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
-            const double r_c = has_near ? near[s_c] : *(const double *)((const char *)rs + 8u * (unsigned)s_c);
-            const double w_c = px_fma(C, r_c, (double)s_c);
+            double r_c, sd_c;
+            if (has_near) {
+                const Double2 rc = *(const Double2 __attribute__((address_space(3))) *)(near + 2 * s_c);
+                r_c = rc.x;
+                sd_c = rc.y;
+            } else {
+                r_c = *(const double *)((const char *)rs + 8u * (unsigned)s_c);
+                sd_c = (double)s_c;
+            }
+            const double w_c = px_fma(C, r_c, sd_c);
             key = px_fma(tg, w_c, A0);
         } else {
             const double2 tgr = *(const double2 *)((const char *)tb.tg + 2u * at);
@@ -818,8 +829,16 @@ __device__ __forceinline__ int sweep_pick_rows(const JobTables &tb, const RunSte
         // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
         int s_c = s_star < s_hi ? s_star : s_hi;
         s_c = s_c > s_lo ? s_c : s_lo;
-        const double r_c = has_near ? near[s_c] : rs[s_c];
-        const double w_c = px_fma(C, r_c, (double)s_c);
+        double r_c, sd_c;
+        if (has_near) {
+            const Double2 rc = *(const Double2 __attribute__((address_space(3))) *)(near + 2 * s_c);
+            r_c = rc.x;
+            sd_c = rc.y;
+        } else {
+            r_c = rs[s_c];
+            sd_c = (double)s_c;
+        }
+        const double w_c = px_fma(C, r_c, sd_c);
         const double key = px_fma(tg, w_c, A0);
         if (feasible && key < kbest) {
             kbest = key;
@@ -1315,7 +1334,7 @@ pairs_kernel(FitnessArgs a)
     // kStage: behind them the table rows most of the workgroup's pairs read (see kStageBase); stage_votes counts, per
     // (class, K), the pairs of the workgroup that read the row
     constexpr bool kStage = CH != 0 && !F32 && !MEMO && ROW1 && !ROW4 && WHOLE;
-    __shared__ __align__(16) double r_lds[2 * kNearRecips + 8 + (kStage ? kStageDoubles : 0)];
+    __shared__ __align__(16) double r_lds[kNearU + kNearRecips + 8 + (kStage ? kStageDoubles : 0)];
     __shared__ int stage_votes[kStage ? 2 * kTableK : 1];
     const bool stage_on = kStage && a.Gm <= kStageGm;
     bool has_near = false;
@@ -1334,10 +1353,11 @@ pairs_kernel(FitnessArgs a)
                 if constexpr (F32) {
                     ((float *)r_lds)[t] = near_f;
                 } else {
-                    r_lds[t] = near_d;
+                    r_lds[2 * t] = near_d;
+                    r_lds[2 * t + 1] = (double)t;
                     for (int e = t; e < a.gs_pad + 8; e += a.gs_pad) {
                         const double ed = (double)e;
-                        r_lds[kNearRecips + e] = e > 0 ? ed * (ed + 1.0) : -1.0;
+                        r_lds[kNearU + e] = e > 0 ? ed * (ed + 1.0) : -1.0;
                     }
                 }
             }
