@@ -44,7 +44,7 @@
 // feasible s, which form an interval s_lo..s_hi that depends on (job, K, m) only and is
 // tabled.  The lane scans w over ALL s, one fused multiply-add per grid point; the four values
 // of a group of four consecutive s are reduced with three v_min_f64, and the running minimum takes
-// that result after its low five mantissa bits have been replaced by the index of the group (so
+// that result after its low five mantissa bits have been replaced by the first position of the group (so
 // the minimum carries the group it came from and equal values resolve to the earlier group; the
 // perturbation is 2^-47 relative).  The s inside the winning group is found once per lane
 // afterwards by an exact comparison: w(s+1) < w(s) precisely when C > (s+1)(s+2), so the argmin is
@@ -413,9 +413,9 @@ __device__ __forceinline__ double goodput_point(const Job &q, double Km, double 
 //                              registers, the addend an inline constant (1, 2, 4) or one of
 //                              twelve register pairs that hold 3, 5, 6, .. 15 for the whole kernel
 //   g    = min of the four                                three v_min_f64
-//   lo   = (31 & G) | (~31 & lo(g))                       v_bfi_b32
+//   lo   = (31 & 4 G) | (~31 & lo(g))                     v_bfi_b32
 //   kmin = min(kmin, key)                                 v_min_f64
-// so the key carries its group G in the low five mantissa bits (equal values resolve to
+// so the key carries its group's first position 4 G in the low five mantissa bits (equal values resolve to
 // the earlier group): nine VALU instructions per four points; the reciprocals arrive through the
 // scalar cache.  Each run of sixteen positions has a minimum of its own (values relative to
 // the run's first position); the runs are merged after the chunk (merge_runs).  The position
@@ -499,7 +499,7 @@ __device__ __forceinline__ void scan_group(double (&kmin)[runs_of(CH)], double C
                      "v_min_f64 %0, %0, %1"
                      : "=&v"(g), "=&v"(g2)
                      : "v"(w0), "v"(w1), "v"(w2), "v"(w3));
-        const double key = tagged<G>(g);
+        const double key = tagged<4 * G>(g);         // the first position of the group: what scan_argmin wants of it
         if constexpr ((4 * G) % kRun == 0) kmin[4 * G / kRun] = key;      // the first group of a run starts its minimum
         else asm volatile("v_min_f64 %0, %0, %1" : "+v"(kmin[4 * G / kRun]) : "v"(key));
     } else {
@@ -553,7 +553,7 @@ __device__ __forceinline__ double merge_runs(double lower, double upper)
 }
 
 // CH points starting at accumulation count s0; rs points at s0.  Returns the smallest key of
-// w over the chunk (values relative to s0, group of four positions in the low five bits).
+// w over the chunk (values relative to s0; in the low five bits the first position of the group of four, or the position).
 template <int CH>
 __device__ __forceinline__ double scan_chunk(double C, const RunSteps &X, ScalarDoubles rs)
 {
@@ -586,16 +586,16 @@ __device__ __forceinline__ double sweep_chunk_plain(double tg, double A0s, doubl
 template <int CH>
 __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDoubles rsc, int Gs, LdsDoubles near, bool has_near)
 {
-    // the argmin of w over all counts (its group of four, where keys carry groups): low bits of the smallest key, chunk by chunk
+    // the argmin of w over all counts (the first count of its group of four, where keys carry groups): low bits of the
+    // smallest key, chunk by chunk
     double wmin = scan_chunk<CH>(C, X, rsc);
-    constexpr int kPerTag = grouped_tags(CH) ? 4 : 1;
     int g_star = __double2loint(wmin) & 31;
     for (int s0 = CH; s0 < Gs; s0 += CH) {
         const double w = scan_chunk<CH>(C, X, rsc + s0);
         const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
         if (moved < wmin) {
             wmin = moved;
-            g_star = s0 / kPerTag + (__double2loint(w) & 31);
+            g_star = s0 + (__double2loint(w) & 31);
         }
     }
     // The keys of the scan carry index bits in their low mantissa bits, so what the scan has found is the
@@ -608,7 +608,7 @@ __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDo
     if constexpr (grouped_tags(CH)) {
         // the scan names a group of four counts 4 g .. 4 g + 3: the argmin is 4 g - 1 plus the number of
         // t = 4 g .. 4 g + 4 with C > U[t]
-        const int t0 = 4 * g_star;
+        const int t0 = g_star;
         s_star = t0 - 1;
         if (has_near) {
             // all five requested together: three reads in a row cost three LDS round trips per batch size, and after
