@@ -675,12 +675,20 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     SyncTerm st = {0.0, 0.0, 1.0, 1.0, 0};
     if constexpr (!TABLED) st = sync_term(q, K, one_node);
 
+    // where this lane's terms of a staged row start in LDS (bytes from `near`): the (C, A0) pairs, the feasible ranges
+    const unsigned at_ca = ((unsigned)lane << 4) + 8u * (unsigned)staged_row;
+    const unsigned at_range = ((unsigned)lane << 2) + 8u * (unsigned)(staged_row + 2 * kStageGm);
+
     double kbest = __builtin_inf();   // smallest h seen by this lane
     int where = 0;                    // its accumulation count | (index of its group of 64 batch sizes) << 16
+    unsigned long long second = 0;    // staged terms: the lanes whose `where` belongs to the second group (no index in `where`)
     const ScalarDoubles rsc = (ScalarDoubles)rs;
 
-    // the counter of this loop is advanced on the scalar unit (it would otherwise be copied to a vector register)
-    for (int i0 = 0; i0 < Gm;) {
+    // One group of 64 batch sizes starting at i0.  G: the group's index when the terms are staged in LDS (the caller
+    // stages only grids of one or two groups, so the index is a compile-time constant and the group's offset goes
+    // into the LDS instructions' immediate fields), else -1.
+    auto group = [&](const int i0, auto G) __attribute__((always_inline)) {
+        constexpr int g = decltype(G)::value;
         const int i = i0 + lane;
         const bool active = WHOLE || i < Gm;
         const int il = active ? i : Gm - 1;
@@ -698,17 +706,14 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         if constexpr (TABLED) {
             double tg, C, A0;                        // A0 = +inf when the batch size has no feasible count
             int bounds;
-            if (WHOLE && staged_row >= 0) {
-                // (uniform byte offsets kept on the scalar unit, as above)
+            if constexpr (g >= 0) {
+                // the row's offset is added to the lane's once per call; the group's is a constant
                 typedef const char __attribute__((address_space(3))) *LdsBytes;
-                unsigned o_ca = i16 + 8u * (unsigned)staged_row, o_tg = i16 + 8u * (unsigned)kStageBase;
-                unsigned o_range = i4 + 8u * (unsigned)(staged_row + 2 * kStageGm);
-                asm("" : "+s"(o_ca), "+s"(o_tg), "+s"(o_range));
-                const Double2 car = *(const Double2 __attribute__((address_space(3))) *)((LdsBytes)near + (((unsigned)lane << 4) + o_ca));
+                const Double2 car = *(const Double2 __attribute__((address_space(3))) *)((LdsBytes)near + at_ca + 16 * kWave * g);
                 C = car.x;
                 A0 = car.y;
-                tg = *(LdsDoubles)((LdsBytes)near + (((unsigned)lane << 4) + o_tg));
-                bounds = *(const int __attribute__((address_space(3))) *)((LdsBytes)near + (((unsigned)lane << 2) + o_range));
+                tg = *(LdsDoubles)((LdsBytes)near + ((unsigned)lane << 4) + (8 * kStageBase + 16 * kWave * g));
+                bounds = *(const int __attribute__((address_space(3))) *)((LdsBytes)near + at_range + 4 * kWave * g);
             } else {
                 tg = *(const double *)((const char *)tb.tg + at16);
                 const double2 car = *(const double2 *)((const char *)carow + at16);
@@ -762,11 +767,30 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                 key = px_fma(B0, rs[s_c], px_fma((double)s_c, tg, A0));
             }
         }
-        if (feasible && key < kbest) {
+        if constexpr (g == 0) {
+            // the first group starts the lane's minimum (a batch size without a feasible count has h = +inf)
+            kbest = key;
+            where = s_c;
+        } else if constexpr (g == 1) {
+            // which lanes hold a batch size of the second group stays a lane mask in scalar registers
+            const bool better = key < kbest;
+            second = __builtin_amdgcn_ballot_w64(better);
+            kbest = better ? key : kbest;
+            where = better ? s_c : where;
+        } else if (feasible && key < kbest) {
             kbest = key;
             where = s_c | ((i0 / kWave) << 16);
         }
-        asm volatile("s_add_i32 %0, %0, 64" : "+s"(i0) : : "scc");
+    };
+    if (TABLED && WHOLE && staged_row >= 0) {
+        group(0, std::integral_constant<int, 0>());
+        if (Gm > kWave) group(kWave, std::integral_constant<int, 1>());
+    } else {
+        // the counter of this loop is advanced on the scalar unit (it would otherwise be copied to a vector register)
+        for (int i0 = 0; i0 < Gm;) {
+            group(i0, std::integral_constant<int, -1>());
+            asm volatile("s_add_i32 %0, %0, 64" : "+s"(i0) : : "scc");
+        }
     }
 
     // positive doubles order like their bit patterns: unsigned 32-bit wave minima, high words first;
@@ -781,6 +805,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
         if (winners & (winners - 1)) {
             // equal values (duplicated batch sizes): the lowest flat index i * Gs + s.  Winners with one
             // group of 64 and one count differ in the lane only, so the lowest lane has it; else a third minimum.
+            where |= (int)((second >> lane) & 1ull) << 16;
             const int first_lane = __ffsll(winners) - 1;
             const int where0 = __builtin_amdgcn_readlane(where, first_lane);
             const unsigned long long same = __builtin_amdgcn_ballot_w64(where == where0);
@@ -794,7 +819,7 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
     }
     const int wl = __ffsll(winners) - 1;
     const int wwhere = __builtin_amdgcn_readlane(where, wl);
-    return Pick{(wwhere >> 16) * kWave + wl, wwhere & 0xFFFF};
+    return Pick{((wwhere >> 16) | (int)((second >> wl) & 1ull)) * kWave + wl, wwhere & 0xFFFF};
 }
 
 // The same election for four (job, K, nodes) at once, one per row of 16 lanes, for small grids, where a sweep per
