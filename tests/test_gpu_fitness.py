@@ -225,6 +225,25 @@ def test_starved_jobs_and_duplicate_batch_sizes():
     assert compare(wl, run_gpu(wl), run_oracle(wl)) == 0
 
 
+@pytest.mark.parametrize("Gm", [64, 128])
+def test_duplicate_batch_sizes_in_grids_of_one_and_two_groups_of_64(Gm):
+    """Rows of 65 to 256 nodes with a grid of 64 or 128 batch sizes: the sweep takes the grid in one or two groups
+    of 64, one batch size per lane.  Grids made of copies put equal goodput values into several lanes of a group,
+    into the same lane of both groups, and into both (whichever copy wins, m* and s* are the same values); a grid
+    with its halves exchanged, or reversed, moves the best points into the other group and to the other end of the
+    lanes.  Elected (m*, s*), goodput and fitness must match the oracle in every case."""
+    cfg = W.custom("wide_ties", P=301, J=48, N=132, cap=8, Gm=Gm, Gs=32)
+    wl = W.make(cfg)
+    base = wl.m_grid.copy()
+    grids = [np.concatenate([base[:, :64]] * (Gm // 64), axis=1),                    # the second group repeats the first
+             np.repeat(base[:, ::4], 4, axis=1),                                      # runs of four equal batch sizes
+             np.concatenate([base[:, :32]] * (Gm // 32), axis=1),                     # lanes l and l + 32, and both groups
+             np.concatenate([base[:, 64:], base[:, :64]], axis=1) if Gm == 128 else base[:, ::-1].copy()]   # best point late in the grid
+    for grid in grids:
+        wl.m_grid[:] = grid
+        assert compare(wl, run_gpu(wl), run_oracle(wl)) == 0
+
+
 def test_deterministic_across_runs():
     wl = W.make("physical")
     a, b = run_gpu(wl), run_gpu(wl)
