@@ -590,6 +590,10 @@ __device__ __forceinline__ int scan_argmin(double C, const RunSteps &X, ScalarDo
     // smallest key, chunk by chunk
     double wmin = scan_chunk<CH>(C, X, rsc);
     int g_star = __double2loint(wmin) & 31;
+    // (the bound goes through an opaque statement: every inlined copy of this loop then tests it with a scalar
+    // comparison of its own, instead of sharing one truth value that the compiler carries around as a lane mask and
+    // negates with two vector instructions)
+    asm volatile("" : "+s"(Gs));
     for (int s0 = CH; s0 < Gs; s0 += CH) {
         const double w = scan_chunk<CH>(C, X, rsc + s0);
         const double moved = w + (double)s0;            // strictly smaller only: ties keep the smaller s
@@ -723,12 +727,14 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
             }
             const int s_lo = bounds & 0xFFFF, s_hi = bounds >> 16;
             feasible = active;
-            const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, has_near);
+            // (rows are staged only in a workgroup that also keeps the table of reciprocals and thresholds in LDS)
+            const bool tables_near = g >= 0 ? true : has_near;
+            const int s_star = scan_argmin<CH>(C, X, rsc, Gs, near, tables_near);
             // convex w, feasible counts s_lo .. s_hi: the constrained argmin is the clamped one
             s_c = s_star < s_hi ? s_star : s_hi;
             s_c = s_c > s_lo ? s_c : s_lo;
             double r_c, sd_c;
-            if (has_near) {
+            if (tables_near) {
                 const Double2 rc = *(const Double2 __attribute__((address_space(3))) *)(near + 2 * s_c);
                 r_c = rc.x;
                 sd_c = rc.y;
@@ -1361,7 +1367,8 @@ pairs_kernel(FitnessArgs a)
     constexpr bool kStage = CH != 0 && !F32 && !MEMO && ROW1 && !ROW4 && WHOLE;
     __shared__ __align__(16) double r_lds[kNearU + kNearRecips + 8 + (kStage ? kStageDoubles : 0)];
     __shared__ int stage_votes[kStage ? 2 * kTableK : 1];
-    const bool stage_on = kStage && a.Gm <= kStageGm;
+    // (only where the table of reciprocals and thresholds is in LDS as well: sweep_pick's staged path reads both)
+    const bool stage_on = kStage && a.Gm <= kStageGm && a.gs_pad <= kNearRecips;
     bool has_near = false;
     // (the instances whose rows fit one 16-byte load per lane fill the table after they have requested their first rows)
     constexpr bool kRowsFirst = CH != 0 && ROW1;
