@@ -36,12 +36,12 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "f2297f39f605a5d08fef780e88300473365b948ecad111764ed91f9cd2e36cde",
-        "traffic_bytes": 2_079_213 * 1024 * 2 + 696_815 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
+        "source_sha256": "be1e1f880bfbfa7b4dede0d1341f24f954617f4977dfbfc9b4485b73d8ada91f",
+        "traffic_bytes": 2_079_137 * 1024 * 2 + 698_183 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
         "fp64_flops": 64 * (8.960e5 + 1.770e7 + 2 * 2.670e8),
-        "valu_insts": 1.01153e9,
+        "valu_insts": 9.95523e8,
         "scan_insts": 2.25 * 1.6777e10 / 64,
-        "valu_busy": 1.02969e9 * 4 / 1024 / (3.42565e7 / 8),           # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
+        "valu_busy": 1.01368e9 * 4 / 1024 / (3.37224e7 / 8),           # SQ_ACTIVE_INST_VALU x 4 cycles / SIMDs / cycles
     },
 }
 GA_SEED = 0x2008_1226_5EED_0001
