@@ -118,11 +118,13 @@ def test_feasible_windows_that_cut_off_the_unconstrained_optimum_on_either_side(
     assert (s[:, 1::3] >= 8).any() and (s[:, 0::3] >= 1).any() and (s >= 32).any()     # the cases are really there
 
 
-def test_more_accumulation_counts_than_the_reciprocal_table_kept_on_chip():
+@pytest.mark.parametrize("P,N,Gm", [(6, 8, 20), (70, 132, 64), (70, 256, 128)])
+def test_more_accumulation_counts_than_the_reciprocal_table_kept_on_chip(P, N, Gm):
     """Gs = 300: the table of 1/(s+1) no longer fits the on-chip copy, so the count inside the winning group of
-    four and the reciprocal at the clamped count come from memory.  Heavy synchronisation costs push the
-    elected count far up; M_max is wide enough to allow it."""
-    cfg = W.custom("long_s", P=6, J=9, N=8, cap=8, Gm=20, Gs=300)
+    four and the reciprocal at the clamped count come from memory (with rows of 65 to 256 nodes and whole groups
+    of 64 batch sizes the terms of a table row are then read from memory too, not from an on-chip copy).  Heavy
+    synchronisation costs push the elected count far up; M_max is wide enough to allow it."""
+    cfg = W.custom("long_s", P=P, J=9, N=N, cap=8, Gm=Gm, Gs=300)
     wl = W.make(cfg)
     ix = W.PARAM_INDEX
     jp = wl.job_params.copy()
@@ -133,7 +135,8 @@ def test_more_accumulation_counts_than_the_reciprocal_table_kept_on_chip():
     g, r = run_gpu(wl, job_params=jp), run_oracle(wl, job_params=jp)
     assert compare(wl, g, r, job_params=jp) == 0
     s = r["best_s"]
-    assert ((s >= 256) & (s < 299)).any() and ((s >= 100) & (s < 256)).any() and (s < 32).any()     # inside the range, not only at its end
+    assert ((s >= 100) & (s < 256)).any() and (s < 32).any()     # inside the range, not only at its end
+    assert Gm > 64 or ((s >= 256) & (s < 299)).any()              # (the grid of 128 batch sizes elects none that far up)
 
 
 def test_status_bits():
