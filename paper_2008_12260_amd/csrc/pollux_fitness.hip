@@ -666,7 +666,8 @@ __device__ __forceinline__ Pick sweep_pick(const Job &q, const JobTables &tb, co
                                            LdsDoubles near = nullptr, bool has_near = false, int staged_row = -1)
 {
     // near: a copy of rs in LDS (quicker to read per lane) when has_near
-    // staged_row: where in `near` the terms of this (class, K) are staged (TABLED and WHOLE; see kStageBase), or -1
+    // staged_row: where in `near` the terms of this (class, K) are staged (TABLED and WHOLE; see kStageBase), or -1;
+    // rows are staged only together with has_near
     const int lane = lane_id();
     K = __builtin_amdgcn_readfirstlane(K);        // the same in every lane (see above): kept in scalar registers
     nodes = __builtin_amdgcn_readfirstlane(nodes);
