@@ -292,7 +292,7 @@ enum {
  * the pollux_fitness calls of a search, PX_FLAG_KEEP_JOB_TABLES included.  workspace_bytes must be at
  * least pollux_workspace_size of these dims with Gm and Gs taken as 1 when they are not positive.
  * Limit: the per-job and per-node bookkeeping of a child lives in the 160 KB of on-chip memory of a
- * compute unit: 16 N + 16 J + 12 E (+ 8 N if J < N) bytes, E = 1.5 J rounded up to a multiple of 256 and
+ * compute unit: 16 N + 16 J + 12 E (+ 8 N if J < N, + 260 N if N <= 64) bytes, E = 1.5 J rounded up to a multiple of 256 and
  * kept within 512..3072, must not exceed 159 KB; beyond that PX_E_INVALID_ARG (e.g. J = 1000 jobs allow up to N = 5349 nodes).
  */
 int pollux_ga_step(const pollux_dims *dims,              /* host; only P, J, N are read */
