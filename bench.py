@@ -36,7 +36,7 @@ FLOPS_PER_EVAL = 7                  # Eq. 4 at one grid point: 5 add/mul + 2 div
 #   valu_busy       fraction of the kernel's cycles in which the vector ALUs were busy
 PROFILED = {
     "large": {
-        "source_sha256": "dcb869d536f9eb4b33807042b761d6f93fe3d6cb7c41f5f802d0403f286a93a0",
+        "source_sha256": "9fc9005fe7fdea90975db54cb86c8be87596f71b8f68e43c9cc4102ab6256aad",
         "traffic_bytes": 2_079_137 * 1024 * 2 + 698_183 * 1024,      # FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 (launches that store m*, s*)
         "fp64_flops": 64 * (8.960e5 + 1.770e7 + 2 * 2.670e8),
         "valu_insts": 9.95523e8,

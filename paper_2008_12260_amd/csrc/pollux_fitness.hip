@@ -1761,7 +1761,8 @@ pairs_kernel(FitnessArgs a)
                 const int nodes = __builtin_amdgcn_ds_bpermute(r << 2, d_meta) & ~kMetaChanged;
                 const bool within = tabled_row(K, nodes == 1, tb.k1);
                 const int K_in = (K < 1 || !within) ? 1 : K;
-                const int found = sweep_pick_rows<CH, WHOLE>(tb, X, a.rs, a.Gm, a.Gs, K_in, nodes == 1 && within, (LdsDoubles)r_lds, has_near);
+                // (this instance is launched only for grids whose tables of reciprocals and thresholds fit LDS)
+                const int found = sweep_pick_rows<CH, WHOLE>(tb, X, a.rs, a.Gm, a.Gs, K_in, nodes == 1 && within, (LdsDoubles)r_lds, WHOLE || has_near);
                 int pi = found < 0 ? -1 : found >> 16, ps = found < 0 ? -1 : found & 0xFFFF;
                 if (K >= 1 && !within) {                     // rare: swept after the loop, outside the hot path
                     pi = kPending;
@@ -2539,6 +2540,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
     }
     if (sweep_start) (void)hipEventRecord(sweep_start, stream);
     const bool whole = d->Gm % kWave == 0;
+    const bool near = a.gs_pad <= kNearRecips;      // the kernels keep reciprocals and thresholds of all counts in LDS
 #define PX_LAUNCH_PAIRS(CH, F32, MEMO, ROW1, WHOLE, ROW4)                                                               \
     do {                                                                                                                \
         if (a.dirty) hipLaunchKernelGGL((pairs_kernel<CH, F32, MEMO, ROW1, WHOLE, ROW4, 2>), dim3(pair_blocks), dim3(256), 0, stream, a); \
@@ -2551,7 +2553,7 @@ int launch_fitness(const pollux_dims *d, const int32_t *population, const double
         if (memo && row4) PX_LAUNCH_PAIRS(CH, F32, true, true, false, true);   \
         else if (memo && row1) PX_LAUNCH_PAIRS(CH, F32, true, true, false, false); \
         else if (memo) PX_LAUNCH_PAIRS(CH, F32, true, false, false, false);    \
-        else if (row4 && whole) PX_LAUNCH_PAIRS(CH, F32, false, true, true, true); \
+        else if (row4 && whole && near) PX_LAUNCH_PAIRS(CH, F32, false, true, true, true); \
         else if (row1 && whole) PX_LAUNCH_PAIRS(CH, F32, false, true, true, false); \
         else if (row1) PX_LAUNCH_PAIRS(CH, F32, false, true, false, false);    \
         else PX_LAUNCH_PAIRS(CH, F32, false, false, false, false);             \
