@@ -118,11 +118,12 @@ def test_feasible_windows_that_cut_off_the_unconstrained_optimum_on_either_side(
     assert (s[:, 1::3] >= 8).any() and (s[:, 0::3] >= 1).any() and (s >= 32).any()     # the cases are really there
 
 
-@pytest.mark.parametrize("P,N,Gm", [(6, 8, 20), (70, 132, 64), (70, 256, 128)])
+@pytest.mark.parametrize("P,N,Gm", [(6, 8, 20), (70, 64, 64), (70, 132, 64), (70, 256, 128)])
 def test_more_accumulation_counts_than_the_reciprocal_table_kept_on_chip(P, N, Gm):
     """Gs = 300: the table of 1/(s+1) no longer fits the on-chip copy, so the count inside the winning group of
     four and the reciprocal at the clamped count come from memory (with rows of 65 to 256 nodes and whole groups
-    of 64 batch sizes the terms of a table row are then read from memory too, not from an on-chip copy).  Heavy
+    of 64 batch sizes the terms of a table row are then read from memory too, not from an on-chip copy; rows of at
+    most 64 nodes are then read one to a wavefront load, not four).  Heavy
     synchronisation costs push the elected count far up; M_max is wide enough to allow it."""
     cfg = W.custom("long_s", P=P, J=9, N=N, cap=8, Gm=Gm, Gs=300)
     wl = W.make(cfg)
